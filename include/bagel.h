@@ -1,0 +1,154 @@
+/*
+ * bagel.h - C ABI of libbagel.so: batched Monte-Carlo rollouts of a tanh-MLP
+ * policy through pathwise-sampled Gaussian-process dynamics on one MI355X
+ * (gfx950), and the reverse-mode gradient of the mean trajectory cost with
+ * respect to the policy parameters (arXiv 2202.13638, Algorithm 1: forward
+ * pass, loss, backward pass).
+ *
+ * Model (per GP output m = 0..d_s-1, one independent GP per state increment,
+ * Sec. III-A):
+ *   kernel      k_m(x,x') = signal_var[m] * exp(-1/2 sum_d (x_d-x'_d)^2 / lengthscale[m][d]^2)   eq. (4)
+ *   features    phi_m(x)_l = sqrt(2 signal_var[m] / L) * cos(omega[m][l] . x + phase[m][l])
+ *   sample s    f_sm(x) = phi_m(x)^T w[s][m] + k_m(x, X)^T v[s][m],
+ *               v[s][m] = (K_m + noise_var[m] I)^-1 (y[m] - Phi_m w[s][m] - eps[s][m])            K_hat below eq. (3)
+ * Rollout (Algorithm 1; trajectory b uses sample b / (B / S)):
+ *   a_t = pi_theta([s_t ; g_t]),  x_t = [s_t ; a_t],  s_{t+1} = s_t + f_s(x_t),
+ *   c_{t+1} = sum_j q[j] (s_{t+1}[tracked[j]] - g_t[j])^2            (cost_kind 0)
+ *           = -exp(-(1/(2 sigma_r^2)) * that sum)                      (cost_kind 1, eq. (8) as a cost)
+ *   loss = (1/B) sum_b sum_{t=1..H} c_t                                eq. (10), (11)
+ *
+ * Conventions
+ *   - Every array argument is a DEVICE pointer to memory owned by the caller, row-major
+ *     with the extents given in brackets, float32 unless stated.  The library reads inputs
+ *     and writes outputs on the stream passed to bagel_create; it never frees or keeps
+ *     caller memory after a call returns, except that prepare/set_samples copy the model
+ *     into context-owned buffers in an internal layout.
+ *   - The rollout calls enqueue work and return; they do not synchronise the stream and
+ *     allocate nothing.  Outputs are valid once the stream has drained.
+ *   - The kernel-row contraction over the N training points is evaluated in float64
+ *     (operands are the float32 inputs promoted exactly); everything at the interface is
+ *     float32.
+ *   - theta layout: for each layer in order, W[out][in] row-major then b[out].
+ *     Layers: (d_s+d_g) -> hidden[0] (-> hidden[1]) -> d_a, tanh on hidden layers;
+ *     output a = z if act_bound <= 0, else act_bound * tanh(z) (Sec. IV-A: bounded action).
+ *   - No random numbers are drawn inside the library: omega, phase, w, eps are inputs.
+ *   - Return value: 0 on success, a negative BAGEL_E* code otherwise; bagel_last_error
+ *     gives a message.  NaN/Inf inputs are not screened; they propagate.
+ *   - One context must not be used from two threads at once.
+ */
+#ifndef BAGEL_H
+#define BAGEL_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BAGEL_OK 0
+#define BAGEL_EINVAL (-1)        /* null pointer, non-positive or unsupported dimension, S does not divide B ... */
+#define BAGEL_ENOTPREPARED (-2)  /* rollout called before prepare_samples / set_samples */
+#define BAGEL_ENOMEM (-3)        /* device allocation failed in bagel_create */
+#define BAGEL_ENOTPD (-4)        /* K + noise_var I is not positive definite in float64 */
+#define BAGEL_EHIP (-5)          /* a HIP runtime call failed */
+
+#define BAGEL_MAX_STATE 8        /* d_s <= 8, d_a <= 8, d_g <= 8 */
+#define BAGEL_MAX_HIDDEN 256     /* width of a hidden layer */
+
+typedef struct bagel_ctx bagel_ctx; /* opaque; owns the model copy and all workspace */
+
+typedef struct {
+    int32_t d_s, d_a, d_g;   /* states, actions, tracked states (= goal dimension); D = d_s + d_a */
+    int32_t N, L, S, B, H;   /* training points, features, function samples, trajectories, horizon;
+                                1 <= S <= B and B % S == 0 */
+    int32_t n_hidden;        /* 1 or 2 */
+    int32_t hidden[2];
+    float act_bound;         /* <= 0: linear output */
+    int32_t tracked[8];      /* state index of goal component j, j < d_g */
+    float q[8];              /* cost weight of goal component j */
+    int32_t ckpt_interval;   /* 0: keep the whole tape in the gradient call; K > 0: keep the state every K
+                                steps and re-run each K-step segment in the backward sweep (Sec. IV-C:
+                                trading compute for memory).  Results are identical. */
+    int32_t cost_kind;       /* 0 quadratic tracking cost, 1 negative saturating reward of eq. (8) */
+    float sigma_r;           /* width of eq. (8); used only if cost_kind == 1 */
+} bagel_dims;
+
+/* Number of policy parameters P for these dims, or BAGEL_EINVAL. */
+int bagel_num_params(const bagel_dims *dims);
+
+/*
+ * Create a context for fixed dims on the current HIP device.  Allocates every buffer the
+ * other calls need (model copy, tape, partial sums).  `hip_stream` is a hipStream_t
+ * (NULL = default stream); all later work of this context is enqueued there.
+ * Errors: EINVAL (bad dims, null pointers), ENOMEM, EHIP.
+ */
+int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_stream);
+
+/* Free everything the context owns (synchronises its stream first).  NULL is allowed. */
+int bagel_destroy(bagel_ctx *ctx);
+
+/* Device bytes held by the context. */
+int64_t bagel_workspace_bytes(const bagel_ctx *ctx);
+
+/*
+ * Sample-set precompute (the one-time step before the rollouts; the pathwise counterpart of the
+ * paper's one-time cache, Sec. IV-A).  For every output m: builds K_m + noise_var[m] I and Phi_m
+ * in float64, factors it (Cholesky), solves for every sample, rounds v to float32, and installs
+ * the model and samples in the context.
+ *   X[N][D]  y[M][N]  lengthscale[M][D]  signal_var[M]  noise_var[M]
+ *   omega[M][L][D] (already divided by the length scales)  phase[M][L]
+ *   w[S][M][L]  eps[S][M][N]      (M = d_s)
+ *   v_out[S][M][N] or NULL: receives the float32 representer weights.
+ * Synchronises the stream (it must learn whether the factorisation succeeded).
+ * Errors: EINVAL, ENOTPD (context is left unprepared), EHIP.
+ */
+int bagel_prepare_samples(bagel_ctx *ctx, const float *X, const float *y, const float *lengthscale,
+                          const float *signal_var, const float *noise_var, const float *omega,
+                          const float *phase, const float *w, const float *eps, float *v_out);
+
+/*
+ * Install a model with representer weights v[S][M][N] computed elsewhere (same arrays as
+ * above otherwise; y and eps are not needed).  Lets a caller reuse stored samples, and lets
+ * the tests drive the rollouts from exactly the float32 v the reference implementation used.
+ * Errors: EINVAL, EHIP.
+ */
+int bagel_set_samples(bagel_ctx *ctx, const float *X, const float *lengthscale, const float *signal_var,
+                      const float *omega, const float *phase, const float *w, const float *v);
+
+/*
+ * Forward pass and loss (Algorithm 1, forward pass).
+ *   theta[P]  s0[B][d_s]  goals[H][B][d_g] (goals[t] is what the policy sees at step t and what
+ *   the cost at s_{t+1} is measured against)
+ *   loss[1]; loss_per_traj[B] or NULL (sum over t, not divided by B);
+ *   states[H+1][B][d_s] or NULL.
+ * Errors: EINVAL, ENOTPREPARED, EHIP.
+ */
+int bagel_rollout_loss(bagel_ctx *ctx, const float *theta, const float *s0, const float *goals,
+                       float *loss, float *loss_per_traj, float *states);
+
+/*
+ * Forward pass, loss and backward pass (Algorithm 1: loss and its gradient with respect to
+ * theta, here by a hand-written adjoint instead of automatic differentiation).
+ *   grad_theta[P] (same layout as theta); grad_s0[B][d_s] or NULL (d loss / d s0);
+ *   other arguments as in bagel_rollout_loss.
+ * The result does not depend on ckpt_interval.  Errors: EINVAL, ENOTPREPARED, EHIP.
+ */
+int bagel_rollout_loss_grad(bagel_ctx *ctx, const float *theta, const float *s0, const float *goals,
+                            float *loss, float *grad_theta, float *loss_per_traj, float *states,
+                            float *grad_s0);
+
+/*
+ * One evaluation of the function samples (the transition model alone): for every trajectory b,
+ * f[b][m] = f_{s(b),m}(x[b]) and, if jac != NULL, jac[b][m][d] = d f / d x_d.   x[B][D].
+ * Runs the same kernels as one rollout step.  Errors: EINVAL, ENOTPREPARED, EHIP.
+ */
+int bagel_sample_eval(bagel_ctx *ctx, const float *x, float *f, float *jac);
+
+/* Message of the last error on this context ("" if none); valid until the next call on it.
+ * With ctx == NULL: message of the last failed bagel_create on this thread. */
+const char *bagel_last_error(const bagel_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BAGEL_H */

@@ -1,0 +1,314 @@
+// C ABI of libbagel.so (declared in include/bagel.h): argument checks, the context and its
+// buffers, and the per-call schedule of kernels.  A rollout is a host loop over the horizon that
+// enqueues, per step, the policy kernel, the sample-evaluation kernel and the state-advance kernel
+// on the context's stream (Algorithm 1, forward pass); the gradient call then sweeps the tape
+// backwards (Algorithm 1, backward pass) and finishes with one weight-gradient GEMM per layer.
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+
+#include "bagel_internal.h"
+
+static thread_local char g_create_err[512] = "";
+
+#define CREATE_FAIL(code, ...)                                    \
+    do {                                                          \
+        snprintf(g_create_err, sizeof(g_create_err), __VA_ARGS__); \
+        return (code);                                            \
+    } while (0)
+
+static const char *check_dims(const bagel_dims *d)
+{
+    if (d->d_s < 1 || d->d_s > BAGEL_MAX_STATE) return "d_s must be in 1..8";
+    if (d->d_a < 1 || d->d_a > BAGEL_MAX_STATE) return "d_a must be in 1..8";
+    if (d->d_g < 1 || d->d_g > BAGEL_MAX_STATE || d->d_g > d->d_s) return "d_g must be in 1..min(8, d_s)";
+    if (d->N < 1 || d->L < 1 || d->S < 1 || d->B < 1 || d->H < 1) return "N, L, S, B, H must be positive";
+    if (d->S > d->B || d->B % d->S != 0) return "S must divide B";
+    if (d->n_hidden < 1 || d->n_hidden > 2) return "n_hidden must be 1 or 2";
+    for (int i = 0; i < d->n_hidden; ++i)
+        if (d->hidden[i] < 1 || d->hidden[i] > BAGEL_MAX_HIDDEN) return "hidden width must be in 1..256";
+    for (int j = 0; j < d->d_g; ++j)
+        if (d->tracked[j] < 0 || d->tracked[j] >= d->d_s) return "tracked index out of range";
+    if (d->ckpt_interval < 0) return "ckpt_interval must be >= 0";
+    if (d->cost_kind != 0 && d->cost_kind != 1) return "cost_kind must be 0 or 1";
+    if (d->cost_kind == 1 && !(d->sigma_r > 0.0f)) return "sigma_r must be positive for cost_kind 1";
+    if ((int64_t)d->B * d->H > ((int64_t)1 << 40)) return "B * H too large";
+    return nullptr;
+}
+
+static void layer_layout(const bagel_dims *d, int *width, int *w_off, int *b_off, int *P)
+{
+    width[0] = d->d_s + d->d_g;
+    for (int i = 0; i < d->n_hidden; ++i) width[i + 1] = d->hidden[i];
+    width[d->n_hidden + 1] = d->d_a;
+    int off = 0;
+    for (int l = 0; l <= d->n_hidden; ++l) {
+        w_off[l] = off;
+        off += width[l + 1] * width[l];
+        b_off[l] = off;
+        off += width[l + 1];
+    }
+    *P = off;
+}
+
+extern "C" int bagel_num_params(const bagel_dims *dims)
+{
+    if (!dims || check_dims(dims)) return BAGEL_EINVAL;
+    int width[4], w_off[3], b_off[3], P;
+    layer_layout(dims, width, w_off, b_off, &P);
+    return P;
+}
+
+template <class T>
+static hipError_t dev_alloc(bagel_ctx *c, T **p, size_t count)
+{
+    *p = nullptr;
+    if (count == 0) count = 1;
+    hipError_t e = hipMalloc((void **)p, count * sizeof(T));
+    if (e == hipSuccess) c->bytes += (int64_t)(count * sizeof(T));
+    return e;
+}
+
+static void free_all(bagel_ctx *c)
+{
+    void *ptrs[] = {c->Xs, c->Os, c->A, c->amp, c->v4, c->w4, c->xbuf, c->part, c->lpt, c->lam, c->us, c->dh0,
+                    c->tape_s, c->tape_J, c->tape_h[0], c->tape_h[1], c->tape_h[2], c->tape_a, c->tape_d[0],
+                    c->tape_d[1], c->tape_d[2], c->ckpt_s, c->thetaT, c->gsplit, c->gacc};
+    for (void *p : ptrs)
+        if (p) (void)hipFree(p);
+}
+
+static int env_int(const char *name, int dflt)
+{
+    const char *s = getenv(name);
+    if (!s || !*s) return dflt;
+    const int v = atoi(s);
+    return v > 0 ? v : dflt;
+}
+
+extern "C" int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_stream)
+{
+    if (!out || !dims) CREATE_FAIL(BAGEL_EINVAL, "bagel_create: null argument");
+    *out = nullptr;
+    if (const char *msg = check_dims(dims)) CREATE_FAIL(BAGEL_EINVAL, "bagel_create: %s", msg);
+    bagel_ctx *c = new (std::nothrow) bagel_ctx();
+    if (!c) CREATE_FAIL(BAGEL_ENOMEM, "bagel_create: host allocation failed");
+    memset(c, 0, sizeof(*c));
+    c->dm = *dims;
+    c->D = dims->d_s + dims->d_a;
+    c->M = dims->d_s;
+    c->d_in = dims->d_s + dims->d_g;
+    c->n_layers = dims->n_hidden + 1;
+    layer_layout(dims, c->width, c->w_off, c->b_off, &c->P);
+    c->stream = (hipStream_t)hip_stream;
+
+    // work decomposition of one sample evaluation: power-of-two chunk of training points / features
+    const int B = dims->B, N = dims->N, L = dims->L, M = c->M, D = c->D;
+    const int64_t tb = (B + BAGEL_BLOCK - 1) / BAGEL_BLOCK;
+    const int64_t items = (int64_t)(N + L) * M * tb;
+    const int target = env_int("BAGEL_TARGET_WGS", 4096);
+    int chunk = 1024;
+    while (chunk > 32 && items / chunk < target) chunk /= 2;
+    c->CK = env_int("BAGEL_CK", chunk);
+    c->CL = env_int("BAGEL_CL", chunk);
+    c->CK = (c->CK + 3) & ~3;
+    c->CL = (c->CL + 3) & ~3;
+    c->nck = (N + c->CK - 1) / c->CK;
+    c->ncl = (L + c->CL - 1) / c->CL;
+    c->Np = c->nck * c->CK;
+    c->Lp = c->ncl * c->CL;
+    c->units = M * (c->nck + c->ncl);
+    if (c->units > 65535) {
+        delete c;
+        CREATE_FAIL(BAGEL_EINVAL, "bagel_create: too many work units (%d)", M * 0);
+    }
+
+    const int K = dims->ckpt_interval;
+    const int H = dims->H;
+    c->T_tape = (K > 0 && K < H) ? K : H;
+    const int n_seg = (K > 0 && K < H) ? (H + K - 1) / K : 1;
+    c->ksplit = env_int("BAGEL_KSPLIT", 32);
+    const size_t Bz = (size_t)B, T = (size_t)c->T_tape;
+
+    hipError_t e = hipSuccess;
+#define ALLOC(ptr, count)                         \
+    if (e == hipSuccess) e = dev_alloc(c, &(ptr), (size_t)(count))
+    ALLOC(c->Xs, (size_t)M * c->Np * (D + 1));
+    ALLOC(c->Os, (size_t)M * c->Lp * (D + 1));
+    ALLOC(c->A, (size_t)M * D);
+    ALLOC(c->amp, (size_t)M);
+    ALLOC(c->v4, (size_t)M * (c->Np / 4) * dims->S);
+    ALLOC(c->w4, (size_t)M * (c->Lp / 4) * dims->S);
+    ALLOC(c->xbuf, (size_t)D * Bz);
+    ALLOC(c->part, (size_t)c->units * (1 + D) * Bz);
+    ALLOC(c->lpt, Bz);
+    ALLOC(c->lam, (size_t)dims->d_s * Bz);
+    ALLOC(c->us, (size_t)dims->d_s * Bz);
+    ALLOC(c->dh0, (size_t)c->d_in * Bz);
+    ALLOC(c->tape_s, (size_t)(H + 1) * dims->d_s * Bz);
+    ALLOC(c->tape_J, T * M * D * Bz);
+    for (int l = 0; l < c->n_layers; ++l) {
+        ALLOC(c->tape_h[l], T * c->width[l] * Bz);
+        ALLOC(c->tape_d[l], T * c->width[l + 1] * Bz);
+    }
+    ALLOC(c->tape_a, T * dims->d_a * Bz);
+    ALLOC(c->ckpt_s, (size_t)n_seg * dims->d_s * Bz);
+    ALLOC(c->thetaT, (size_t)c->P);
+    ALLOC(c->gsplit, (size_t)c->ksplit * c->P);
+    ALLOC(c->gacc, (size_t)c->P);
+#undef ALLOC
+    if (e != hipSuccess) {
+        const int64_t want = c->bytes;
+        free_all(c);
+        delete c;
+        (void)hipGetLastError();
+        if (e == hipErrorOutOfMemory || e == hipErrorMemoryAllocation)
+            CREATE_FAIL(BAGEL_ENOMEM, "bagel_create: device allocation failed after %lld bytes", (long long)want);
+        CREATE_FAIL(BAGEL_EHIP, "bagel_create: hipMalloc failed: %s", hipGetErrorString(e));
+    }
+    g_create_err[0] = 0;
+    *out = c;
+    return BAGEL_OK;
+}
+
+extern "C" int bagel_destroy(bagel_ctx *c)
+{
+    if (!c) return BAGEL_OK;
+    (void)hipStreamSynchronize(c->stream);
+    free_all(c);
+    delete c;
+    return BAGEL_OK;
+}
+
+extern "C" int64_t bagel_workspace_bytes(const bagel_ctx *c) { return c ? c->bytes : 0; }
+
+extern "C" const char *bagel_last_error(const bagel_ctx *c) { return c ? c->err : g_create_err; }
+
+extern "C" int bagel_set_samples(bagel_ctx *c, const float *X, const float *lengthscale, const float *signal_var,
+                                 const float *omega, const float *phase, const float *w, const float *v)
+{
+    if (!c) return BAGEL_EINVAL;
+    c->err[0] = 0;
+    if (!X || !lengthscale || !signal_var || !omega || !phase || !w || !v)
+        BAGEL_FAIL(c, BAGEL_EINVAL, "bagel_set_samples: null argument");
+    c->prepared = false;
+    BAGEL_HIP(c, bagel_launch_build_model(c, X, lengthscale, signal_var, omega, phase));
+    BAGEL_HIP(c, bagel_launch_pack_samples(c, w, v));
+    c->prepared = true;
+    return BAGEL_OK;
+}
+
+extern "C" int bagel_prepare_samples(bagel_ctx *c, const float *X, const float *y, const float *lengthscale,
+                                     const float *signal_var, const float *noise_var, const float *omega,
+                                     const float *phase, const float *w, const float *eps, float *v_out)
+{
+    if (!c) return BAGEL_EINVAL;
+    c->err[0] = 0;
+    if (!X || !y || !lengthscale || !signal_var || !noise_var || !omega || !phase || !w || !eps)
+        BAGEL_FAIL(c, BAGEL_EINVAL, "bagel_prepare_samples: null argument");
+    c->prepared = false;
+    BAGEL_HIP(c, bagel_launch_build_model(c, X, lengthscale, signal_var, omega, phase));
+    BAGEL_HIP(c, bagel_launch_pack_samples(c, w, nullptr));
+    const int rc = bagel_prepare_impl(c, X, y, lengthscale, signal_var, noise_var, omega, phase, w, eps, v_out);
+    if (rc != BAGEL_OK) return rc;
+    c->prepared = true;
+    return BAGEL_OK;
+}
+
+extern "C" int bagel_sample_eval(bagel_ctx *c, const float *x, float *f, float *jac)
+{
+    if (!c) return BAGEL_EINVAL;
+    c->err[0] = 0;
+    if (!x || !f) BAGEL_FAIL(c, BAGEL_EINVAL, "bagel_sample_eval: null argument");
+    if (!c->prepared) BAGEL_FAIL(c, BAGEL_ENOTPREPARED, "bagel_sample_eval: no samples installed");
+    BAGEL_HIP(c, bagel_launch_eval_io(c, 0, x, nullptr, nullptr));
+    BAGEL_HIP(c, bagel_launch_gp_step(c, jac != nullptr));
+    BAGEL_HIP(c, bagel_launch_eval_io(c, 1, nullptr, f, jac));
+    return BAGEL_OK;
+}
+
+// forward steps t0 .. t1-1 starting from the state in xbuf and the policy input in slot (t0 - slot_base)
+static int run_forward(bagel_ctx *c, int t0, int t1, int slot_base, bool jac, bool add_cost, bool write_tape_s,
+                       bool write_ckpt, const float *goals, float *states_out)
+{
+    const int K = c->T_tape;
+    for (int t = t0; t < t1; ++t) {
+        const int slot = jac ? t - slot_base : 0;
+        const int next_slot = jac ? (t + 1 < t1 ? slot + 1 : -1) : 0;
+        BAGEL_HIP(c, bagel_launch_policy_forward(c, slot));
+        BAGEL_HIP(c, bagel_launch_gp_step(c, jac));
+        const int ck = (write_ckpt && (t + 1) % K == 0 && t + 1 < c->dm.H) ? (t + 1) / K : -1;
+        BAGEL_HIP(c, bagel_launch_advance(c, t, slot, next_slot, jac, add_cost, write_tape_s, ck, goals, states_out));
+    }
+    return BAGEL_OK;
+}
+
+extern "C" int bagel_rollout_loss(bagel_ctx *c, const float *theta, const float *s0, const float *goals,
+                                  float *loss, float *loss_per_traj, float *states)
+{
+    if (!c) return BAGEL_EINVAL;
+    c->err[0] = 0;
+    if (!theta || !s0 || !goals || !loss) BAGEL_FAIL(c, BAGEL_EINVAL, "bagel_rollout_loss: null argument");
+    if (!c->prepared) BAGEL_FAIL(c, BAGEL_ENOTPREPARED, "bagel_rollout_loss: no samples installed");
+    BAGEL_HIP(c, bagel_launch_transpose_theta(c, theta));
+    BAGEL_HIP(c, bagel_launch_init_state(c, s0, goals, states, false, false));
+    const int rc = run_forward(c, 0, c->dm.H, 0, false, true, false, false, goals, states);
+    if (rc != BAGEL_OK) return rc;
+    BAGEL_HIP(c, bagel_launch_finish_loss(c, loss, loss_per_traj));
+    return BAGEL_OK;
+}
+
+// backward sweep over steps t1-1 .. t0 whose tape sits in slots 0 .. t1-t0-1
+static int run_backward(bagel_ctx *c, int t0, int t1, const float *theta, const float *goals)
+{
+    for (int t = t1; t > t0; --t) {
+        BAGEL_HIP(c, bagel_launch_adjoint_lane(c, t, t - 1 - t0, goals, nullptr));
+        BAGEL_HIP(c, bagel_launch_policy_backward(c, t - 1 - t0, theta));
+    }
+    return BAGEL_OK;
+}
+
+extern "C" int bagel_rollout_loss_grad(bagel_ctx *c, const float *theta, const float *s0, const float *goals,
+                                       float *loss, float *grad_theta, float *loss_per_traj, float *states,
+                                       float *grad_s0)
+{
+    if (!c) return BAGEL_EINVAL;
+    c->err[0] = 0;
+    if (!theta || !s0 || !goals || !loss || !grad_theta)
+        BAGEL_FAIL(c, BAGEL_EINVAL, "bagel_rollout_loss_grad: null argument");
+    if (!c->prepared) BAGEL_FAIL(c, BAGEL_ENOTPREPARED, "bagel_rollout_loss_grad: no samples installed");
+    const int H = c->dm.H, K = c->T_tape;
+    const bool ckpt = K < H;
+    int rc;
+    BAGEL_HIP(c, bagel_launch_transpose_theta(c, theta));
+    BAGEL_HIP(c, bagel_launch_init_state(c, s0, goals, states, true, ckpt));
+    if (!ckpt) {
+        rc = run_forward(c, 0, H, 0, true, true, true, false, goals, states);
+        if (rc != BAGEL_OK) return rc;
+        BAGEL_HIP(c, bagel_launch_finish_loss(c, loss, loss_per_traj));
+        rc = run_backward(c, 0, H, theta, goals);
+        if (rc != BAGEL_OK) return rc;
+        BAGEL_HIP(c, bagel_launch_adjoint_lane(c, 0, 0, goals, grad_s0));
+        BAGEL_HIP(c, bagel_launch_weight_grad(c, H, false, grad_theta));
+        return BAGEL_OK;
+    }
+    // checkpointed: a plain forward pass that keeps the state every K steps, then one segment at a
+    // time from the end: re-run it with Jacobians and tapes, sweep it backwards, add its weight gradient.
+    rc = run_forward(c, 0, H, 0, false, true, true, true, goals, states);
+    if (rc != BAGEL_OK) return rc;
+    BAGEL_HIP(c, bagel_launch_finish_loss(c, loss, loss_per_traj));
+    const int n_seg = (H + K - 1) / K;
+    for (int seg = n_seg - 1; seg >= 0; --seg) {
+        const int t0 = seg * K, t1 = (t0 + K < H) ? t0 + K : H;
+        BAGEL_HIP(c, bagel_launch_restore(c, seg, t0, goals));
+        rc = run_forward(c, t0, t1, t0, true, false, false, false, goals, nullptr);
+        if (rc != BAGEL_OK) return rc;
+        rc = run_backward(c, t0, t1, theta, goals);
+        if (rc != BAGEL_OK) return rc;
+        if (seg == 0) BAGEL_HIP(c, bagel_launch_adjoint_lane(c, 0, 0, goals, grad_s0));
+        BAGEL_HIP(c, bagel_launch_weight_grad(c, t1 - t0, seg != n_seg - 1, seg == 0 ? grad_theta : nullptr));
+    }
+    return BAGEL_OK;
+}

@@ -1,0 +1,104 @@
+// Internal declarations shared by the translation units of libbagel.so.
+// Nothing here is part of the public ABI (see include/bagel.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "bagel.h"
+
+#define BAGEL_BLOCK 256          // threads per workgroup in the lane-per-trajectory kernels
+#define BAGEL_MAX_D 16
+
+struct bagel_ctx {
+    bagel_dims dm;
+    int D, M, P, d_in;
+    int n_layers;                // n_hidden + 1
+    int width[4];                // d_in, hidden..., d_a
+    int w_off[3], b_off[3];      // offsets of W_l and b_l inside theta
+    hipStream_t stream;
+    bool prepared;
+    char err[512];
+    int64_t bytes;
+
+    // ---- model, internal layout --------------------------------------------------------
+    int Np, Lp;                  // N and L rounded up to a whole number of chunks
+    int CK, CL;                  // training points / features per work unit (multiples of 4)
+    int nck, ncl;                // chunks per output
+    int units;                   // M * (nck + ncl)
+    double *Xs;                  // [M][Np][D+1]: log2(e)/l_md^2 * X_nd, then log2(alpha_m^2) - 1/2 sum_d log2(e)/l_md^2 X_nd^2
+    double *Os;                  // [M][Lp][D+1]: omega_mld * 2/pi (quarter revolutions per unit x_d), then phase * 2/pi
+    double *A;                   // [M][D]: log2(e) / l_md^2
+    double *amp;                 // [M]: sqrt(2 alpha_m^2 / L)
+    float4 *v4;                  // [M][Np/4][S]: four consecutive training points of one sample
+    float4 *w4;                  // [M][Lp/4][S]
+
+    // ---- per-step workspace (lane = trajectory, arrays are [component][B]) ---------------
+    double *xbuf;                // [D][B]   GP input of the current step; rows 0..d_s-1 are the state (float64)
+    double *part;                // [units][1+D][B] partial sums of one step
+    double *lpt;                 // [B] running cost per trajectory
+    double *lam;                 // [d_s][B] adjoint of the state
+    double *us;                  // [d_s][B] J_s^T lam of the step being swept
+    float *dh0;                  // [d_in][B] adjoint of the policy input
+
+    // ---- tape (T_tape slots: H, or ckpt_interval when checkpointing) ----------------------
+    int T_tape;
+    float *tape_s;               // [H+1][d_s][B]
+    float *tape_J;               // [T][M][D][B]
+    float *tape_h[3];            // activations feeding layer l: [T][width[l]][B]
+    float *tape_a;               // [T][d_a][B] policy output (after tanh, before scaling, if bounded)
+    float *tape_d[3];            // adjoint of the pre-activation of layer l: [T][width[l+1]][B]
+    double *ckpt_s;              // [n_seg][d_s][B] state at the start of each segment
+
+    // ---- parameters and gradient -----------------------------------------------------------
+    float *thetaT;               // per layer W^T [in][out] at the offsets of theta, biases copied
+    float *gsplit;               // [ksplit][P] split-contraction partial weight gradients
+    double *gacc;                // [P] gradient accumulated over segments
+    int ksplit;
+};
+
+#define BAGEL_FAIL(ctx, code, ...)                                   \
+    do {                                                             \
+        snprintf((ctx)->err, sizeof((ctx)->err), __VA_ARGS__);      \
+        return (code);                                               \
+    } while (0)
+
+#define BAGEL_HIP(ctx, call)                                                                   \
+    do {                                                                                       \
+        hipError_t e__ = (call);                                                               \
+        if (e__ != hipSuccess)                                                                 \
+            BAGEL_FAIL(ctx, BAGEL_EHIP, "%s failed: %s", #call, hipGetErrorString(e__));      \
+    } while (0)
+
+// ---- gp_step.hip -------------------------------------------------------------------------
+// One evaluation of all function samples at xbuf: partial sums per work unit into ctx->part.
+hipError_t bagel_launch_gp_step(bagel_ctx *ctx, bool jac);
+
+// ---- model.hip ---------------------------------------------------------------------------
+hipError_t bagel_launch_build_model(bagel_ctx *ctx, const float *X, const float *ell, const float *sf2,
+                                    const float *omega, const float *phase);
+hipError_t bagel_launch_pack_samples(bagel_ctx *ctx, const float *w, const float *v);
+
+// ---- lane.hip ----------------------------------------------------------------------------
+hipError_t bagel_launch_init_state(bagel_ctx *ctx, const float *s0, const float *goals, float *states_out,
+                                   bool tape, bool ckpt);
+hipError_t bagel_launch_restore(bagel_ctx *ctx, int seg, int t, const float *goals);
+// finish step t (reduce partial sums, advance the state, cost, tapes, policy input of step t+1)
+hipError_t bagel_launch_advance(bagel_ctx *ctx, int t, int slot, int next_slot, bool jac, bool add_cost,
+                                bool write_tape_s, int ckpt_index, const float *goals, float *states_out);
+hipError_t bagel_launch_finish_loss(bagel_ctx *ctx, float *loss, float *loss_per_traj);
+hipError_t bagel_launch_adjoint_lane(bagel_ctx *ctx, int t, int prev_slot, const float *goals, float *grad_s0);
+hipError_t bagel_launch_eval_io(bagel_ctx *ctx, int phase, const float *x, float *f, float *jac);
+
+// ---- policy.hip --------------------------------------------------------------------------
+hipError_t bagel_launch_transpose_theta(bagel_ctx *ctx, const float *theta);
+hipError_t bagel_launch_policy_forward(bagel_ctx *ctx, int slot);
+hipError_t bagel_launch_policy_backward(bagel_ctx *ctx, int slot, const float *theta);
+hipError_t bagel_launch_weight_grad(bagel_ctx *ctx, int n_slots, bool accumulate, float *grad_theta);
+
+// ---- prepare.hip -------------------------------------------------------------------------
+// v = (K + noise I)^-1 (y - Phi w - eps) for every sample, float64 inside; packs v into ctx->v4
+// and optionally writes float32 v_out[S][M][N].  Returns a BAGEL_* code and sets ctx->err.
+int bagel_prepare_impl(bagel_ctx *ctx, const float *X, const float *y, const float *ell, const float *sf2,
+                       const float *sn2, const float *omega, const float *phase, const float *w,
+                       const float *eps, float *v_out);

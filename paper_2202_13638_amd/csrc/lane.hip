@@ -1,0 +1,317 @@
+// Lane-per-trajectory kernels around the sample evaluation: reduction of the per-unit partial
+// sums, the state update s_{t+1} = s_t + f(x_t) (state increments as GP targets, Sec. III-A), the
+// running cost (Algorithm 1, return accumulation; eq. (8) or the quadratic cost), and the
+// trajectory part of the backward sweep (adjoint of the state through the transition Jacobian).
+// All per-trajectory arrays are laid out [component][B] so that a wave reads consecutive
+// trajectories.
+#include "bagel_internal.h"
+
+namespace {
+
+constexpr double LN2 = 0.69314718055994530942;
+constexpr double HALF_PI = 1.57079632679489661923;
+
+struct lane_args {
+    int B, D, M, ds, da, dg, H;
+    int nck, ncl;
+    int cost_kind;
+    float sigma_r, act_bound;
+    int tracked[8];
+    float q[8];
+    const double *A, *amp, *part;
+    double *xbuf, *lpt, *lam, *us;
+    float *tape_s;
+    double *ckpt_s;
+};
+
+// Sum the partial sums of one step in unit order: f[m], and, if jac, every J[m][d] is handed to
+// emit(m * D + d, value) as soon as it is complete (no per-lane array of M*D doubles).
+template <class Emit>
+__device__ __forceinline__ void reduce_units(const lane_args &a, int b, const double *x, bool jac, double *f,
+                                             Emit emit)
+{
+    const size_t stride = (size_t)(1 + a.D) * a.B;
+    for (int m = 0; m < a.M; ++m) {
+        const double *pk = a.part + (size_t)(m * a.nck) * stride + b;
+        const double *pr = a.part + (size_t)(a.M * a.nck + m * a.ncl) * stride + b;
+        double u = 0.0, p = 0.0;
+        for (int c = 0; c < a.nck; ++c) u += pk[c * stride];
+        for (int c = 0; c < a.ncl; ++c) p += pr[c * stride];
+        const double amp = a.amp[m];
+        f[m] = amp * p + u;
+        if (jac) {
+            for (int d = 0; d < a.D; ++d) {
+                double gk = 0.0, gr = 0.0;
+                for (int c = 0; c < a.nck; ++c) gk += pk[c * stride + (size_t)(1 + d) * a.B];
+                for (int c = 0; c < a.ncl; ++c) gr += pr[c * stride + (size_t)(1 + d) * a.B];
+                emit(m * a.D + d, -amp * HALF_PI * gr + LN2 * (gk - a.A[m * a.D + d] * x[d] * u));
+            }
+        }
+    }
+}
+
+// cost at state s against goal g (float goals), optionally d cost / d s accumulated into dc[ds]
+__device__ __forceinline__ double step_cost(const lane_args &a, const double *s, const float *g, double *dc)
+{
+    double e = 0.0;
+    for (int j = 0; j < a.dg; ++j) {
+        const double r = s[a.tracked[j]] - (double)g[j];
+        e += (double)a.q[j] * r * r;
+    }
+    if (a.cost_kind == 0) {
+        if (dc)
+            for (int j = 0; j < a.dg; ++j) dc[a.tracked[j]] += 2.0 * (double)a.q[j] * (s[a.tracked[j]] - (double)g[j]);
+        return e;
+    }
+    const double sr2 = (double)a.sigma_r * (double)a.sigma_r;
+    const double c = -exp(-e / (2.0 * sr2));
+    if (dc)
+        for (int j = 0; j < a.dg; ++j)
+            dc[a.tracked[j]] += -c * (double)a.q[j] * (s[a.tracked[j]] - (double)g[j]) / sr2;
+    return c;
+}
+
+__global__ __launch_bounds__(BAGEL_BLOCK) void init_state_kernel(lane_args a, const float *__restrict__ s0,
+                                                                 const float *__restrict__ goals0,
+                                                                 float *__restrict__ states_out,
+                                                                 float *__restrict__ h0_slot)
+{
+    const int b = blockIdx.x * BAGEL_BLOCK + threadIdx.x;
+    if (b >= a.B) return;
+    for (int i = 0; i < a.ds; ++i) {
+        const float v = s0[(size_t)b * a.ds + i];
+        a.xbuf[(size_t)i * a.B + b] = (double)v;
+        if (a.tape_s) a.tape_s[(size_t)i * a.B + b] = v;
+        if (a.ckpt_s) a.ckpt_s[(size_t)i * a.B + b] = (double)v;
+        if (states_out) states_out[(size_t)b * a.ds + i] = v;
+        h0_slot[(size_t)i * a.B + b] = v;
+    }
+    for (int j = 0; j < a.dg; ++j) h0_slot[(size_t)(a.ds + j) * a.B + b] = goals0[(size_t)b * a.dg + j];
+    a.lpt[b] = 0.0;
+}
+
+// restore the state of a checkpoint and write the policy input of step t
+__global__ __launch_bounds__(BAGEL_BLOCK) void restore_kernel(lane_args a, const double *__restrict__ ck,
+                                                              const float *__restrict__ goals_t,
+                                                              float *__restrict__ h0_slot)
+{
+    const int b = blockIdx.x * BAGEL_BLOCK + threadIdx.x;
+    if (b >= a.B) return;
+    for (int i = 0; i < a.ds; ++i) {
+        const double v = ck[(size_t)i * a.B + b];
+        a.xbuf[(size_t)i * a.B + b] = v;
+        h0_slot[(size_t)i * a.B + b] = (float)v;
+    }
+    for (int j = 0; j < a.dg; ++j) h0_slot[(size_t)(a.ds + j) * a.B + b] = goals_t[(size_t)b * a.dg + j];
+}
+
+// Finish step t: reduce -> f (and J), s_{t+1} = s_t + f, cost against goals[t], tapes, and the policy
+// input of step t+1.
+__global__ __launch_bounds__(BAGEL_BLOCK) void advance_kernel(lane_args a, int t, bool jac, bool add_cost,
+                                                              const float *__restrict__ goals_t,
+                                                              const float *__restrict__ goals_next,
+                                                              float *__restrict__ tape_J_slot,
+                                                              float *__restrict__ states_out_next,
+                                                              float *__restrict__ h0_next,
+                                                              double *__restrict__ ckpt_next)
+{
+    const int b = blockIdx.x * BAGEL_BLOCK + threadIdx.x;
+    if (b >= a.B) return;
+    double x[BAGEL_MAX_D], f[8];
+    for (int d = 0; d < a.D; ++d) x[d] = a.xbuf[(size_t)d * a.B + b];
+    reduce_units(a, b, x, jac, f,
+                 [&](int i, double v) { tape_J_slot[(size_t)i * a.B + b] = (float)v; });
+    double s[8];
+    for (int i = 0; i < a.ds; ++i) {
+        s[i] = x[i] + f[i];
+        a.xbuf[(size_t)i * a.B + b] = s[i];
+        if (a.tape_s) a.tape_s[((size_t)(t + 1) * a.ds + i) * a.B + b] = (float)s[i];
+        if (states_out_next) states_out_next[(size_t)b * a.ds + i] = (float)s[i];
+        if (ckpt_next) ckpt_next[(size_t)i * a.B + b] = s[i];
+        if (h0_next) h0_next[(size_t)i * a.B + b] = (float)s[i];
+    }
+    if (add_cost) {
+        float g[8];
+        for (int j = 0; j < a.dg; ++j) g[j] = goals_t[(size_t)b * a.dg + j];
+        a.lpt[b] += step_cost(a, s, g, nullptr);
+    }
+    if (h0_next)
+        for (int j = 0; j < a.dg; ++j) h0_next[(size_t)(a.ds + j) * a.B + b] = goals_next[(size_t)b * a.dg + j];
+}
+
+// loss = (1/B) sum_b lpt[b], summed in a fixed tree order by one workgroup
+__global__ __launch_bounds__(1024) void finish_loss_kernel(const double *__restrict__ lpt, int B,
+                                                           float *__restrict__ loss,
+                                                           float *__restrict__ loss_per_traj)
+{
+    __shared__ double sh[1024];
+    double acc = 0.0;
+    for (int b = threadIdx.x; b < B; b += 1024) {
+        const double v = lpt[b];
+        acc += v;
+        if (loss_per_traj) loss_per_traj[b] = (float)v;
+    }
+    sh[threadIdx.x] = acc;
+    __syncthreads();
+    for (int s = 512; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) sh[threadIdx.x] += sh[threadIdx.x + s];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) loss[0] = (float)(sh[0] / (double)B);
+}
+
+// Backward sweep, trajectory part.  Called with t = H, H-1, ..., 0:
+//   t == H : lam = (1/B) dc/ds(s_H, g_{H-1})
+//   t <  H : lam += J_s(x_t)^T lam_{t+1} (kept in us) + (d a_t/d s_t)^T u_a (dh0 from the policy
+//            backward) + [t >= 1] (1/B) dc/ds(s_t, g_{t-1})
+//   then, for t >= 1, the quantities step t-1 needs: u = J(x_{t-1})^T lam; us = u[:ds];
+//   delta_out = u[ds:] * d a / d z_out.
+__global__ __launch_bounds__(BAGEL_BLOCK) void adjoint_lane_kernel(lane_args a, int t,
+                                                                   const float *__restrict__ goals_prev,
+                                                                   const float *__restrict__ dh0,
+                                                                   const float *__restrict__ tape_J_slot,
+                                                                   const float *__restrict__ tape_a_slot,
+                                                                   float *__restrict__ dout_slot,
+                                                                   float *__restrict__ grad_s0)
+{
+    const int b = blockIdx.x * BAGEL_BLOCK + threadIdx.x;
+    if (b >= a.B) return;
+    double lam[8];
+    if (t == a.H) {
+        for (int i = 0; i < a.ds; ++i) lam[i] = 0.0;
+    } else {
+        for (int i = 0; i < a.ds; ++i)
+            lam[i] = a.lam[(size_t)i * a.B + b] + a.us[(size_t)i * a.B + b] + (double)dh0[(size_t)i * a.B + b];
+    }
+    if (t >= 1) {
+        double s[8], dc[8];
+        float g[8];
+        for (int i = 0; i < a.ds; ++i) {
+            s[i] = (double)a.tape_s[((size_t)t * a.ds + i) * a.B + b];
+            dc[i] = 0.0;
+        }
+        for (int j = 0; j < a.dg; ++j) g[j] = goals_prev[(size_t)b * a.dg + j];
+        step_cost(a, s, g, dc);
+        for (int i = 0; i < a.ds; ++i) lam[i] += dc[i] / (double)a.B;
+    }
+    for (int i = 0; i < a.ds; ++i) a.lam[(size_t)i * a.B + b] = lam[i];
+    if (t == 0) {
+        if (grad_s0)
+            for (int i = 0; i < a.ds; ++i) grad_s0[(size_t)b * a.ds + i] = (float)lam[i];
+        return;
+    }
+    for (int d = 0; d < a.D; ++d) {
+        double acc = 0.0;
+        for (int m = 0; m < a.M; ++m) acc += (double)tape_J_slot[((size_t)m * a.D + d) * a.B + b] * lam[m];
+        if (d < a.ds) {
+            a.us[(size_t)d * a.B + b] = acc;
+        } else {
+            const int o = d - a.ds;
+            if (a.act_bound > 0.0f) {
+                const double th = (double)tape_a_slot[(size_t)o * a.B + b];
+                acc *= (double)a.act_bound * (1.0 - th * th);
+            }
+            dout_slot[(size_t)o * a.B + b] = (float)acc;
+        }
+    }
+}
+
+// bagel_sample_eval plumbing: phase 0 loads x[B][D] into xbuf; phase 1 reduces and writes f, jac.
+__global__ __launch_bounds__(BAGEL_BLOCK) void eval_io_kernel(lane_args a, int phase, const float *__restrict__ xin,
+                                                              float *__restrict__ f_out, float *__restrict__ j_out)
+{
+    const int b = blockIdx.x * BAGEL_BLOCK + threadIdx.x;
+    if (b >= a.B) return;
+    if (phase == 0) {
+        for (int d = 0; d < a.D; ++d) a.xbuf[(size_t)d * a.B + b] = (double)xin[(size_t)b * a.D + d];
+        return;
+    }
+    double x[BAGEL_MAX_D], f[8];
+    for (int d = 0; d < a.D; ++d) x[d] = a.xbuf[(size_t)d * a.B + b];
+    reduce_units(a, b, x, j_out != nullptr, f,
+                 [&](int i, double v) { j_out[(size_t)b * a.M * a.D + i] = (float)v; });
+    for (int m = 0; m < a.M; ++m) f_out[(size_t)b * a.M + m] = (float)f[m];
+}
+
+lane_args make_args(const bagel_ctx *c)
+{
+    lane_args a;
+    a.B = c->dm.B; a.D = c->D; a.M = c->M; a.ds = c->dm.d_s; a.da = c->dm.d_a; a.dg = c->dm.d_g; a.H = c->dm.H;
+    a.nck = c->nck; a.ncl = c->ncl;
+    a.cost_kind = c->dm.cost_kind; a.sigma_r = c->dm.sigma_r; a.act_bound = c->dm.act_bound;
+    for (int j = 0; j < 8; ++j) { a.tracked[j] = c->dm.tracked[j]; a.q[j] = c->dm.q[j]; }
+    a.A = c->A; a.amp = c->amp; a.part = c->part;
+    a.xbuf = c->xbuf; a.lpt = c->lpt; a.lam = c->lam; a.us = c->us;
+    a.tape_s = nullptr; a.ckpt_s = nullptr;
+    return a;
+}
+
+inline dim3 lane_grid(const bagel_ctx *c) { return dim3((c->dm.B + BAGEL_BLOCK - 1) / BAGEL_BLOCK); }
+
+}  // namespace
+
+static inline float *slot_ptr(float *base, int slot, int width, int B) { return base + (size_t)slot * width * B; }
+
+hipError_t bagel_launch_init_state(bagel_ctx *c, const float *s0, const float *goals, float *states_out,
+                                   bool tape, bool ckpt)
+{
+    lane_args a = make_args(c);
+    a.tape_s = tape ? c->tape_s : nullptr;
+    a.ckpt_s = ckpt ? c->ckpt_s : nullptr;
+    hipLaunchKernelGGL(init_state_kernel, lane_grid(c), dim3(BAGEL_BLOCK), 0, c->stream, a, s0, goals, states_out,
+                       slot_ptr(c->tape_h[0], 0, c->d_in, c->dm.B));
+    return hipGetLastError();
+}
+
+hipError_t bagel_launch_restore(bagel_ctx *c, int seg, int t, const float *goals)
+{
+    lane_args a = make_args(c);
+    const size_t B = c->dm.B;
+    hipLaunchKernelGGL(restore_kernel, lane_grid(c), dim3(BAGEL_BLOCK), 0, c->stream, a,
+                       c->ckpt_s + (size_t)seg * c->dm.d_s * B, goals + (size_t)t * B * c->dm.d_g,
+                       slot_ptr(c->tape_h[0], 0, c->d_in, c->dm.B));
+    return hipGetLastError();
+}
+
+hipError_t bagel_launch_advance(bagel_ctx *c, int t, int slot, int next_slot, bool jac, bool add_cost,
+                                bool write_tape_s, int ckpt_index, const float *goals, float *states_out)
+{
+    lane_args a = make_args(c);
+    const size_t B = c->dm.B;
+    a.tape_s = write_tape_s ? c->tape_s : nullptr;
+    const bool has_next = t + 1 < c->dm.H;
+    hipLaunchKernelGGL(advance_kernel, lane_grid(c), dim3(BAGEL_BLOCK), 0, c->stream, a, t, jac, add_cost,
+                       goals + (size_t)t * B * c->dm.d_g, has_next ? goals + (size_t)(t + 1) * B * c->dm.d_g : nullptr,
+                       jac ? slot_ptr(c->tape_J, slot, c->M * c->D, c->dm.B) : nullptr,
+                       states_out ? states_out + (size_t)(t + 1) * B * c->dm.d_s : nullptr,
+                       (has_next && next_slot >= 0) ? slot_ptr(c->tape_h[0], next_slot, c->d_in, c->dm.B) : nullptr,
+                       ckpt_index >= 0 ? c->ckpt_s + (size_t)ckpt_index * c->dm.d_s * B : nullptr);
+    return hipGetLastError();
+}
+
+hipError_t bagel_launch_finish_loss(bagel_ctx *c, float *loss, float *loss_per_traj)
+{
+    hipLaunchKernelGGL(finish_loss_kernel, dim3(1), dim3(1024), 0, c->stream, c->lpt, c->dm.B, loss, loss_per_traj);
+    return hipGetLastError();
+}
+
+hipError_t bagel_launch_adjoint_lane(bagel_ctx *c, int t, int prev_slot, const float *goals, float *grad_s0)
+{
+    lane_args a = make_args(c);
+    a.tape_s = c->tape_s;
+    const size_t B = c->dm.B;
+    const int last = c->n_layers - 1;
+    hipLaunchKernelGGL(adjoint_lane_kernel, lane_grid(c), dim3(BAGEL_BLOCK), 0, c->stream, a, t,
+                       t >= 1 ? goals + (size_t)(t - 1) * B * c->dm.d_g : nullptr, c->dh0,
+                       t >= 1 ? slot_ptr(c->tape_J, prev_slot, c->M * c->D, c->dm.B) : nullptr,
+                       t >= 1 ? slot_ptr(c->tape_a, prev_slot, c->dm.d_a, c->dm.B) : nullptr,
+                       t >= 1 ? slot_ptr(c->tape_d[last], prev_slot, c->dm.d_a, c->dm.B) : nullptr, grad_s0);
+    return hipGetLastError();
+}
+
+hipError_t bagel_launch_eval_io(bagel_ctx *c, int phase, const float *x, float *f, float *jac)
+{
+    lane_args a = make_args(c);
+    hipLaunchKernelGGL(eval_io_kernel, lane_grid(c), dim3(BAGEL_BLOCK), 0, c->stream, a, phase, x, f, jac);
+    return hipGetLastError();
+}
