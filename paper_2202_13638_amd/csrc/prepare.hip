@@ -1,8 +1,359 @@
+// Sample-set precompute: v_sm = (K_m + noise_m I)^-1 (y_m - Phi_m w_sm - eps_sm) for every
+// function sample s and output m (Matheron update of a pathwise sample; K_hat as defined below
+// eq. (3), kernel of eq. (4)).  Everything is float64 on the device: the condition number of
+// K_hat is ~ signal/noise variance times N, far beyond float32.  Per output:
+//   1. K_hat (padded to a multiple of 64 with an identity block) and Phi are built from the
+//      float32 inputs;
+//   2. blocked right-looking Cholesky: 64x64 diagonal factorisation, panel solve, trailing
+//      update of the lower triangle with a tiled float64 GEMM;
+//   3. R = y 1^T - Phi W^T - Eps^T as one GEMM over the L features (R is [N][S]);
+//   4. blocked forward and backward substitution on all S right-hand sides at once, again
+//      GEMM-dominated;
+//   5. v is rounded to float32 once, written to v_out[S][M][N] and packed for the step kernel.
+// This is set-up work outside the timed rollouts; buffers are allocated here and freed on return.
 #include <stdio.h>
+
 #include "bagel_internal.h"
 
-int bagel_prepare_impl(bagel_ctx *c, const float *, const float *, const float *, const float *, const float *,
-                       const float *, const float *, const float *, const float *, float *)
+namespace {
+
+constexpr int NB = 64;    // Cholesky / substitution block
+constexpr int TM = 64, TN = 64, TK = 16;   // GEMM tile
+
+// K_hat[i][j] for i, j < Np (row-major, leading dimension Np); identity on the padding
+__global__ void build_khat_kernel(const float *__restrict__ X, const float *__restrict__ ell, float sf2, float sn2,
+                                  double *__restrict__ K, int N, int Np, int D)
 {
-    BAGEL_FAIL(c, BAGEL_EHIP, "bagel_prepare_samples: not implemented yet");
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    const int i = blockIdx.y;
+    if (j >= Np) return;
+    double val;
+    if (i < N && j < N) {
+        double r = 0.0;
+        for (int d = 0; d < D; ++d) {
+            const double t = ((double)X[(size_t)i * D + d] - (double)X[(size_t)j * D + d]) / (double)ell[d];
+            r += t * t;
+        }
+        val = (double)sf2 * exp(-0.5 * r);
+        if (i == j) val += (double)sn2;
+    } else {
+        val = (i == j) ? 1.0 : 0.0;
+    }
+    K[(size_t)i * Np + j] = val;
+}
+
+// Phi[n][l] = sqrt(2 sf2 / L) cos(omega_l . X_n + phase_l); zero rows on the padding
+__global__ void build_phi_kernel(const float *__restrict__ X, const float *__restrict__ omega,
+                                 const float *__restrict__ phase, float sf2, double *__restrict__ Phi, int N,
+                                 int Np, int L, int D)
+{
+    const int l = blockIdx.x * blockDim.x + threadIdx.x;
+    const int n = blockIdx.y;
+    if (l >= L) return;
+    double val = 0.0;
+    if (n < N) {
+        double z = (double)phase[l];
+        for (int d = 0; d < D; ++d) z += (double)omega[(size_t)l * D + d] * (double)X[(size_t)n * D + d];
+        val = sqrt(2.0 * (double)sf2 / (double)L) * cos(z);
+    }
+    Phi[(size_t)n * L + l] = val;
+}
+
+// R[n][s] = y[n] - eps[s][n] (zero on the padding); eps is [S][M][N] at output m
+__global__ void init_rhs_kernel(const float *__restrict__ y_m, const float *__restrict__ eps, double *__restrict__ R,
+                                int N, int Np, int S, int M, int m)
+{
+    const int s = blockIdx.x * blockDim.x + threadIdx.x;
+    const int n = blockIdx.y;
+    if (s >= S) return;
+    double val = 0.0;
+    if (n < N) val = (double)y_m[n] - (double)eps[((size_t)s * M + m) * N + n];
+    R[(size_t)n * S + s] = val;
+}
+
+// Wd[s][l] = w[s][m][l]
+__global__ void convert_w_kernel(const float *__restrict__ w, double *__restrict__ Wd, int S, int M, int L, int m)
+{
+    const int l = blockIdx.x * blockDim.x + threadIdx.x;
+    const int s = blockIdx.y;
+    if (l < L) Wd[(size_t)s * L + l] = (double)w[((size_t)s * M + m) * L + l];
+}
+
+// C[i][j] (ldc) += alpha * sum_k A(i,k) * B(k,j), A(i,k) = A[i*sai + k*sak], B(k,j) = B[k*sbk + j*sbj].
+// lower_only: skip tiles entirely above the diagonal (used for the symmetric trailing update).
+__global__ __launch_bounds__(256) void dgemm_kernel(int Mr, int Nc, int Kd, double alpha,
+                                                    const double *__restrict__ A, long sai, long sak,
+                                                    const double *__restrict__ Bm, long sbk, long sbj,
+                                                    double *__restrict__ Cm, long ldc, int lower_only)
+{
+    const int i0 = blockIdx.y * TM, j0 = blockIdx.x * TN;
+    if (lower_only && j0 > i0 + TM - 1) return;
+    __shared__ double As[TK][TM + 1];
+    __shared__ double Bs[TK][TN + 1];
+    const int tid = threadIdx.x;
+    const int tx = tid & 15, ty = tid >> 4;
+    double acc[4][4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[r][c] = 0.0;
+    // loaders: pick the thread->element map that walks the unit-stride direction fastest
+    const bool a_k_fast = (sak == 1);
+    const bool b_j_fast = (sbj == 1);
+    for (int k0 = 0; k0 < Kd; k0 += TK) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int idx = tid + e * 256;            // 0..1023 = TM*TK
+            int ii, kk;
+            if (a_k_fast) { kk = idx % TK; ii = idx / TK; } else { ii = idx % TM; kk = idx / TM; }
+            const int gi = i0 + ii, gk = k0 + kk;
+            As[kk][ii] = (gi < Mr && gk < Kd) ? A[(long)gi * sai + (long)gk * sak] : 0.0;
+            int jj, kb;
+            if (b_j_fast) { jj = idx % TN; kb = idx / TN; } else { kb = idx % TK; jj = idx / TK; }
+            const int gj = j0 + jj, gkb = k0 + kb;
+            Bs[kb][jj] = (gj < Nc && gkb < Kd) ? Bm[(long)gkb * sbk + (long)gj * sbj] : 0.0;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < TK; ++k) {
+            double av[4], bv[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) av[r] = As[k][ty * 4 + r];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) bv[c] = Bs[k][tx * 4 + c];
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) acc[r][c] = fma(av[r], bv[c], acc[r][c]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int gi = i0 + ty * 4 + r;
+        if (gi >= Mr) continue;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int gj = j0 + tx * 4 + c;
+            if (gj < Nc) Cm[(long)gi * ldc + gj] += alpha * acc[r][c];
+        }
+    }
+}
+
+// Factor the NB x NB diagonal block at (k,k) in place (lower).  One workgroup of NB threads,
+// thread = row.  Sets *flag = 1 + global row index on a pivot that is not positive.
+__global__ __launch_bounds__(NB) void potrf_diag_kernel(double *__restrict__ K, int Np, int k, int flag_base,
+                                                        int *__restrict__ flag)
+{
+    __shared__ double Ls[NB][NB + 1];
+    const int r = threadIdx.x;
+    for (int c = 0; c < NB; ++c) Ls[r][c] = K[(size_t)(k + r) * Np + k + c];
+    __syncthreads();
+    for (int j = 0; j < NB; ++j) {
+        const double d = Ls[j][j];
+        if (!(d > 0.0)) {
+            if (r == 0) atomicCAS(flag, 0, 1 + flag_base + k + j);
+            // keep going with a harmless pivot so every thread leaves the loop together
+        }
+        const double piv = (d > 0.0) ? sqrt(d) : 1.0;
+        __syncthreads();
+        if (r == j) Ls[j][j] = piv;
+        if (r > j) Ls[r][j] = Ls[r][j] / piv;
+        __syncthreads();
+        if (r > j)
+            for (int c = j + 1; c <= r; ++c) Ls[r][c] -= Ls[r][j] * Ls[c][j];
+        __syncthreads();
+    }
+    for (int c = 0; c < NB; ++c) K[(size_t)(k + r) * Np + k + c] = (c <= r) ? Ls[r][c] : 0.0;
+}
+
+// Panel solve: rows i >= k+NB of columns k..k+NB-1:  P <- P * L_kk^-T.  Thread = row.
+__global__ __launch_bounds__(256) void trsm_panel_kernel(double *__restrict__ K, int Np, int k)
+{
+    __shared__ double Ls[NB][NB + 1];
+    for (int idx = threadIdx.x; idx < NB * NB; idx += 256) Ls[idx / NB][idx % NB] = K[(size_t)(k + idx / NB) * Np + k + idx % NB];
+    __syncthreads();
+    const int i = k + NB + blockIdx.x * 256 + threadIdx.x;
+    if (i >= Np) return;
+    double *row = K + (size_t)i * Np + k;
+    double x[NB];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) x[j] = row[j];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        double s = x[j];
+#pragma unroll
+        for (int c = 0; c < j; ++c) s -= x[c] * Ls[j][c];
+        x[j] = s / Ls[j][j];
+    }
+#pragma unroll
+    for (int j = 0; j < NB; ++j) row[j] = x[j];
+}
+
+// Forward substitution on block k for all right-hand sides: Z_k = L_kk^-1 R_k.  Thread = column s.
+__global__ __launch_bounds__(256) void trsv_fwd_kernel(const double *__restrict__ K, int Np, int k,
+                                                       double *__restrict__ R, int S)
+{
+    __shared__ double Ls[NB][NB + 1];
+    for (int idx = threadIdx.x; idx < NB * NB; idx += 256) Ls[idx / NB][idx % NB] = K[(size_t)(k + idx / NB) * Np + k + idx % NB];
+    __syncthreads();
+    const int s = blockIdx.x * 256 + threadIdx.x;
+    if (s >= S) return;
+    double z[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) z[i] = R[(size_t)(k + i) * S + s];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        double acc = z[i];
+#pragma unroll
+        for (int j = 0; j < i; ++j) acc -= Ls[i][j] * z[j];
+        z[i] = acc / Ls[i][i];
+    }
+#pragma unroll
+    for (int i = 0; i < NB; ++i) R[(size_t)(k + i) * S + s] = z[i];
+}
+
+// Backward substitution on block k: V_k = L_kk^-T Z_k.
+__global__ __launch_bounds__(256) void trsv_bwd_kernel(const double *__restrict__ K, int Np, int k,
+                                                       double *__restrict__ R, int S)
+{
+    __shared__ double Ls[NB][NB + 1];
+    for (int idx = threadIdx.x; idx < NB * NB; idx += 256) Ls[idx / NB][idx % NB] = K[(size_t)(k + idx / NB) * Np + k + idx % NB];
+    __syncthreads();
+    const int s = blockIdx.x * 256 + threadIdx.x;
+    if (s >= S) return;
+    double z[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) z[i] = R[(size_t)(k + i) * S + s];
+#pragma unroll
+    for (int i = NB - 1; i >= 0; --i) {
+        double acc = z[i];
+#pragma unroll
+        for (int j = i + 1; j < NB; ++j) acc -= Ls[j][i] * z[j];
+        z[i] = acc / Ls[i][i];
+    }
+#pragma unroll
+    for (int i = 0; i < NB; ++i) R[(size_t)(k + i) * S + s] = z[i];
+}
+
+// V[n][s] (float64) -> v_out[s][m][n] (float32) and the packed stream v4[m][n4][s]
+__global__ void emit_v_kernel(const double *__restrict__ V, float *__restrict__ v_out, float4 *__restrict__ v4,
+                              int N, int Npk, int S, int M, int m)
+{
+    const int s = blockIdx.x * blockDim.x + threadIdx.x;
+    const int n4 = blockIdx.y;
+    if (s >= S) return;
+    float t[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int n = n4 * 4 + j;
+        t[j] = n < N ? (float)V[(size_t)n * S + s] : 0.0f;
+        if (v_out && n < N) v_out[((size_t)s * M + m) * N + n] = t[j];
+    }
+    v4[((size_t)m * (Npk / 4) + n4) * S + s] = make_float4(t[0], t[1], t[2], t[3]);
+}
+
+void gemm(hipStream_t st, int Mr, int Nc, int Kd, double alpha, const double *A, long sai, long sak,
+          const double *Bm, long sbk, long sbj, double *Cm, long ldc, bool lower_only)
+{
+    if (Mr <= 0 || Nc <= 0 || Kd <= 0) return;
+    dim3 grid((Nc + TN - 1) / TN, (Mr + TM - 1) / TM);
+    hipLaunchKernelGGL(dgemm_kernel, grid, dim3(256), 0, st, Mr, Nc, Kd, alpha, A, sai, sak, Bm, sbk, sbj, Cm, ldc,
+                       lower_only ? 1 : 0);
+}
+
+}  // namespace
+
+int bagel_prepare_impl(bagel_ctx *c, const float *X, const float *y, const float *ell, const float *sf2,
+                       const float *sn2, const float *omega, const float *phase, const float *w,
+                       const float *eps, float *v_out)
+{
+    const int N = c->dm.N, L = c->dm.L, S = c->dm.S, M = c->M, D = c->D;
+    const int Np = (N + NB - 1) / NB * NB;
+    hipStream_t st = c->stream;
+    double *K = nullptr, *Phi = nullptr, *R = nullptr, *Wd = nullptr;
+    int *flag = nullptr;
+    float h_sf2[8], h_sn2[8];
+    int rc = BAGEL_OK;
+    int h_flag = 0;
+
+#define P_HIP(call)                                                                              \
+    do {                                                                                         \
+        hipError_t e__ = (call);                                                                 \
+        if (e__ != hipSuccess) {                                                                 \
+            snprintf(c->err, sizeof(c->err), "bagel_prepare_samples: %s failed: %s", #call,      \
+                     hipGetErrorString(e__));                                                    \
+            rc = (e__ == hipErrorOutOfMemory) ? BAGEL_ENOMEM : BAGEL_EHIP;                       \
+            goto done;                                                                           \
+        }                                                                                        \
+    } while (0)
+
+    P_HIP(hipMalloc((void **)&K, (size_t)Np * Np * sizeof(double)));
+    P_HIP(hipMalloc((void **)&Phi, (size_t)Np * L * sizeof(double)));
+    P_HIP(hipMalloc((void **)&R, (size_t)Np * S * sizeof(double)));
+    P_HIP(hipMalloc((void **)&Wd, (size_t)S * L * sizeof(double)));
+    P_HIP(hipMalloc((void **)&flag, sizeof(int)));
+    P_HIP(hipMemsetAsync(flag, 0, sizeof(int), st));
+    P_HIP(hipMemcpyAsync(h_sf2, sf2, M * sizeof(float), hipMemcpyDeviceToHost, st));
+    P_HIP(hipMemcpyAsync(h_sn2, sn2, M * sizeof(float), hipMemcpyDeviceToHost, st));
+    P_HIP(hipStreamSynchronize(st));
+
+    for (int m = 0; m < M; ++m) {
+        hipLaunchKernelGGL(build_khat_kernel, dim3((Np + 255) / 256, Np), dim3(256), 0, st, X, ell + (size_t)m * D,
+                           h_sf2[m], h_sn2[m], K, N, Np, D);
+        hipLaunchKernelGGL(build_phi_kernel, dim3((L + 255) / 256, Np), dim3(256), 0, st, X,
+                           omega + (size_t)m * L * D, phase + (size_t)m * L, h_sf2[m], Phi, N, Np, L, D);
+        hipLaunchKernelGGL(init_rhs_kernel, dim3((S + 255) / 256, Np), dim3(256), 0, st, y + (size_t)m * N, eps, R, N,
+                           Np, S, M, m);
+        // W of output m as float64 [S][L], so the GEMM reads one layout
+        hipLaunchKernelGGL(convert_w_kernel, dim3((L + 255) / 256, S), dim3(256), 0, st, w, Wd, S, M, L, m);
+        // R -= Phi W^T : A = Phi [Np][L] (k fast), B(k=l, j=s) = Wd[s][l]
+        gemm(st, Np, S, L, -1.0, Phi, L, 1, Wd, 1, L, R, S, false);
+
+        // Cholesky
+        for (int k = 0; k < Np; k += NB) {
+            hipLaunchKernelGGL(potrf_diag_kernel, dim3(1), dim3(NB), 0, st, K, Np, k, m * Np, flag);
+            const int rest = Np - k - NB;
+            if (rest > 0) {
+                hipLaunchKernelGGL(trsm_panel_kernel, dim3((rest + 255) / 256), dim3(256), 0, st, K, Np, k);
+                const double *Pn = K + (size_t)(k + NB) * Np + k;
+                // trailing[i][j] -= sum_c P[i][c] P[j][c]
+                gemm(st, rest, rest, NB, -1.0, Pn, Np, 1, Pn, 1, Np, K + (size_t)(k + NB) * Np + (k + NB), Np, true);
+            }
+        }
+        // forward substitution  L Z = R
+        for (int k = 0; k < Np; k += NB) {
+            hipLaunchKernelGGL(trsv_fwd_kernel, dim3((S + 255) / 256), dim3(256), 0, st, K, Np, k, R, S);
+            const int rest = Np - k - NB;
+            if (rest > 0)
+                gemm(st, rest, S, NB, -1.0, K + (size_t)(k + NB) * Np + k, Np, 1, R + (size_t)k * S, S, 1,
+                     R + (size_t)(k + NB) * S, S, false);
+        }
+        // backward substitution  L^T V = Z
+        for (int k = Np - NB; k >= 0; k -= NB) {
+            hipLaunchKernelGGL(trsv_bwd_kernel, dim3((S + 255) / 256), dim3(256), 0, st, K, Np, k, R, S);
+            if (k > 0)   // R[0:k] -= L[k:k+NB, 0:k]^T V_k : A(i, c) = K[(k+c)*Np + i]
+                gemm(st, k, S, NB, -1.0, K + (size_t)k * Np, 1, Np, R + (size_t)k * S, S, 1, R, S, false);
+        }
+        hipLaunchKernelGGL(emit_v_kernel, dim3((S + 255) / 256, c->Np / 4), dim3(256), 0, st, R, v_out, c->v4, N, c->Np,
+                           S, M, m);
+        P_HIP(hipGetLastError());
+    }
+    P_HIP(hipMemcpyAsync(&h_flag, flag, sizeof(int), hipMemcpyDeviceToHost, st));
+    P_HIP(hipStreamSynchronize(st));
+    if (h_flag != 0) {
+        snprintf(c->err, sizeof(c->err),
+                 "bagel_prepare_samples: K + noise_var I is not positive definite (output %d, pivot %d)",
+                 (h_flag - 1) / Np, (h_flag - 1) % Np);
+        rc = BAGEL_ENOTPD;
+    }
+done:
+    (void)hipStreamSynchronize(st);
+    if (K) (void)hipFree(K);
+    if (Phi) (void)hipFree(Phi);
+    if (R) (void)hipFree(R);
+    if (Wd) (void)hipFree(Wd);
+    if (flag) (void)hipFree(flag);
+    return rc;
+#undef P_HIP
 }

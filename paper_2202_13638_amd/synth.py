@@ -84,7 +84,7 @@ CONFIGS: Dict[str, Config] = {
         Config("small", 1, 4, 1, 1, 512, 1024, 256, 100, (64, 64), 0.0, "sinusoid", "const", 0, 1.0),
         Config("medium", 2, 4, 1, 1, 2048, 2048, 1024, 200, (64, 64), 0.0, "sinusoid", "steps", 0, 1.0),
         Config("large_policy", 3, 4, 1, 1, 4096, 2048, 4096, 500, (256, 256), 0.0, "sinusoid", "steps", 50, 1.0),
-        Config("stress", 4, 6, 2, 2, 8192, 4096, 8192, 1000, (256, 256), 1.0, "sinusoid", "steps", 0, 1.0),
+        Config("stress", 4, 6, 2, 2, 8192, 4096, 8192, 1000, (256, 256), 1.0, "sinusoid", "steps", 0, 0.01),
     ]
 }
 
