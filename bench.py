@@ -1,0 +1,165 @@
+#!/usr/bin/env python3
+"""Throughput of the rollout + policy-gradient hot path on one MI355X.
+
+A "step" is one call of bagel_rollout_loss_grad over the whole batch: B trajectories x H rollout
+steps forward (policy, sampled GP transition with Jacobian, cost) and the backward sweep to the
+policy gradient.  The metric is trajectory-steps per second (forward + backward) on the largest
+single-GPU workload ("stress": N=8192, D=8, M=6, L=4096, B=S=8192, H=1000, policy 8-256-256-2).
+Inputs are seeded synthetic data (paper_2202_13638_amd/synth.py), resident in HBM before the
+timed region; the sample-set precompute (bagel_prepare_samples) runs before it, untimed.
+
+Prints ONE JSON line, with
+  roofline     the dominant kernel (sample evaluation with Jacobian, one launch per rollout step):
+               algorithmic flops per launch / average launch duration measured with HIP events on
+               the library's stream during the timed steps, against the float64 vector peak.
+  cpu_baseline the float64 oracle timed on this host's cores on a bounded sample of the workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2202_13638_amd import synth  # noqa: E402
+
+PEAK_FP64_VECTOR_TFLOPS = 78.6   # MI355X vector float64 (= unpacked float32) peak
+
+
+def algorithmic_flops_per_traj_step(cfg, jac=True):
+    """Sample evaluation only: FMA = 2 flops, each exp / sin / cos = 1 flop."""
+    M, N, L, D = cfg.M, cfg.N, cfg.L, cfg.D
+    fma = (2 if jac else 1) * M * (N + L) * (D + 1)
+    return 2 * fma + M * N + (2 if jac else 1) * M * L
+
+
+def cpu_baseline(cfg, inp, seconds_target=15.0):
+    """Time the oracle's loss+gradient on a bounded sample: min(B, 4*cores) trajectories, full N, L,
+    policy; horizon chosen so the run takes about `seconds_target`.  v is a random stand-in of the
+    right scale (the oracle's own prepare at N=8192 would take minutes and its values do not change
+    the work)."""
+    import oracle
+    cores = oracle.num_threads()
+    Bc = min(cfg.B, 4 * cores)
+    idx = np.arange(Bc) * (cfg.B // Bc)
+    rng = np.random.default_rng(7)
+    v = (100.0 * rng.standard_normal((Bc, cfg.M, cfg.N))).astype(np.float32)
+
+    def run(H):
+        sub = synth.scaled(cfg, B=Bc, H=H)
+        m = dict(inp)
+        m["w"] = np.ascontiguousarray(inp["w"][idx])
+        m["s0"] = np.ascontiguousarray(inp["s0"][idx])
+        m["goals"] = np.ascontiguousarray(inp["goals"][:H, idx])
+        dm = oracle.dims_from_config(sub)
+        t0 = time.perf_counter()
+        oracle.rollout(dm, m, v, grad=True, want_states=False)
+        return time.perf_counter() - t0
+
+    t_probe = run(2)
+    H = int(max(2, min(cfg.H, 50, round(2 * seconds_target / max(t_probe, 1e-3)))))
+    t = run(H)
+    return {"value": Bc * H / t, "unit": "trajectory-steps/s", "cores": cores, "kind": "oracle",
+            "sample": f"{Bc} trajectories x {H} steps at full N={cfg.N}, L={cfg.L}, policy {cfg.hidden}; "
+                      f"random v of the workload's scale; {t:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="stress", choices=list(synth.CONFIGS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-every", type=int, default=8, help="time every n-th sample-evaluation launch")
+    ap.add_argument("--ckpt", type=int, default=None, help="override ckpt_interval")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+
+    import torch
+    from paper_2202_13638_amd import binding
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    cfg = synth.CONFIGS[args.workload]
+    t0 = time.perf_counter()
+    inp = synth.make_inputs(cfg)
+    t_gen = time.perf_counter() - t0
+
+    dims = binding.dims_from_config(cfg) if args.ckpt is None else binding.dims_from_config(cfg, ckpt_interval=args.ckpt)
+    ctx = binding.Bagel(dims)
+    g = {k: torch.from_numpy(a).cuda() for k, a in inp.items()}
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ctx.bagel_prepare_samples(g["X"], g["y"], g["lengthscale"], g["signal_var"], g["noise_var"], g["omega"],
+                              g["phase"], g["w"], g["eps"], None)
+    torch.cuda.synchronize()
+    t_prep = time.perf_counter() - t0
+    for k in ("w", "eps", "y"):
+        del g[k]
+    torch.cuda.empty_cache()
+
+    loss = torch.zeros(1, device="cuda")
+    grad = torch.zeros(ctx.P, device="cuda")
+
+    def step():
+        ctx.bagel_rollout_loss_grad(g["theta"], g["s0"], g["goals"], loss, grad)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ctx.bagel_profile_enable(args.profile_every)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    k_ms, k_n = ctx.bagel_profile_read()
+    ctx.bagel_profile_enable(0)
+    assert np.isfinite(loss.item()) and bool(torch.isfinite(grad).all())
+
+    traj_steps = cfg.B * cfg.H
+    value = traj_steps * args.steps / elapsed
+    ckpt = dims.ckpt_interval if 0 < dims.ckpt_interval < cfg.H else 0
+    flops_launch = algorithmic_flops_per_traj_step(cfg, jac=True) * cfg.B
+    avg_ms = k_ms / max(k_n, 1)
+    achieved = flops_launch / (avg_ms * 1e-3) / 1e12 if k_n else float("nan")
+    out = {
+        "metric": "trajectory-steps/sec (fwd+bwd)",
+        "value": value,
+        "unit": "trajectory-steps/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": 1e3 * elapsed / args.steps,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f64",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "N": cfg.N, "D": cfg.D, "M": cfg.M, "L": cfg.L, "B": cfg.B, "S": cfg.B,
+                   "H": cfg.H, "policy": [cfg.d_in, *cfg.hidden, cfg.d_a], "ckpt_interval": ckpt,
+                   "arithmetic": "kernel row and feature phase in f64, policy and sin/cos in f32, f32 interface",
+                   "prepare_s": round(t_prep, 3), "input_generation_s": round(t_gen, 1),
+                   "workspace_GB": round(ctx.workspace_bytes() / 1e9, 2)},
+        "roofline": {"bound": "alu", "kernel": "gp_step_kernel<D,jac>", "achieved": achieved,
+                     "peak": PEAK_FP64_VECTOR_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP64_VECTOR_TFLOPS,
+                     "traffic": None, "avg_launch_ms": avg_ms, "timed_launches": k_n,
+                     "flops_per_launch": flops_launch,
+                     "share_of_step": (avg_ms * cfg.H * (2 if ckpt else 1)) / (1e3 * elapsed / args.steps)},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, inp)
+    ctx.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

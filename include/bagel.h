@@ -144,6 +144,17 @@ int bagel_rollout_loss_grad(bagel_ctx *ctx, const float *theta, const float *s0,
  */
 int bagel_sample_eval(bagel_ctx *ctx, const float *x, float *f, float *jac);
 
+/*
+ * Measurement hooks (used by bench.py; not part of the method).  With every > 0, every
+ * `every`-th launch of the sample-evaluation kernel inside the rollout calls is bracketed by
+ * HIP events on the context's stream (at most 4096 timed launches between two reads; further
+ * ones are skipped).  bagel_profile_read synchronises the stream, returns the summed elapsed
+ * milliseconds and the number of timed launches since the last read, and resets both.
+ * Errors: EINVAL, EHIP.
+ */
+int bagel_profile_enable(bagel_ctx *ctx, int every);
+int bagel_profile_read(bagel_ctx *ctx, double *kernel_ms, int *launches);
+
 /* Message of the last error on this context ("" if none); valid until the next call on it.
  * With ctx == NULL: message of the last failed bagel_create on this thread. */
 const char *bagel_last_error(const bagel_ctx *ctx);

@@ -20,7 +20,8 @@ _NAMES = {EINVAL: "BAGEL_EINVAL", ENOTPREPARED: "BAGEL_ENOTPREPARED", ENOMEM: "B
 
 EXPORTS = ["bagel_num_params", "bagel_create", "bagel_destroy", "bagel_workspace_bytes",
            "bagel_prepare_samples", "bagel_set_samples", "bagel_rollout_loss",
-           "bagel_rollout_loss_grad", "bagel_sample_eval", "bagel_last_error"]
+           "bagel_rollout_loss_grad", "bagel_sample_eval", "bagel_last_error",
+           "bagel_profile_enable", "bagel_profile_read"]
 
 
 class BagelError(RuntimeError):
@@ -72,6 +73,9 @@ def load():
     """Load libbagel.so; raises if it has not been built (python -m paper_2202_13638_amd.build)."""
     global _lib
     if _lib is None:
+        # torch first: the library must bind to the HIP runtime that torch has already loaded, so
+        # that device pointers and streams handed over belong to the same runtime instance
+        import torch  # noqa: F401
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2202_13638_amd.build`")
         L = C.CDLL(LIB_PATH)
@@ -94,6 +98,10 @@ def load():
         L.bagel_rollout_loss_grad.argtypes = [vp] + [fp] * 8
         L.bagel_sample_eval.restype = C.c_int
         L.bagel_sample_eval.argtypes = [vp] + [fp] * 3
+        L.bagel_profile_enable.restype = C.c_int
+        L.bagel_profile_enable.argtypes = [vp, C.c_int]
+        L.bagel_profile_read.restype = C.c_int
+        L.bagel_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int)]
         L.bagel_last_error.restype = C.c_char_p
         L.bagel_last_error.argtypes = [vp]
         _lib = L
@@ -190,6 +198,14 @@ class Bagel:
             _ptr(loss_per_traj, (d.B,), "loss_per_traj", optional=True),
             _ptr(states, (d.H + 1, d.B, d.d_s), "states", optional=True),
             _ptr(grad_s0, (d.B, d.d_s), "grad_s0", optional=True)))
+
+    def bagel_profile_enable(self, every: int):
+        self._check(self._lib.bagel_profile_enable(self._h, int(every)))
+
+    def bagel_profile_read(self):
+        ms, n = C.c_double(), C.c_int()
+        self._check(self._lib.bagel_profile_read(self._h, C.byref(ms), C.byref(n)))
+        return ms.value, n.value
 
     def bagel_sample_eval(self, x, f, jac=None):
         d = self.dims

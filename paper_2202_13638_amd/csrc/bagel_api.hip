@@ -122,7 +122,7 @@ extern "C" int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_s
     c->units = M * (c->nck + c->ncl);
     if (c->units > 65535) {
         delete c;
-        CREATE_FAIL(BAGEL_EINVAL, "bagel_create: too many work units (%d)", M * 0);
+        CREATE_FAIL(BAGEL_EINVAL, "bagel_create: too many work units (%d)", M * (int)((N + 31) / 32 + (L + 31) / 32));
     }
 
     const int K = dims->ckpt_interval;
@@ -177,6 +177,11 @@ extern "C" int bagel_destroy(bagel_ctx *c)
 {
     if (!c) return BAGEL_OK;
     (void)hipStreamSynchronize(c->stream);
+    if (c->prof_ev) {
+        for (int i = 0; i < 2 * BAGEL_PROF_MAX; ++i)
+            if (c->prof_ev[i]) (void)hipEventDestroy(c->prof_ev[i]);
+        free(c->prof_ev);
+    }
     free_all(c);
     delete c;
     return BAGEL_OK;
@@ -229,6 +234,58 @@ extern "C" int bagel_sample_eval(bagel_ctx *c, const float *x, float *f, float *
     return BAGEL_OK;
 }
 
+// the sample-evaluation launch, optionally bracketed by events
+static hipError_t gp_step_timed(bagel_ctx *c, bool jac)
+{
+    bool timed = false;
+    if (c->prof_every > 0) {
+        timed = (c->prof_seen++ % c->prof_every == 0) && c->prof_used < BAGEL_PROF_MAX;
+        if (timed) {
+            hipError_t e = hipEventRecord(c->prof_ev[2 * c->prof_used], c->stream);
+            if (e != hipSuccess) return e;
+        }
+    }
+    hipError_t e = bagel_launch_gp_step(c, jac);
+    if (timed && e == hipSuccess) {
+        e = hipEventRecord(c->prof_ev[2 * c->prof_used + 1], c->stream);
+        c->prof_used++;
+    }
+    return e;
+}
+
+extern "C" int bagel_profile_enable(bagel_ctx *c, int every)
+{
+    if (!c || every < 0) return BAGEL_EINVAL;
+    c->err[0] = 0;
+    if (every > 0 && !c->prof_ev) {
+        c->prof_ev = (hipEvent_t *)calloc(2 * BAGEL_PROF_MAX, sizeof(hipEvent_t));
+        if (!c->prof_ev) BAGEL_FAIL(c, BAGEL_ENOMEM, "bagel_profile_enable: host allocation failed");
+        for (int i = 0; i < 2 * BAGEL_PROF_MAX; ++i) BAGEL_HIP(c, hipEventCreate(&c->prof_ev[i]));
+    }
+    c->prof_every = every;
+    c->prof_seen = 0;
+    c->prof_used = 0;
+    return BAGEL_OK;
+}
+
+extern "C" int bagel_profile_read(bagel_ctx *c, double *kernel_ms, int *launches)
+{
+    if (!c || !kernel_ms || !launches) return BAGEL_EINVAL;
+    c->err[0] = 0;
+    BAGEL_HIP(c, hipStreamSynchronize(c->stream));
+    double total = 0.0;
+    for (int i = 0; i < c->prof_used; ++i) {
+        float ms = 0.0f;
+        BAGEL_HIP(c, hipEventElapsedTime(&ms, c->prof_ev[2 * i], c->prof_ev[2 * i + 1]));
+        total += (double)ms;
+    }
+    *kernel_ms = total;
+    *launches = c->prof_used;
+    c->prof_used = 0;
+    c->prof_seen = 0;
+    return BAGEL_OK;
+}
+
 // forward steps t0 .. t1-1 starting from the state in xbuf and the policy input in slot (t0 - slot_base)
 static int run_forward(bagel_ctx *c, int t0, int t1, int slot_base, bool jac, bool add_cost, bool write_tape_s,
                        bool write_ckpt, const float *goals, float *states_out)
@@ -238,7 +295,7 @@ static int run_forward(bagel_ctx *c, int t0, int t1, int slot_base, bool jac, bo
         const int slot = jac ? t - slot_base : 0;
         const int next_slot = jac ? (t + 1 < t1 ? slot + 1 : -1) : 0;
         BAGEL_HIP(c, bagel_launch_policy_forward(c, slot));
-        BAGEL_HIP(c, bagel_launch_gp_step(c, jac));
+        BAGEL_HIP(c, gp_step_timed(c, jac));
         const int ck = (write_ckpt && (t + 1) % K == 0 && t + 1 < c->dm.H) ? (t + 1) / K : -1;
         BAGEL_HIP(c, bagel_launch_advance(c, t, slot, next_slot, jac, add_cost, write_tape_s, ck, goals, states_out));
     }

@@ -55,7 +55,12 @@ struct bagel_ctx {
     float *gsplit;               // [ksplit][P] split-contraction partial weight gradients
     double *gacc;                // [P] gradient accumulated over segments
     int ksplit;
+
+    // ---- measurement hooks -------------------------------------------------------------------
+    int prof_every, prof_seen, prof_used;
+    hipEvent_t *prof_ev;         // 2 * BAGEL_PROF_MAX events, created on enable
 };
+#define BAGEL_PROF_MAX 4096
 
 #define BAGEL_FAIL(ctx, code, ...)                                   \
     do {                                                             \
