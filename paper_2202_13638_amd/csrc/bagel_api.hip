@@ -75,7 +75,7 @@ static void free_all(bagel_ctx *c)
 {
     void *ptrs[] = {c->Xs, c->Os, c->A, c->amp, c->v4, c->w4, c->xbuf, c->part, c->lpt, c->lam, c->us, c->dh0,
                     c->tape_s, c->tape_J, c->tape_h[0], c->tape_h[1], c->tape_h[2], c->tape_a, c->tape_d[0],
-                    c->tape_d[1], c->tape_d[2], c->ckpt_s, c->thetaT, c->gsplit, c->gacc};
+                    c->tape_d[1], c->tape_d[2], c->ckpt_s, c->thetaT, c->gsplit, c->gacc, c->fbuf};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
 }
@@ -147,6 +147,7 @@ extern "C" int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_s
     ALLOC(c->lam, (size_t)dims->d_s * Bz);
     ALLOC(c->us, (size_t)dims->d_s * Bz);
     ALLOC(c->dh0, (size_t)c->d_in * Bz);
+    ALLOC(c->fbuf, (size_t)M * Bz);
     ALLOC(c->tape_s, (size_t)(H + 1) * dims->d_s * Bz);
     ALLOC(c->tape_J, T * M * D * Bz);
     for (int l = 0; l < c->n_layers; ++l) {
@@ -228,9 +229,10 @@ extern "C" int bagel_sample_eval(bagel_ctx *c, const float *x, float *f, float *
     c->err[0] = 0;
     if (!x || !f) BAGEL_FAIL(c, BAGEL_EINVAL, "bagel_sample_eval: null argument");
     if (!c->prepared) BAGEL_FAIL(c, BAGEL_ENOTPREPARED, "bagel_sample_eval: no samples installed");
-    BAGEL_HIP(c, bagel_launch_eval_io(c, 0, x, nullptr, nullptr));
+    BAGEL_HIP(c, bagel_launch_eval_io(c, 0, x, nullptr));
     BAGEL_HIP(c, bagel_launch_gp_step(c, jac != nullptr));
-    BAGEL_HIP(c, bagel_launch_eval_io(c, 1, nullptr, f, jac));
+    BAGEL_HIP(c, bagel_launch_finalize(c, jac != nullptr, -1, jac));
+    BAGEL_HIP(c, bagel_launch_eval_io(c, 1, nullptr, f));
     return BAGEL_OK;
 }
 
@@ -296,6 +298,7 @@ static int run_forward(bagel_ctx *c, int t0, int t1, int slot_base, bool jac, bo
         const int next_slot = jac ? (t + 1 < t1 ? slot + 1 : -1) : 0;
         BAGEL_HIP(c, bagel_launch_policy_forward(c, slot));
         BAGEL_HIP(c, gp_step_timed(c, jac));
+        BAGEL_HIP(c, bagel_launch_finalize(c, jac, slot, nullptr));
         const int ck = (write_ckpt && (t + 1) % K == 0 && t + 1 < c->dm.H) ? (t + 1) / K : -1;
         BAGEL_HIP(c, bagel_launch_advance(c, t, slot, next_slot, jac, add_cost, write_tape_s, ck, goals, states_out));
     }

@@ -40,6 +40,7 @@ struct bagel_ctx {
     double *lam;                 // [d_s][B] adjoint of the state
     double *us;                  // [d_s][B] J_s^T lam of the step being swept
     float *dh0;                  // [d_in][B] adjoint of the policy input
+    double *fbuf;                // [M][B] sample values of the current step, summed over work units
 
     // ---- tape (T_tape slots: H, or ckpt_interval when checkpointing) ----------------------
     int T_tape;
@@ -93,7 +94,9 @@ hipError_t bagel_launch_advance(bagel_ctx *ctx, int t, int slot, int next_slot, 
                                 bool write_tape_s, int ckpt_index, const float *goals, float *states_out);
 hipError_t bagel_launch_finish_loss(bagel_ctx *ctx, float *loss, float *loss_per_traj);
 hipError_t bagel_launch_adjoint_lane(bagel_ctx *ctx, int t, int prev_slot, const float *goals, float *grad_s0);
-hipError_t bagel_launch_eval_io(bagel_ctx *ctx, int phase, const float *x, float *f, float *jac);
+hipError_t bagel_launch_eval_io(bagel_ctx *ctx, int phase, const float *x, float *f);
+// add up the per-unit partial sums: value into fbuf, Jacobian into tape slot `slot` (or jac_out if slot < 0)
+hipError_t bagel_launch_finalize(bagel_ctx *ctx, bool jac, int slot, float *jac_out);
 
 // ---- policy.hip --------------------------------------------------------------------------
 hipError_t bagel_launch_transpose_theta(bagel_ctx *ctx, const float *theta);

@@ -24,29 +24,37 @@ struct lane_args {
     double *ckpt_s;
 };
 
-// Sum the partial sums of one step in unit order: f[m], and, if jac, every J[m][d] is handed to
-// emit(m * D + d, value) as soon as it is complete (no per-lane array of M*D doubles).
-template <class Emit>
-__device__ __forceinline__ void reduce_units(const lane_args &a, int b, const double *x, bool jac, double *f,
-                                             Emit emit)
+// Add up the partial sums of one sample evaluation in unit order and finish value and Jacobian.
+// One thread per (trajectory, output m, component): component 0 is the value
+//   f[m] = amp_m * sum_c p_c + sum_c u_c,
+// component 1+d the Jacobian entry
+//   J[m][d] = -amp_m (pi/2) sum_c Gr_c[d] + ln2 (sum_c Gk_c[d] - log2(e)/l_md^2 x_d sum_c u_c).
+// f goes to fbuf[m][b] (float64); J[m][d] to jdst[(m*D+d)*js_i + b*js_b] (float32), which is either a
+// tape slot ([M][D][B]) or a caller array ([B][M][D]).
+__global__ __launch_bounds__(BAGEL_BLOCK) void finalize_kernel(lane_args a, int ncomp, double *__restrict__ fbuf,
+                                                               float *__restrict__ jdst, long js_i, long js_b)
 {
+    const int b = blockIdx.x * BAGEL_BLOCK + threadIdx.x;
+    if (b >= a.B) return;
+    const int m = blockIdx.y / ncomp, comp = blockIdx.y - m * ncomp;
     const size_t stride = (size_t)(1 + a.D) * a.B;
-    for (int m = 0; m < a.M; ++m) {
-        const double *pk = a.part + (size_t)(m * a.nck) * stride + b;
-        const double *pr = a.part + (size_t)(a.M * a.nck + m * a.ncl) * stride + b;
-        double u = 0.0, p = 0.0;
-        for (int c = 0; c < a.nck; ++c) u += pk[c * stride];
+    const double *pk = a.part + (size_t)(m * a.nck) * stride + b;
+    const double *pr = a.part + (size_t)(a.M * a.nck + m * a.ncl) * stride + b;
+    double u = 0.0;
+    for (int c = 0; c < a.nck; ++c) u += pk[c * stride];
+    const double amp = a.amp[m];
+    if (comp == 0) {
+        double p = 0.0;
         for (int c = 0; c < a.ncl; ++c) p += pr[c * stride];
-        const double amp = a.amp[m];
-        f[m] = amp * p + u;
-        if (jac) {
-            for (int d = 0; d < a.D; ++d) {
-                double gk = 0.0, gr = 0.0;
-                for (int c = 0; c < a.nck; ++c) gk += pk[c * stride + (size_t)(1 + d) * a.B];
-                for (int c = 0; c < a.ncl; ++c) gr += pr[c * stride + (size_t)(1 + d) * a.B];
-                emit(m * a.D + d, -amp * HALF_PI * gr + LN2 * (gk - a.A[m * a.D + d] * x[d] * u));
-            }
-        }
+        fbuf[(size_t)m * a.B + b] = amp * p + u;
+    } else {
+        const int d = comp - 1;
+        double gk = 0.0, gr = 0.0;
+        for (int c = 0; c < a.nck; ++c) gk += pk[c * stride + (size_t)comp * a.B];
+        for (int c = 0; c < a.ncl; ++c) gr += pr[c * stride + (size_t)comp * a.B];
+        const double x = a.xbuf[(size_t)d * a.B + b];
+        const double J = -amp * HALF_PI * gr + LN2 * (gk - a.A[m * a.D + d] * x * u);
+        jdst[(long)(m * a.D + d) * js_i + (long)b * js_b] = (float)J;
     }
 }
 
@@ -105,25 +113,21 @@ __global__ __launch_bounds__(BAGEL_BLOCK) void restore_kernel(lane_args a, const
     for (int j = 0; j < a.dg; ++j) h0_slot[(size_t)(a.ds + j) * a.B + b] = goals_t[(size_t)b * a.dg + j];
 }
 
-// Finish step t: reduce -> f (and J), s_{t+1} = s_t + f, cost against goals[t], tapes, and the policy
-// input of step t+1.
+// Finish step t: s_{t+1} = s_t + f (f from finalize_kernel), cost against goals[t], tapes, and the
+// policy input of step t+1.
 __global__ __launch_bounds__(BAGEL_BLOCK) void advance_kernel(lane_args a, int t, bool jac, bool add_cost,
                                                               const float *__restrict__ goals_t,
                                                               const float *__restrict__ goals_next,
-                                                              float *__restrict__ tape_J_slot,
+                                                              const double *__restrict__ fbuf,
                                                               float *__restrict__ states_out_next,
                                                               float *__restrict__ h0_next,
                                                               double *__restrict__ ckpt_next)
 {
     const int b = blockIdx.x * BAGEL_BLOCK + threadIdx.x;
     if (b >= a.B) return;
-    double x[BAGEL_MAX_D], f[8];
-    for (int d = 0; d < a.D; ++d) x[d] = a.xbuf[(size_t)d * a.B + b];
-    reduce_units(a, b, x, jac, f,
-                 [&](int i, double v) { tape_J_slot[(size_t)i * a.B + b] = (float)v; });
     double s[8];
     for (int i = 0; i < a.ds; ++i) {
-        s[i] = x[i] + f[i];
+        s[i] = a.xbuf[(size_t)i * a.B + b] + fbuf[(size_t)i * a.B + b];
         a.xbuf[(size_t)i * a.B + b] = s[i];
         if (a.tape_s) a.tape_s[((size_t)(t + 1) * a.ds + i) * a.B + b] = (float)s[i];
         if (states_out_next) states_out_next[(size_t)b * a.ds + i] = (float)s[i];
@@ -216,9 +220,10 @@ __global__ __launch_bounds__(BAGEL_BLOCK) void adjoint_lane_kernel(lane_args a, 
     }
 }
 
-// bagel_sample_eval plumbing: phase 0 loads x[B][D] into xbuf; phase 1 reduces and writes f, jac.
+// bagel_sample_eval plumbing: phase 0 loads x[B][D] into xbuf; phase 1 writes f[B][M] from fbuf.
 __global__ __launch_bounds__(BAGEL_BLOCK) void eval_io_kernel(lane_args a, int phase, const float *__restrict__ xin,
-                                                              float *__restrict__ f_out, float *__restrict__ j_out)
+                                                              const double *__restrict__ fbuf,
+                                                              float *__restrict__ f_out)
 {
     const int b = blockIdx.x * BAGEL_BLOCK + threadIdx.x;
     if (b >= a.B) return;
@@ -226,11 +231,7 @@ __global__ __launch_bounds__(BAGEL_BLOCK) void eval_io_kernel(lane_args a, int p
         for (int d = 0; d < a.D; ++d) a.xbuf[(size_t)d * a.B + b] = (double)xin[(size_t)b * a.D + d];
         return;
     }
-    double x[BAGEL_MAX_D], f[8];
-    for (int d = 0; d < a.D; ++d) x[d] = a.xbuf[(size_t)d * a.B + b];
-    reduce_units(a, b, x, j_out != nullptr, f,
-                 [&](int i, double v) { j_out[(size_t)b * a.M * a.D + i] = (float)v; });
-    for (int m = 0; m < a.M; ++m) f_out[(size_t)b * a.M + m] = (float)f[m];
+    for (int m = 0; m < a.M; ++m) f_out[(size_t)b * a.M + m] = (float)fbuf[(size_t)m * a.B + b];
 }
 
 lane_args make_args(const bagel_ctx *c)
@@ -282,7 +283,7 @@ hipError_t bagel_launch_advance(bagel_ctx *c, int t, int slot, int next_slot, bo
     const bool has_next = t + 1 < c->dm.H;
     hipLaunchKernelGGL(advance_kernel, lane_grid(c), dim3(BAGEL_BLOCK), 0, c->stream, a, t, jac, add_cost,
                        goals + (size_t)t * B * c->dm.d_g, has_next ? goals + (size_t)(t + 1) * B * c->dm.d_g : nullptr,
-                       jac ? slot_ptr(c->tape_J, slot, c->M * c->D, c->dm.B) : nullptr,
+                       c->fbuf,
                        states_out ? states_out + (size_t)(t + 1) * B * c->dm.d_s : nullptr,
                        (has_next && next_slot >= 0) ? slot_ptr(c->tape_h[0], next_slot, c->d_in, c->dm.B) : nullptr,
                        ckpt_index >= 0 ? c->ckpt_s + (size_t)ckpt_index * c->dm.d_s * B : nullptr);
@@ -309,9 +310,25 @@ hipError_t bagel_launch_adjoint_lane(bagel_ctx *c, int t, int prev_slot, const f
     return hipGetLastError();
 }
 
-hipError_t bagel_launch_eval_io(bagel_ctx *c, int phase, const float *x, float *f, float *jac)
+hipError_t bagel_launch_eval_io(bagel_ctx *c, int phase, const float *x, float *f)
 {
     lane_args a = make_args(c);
-    hipLaunchKernelGGL(eval_io_kernel, lane_grid(c), dim3(BAGEL_BLOCK), 0, c->stream, a, phase, x, f, jac);
+    hipLaunchKernelGGL(eval_io_kernel, lane_grid(c), dim3(BAGEL_BLOCK), 0, c->stream, a, phase, x, c->fbuf, f);
+    return hipGetLastError();
+}
+
+// slot >= 0: Jacobian into that tape slot; slot < 0: into jac_out[B][M][D] (may be null: value only)
+hipError_t bagel_launch_finalize(bagel_ctx *c, bool jac, int slot, float *jac_out)
+{
+    lane_args a = make_args(c);
+    const int ncomp = jac ? 1 + c->D : 1;
+    dim3 grid((c->dm.B + BAGEL_BLOCK - 1) / BAGEL_BLOCK, c->M * ncomp);
+    float *jdst = nullptr;
+    long js_i = 0, js_b = 0;
+    if (jac) {
+        if (slot >= 0) { jdst = slot_ptr(c->tape_J, slot, c->M * c->D, c->dm.B); js_i = c->dm.B; js_b = 1; }
+        else { jdst = jac_out; js_i = 1; js_b = (long)c->M * c->D; }
+    }
+    hipLaunchKernelGGL(finalize_kernel, grid, dim3(BAGEL_BLOCK), 0, c->stream, a, ncomp, c->fbuf, jdst, js_i, js_b);
     return hipGetLastError();
 }
