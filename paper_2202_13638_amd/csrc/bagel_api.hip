@@ -75,7 +75,7 @@ static void free_all(bagel_ctx *c)
 {
     void *ptrs[] = {c->Xs, c->Os, c->A, c->amp, c->v4, c->w4, c->xbuf, c->part, c->lpt, c->lam, c->us, c->dh0,
                     c->tape_s, c->tape_J, c->tape_h[0], c->tape_h[1], c->tape_h[2], c->tape_a, c->tape_d[0],
-                    c->tape_d[1], c->tape_d[2], c->ckpt_s, c->thetaT, c->gsplit, c->gacc, c->fbuf};
+                    c->tape_d[1], c->tape_d[2], c->ckpt_s, c->wpad_f, c->wpad_b, c->gsplit, c->gacc, c->fbuf};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
 }
@@ -129,7 +129,15 @@ extern "C" int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_s
     const int H = dims->H;
     c->T_tape = (K > 0 && K < H) ? K : H;
     const int n_seg = (K > 0 && K < H) ? (H + K - 1) / K : 1;
-    c->ksplit = env_int("BAGEL_KSPLIT", 32);
+    c->ksplit = env_int("BAGEL_KSPLIT", 256);
+    int wf_total = 0, wb_total = 0;
+    for (int l = 0; l < c->n_layers; ++l) {
+        const int no = c->width[l + 1], ni = c->width[l];
+        c->wpf_off[l] = wf_total; c->wpf_rp[l] = (no + 31) / 32 * 32; c->wpf_kp[l] = (ni + 7) / 8 * 8;
+        wf_total += c->wpf_rp[l] * c->wpf_kp[l];
+        c->wpb_off[l] = wb_total; c->wpb_rp[l] = (ni + 31) / 32 * 32; c->wpb_kp[l] = (no + 7) / 8 * 8;
+        wb_total += c->wpb_rp[l] * c->wpb_kp[l];
+    }
     const size_t Bz = (size_t)B, T = (size_t)c->T_tape;
 
     hipError_t e = hipSuccess;
@@ -156,7 +164,8 @@ extern "C" int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_s
     }
     ALLOC(c->tape_a, T * dims->d_a * Bz);
     ALLOC(c->ckpt_s, (size_t)n_seg * dims->d_s * Bz);
-    ALLOC(c->thetaT, (size_t)c->P);
+    ALLOC(c->wpad_f, (size_t)wf_total);
+    ALLOC(c->wpad_b, (size_t)wb_total);
     ALLOC(c->gsplit, (size_t)c->ksplit * c->P);
     ALLOC(c->gacc, (size_t)c->P);
 #undef ALLOC
@@ -290,13 +299,13 @@ extern "C" int bagel_profile_read(bagel_ctx *c, double *kernel_ms, int *launches
 
 // forward steps t0 .. t1-1 starting from the state in xbuf and the policy input in slot (t0 - slot_base)
 static int run_forward(bagel_ctx *c, int t0, int t1, int slot_base, bool jac, bool add_cost, bool write_tape_s,
-                       bool write_ckpt, const float *goals, float *states_out)
+                       bool write_ckpt, const float *theta, const float *goals, float *states_out)
 {
     const int K = c->T_tape;
     for (int t = t0; t < t1; ++t) {
         const int slot = jac ? t - slot_base : 0;
         const int next_slot = jac ? (t + 1 < t1 ? slot + 1 : -1) : 0;
-        BAGEL_HIP(c, bagel_launch_policy_forward(c, slot));
+        BAGEL_HIP(c, bagel_launch_policy_forward(c, slot, theta));
         BAGEL_HIP(c, gp_step_timed(c, jac));
         BAGEL_HIP(c, bagel_launch_finalize(c, jac, slot, nullptr));
         const int ck = (write_ckpt && (t + 1) % K == 0 && t + 1 < c->dm.H) ? (t + 1) / K : -1;
@@ -312,9 +321,9 @@ extern "C" int bagel_rollout_loss(bagel_ctx *c, const float *theta, const float 
     c->err[0] = 0;
     if (!theta || !s0 || !goals || !loss) BAGEL_FAIL(c, BAGEL_EINVAL, "bagel_rollout_loss: null argument");
     if (!c->prepared) BAGEL_FAIL(c, BAGEL_ENOTPREPARED, "bagel_rollout_loss: no samples installed");
-    BAGEL_HIP(c, bagel_launch_transpose_theta(c, theta));
+    BAGEL_HIP(c, bagel_launch_pack_theta(c, theta));
     BAGEL_HIP(c, bagel_launch_init_state(c, s0, goals, states, false, false));
-    const int rc = run_forward(c, 0, c->dm.H, 0, false, true, false, false, goals, states);
+    const int rc = run_forward(c, 0, c->dm.H, 0, false, true, false, false, theta, goals, states);
     if (rc != BAGEL_OK) return rc;
     BAGEL_HIP(c, bagel_launch_finish_loss(c, loss, loss_per_traj));
     return BAGEL_OK;
@@ -342,10 +351,10 @@ extern "C" int bagel_rollout_loss_grad(bagel_ctx *c, const float *theta, const f
     const int H = c->dm.H, K = c->T_tape;
     const bool ckpt = K < H;
     int rc;
-    BAGEL_HIP(c, bagel_launch_transpose_theta(c, theta));
+    BAGEL_HIP(c, bagel_launch_pack_theta(c, theta));
     BAGEL_HIP(c, bagel_launch_init_state(c, s0, goals, states, true, ckpt));
     if (!ckpt) {
-        rc = run_forward(c, 0, H, 0, true, true, true, false, goals, states);
+        rc = run_forward(c, 0, H, 0, true, true, true, false, theta, goals, states);
         if (rc != BAGEL_OK) return rc;
         BAGEL_HIP(c, bagel_launch_finish_loss(c, loss, loss_per_traj));
         rc = run_backward(c, 0, H, theta, goals);
@@ -356,14 +365,14 @@ extern "C" int bagel_rollout_loss_grad(bagel_ctx *c, const float *theta, const f
     }
     // checkpointed: a plain forward pass that keeps the state every K steps, then one segment at a
     // time from the end: re-run it with Jacobians and tapes, sweep it backwards, add its weight gradient.
-    rc = run_forward(c, 0, H, 0, false, true, true, true, goals, states);
+    rc = run_forward(c, 0, H, 0, false, true, true, true, theta, goals, states);
     if (rc != BAGEL_OK) return rc;
     BAGEL_HIP(c, bagel_launch_finish_loss(c, loss, loss_per_traj));
     const int n_seg = (H + K - 1) / K;
     for (int seg = n_seg - 1; seg >= 0; --seg) {
         const int t0 = seg * K, t1 = (t0 + K < H) ? t0 + K : H;
         BAGEL_HIP(c, bagel_launch_restore(c, seg, t0, goals));
-        rc = run_forward(c, t0, t1, t0, true, false, false, false, goals, nullptr);
+        rc = run_forward(c, t0, t1, t0, true, false, false, false, theta, goals, nullptr);
         if (rc != BAGEL_OK) return rc;
         rc = run_backward(c, t0, t1, theta, goals);
         if (rc != BAGEL_OK) return rc;

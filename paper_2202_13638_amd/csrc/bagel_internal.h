@@ -52,7 +52,9 @@ struct bagel_ctx {
     double *ckpt_s;              // [n_seg][d_s][B] state at the start of each segment
 
     // ---- parameters and gradient -----------------------------------------------------------
-    float *thetaT;               // per layer W^T [in][out] at the offsets of theta, biases copied
+    float *wpad_f, *wpad_b;      // zero-padded weights: forward [out pad 32][in pad 8], backward [in pad 32][out pad 8]
+    int wpf_off[3], wpf_rp[3], wpf_kp[3];
+    int wpb_off[3], wpb_rp[3], wpb_kp[3];
     float *gsplit;               // [ksplit][P] split-contraction partial weight gradients
     double *gacc;                // [P] gradient accumulated over segments
     int ksplit;
@@ -99,8 +101,8 @@ hipError_t bagel_launch_eval_io(bagel_ctx *ctx, int phase, const float *x, float
 hipError_t bagel_launch_finalize(bagel_ctx *ctx, bool jac, int slot, float *jac_out);
 
 // ---- policy.hip --------------------------------------------------------------------------
-hipError_t bagel_launch_transpose_theta(bagel_ctx *ctx, const float *theta);
-hipError_t bagel_launch_policy_forward(bagel_ctx *ctx, int slot);
+hipError_t bagel_launch_pack_theta(bagel_ctx *ctx, const float *theta);
+hipError_t bagel_launch_policy_forward(bagel_ctx *ctx, int slot, const float *theta);
 hipError_t bagel_launch_policy_backward(bagel_ctx *ctx, int slot, const float *theta);
 hipError_t bagel_launch_weight_grad(bagel_ctx *ctx, int n_slots, bool accumulate, float *grad_theta);
 

@@ -1,20 +1,30 @@
 // Policy network pi_theta([s ; g]): tanh MLP with a linear or saturating output (Sec. III-B and
 // IV-A: feed-forward policy, bounded action), its backward pass, and the weight gradients.
+// All three are dense float32 contractions and run on the matrix cores
+// (v_mfma_f32_32x32x2_f32: D[32x32] += A[32x2] B[2x32]).
 //
-// Forward / backward of one step: a workgroup holds 64 trajectories (lane = trajectory) and 16
-// waves; each wave owns a contiguous group of output units of the current layer.  The layer's
-// input activations live in LDS as [unit][lane] (conflict free), the weights are wave-uniform and
-// arrive as scalar operands, so each LDS read feeds up to 16 FMAs.  Activations and adjoints are
-// also written to the tape in HBM as [unit][B].
+// Forward / backward of one step.  A workgroup holds 64 trajectories and 16 waves; wave (rt, ct)
+// owns the 32x32 output tile of units [32 rt, 32 rt + 32) x trajectories [32 ct, 32 ct + 32).
+//   A operand = weights, zero-padded to [rows % 32 == 0][K % 8 == 0] once per call, so a lane
+//               reads four consecutive K values of its row with one 16-byte load;
+//   B operand = the layer's input activations, kept in LDS as [K/4][trajectory][4] so a lane
+//               reads the matching four K values of its trajectory with one 16-byte load.
+// Lanes 0-31 feed K = k0..k0+3 and lanes 32-63 feed K = k0+4..k0+7 over four MFMAs; the order in
+// which K is consumed does not matter as long as A and B agree.  The epilogue (bias, tanh, or the
+// tanh derivative in the backward pass) writes the next layer's input back to LDS in the same
+// layout and to the tape in HBM as [unit][B].
 //
-// Weight gradients are not accumulated inside the sweep: for each layer
+// Weight gradients are not accumulated inside the sweep.  For each layer
 //   dW[o][i] = sum_{t,b} delta[t][o][b] * h[t][i][b],   db[o] = sum_{t,b} delta[t][o][b]
-// is one tall-skinny GEMM over the taped arrays with the contraction over (step, trajectory),
-// computed with a fixed split of the contraction range and a fixed-order final sum, so the result
-// is bitwise reproducible.
+// is one GEMM over the taped arrays with the contraction over (step, trajectory).  Both operands
+// are contiguous along the contraction, so lanes load their MFMA operands straight from HBM/L2;
+// the contraction range is split over workgroups in a fixed way and the partial results are
+// added in a fixed order, so the gradient is bitwise reproducible.
 #include "bagel_internal.h"
 
 namespace {
+
+typedef float f16v __attribute__((ext_vector_type(16)));
 
 constexpr int PW = 16;   // waves per workgroup
 constexpr int PL = 64;   // trajectories per workgroup
@@ -22,9 +32,12 @@ constexpr int PL = 64;   // trajectories per workgroup
 struct policy_args {
     int B, nl, ds;
     int width[4];
-    int w_off[3], b_off[3];
+    int b_off[3];         // bias offsets inside theta
+    int wp_off[3];        // offsets of the padded weight matrices
+    int kp[3], rp[3];     // padded contraction length and row count per layer
     float act_bound;
-    const float *W;       // forward: transposed weights [in][out]; backward: theta itself [out][in]
+    const float *theta;
+    const float *Wp;      // padded weights: forward [out][in], backward [in][out]
     float *h[3];          // tape slots of the layer inputs
     float *d[3];          // tape slots of the pre-activation adjoints
     float *a_slot;        // [d_a][B]
@@ -32,96 +45,90 @@ struct policy_args {
     double *xbuf;         // [D][B]
 };
 
-// acc[jj] += sum_k Wk[k][j0+jj] * act[k][lane]; Wk is [nk][nj] row-major, j0 wave-uniform
-template <int JPW>
-__device__ __forceinline__ void dense(const float *__restrict__ Wk, int nk, int nj, int j0,
-                                      const float *__restrict__ act, int lane, float *acc)
+// acc += W[32 rt .. +32][0..kp) * act[0..kp)[32 ct .. +32]
+__device__ __forceinline__ f16v tile_contract(const float *__restrict__ W, int kp, int rt, int ct, int c, int hf,
+                                              const float4 *__restrict__ act4)
 {
-    for (int k = 0; k < nk; ++k) {
-        const float hk = act[k * PL + lane];
-        const float *__restrict__ row = Wk + (size_t)k * nj + j0;
+    f16v acc;
 #pragma unroll
-        for (int jj = 0; jj < JPW; ++jj) acc[jj] = fmaf(row[jj], hk, acc[jj]);
+    for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+    const float *wrow = W + (size_t)(rt * 32 + c) * kp + 4 * hf;
+    const float4 *bcol = act4 + hf * PL + ct * 32 + c;
+    for (int k0 = 0; k0 < kp; k0 += 8) {
+        const float4 av = *reinterpret_cast<const float4 *>(wrow + k0);
+        const float4 bv = bcol[(k0 >> 2) * PL];
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av.x, bv.x, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av.y, bv.y, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av.z, bv.z, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av.w, bv.w, acc, 0, 0, 0);
     }
+    return acc;
 }
 
-__device__ __forceinline__ void dense_dispatch(int jpw, const float *Wk, int nk, int nj, int j0,
-                                               const float *act, int lane, float *acc)
+// rows of a [n][B] array -> LDS [k/4][trajectory][4], zero-filled up to kp rows
+__device__ __forceinline__ void stage_input(const float *__restrict__ src, int n, int kp, int B, int b0,
+                                            float4 *__restrict__ act4)
 {
-    switch (jpw) {
-        case 1: dense<1>(Wk, nk, nj, j0, act, lane, acc); break;
-        case 2: dense<2>(Wk, nk, nj, j0, act, lane, acc); break;
-        case 4: dense<4>(Wk, nk, nj, j0, act, lane, acc); break;
-        case 8: dense<8>(Wk, nk, nj, j0, act, lane, acc); break;
-        default: dense<16>(Wk, nk, nj, j0, act, lane, acc); break;
+    const int bl = threadIdx.x & (PL - 1);
+    int b = b0 + bl;
+    if (b >= B) b = B - 1;
+    for (int kg = threadIdx.x >> 6; kg < (kp >> 2); kg += PW) {
+        float t[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int k = kg * 4 + e;
+            t[e] = k < n ? src[(size_t)k * B + b] : 0.0f;
+        }
+        act4[kg * PL + bl] = make_float4(t[0], t[1], t[2], t[3]);
     }
-}
-
-// units per wave: smallest power of two p with 16 p >= nj
-__device__ __host__ inline int units_per_wave(int nj)
-{
-    int p = 1;
-    while (p * PW < nj) p *= 2;
-    return p;
 }
 
 __global__ __launch_bounds__(PW * PL) void policy_forward_kernel(policy_args a)
 {
-    __shared__ float act[BAGEL_MAX_HIDDEN * PL];
-    const int lane = threadIdx.x & (PL - 1);
+    __shared__ float4 act4[(BAGEL_MAX_HIDDEN / 4) * PL];
+    const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int b_raw = blockIdx.x * PL + lane;
-    const bool live = b_raw < a.B;
-    const int b = live ? b_raw : a.B - 1;
+    const int rt = wave >> 1, ct = wave & 1;
+    const int c = lane & 31, hf = lane >> 5;
+    const int b0 = blockIdx.x * PL;
+    const int b = b0 + ct * 32 + c;
+    const bool live = b < a.B;
 
-    for (int k = wave; k < a.width[0]; k += PW) act[k * PL + lane] = a.h[0][(size_t)k * a.B + b];
+    stage_input(a.h[0], a.width[0], a.kp[0], a.B, b0, act4);
     __syncthreads();
 
     for (int l = 0; l < a.nl; ++l) {
-        const int nk = a.width[l], nj = a.width[l + 1];
-        const int jpw = units_per_wave(nj);
-        const int j0 = wave * jpw;
-        float acc[16];
-        const bool active = j0 < nj;    // nj is a multiple of jpw or smaller than 16 (jpw == 1)
-        if (active) {
-            const float *bias = a.W + a.b_off[l];
-#pragma unroll
-            for (int jj = 0; jj < 16; ++jj) acc[jj] = (jj < jpw && j0 + jj < nj) ? bias[j0 + jj] : 0.0f;
-            if (j0 + jpw <= nj) {
-                dense_dispatch(jpw, a.W + a.w_off[l], nk, nj, j0, act, lane, acc);
-            } else {
-                // ragged last group: one unit at a time
-                for (int jj = 0; j0 + jj < nj; ++jj) {
-                    float s = acc[jj];
-                    dense<1>(a.W + a.w_off[l], nk, nj, j0 + jj, act, lane, &s);
-                    acc[jj] = s;
-                }
-            }
-        }
+        const int nj = a.width[l + 1];
+        const bool active = rt * 32 < nj;
+        f16v acc;
+        if (active) acc = tile_contract(a.Wp + a.wp_off[l], a.kp[l], rt, ct, c, hf, act4);
         __syncthreads();
         if (active) {
-            if (l < a.nl - 1) {
+            const float *bias = a.theta + a.b_off[l];
 #pragma unroll
-                for (int jj = 0; jj < 16; ++jj) {
-                    if (jj < jpw && j0 + jj < nj) {
-                        const float hv = tanhf(acc[jj]);
-                        act[(j0 + jj) * PL + lane] = hv;
-                        if (live) a.h[l + 1][(size_t)(j0 + jj) * a.B + b] = hv;
-                    }
-                }
-            } else {
+            for (int g = 0; g < 4; ++g) {
+                const int jb = rt * 32 + 8 * g + 4 * hf;
+                float out[4];
 #pragma unroll
-                for (int jj = 0; jj < 16; ++jj) {
-                    if (jj < jpw && j0 + jj < nj && live) {
-                        float out = acc[jj], act_v = acc[jj];
+                for (int e = 0; e < 4; ++e) {
+                    const int j = jb + e;
+                    float z = 0.0f;
+                    if (j < nj) z = acc[4 * g + e] + bias[j];
+                    if (l < a.nl - 1) {
+                        const float hv = j < nj ? tanhf(z) : 0.0f;
+                        out[e] = hv;
+                        if (live && j < nj) a.h[l + 1][(size_t)j * a.B + b] = hv;
+                    } else if (live && j < nj) {
+                        float act_v = z, act_out = z;
                         if (a.act_bound > 0.0f) {
-                            act_v = tanhf(acc[jj]);
-                            out = a.act_bound * act_v;
+                            act_v = tanhf(z);
+                            act_out = a.act_bound * act_v;
                         }
-                        a.a_slot[(size_t)(j0 + jj) * a.B + b] = act_v;
-                        a.xbuf[(size_t)(a.ds + j0 + jj) * a.B + b] = (double)out;
+                        a.a_slot[(size_t)j * a.B + b] = act_v;
+                        a.xbuf[(size_t)(a.ds + j) * a.B + b] = (double)act_out;
                     }
                 }
+                if (l < a.nl - 1) act4[(jb >> 2) * PL + ct * 32 + c] = make_float4(out[0], out[1], out[2], out[3]);
             }
         }
         __syncthreads();
@@ -130,140 +137,150 @@ __global__ __launch_bounds__(PW * PL) void policy_forward_kernel(policy_args a)
 
 __global__ __launch_bounds__(PW * PL) void policy_backward_kernel(policy_args a)
 {
-    __shared__ float act[BAGEL_MAX_HIDDEN * PL];
-    const int lane = threadIdx.x & (PL - 1);
+    __shared__ float4 act4[(BAGEL_MAX_HIDDEN / 4) * PL];
+    const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int b_raw = blockIdx.x * PL + lane;
-    const bool live = b_raw < a.B;
-    const int b = live ? b_raw : a.B - 1;
-
+    const int rt = wave >> 1, ct = wave & 1;
+    const int c = lane & 31, hf = lane >> 5;
+    const int b0 = blockIdx.x * PL;
+    const int b = b0 + ct * 32 + c;
+    const bool live = b < a.B;
     const int last = a.nl - 1;
-    for (int k = wave; k < a.width[a.nl]; k += PW) act[k * PL + lane] = a.d[last][(size_t)k * a.B + b];
+
+    stage_input(a.d[last], a.width[a.nl], a.kp[last], a.B, b0, act4);
     __syncthreads();
 
     for (int l = last; l >= 0; --l) {
-        const int nk = a.width[l + 1], nj = a.width[l];   // contraction over outputs o, result per input i
-        const int jpw = units_per_wave(nj);
-        const int j0 = wave * jpw;
-        float acc[16];
-        const bool active = j0 < nj;
-        if (active) {
-#pragma unroll
-            for (int jj = 0; jj < 16; ++jj) acc[jj] = 0.0f;
-            if (j0 + jpw <= nj) {
-                dense_dispatch(jpw, a.W + a.w_off[l], nk, nj, j0, act, lane, acc);
-            } else {
-                for (int jj = 0; j0 + jj < nj; ++jj) {
-                    float s = 0.0f;
-                    dense<1>(a.W + a.w_off[l], nk, nj, j0 + jj, act, lane, &s);
-                    acc[jj] = s;
-                }
-            }
-        }
+        const int ni = a.width[l];       // result rows: inputs of layer l; contraction over its outputs
+        const bool active = rt * 32 < ni;
+        f16v acc;
+        if (active) acc = tile_contract(a.Wp + a.wp_off[l], a.kp[l], rt, ct, c, hf, act4);
         __syncthreads();
         if (active) {
 #pragma unroll
-            for (int jj = 0; jj < 16; ++jj) {
-                if (jj < jpw && j0 + jj < nj) {
-                    const int j = j0 + jj;
-                    if (l > 0) {
-                        const float hv = a.h[l][(size_t)j * a.B + b];
-                        const float dv = acc[jj] * (1.0f - hv * hv);
-                        act[j * PL + lane] = dv;
-                        if (live) a.d[l - 1][(size_t)j * a.B + b] = dv;
-                    } else if (live) {
-                        a.dh0[(size_t)j * a.B + b] = acc[jj];
+            for (int g = 0; g < 4; ++g) {
+                const int ib = rt * 32 + 8 * g + 4 * hf;
+                float out[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int i = ib + e;
+                    float dv = 0.0f;
+                    if (i < ni) {
+                        dv = acc[4 * g + e];
+                        if (l > 0) {
+                            const float hv = a.h[l][(size_t)i * a.B + (live ? b : a.B - 1)];
+                            dv *= (1.0f - hv * hv);
+                            if (live) a.d[l - 1][(size_t)i * a.B + b] = dv;
+                        } else if (live) {
+                            a.dh0[(size_t)i * a.B + b] = dv;
+                        }
                     }
+                    out[e] = dv;
                 }
+                if (l > 0) act4[(ib >> 2) * PL + ct * 32 + c] = make_float4(out[0], out[1], out[2], out[3]);
             }
         }
         __syncthreads();
     }
 }
 
-__global__ void transpose_theta_kernel(const float *__restrict__ theta, float *__restrict__ thetaT, int no,
-                                       int ni, int w_off, int b_off)
+// theta -> zero-padded forward [rp][kp] (rows = outputs) and backward [rp][kp] (rows = inputs) matrices
+__global__ void pack_theta_kernel(const float *__restrict__ theta, float *__restrict__ Wf, float *__restrict__ Wb,
+                                  int no, int ni, int w_off, int f_off, int f_rp, int f_kp, int b_off, int b_rp,
+                                  int b_kp)
 {
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx < no * ni) {
-        const int o = idx / ni, i = idx - o * ni;
-        thetaT[w_off + i * no + o] = theta[w_off + idx];
+    if (idx < f_rp * f_kp) {
+        const int j = idx / f_kp, k = idx - j * f_kp;
+        Wf[f_off + idx] = (j < no && k < ni) ? theta[w_off + j * ni + k] : 0.0f;
     }
-    if (idx < no) thetaT[b_off + idx] = theta[b_off + idx];
+    if (idx < b_rp * b_kp) {
+        const int i = idx / b_kp, o = idx - i * b_kp;
+        Wb[b_off + idx] = (i < ni && o < no) ? theta[w_off + o * ni + i] : 0.0f;
+    }
 }
 
 // ---- weight gradient GEMM ------------------------------------------------------------------
-// C[o][i] = sum_k Dl[o][k] * Hl[i][k], k = (slot, b); column i == ni is the bias (Hl == 1).
-// 64x64 tile per workgroup, 4x4 per thread, contraction in chunks of 32 staged through LDS.
-constexpr int GT = 64, GK = 32;
-
-__global__ __launch_bounds__(256) void weight_grad_kernel(const float *__restrict__ Dl, const float *__restrict__ Hl,
-                                                          float *__restrict__ gsplit, int no, int ni, int B,
-                                                          int n_slots, int chunks_per_slot, int chunks_per_split,
-                                                          int w_off, int b_off, int P)
+// C[o][i] = sum_kk Dl[o][kk] * Hl[i][kk], kk = (slot, b); db[o] = sum_kk Dl[o][kk].
+// Wave (wr, wc) of the 4x4 wave grid owns rows [64 wr, +64) x columns [64 wc, +64) as 2x2 MFMA tiles.
+__device__ __forceinline__ float4 load4_guard(const float *__restrict__ row, int bb, int B, bool row_ok, bool fast)
 {
-    __shared__ float As[GK][GT + 4];
-    __shared__ float Bs[GK][GT + 4];
-    const int tid = threadIdx.x;
-    const int tx = tid & 15, ty = tid >> 4;
-    const int o0 = blockIdx.y * GT, i0 = blockIdx.x * GT;
-    const int total_chunks = n_slots * chunks_per_slot;
-    const int c_begin = blockIdx.z * chunks_per_split;
-    const int c_end = min(total_chunks, c_begin + chunks_per_split);
-    float acc[4][4];
+    if (!row_ok) return make_float4(0.f, 0.f, 0.f, 0.f);
+    if (fast && bb + 3 < B) return *reinterpret_cast<const float4 *>(row + bb);
+    float t[4];
 #pragma unroll
-    for (int r = 0; r < 4; ++r)
-#pragma unroll
-        for (int s = 0; s < 4; ++s) acc[r][s] = 0.0f;
+    for (int e = 0; e < 4; ++e) t[e] = (bb + e < B) ? row[bb + e] : 0.0f;
+    return make_float4(t[0], t[1], t[2], t[3]);
+}
 
-    const int lr = tid >> 3;          // 0..31: row within the tile (and +32)
-    const int lk = (tid & 7) * 4;     // k offset of this thread's 4 consecutive elements
+__global__ __launch_bounds__(1024) void weight_grad_kernel(const float *__restrict__ Dl, const float *__restrict__ Hl,
+                                                           float *__restrict__ gsplit, int no, int ni, int B,
+                                                           int n_slots, int chunks_per_slot, int chunks_per_split,
+                                                           int w_off, int b_off, int P)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wr = wave >> 2, wc = wave & 3;
+    const int cl = lane & 31, hf = lane >> 5;
+    const int o_base = blockIdx.y * 256 + wr * 64, i_base = blockIdx.z * 256 + wc * 64;
+    if (o_base >= no || i_base >= ni) return;   // whole wave has nothing to do (no barriers in this kernel)
+    const bool fa_on[2] = {true, o_base + 32 < no};
+    const bool fb_on[2] = {true, i_base + 32 < ni};
+    const bool fast = (B & 3) == 0;
+    const int total_chunks = n_slots * chunks_per_slot;
+    const int c_begin = blockIdx.x * chunks_per_split;
+    const int c_end = min(total_chunks, c_begin + chunks_per_split);
+
+    f16v acc[2][2];
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+#pragma unroll
+        for (int y = 0; y < 2; ++y)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.0f;
+    float bsum[2] = {0.0f, 0.0f};
+    const int orow[2] = {o_base + cl, o_base + 32 + cl};
+    const int irow[2] = {i_base + cl, i_base + 32 + cl};
 
     for (int c = c_begin; c < c_end; ++c) {
         const int slot = c / chunks_per_slot;
-        const int kb = (c - slot * chunks_per_slot) * GK;
+        const int bb = (c - slot * chunks_per_slot) * 8 + 4 * hf;
+        float4 a4[2], b4[2];
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            const int r = lr + half * 32;
-            const int o = o0 + r, i = i0 + r;
+        for (int f = 0; f < 2; ++f) {
+            a4[f] = load4_guard(Dl + ((size_t)slot * no + min(orow[f], no - 1)) * B, bb, B, orow[f] < no, fast);
+            b4[f] = load4_guard(Hl + ((size_t)slot * ni + min(irow[f], ni - 1)) * B, bb, B, irow[f] < ni, fast);
+            bsum[f] += (a4[f].x + a4[f].y) + (a4[f].z + a4[f].w);
+        }
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int bb = kb + lk + e;
-                float av = 0.0f, bv = 0.0f;
-                if (bb < B) {
-                    if (o < no) av = Dl[((size_t)slot * no + o) * B + bb];
-                    if (i < ni) bv = Hl[((size_t)slot * ni + i) * B + bb];
-                    else if (i == ni) bv = 1.0f;
-                }
-                As[lk + e][r] = av;
-                Bs[lk + e][r] = bv;
+        for (int x = 0; x < 2; ++x) {
+            if (!fa_on[x]) continue;
+#pragma unroll
+            for (int y = 0; y < 2; ++y) {
+                if (!fb_on[y]) continue;
+                acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[x].x, b4[y].x, acc[x][y], 0, 0, 0);
+                acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[x].y, b4[y].y, acc[x][y], 0, 0, 0);
+                acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[x].z, b4[y].z, acc[x][y], 0, 0, 0);
+                acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[x].w, b4[y].w, acc[x][y], 0, 0, 0);
             }
         }
-        __syncthreads();
-#pragma unroll
-        for (int k = 0; k < GK; ++k) {
-            float av[4], bv[4];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) av[r] = As[k][ty * 4 + r];
-#pragma unroll
-            for (int s = 0; s < 4; ++s) bv[s] = Bs[k][tx * 4 + s];
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-#pragma unroll
-                for (int s = 0; s < 4; ++s) acc[r][s] = fmaf(av[r], bv[s], acc[r][s]);
-        }
-        __syncthreads();
     }
-    float *g = gsplit + (size_t)blockIdx.z * P;
+    float *g = gsplit + (size_t)blockIdx.x * P;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int o = o0 + ty * 4 + r;
-        if (o >= no) continue;
+    for (int x = 0; x < 2; ++x)
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const int i = i0 + tx * 4 + s;
-            if (i < ni) g[w_off + (size_t)o * ni + i] = acc[r][s];
-            else if (i == ni) g[b_off + o] = acc[r][s];
+        for (int y = 0; y < 2; ++y)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int o = o_base + x * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
+                const int i = i_base + y * 32 + cl;
+                if (o < no && i < ni) g[w_off + (size_t)o * ni + i] = acc[x][y][r];
+            }
+    if (blockIdx.z == 0 && wc == 0) {
+#pragma unroll
+        for (int f = 0; f < 2; ++f) {
+            const float tot = bsum[f] + __shfl_xor(bsum[f], 32);
+            if (hf == 0 && orow[f] < no) g[b_off + orow[f]] = tot;
         }
     }
 }
@@ -280,12 +297,17 @@ __global__ void grad_reduce_kernel(const float *__restrict__ gsplit, double *__r
     if (grad_theta) grad_theta[p] = (float)s;
 }
 
-policy_args make_pargs(const bagel_ctx *c, int slot)
+policy_args make_pargs(const bagel_ctx *c, int slot, bool backward)
 {
     policy_args a;
     a.B = c->dm.B; a.nl = c->n_layers; a.ds = c->dm.d_s;
     for (int i = 0; i < 4; ++i) a.width[i] = c->width[i];
-    for (int i = 0; i < 3; ++i) { a.w_off[i] = c->w_off[i]; a.b_off[i] = c->b_off[i]; }
+    for (int i = 0; i < 3; ++i) {
+        a.b_off[i] = c->b_off[i];
+        a.wp_off[i] = backward ? c->wpb_off[i] : c->wpf_off[i];
+        a.kp[i] = backward ? c->wpb_kp[i] : c->wpf_kp[i];
+        a.rp[i] = backward ? c->wpb_rp[i] : c->wpf_rp[i];
+    }
     a.act_bound = c->dm.act_bound;
     const size_t B = c->dm.B;
     for (int l = 0; l < 3; ++l) {
@@ -295,34 +317,38 @@ policy_args make_pargs(const bagel_ctx *c, int slot)
     a.a_slot = c->tape_a + (size_t)slot * c->dm.d_a * B;
     a.dh0 = c->dh0;
     a.xbuf = c->xbuf;
-    a.W = nullptr;
+    a.theta = nullptr;
+    a.Wp = backward ? c->wpad_b : c->wpad_f;
     return a;
 }
 
 }  // namespace
 
-hipError_t bagel_launch_transpose_theta(bagel_ctx *c, const float *theta)
+hipError_t bagel_launch_pack_theta(bagel_ctx *c, const float *theta)
 {
     for (int l = 0; l < c->n_layers; ++l) {
         const int no = c->width[l + 1], ni = c->width[l];
-        hipLaunchKernelGGL(transpose_theta_kernel, dim3((no * ni + 255) / 256), dim3(256), 0, c->stream, theta,
-                           c->thetaT, no, ni, c->w_off[l], c->b_off[l]);
+        const int nf = c->wpf_rp[l] * c->wpf_kp[l], nb = c->wpb_rp[l] * c->wpb_kp[l];
+        const int n = nf > nb ? nf : nb;
+        hipLaunchKernelGGL(pack_theta_kernel, dim3((n + 255) / 256), dim3(256), 0, c->stream, theta, c->wpad_f,
+                           c->wpad_b, no, ni, c->w_off[l], c->wpf_off[l], c->wpf_rp[l], c->wpf_kp[l], c->wpb_off[l],
+                           c->wpb_rp[l], c->wpb_kp[l]);
     }
     return hipGetLastError();
 }
 
-hipError_t bagel_launch_policy_forward(bagel_ctx *c, int slot)
+hipError_t bagel_launch_policy_forward(bagel_ctx *c, int slot, const float *theta)
 {
-    policy_args a = make_pargs(c, slot);
-    a.W = c->thetaT;
+    policy_args a = make_pargs(c, slot, false);
+    a.theta = theta;
     hipLaunchKernelGGL(policy_forward_kernel, dim3((c->dm.B + PL - 1) / PL), dim3(PW * PL), 0, c->stream, a);
     return hipGetLastError();
 }
 
 hipError_t bagel_launch_policy_backward(bagel_ctx *c, int slot, const float *theta)
 {
-    policy_args a = make_pargs(c, slot);
-    a.W = theta;
+    policy_args a = make_pargs(c, slot, true);
+    a.theta = theta;
     hipLaunchKernelGGL(policy_backward_kernel, dim3((c->dm.B + PL - 1) / PL), dim3(PW * PL), 0, c->stream, a);
     return hipGetLastError();
 }
@@ -330,16 +356,16 @@ hipError_t bagel_launch_policy_backward(bagel_ctx *c, int slot, const float *the
 hipError_t bagel_launch_weight_grad(bagel_ctx *c, int n_slots, bool accumulate, float *grad_theta)
 {
     const int B = c->dm.B;
-    const int chunks_per_slot = (B + GK - 1) / GK;
+    const int chunks_per_slot = (B + 7) / 8;
     const int total = n_slots * chunks_per_slot;
     const int ksplit = total < c->ksplit ? total : c->ksplit;
     const int per = (total + ksplit - 1) / ksplit;
     const int nz = (total + per - 1) / per;
     for (int l = 0; l < c->n_layers; ++l) {
         const int no = c->width[l + 1], ni = c->width[l];
-        dim3 grid((ni + 1 + GT - 1) / GT, (no + GT - 1) / GT, nz);
-        hipLaunchKernelGGL(weight_grad_kernel, grid, dim3(256), 0, c->stream, c->tape_d[l], c->tape_h[l], c->gsplit, no,
-                           ni, B, n_slots, chunks_per_slot, per, c->w_off[l], c->b_off[l], c->P);
+        dim3 grid(nz, (no + 255) / 256, (ni + 255) / 256);
+        hipLaunchKernelGGL(weight_grad_kernel, grid, dim3(1024), 0, c->stream, c->tape_d[l], c->tape_h[l], c->gsplit,
+                           no, ni, B, n_slots, chunks_per_slot, per, c->w_off[l], c->b_off[l], c->P);
     }
     hipLaunchKernelGGL(grad_reduce_kernel, dim3((c->P + 255) / 256), dim3(256), 0, c->stream, c->gsplit, c->gacc, c->P,
                        nz, accumulate, grad_theta);
