@@ -21,57 +21,32 @@
 //   log2 k_mn(x) = q_m(x) + c_mn + sum_d x_d * Xs_mnd,
 //   Xs_mnd = log2(e)/l_md^2 * X_nd,  c_mn = log2(alpha_m^2) - 1/2 sum_d Xs_mnd X_nd,
 //   q_m(x) = -1/2 sum_d log2(e)/l_md^2 x_d^2.
-// exp2 is a degree-10 polynomial on [-1/2, 1/2] after splitting off the integer part.
+// exp2 splits off the integer part and squares a degree-7 polynomial for 2^(f/2) on [-1/2, 1/2].
 // Jacobian: d k_mn / d x_d = ln2 * k_mn * (Xs_mnd - log2(e)/l_md^2 x_d); the kernel
 // accumulates G_d = sum_n v_n k_n Xs_mnd and u = sum_n v_n k_n, the reduction finishes it.
 //
-// The random-feature phase is accumulated in float64 in quarter revolutions, reduced
-// exactly to [-1/2, 1/2] and only then rounded to float32 for a polynomial sin/cos.
+// The random-feature phase is accumulated in float64 in revolutions, reduced exactly to
+// [0, 1) and only then rounded to float32 for the hardware sin / cos (which take revolutions).
 #include "bagel_internal.h"
 
 namespace {
 
+// 2^t for t <= log2(alpha^2): split off the integer part, evaluate 2^(f/2) for |f| <= 1/2 with a
+// degree-7 polynomial and square it (relative error 4e-13), scale with ldexp.  Very negative t
+// underflows to zero in ldexp.
 __device__ __forceinline__ double exp2_poly(double t)
 {
-    // t <= log2(alpha^2); clamp the far tail so the integer part stays representable
-    t = fmax(t, -1040.0);
     const double n = rint(t);
     const double f = t - n;                       // exact, |f| <= 1/2
-    double p = 6.767963482574983e-09;
-    p = fma(p, f, 1.0206977921453389e-07);
-    p = fma(p, f, 1.3217210256367588e-06);
-    p = fma(p, f, 1.525266622014565e-05);
-    p = fma(p, f, 0.00015403526882354606);
-    p = fma(p, f, 0.0013333558214738293);
-    p = fma(p, f, 0.00961812911053657);
-    p = fma(p, f, 0.055504108664544756);
-    p = fma(p, f, 0.24022650695901254);
-    p = fma(p, f, 0.6931471805599483);
-    p = fma(p, f, 1.0);
-    return ldexp(p, (int)n);
-}
-
-// sin and cos of (pi/2) * (j + y), j integer, |y| <= 1/2
-__device__ __forceinline__ void sincos_quarter(float y, int j, float &sn, float &cs)
-{
-    const float u = y * y;
-    float s = -0.004602149212814766f;
-    s = fmaf(s, u, 0.07968021764776267f);
-    s = fmaf(s, u, -0.6459634776648127f);
-    s = fmaf(s, u, 1.5707963219532366f);
-    s *= y;
-    float c = 0.0009036280586426939f;
-    c = fmaf(c, u, -0.02086006949632079f);
-    c = fmaf(c, u, 0.25366920365446266f);
-    c = fmaf(c, u, -1.2337005406331254f);
-    c = fmaf(c, u, 1.0f);
-    // rotate by j quarter turns
-    const bool swap = (j & 1) != 0;
-    float a = swap ? c : s;       // |sin|
-    float b = swap ? s : c;       // |cos|
-    // sin((pi/2)(j+y)): j=0: s, 1: c, 2: -s, 3: -c ; cos: j=0: c, 1: -s, 2: -c, 3: s
-    sn = (j & 2) ? -a : a;
-    cs = ((j + 1) & 2) ? -b : b;
+    double p = 1.192611307487823e-07;
+    p = fma(p, f, 2.409383341728244e-06);
+    p = fma(p, f, 4.1667353769980764e-05);
+    p = fma(p, f, 0.0006011326659205452);
+    p = fma(p, f, 0.006938013583872582);
+    p = fma(p, f, 0.060056626759929704);
+    p = fma(p, f, 0.3465735902799663);
+    p = fma(p, f, 0.9999999999998426);
+    return ldexp(p * p, (int)n);
 }
 
 template <int D, bool JAC>
@@ -149,12 +124,11 @@ __global__ __launch_bounds__(BAGEL_BLOCK) void gp_step_kernel(
                 double z = r[D];
 #pragma unroll
                 for (int d = 0; d < D; ++d) z = fma(x[d], r[d], z);
-                const double zi = rint(z);
-                const float y = (float)(z - zi);
-                // the quadrant only matters modulo 4; reduce in float64 before converting
-                const int jq = (int)(zi - 4.0 * floor(zi * 0.25));
-                float sn, cs;
-                sincos_quarter(y, jq, sn, cs);
+                // z is the phase in revolutions; its fractional part is exact in float64 and the
+                // hardware sin / cos take revolutions (absolute error about one float32 ulp)
+                const float y = (float)__builtin_amdgcn_fract(z);
+                const float sn = __builtin_amdgcn_sinf(y);
+                const float cs = __builtin_amdgcn_cosf(y);
                 p = fmaf(wj[j], cs, p);
                 if (JAC) {
                     const double ws = (double)(wj[j] * sn);

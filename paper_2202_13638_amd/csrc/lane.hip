@@ -9,7 +9,7 @@
 namespace {
 
 constexpr double LN2 = 0.69314718055994530942;
-constexpr double HALF_PI = 1.57079632679489661923;
+constexpr double TWO_PI = 6.28318530717958647693;
 
 struct lane_args {
     int B, D, M, ds, da, dg, H;
@@ -28,7 +28,7 @@ struct lane_args {
 // One thread per (trajectory, output m, component): component 0 is the value
 //   f[m] = amp_m * sum_c p_c + sum_c u_c,
 // component 1+d the Jacobian entry
-//   J[m][d] = -amp_m (pi/2) sum_c Gr_c[d] + ln2 (sum_c Gk_c[d] - log2(e)/l_md^2 x_d sum_c u_c).
+//   J[m][d] = -amp_m (2 pi) sum_c Gr_c[d] + ln2 (sum_c Gk_c[d] - log2(e)/l_md^2 x_d sum_c u_c).
 // f goes to fbuf[m][b] (float64); J[m][d] to jdst[(m*D+d)*js_i + b*js_b] (float32), which is either a
 // tape slot ([M][D][B]) or a caller array ([B][M][D]).
 __global__ __launch_bounds__(BAGEL_BLOCK) void finalize_kernel(lane_args a, int ncomp, double *__restrict__ fbuf,
@@ -53,7 +53,7 @@ __global__ __launch_bounds__(BAGEL_BLOCK) void finalize_kernel(lane_args a, int 
         for (int c = 0; c < a.nck; ++c) gk += pk[c * stride + (size_t)comp * a.B];
         for (int c = 0; c < a.ncl; ++c) gr += pr[c * stride + (size_t)comp * a.B];
         const double x = a.xbuf[(size_t)d * a.B + b];
-        const double J = -amp * HALF_PI * gr + LN2 * (gk - a.A[m * a.D + d] * x * u);
+        const double J = -amp * TWO_PI * gr + LN2 * (gk - a.A[m * a.D + d] * x * u);
         jdst[(long)(m * a.D + d) * js_i + (long)b * js_b] = (float)J;
     }
 }

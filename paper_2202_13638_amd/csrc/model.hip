@@ -1,6 +1,6 @@
 // Re-layout of the model and of the per-sample streams into the form the step kernel reads.
 //   Xs[m][n][0..D-1] = log2(e)/l_md^2 * X_nd,   Xs[m][n][D] = log2(alpha_m^2) - 1/2 sum_d Xs_mnd X_nd
-//   Os[m][l][0..D-1] = (2/pi) omega_mld,        Os[m][l][D] = (2/pi) phase_ml     (quarter revolutions)
+//   Os[m][l][0..D-1] = omega_mld / (2 pi),      Os[m][l][D] = phase_ml / (2 pi)   (revolutions)
 //   v4[m][n/4][s] = v[s][m][4(n/4) .. +3],      w4[m][l/4][s] likewise
 // Rows past N (or L) are padding: they evaluate to a kernel value of zero (or a feature of one)
 // and carry a zero weight, so they add nothing.  Everything is computed in float64 from the
@@ -10,7 +10,7 @@
 namespace {
 
 constexpr double LOG2E = 1.4426950408889634074;
-constexpr double TWO_OVER_PI = 0.63661977236758134308;
+constexpr double INV_TWO_PI = 0.15915494309189533577;
 
 __global__ void build_model_kernel(const float *__restrict__ X, const float *__restrict__ ell,
                                    const float *__restrict__ sf2, const float *__restrict__ omega,
@@ -40,8 +40,8 @@ __global__ void build_model_kernel(const float *__restrict__ X, const float *__r
     if (i < Lp) {
         double *row = Os + ((size_t)m * Lp + i) * (D + 1);
         if (i < L) {
-            for (int d = 0; d < D; ++d) row[d] = TWO_OVER_PI * (double)omega[((size_t)m * L + i) * D + d];
-            row[D] = TWO_OVER_PI * (double)phase[(size_t)m * L + i];
+            for (int d = 0; d < D; ++d) row[d] = INV_TWO_PI * (double)omega[((size_t)m * L + i) * D + d];
+            row[D] = INV_TWO_PI * (double)phase[(size_t)m * L + i];
         } else {
             for (int d = 0; d <= D; ++d) row[d] = 0.0;
         }
