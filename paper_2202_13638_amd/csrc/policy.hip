@@ -3,10 +3,11 @@
 // All three are dense float32 contractions and run on the matrix cores
 // (v_mfma_f32_32x32x2_f32: D[32x32] += A[32x2] B[2x32]).
 //
-// Forward / backward of one step.  A workgroup holds 64 trajectories and 16 waves; wave (rt, ct)
-// owns the 32x32 output tile of units [32 rt, 32 rt + 32) x trajectories [32 ct, 32 ct + 32).
-//   A operand = weights, zero-padded to [rows % 32 == 0][K % 8 == 0] once per call, so a lane
-//               reads four consecutive K values of its row with one 16-byte load;
+// Forward / backward of one step.  A workgroup holds 32 trajectories and 8 waves; a wave owns the
+// 32x32 output tile of units [32 rt, 32 rt + 32) x the 32 trajectories (and, when a layer has fewer
+// than 8 row tiles, one slice of the contraction; slices are added through LDS in a fixed order).
+//   A operand = weights, zero-padded to [rows % 32 == 0][K % 8 == 0] and re-ordered once per call
+//               so that a wave reads the operands of four MFMAs as 1 KB of contiguous memory;
 //   B operand = the layer's input activations, kept in LDS as [K/4][trajectory][4] so a lane
 //               reads the matching four K values of its trajectory with one 16-byte load.
 // Lanes 0-31 feed K = k0..k0+3 and lanes 32-63 feed K = k0+4..k0+7 over four MFMAs; the order in
@@ -26,18 +27,18 @@ namespace {
 
 typedef float f16v __attribute__((ext_vector_type(16)));
 
-constexpr int PW = 16;   // waves per workgroup
-constexpr int PL = 64;   // trajectories per workgroup
+constexpr int PW = 8;    // waves per workgroup
+constexpr int PL = 32;   // trajectories per workgroup
 
 struct policy_args {
     int B, nl, ds;
     int width[4];
     int b_off[3];         // bias offsets inside theta
-    int wp_off[3];        // offsets of the padded weight matrices
+    int wp_off[3];        // offsets of the packed weight matrices
     int kp[3], rp[3];     // padded contraction length and row count per layer
     float act_bound;
     const float *theta;
-    const float *Wp;      // padded weights: forward [out][in], backward [in][out]
+    const float *Wp;      // packed weights: forward rows = outputs, backward rows = inputs
     float *h[3];          // tape slots of the layer inputs
     float *d[3];          // tape slots of the pre-activation adjoints
     float *a_slot;        // [d_a][B]
@@ -45,24 +46,74 @@ struct policy_args {
     double *xbuf;         // [D][B]
 };
 
-// acc += W[32 rt .. +32][0..kp) * act[0..kp)[32 ct .. +32]
-__device__ __forceinline__ f16v tile_contract(const float *__restrict__ W, int kp, int rt, int ct, int c, int hf,
+// How the 8 waves share a layer with `rows` output rows and padded contraction length kp: wave =
+// ks * nrt + rt owns row tile rt and the ks-th slice of the contraction.  Layers with fewer than 8
+// row tiles split the contraction instead of idling waves.
+struct wave_plan {
+    int nrt, ksplit, rt, ks, k_begin, k_end;
+    bool active;
+};
+
+__device__ __forceinline__ wave_plan plan_layer(int rows, int kp, int wave)
+{
+    wave_plan p;
+    p.nrt = (rows + 31) >> 5;
+    p.ksplit = PW / p.nrt;
+    if (p.ksplit < 1) p.ksplit = 1;
+    const int k8 = kp >> 3;                       // contraction length in groups of 8
+    if (p.ksplit > k8) p.ksplit = k8;
+    p.rt = wave % p.nrt;
+    p.ks = wave / p.nrt;
+    p.active = p.ks < p.ksplit;
+    const int per = (k8 + p.ksplit - 1) / p.ksplit;
+    p.k_begin = p.ks * per;
+    p.k_end = p.k_begin + per < k8 ? p.k_begin + per : k8;
+    return p;
+}
+
+// acc = W[32 rt .. +32][8 k_begin .. 8 k_end) * act[same K][32 trajectories].
+// Packed weights: element W[32 rt + c][8 k8 + 4 hf + e] sits at ((rt * kp/8 + k8) * 64 + c + 32 hf) * 4 + e,
+// so a wave reads 1 KB contiguous per 8 values of K.
+__device__ __forceinline__ f16v tile_contract(const float *__restrict__ W, int kp, const wave_plan &p, int lane,
                                               const float4 *__restrict__ act4)
 {
     f16v acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
-    const float *wrow = W + (size_t)(rt * 32 + c) * kp + 4 * hf;
-    const float4 *bcol = act4 + hf * PL + ct * 32 + c;
-    for (int k0 = 0; k0 < kp; k0 += 8) {
-        const float4 av = *reinterpret_cast<const float4 *>(wrow + k0);
-        const float4 bv = bcol[(k0 >> 2) * PL];
+    const int c = lane & 31, hf = lane >> 5;
+    const float4 *wfrag = reinterpret_cast<const float4 *>(W) + (size_t)p.rt * (kp >> 3) * 64 + lane;
+    const float4 *bcol = act4 + hf * PL + c;
+    for (int k8 = p.k_begin; k8 < p.k_end; ++k8) {
+        const float4 av = wfrag[(size_t)k8 * 64];
+        const float4 bv = bcol[(k8 * 2) * PL];
         acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av.x, bv.x, acc, 0, 0, 0);
         acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av.y, bv.y, acc, 0, 0, 0);
         acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av.z, bv.z, acc, 0, 0, 0);
         acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av.w, bv.w, acc, 0, 0, 0);
     }
     return acc;
+}
+
+// Add the partial tiles of the other contraction slices (through LDS, fixed order).  Contains the
+// barrier that also separates the reads of the layer input from the writes of the next one.
+__device__ __forceinline__ void combine_slices(f16v &acc, const wave_plan &p, int wave, int lane, float4 *red4)
+{
+    if (p.ksplit > 1 && p.active && p.ks > 0) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+            red4[(wave * 4 + g) * 64 + lane] = make_float4(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]);
+    }
+    __syncthreads();
+    if (p.ksplit > 1 && p.active && p.ks == 0) {
+        for (int s = 1; s < p.ksplit; ++s) {
+            const int w = s * p.nrt + p.rt;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const float4 t = red4[(w * 4 + g) * 64 + lane];
+                acc[4 * g] += t.x; acc[4 * g + 1] += t.y; acc[4 * g + 2] += t.z; acc[4 * g + 3] += t.w;
+            }
+        }
+    }
 }
 
 // rows of a [n][B] array -> LDS [k/4][trajectory][4], zero-filled up to kp rows
@@ -72,7 +123,7 @@ __device__ __forceinline__ void stage_input(const float *__restrict__ src, int n
     const int bl = threadIdx.x & (PL - 1);
     int b = b0 + bl;
     if (b >= B) b = B - 1;
-    for (int kg = threadIdx.x >> 6; kg < (kp >> 2); kg += PW) {
+    for (int kg = threadIdx.x / PL; kg < (kp >> 2); kg += PW * 64 / PL) {
         float t[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -83,15 +134,15 @@ __device__ __forceinline__ void stage_input(const float *__restrict__ src, int n
     }
 }
 
-__global__ __launch_bounds__(PW * PL) void policy_forward_kernel(policy_args a)
+__global__ __launch_bounds__(PW * 64) void policy_forward_kernel(policy_args a)
 {
-    __shared__ float4 act4[(BAGEL_MAX_HIDDEN / 4) * PL];
+    __shared__ float4 act4[(BAGEL_MAX_HIDDEN / 4) * PL];   // layer input  [K/4][trajectory]
+    __shared__ float4 red4[PW * 4 * 64];                   // partial tiles of split contractions
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int rt = wave >> 1, ct = wave & 1;
     const int c = lane & 31, hf = lane >> 5;
     const int b0 = blockIdx.x * PL;
-    const int b = b0 + ct * 32 + c;
+    const int b = b0 + c;
     const bool live = b < a.B;
 
     stage_input(a.h[0], a.width[0], a.kp[0], a.B, b0, act4);
@@ -99,21 +150,22 @@ __global__ __launch_bounds__(PW * PL) void policy_forward_kernel(policy_args a)
 
     for (int l = 0; l < a.nl; ++l) {
         const int nj = a.width[l + 1];
-        const bool active = rt * 32 < nj;
+        const wave_plan p = plan_layer(nj, a.kp[l], wave);
         f16v acc;
-        if (active) acc = tile_contract(a.Wp + a.wp_off[l], a.kp[l], rt, ct, c, hf, act4);
-        __syncthreads();
-        if (active) {
+        if (p.active) acc = tile_contract(a.Wp + a.wp_off[l], a.kp[l], p, lane, act4);
+        combine_slices(acc, p, wave, lane, red4);
+        if (p.active && p.ks == 0) {
             const float *bias = a.theta + a.b_off[l];
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const int jb = rt * 32 + 8 * g + 4 * hf;
+                const int jb = p.rt * 32 + 8 * g + 4 * hf;
                 float out[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int j = jb + e;
                     float z = 0.0f;
                     if (j < nj) z = acc[4 * g + e] + bias[j];
+                    out[e] = 0.0f;
                     if (l < a.nl - 1) {
                         const float hv = j < nj ? tanhf(z) : 0.0f;
                         out[e] = hv;
@@ -128,22 +180,22 @@ __global__ __launch_bounds__(PW * PL) void policy_forward_kernel(policy_args a)
                         a.xbuf[(size_t)(a.ds + j) * a.B + b] = (double)act_out;
                     }
                 }
-                if (l < a.nl - 1) act4[(jb >> 2) * PL + ct * 32 + c] = make_float4(out[0], out[1], out[2], out[3]);
+                if (l < a.nl - 1) act4[(jb >> 2) * PL + c] = make_float4(out[0], out[1], out[2], out[3]);
             }
         }
         __syncthreads();
     }
 }
 
-__global__ __launch_bounds__(PW * PL) void policy_backward_kernel(policy_args a)
+__global__ __launch_bounds__(PW * 64) void policy_backward_kernel(policy_args a)
 {
     __shared__ float4 act4[(BAGEL_MAX_HIDDEN / 4) * PL];
+    __shared__ float4 red4[PW * 4 * 64];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int rt = wave >> 1, ct = wave & 1;
     const int c = lane & 31, hf = lane >> 5;
     const int b0 = blockIdx.x * PL;
-    const int b = b0 + ct * 32 + c;
+    const int b = b0 + c;
     const bool live = b < a.B;
     const int last = a.nl - 1;
 
@@ -152,14 +204,14 @@ __global__ __launch_bounds__(PW * PL) void policy_backward_kernel(policy_args a)
 
     for (int l = last; l >= 0; --l) {
         const int ni = a.width[l];       // result rows: inputs of layer l; contraction over its outputs
-        const bool active = rt * 32 < ni;
+        const wave_plan p = plan_layer(ni, a.kp[l], wave);
         f16v acc;
-        if (active) acc = tile_contract(a.Wp + a.wp_off[l], a.kp[l], rt, ct, c, hf, act4);
-        __syncthreads();
-        if (active) {
+        if (p.active) acc = tile_contract(a.Wp + a.wp_off[l], a.kp[l], p, lane, act4);
+        combine_slices(acc, p, wave, lane, red4);
+        if (p.active && p.ks == 0) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const int ib = rt * 32 + 8 * g + 4 * hf;
+                const int ib = p.rt * 32 + 8 * g + 4 * hf;
                 float out[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -177,25 +229,36 @@ __global__ __launch_bounds__(PW * PL) void policy_backward_kernel(policy_args a)
                     }
                     out[e] = dv;
                 }
-                if (l > 0) act4[(ib >> 2) * PL + ct * 32 + c] = make_float4(out[0], out[1], out[2], out[3]);
+                if (l > 0) act4[(ib >> 2) * PL + c] = make_float4(out[0], out[1], out[2], out[3]);
             }
         }
         __syncthreads();
     }
 }
 
-// theta -> zero-padded forward [rp][kp] (rows = outputs) and backward [rp][kp] (rows = inputs) matrices
+// theta -> packed, zero-padded forward (rows = outputs, K = inputs) and backward (rows = inputs,
+// K = outputs) matrices in the fragment order tile_contract reads
+__device__ __forceinline__ void unpack_index(int idx, int kp, int &row, int &k)
+{
+    const int e = idx & 3, lane = (idx >> 2) & 63, blk = idx >> 8;     // blk = rt * (kp/8) + k8
+    const int k8 = blk % (kp >> 3), rt = blk / (kp >> 3);
+    row = rt * 32 + (lane & 31);
+    k = k8 * 8 + 4 * (lane >> 5) + e;
+}
+
 __global__ void pack_theta_kernel(const float *__restrict__ theta, float *__restrict__ Wf, float *__restrict__ Wb,
                                   int no, int ni, int w_off, int f_off, int f_rp, int f_kp, int b_off, int b_rp,
                                   int b_kp)
 {
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
     if (idx < f_rp * f_kp) {
-        const int j = idx / f_kp, k = idx - j * f_kp;
+        int j, k;
+        unpack_index(idx, f_kp, j, k);
         Wf[f_off + idx] = (j < no && k < ni) ? theta[w_off + j * ni + k] : 0.0f;
     }
     if (idx < b_rp * b_kp) {
-        const int i = idx / b_kp, o = idx - i * b_kp;
+        int i, o;
+        unpack_index(idx, b_kp, i, o);
         Wb[b_off + idx] = (i < ni && o < no) ? theta[w_off + o * ni + i] : 0.0f;
     }
 }
@@ -341,7 +404,7 @@ hipError_t bagel_launch_policy_forward(bagel_ctx *c, int slot, const float *thet
 {
     policy_args a = make_pargs(c, slot, false);
     a.theta = theta;
-    hipLaunchKernelGGL(policy_forward_kernel, dim3((c->dm.B + PL - 1) / PL), dim3(PW * PL), 0, c->stream, a);
+    hipLaunchKernelGGL(policy_forward_kernel, dim3((c->dm.B + PL - 1) / PL), dim3(PW * 64), 0, c->stream, a);
     return hipGetLastError();
 }
 
@@ -349,7 +412,7 @@ hipError_t bagel_launch_policy_backward(bagel_ctx *c, int slot, const float *the
 {
     policy_args a = make_pargs(c, slot, true);
     a.theta = theta;
-    hipLaunchKernelGGL(policy_backward_kernel, dim3((c->dm.B + PL - 1) / PL), dim3(PW * PL), 0, c->stream, a);
+    hipLaunchKernelGGL(policy_backward_kernel, dim3((c->dm.B + PL - 1) / PL), dim3(PW * 64), 0, c->stream, a);
     return hipGetLastError();
 }
 
