@@ -40,13 +40,13 @@ def algorithmic_flops_per_traj_step(cfg, jac=True):
 
 
 def cpu_baseline(cfg, inp, seconds_target=15.0):
-    """Time the oracle's loss+gradient on a bounded sample: min(B, 4*cores) trajectories, full N, L,
+    """Time the oracle's loss+gradient on a bounded sample: min(B, 16*cores) trajectories, full N, L,
     policy; horizon chosen so the run takes about `seconds_target`.  v is a random stand-in of the
     right scale (the oracle's own prepare at N=8192 would take minutes and its values do not change
     the work)."""
     import oracle
     cores = oracle.num_threads()
-    Bc = min(cfg.B, 4 * cores)
+    Bc = min(cfg.B, 16 * cores)
     idx = np.arange(Bc) * (cfg.B // Bc)
     rng = np.random.default_rng(7)
     v = (100.0 * rng.standard_normal((Bc, cfg.M, cfg.N))).astype(np.float32)
@@ -63,7 +63,7 @@ def cpu_baseline(cfg, inp, seconds_target=15.0):
         return time.perf_counter() - t0
 
     t_probe = run(2)
-    H = int(max(2, min(cfg.H, 50, round(2 * seconds_target / max(t_probe, 1e-3)))))
+    H = int(max(2, min(cfg.H, round(2 * seconds_target / max(t_probe, 1e-3)))))
     t = run(H)
     return {"value": Bc * H / t, "unit": "trajectory-steps/s", "cores": cores, "kind": "oracle",
             "sample": f"{Bc} trajectories x {H} steps at full N={cfg.N}, L={cfg.L}, policy {cfg.hidden}; "

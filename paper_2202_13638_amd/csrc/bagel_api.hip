@@ -232,6 +232,8 @@ extern "C" int bagel_prepare_samples(bagel_ctx *c, const float *X, const float *
     return BAGEL_OK;
 }
 
+static hipError_t gp_step_timed(bagel_ctx *c, bool jac);
+
 extern "C" int bagel_sample_eval(bagel_ctx *c, const float *x, float *f, float *jac)
 {
     if (!c) return BAGEL_EINVAL;
@@ -239,7 +241,7 @@ extern "C" int bagel_sample_eval(bagel_ctx *c, const float *x, float *f, float *
     if (!x || !f) BAGEL_FAIL(c, BAGEL_EINVAL, "bagel_sample_eval: null argument");
     if (!c->prepared) BAGEL_FAIL(c, BAGEL_ENOTPREPARED, "bagel_sample_eval: no samples installed");
     BAGEL_HIP(c, bagel_launch_eval_io(c, 0, x, nullptr));
-    BAGEL_HIP(c, bagel_launch_gp_step(c, jac != nullptr));
+    BAGEL_HIP(c, gp_step_timed(c, jac != nullptr));
     BAGEL_HIP(c, bagel_launch_finalize(c, jac != nullptr, -1, jac));
     BAGEL_HIP(c, bagel_launch_eval_io(c, 1, nullptr, f));
     return BAGEL_OK;
