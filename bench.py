@@ -30,6 +30,9 @@ sys.path.insert(0, ROOT)
 from paper_2202_13638_amd import synth  # noqa: E402
 
 PEAK_FP64_VECTOR_TFLOPS = 78.6   # MI355X vector float64 (= unpacked float32) peak
+# HBM bytes per launch of gp_step_kernel<8,true> on the stress workload from rocprofv3 --pmc
+# (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, factors from a plain 1 GiB copy): profiles/gp_step_stress_pmc.md
+STRESS_GP_STEP_TRAFFIC_BYTES = 2.508e9 + 8.49e7
 
 
 def algorithmic_flops_per_traj_step(cfg, jac=True):
@@ -79,6 +82,11 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-every", type=int, default=8, help="time every n-th sample-evaluation launch")
     ap.add_argument("--ckpt", type=int, default=None, help="override ckpt_interval")
+    ap.add_argument("--horizon", type=int, default=None,
+                    help="profiling runs only: shorter horizon (per-launch figures do not depend on it)")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="profiling runs only: also run one plain 1 GiB device copy, whose FETCH_SIZE / WRITE_SIZE "
+                         "readings calibrate the counters")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -89,6 +97,8 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
     cfg = synth.CONFIGS[args.workload]
+    if args.horizon is not None:
+        cfg = synth.scaled(cfg, H=args.horizon)
     t0 = time.perf_counter()
     inp = synth.make_inputs(cfg)
     t_gen = time.perf_counter() - t0
@@ -108,6 +118,12 @@ def main():
 
     loss = torch.zeros(1, device="cuda")
     grad = torch.zeros(ctx.P, device="cuda")
+    if args.pmc_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     def step():
         ctx.bagel_rollout_loss_grad(g["theta"], g["s0"], g["goals"], loss, grad)
@@ -151,7 +167,8 @@ def main():
                    "workspace_GB": round(ctx.workspace_bytes() / 1e9, 2)},
         "roofline": {"bound": "alu", "kernel": "gp_step_kernel<D,jac>", "achieved": achieved,
                      "peak": PEAK_FP64_VECTOR_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP64_VECTOR_TFLOPS,
-                     "traffic": None, "avg_launch_ms": avg_ms, "timed_launches": k_n,
+                     "traffic": STRESS_GP_STEP_TRAFFIC_BYTES if (cfg.name == "stress" and args.horizon is None) else None,
+                     "avg_launch_ms": avg_ms, "timed_launches": k_n,
                      "flops_per_launch": flops_launch,
                      "share_of_step": (avg_ms * cfg.H * (2 if ckpt else 1)) / (1e3 * elapsed / args.steps)},
     }
