@@ -37,17 +37,83 @@ def test_medium_full_config():
     harness.assert_parity(ref, harness.gpu_rollout(cfg, inp, ref["v32"]), label="medium/grad")
 
 
-@pytest.mark.timeout(900)
-def test_large_policy_subset_with_checkpointing():
-    """Full N, L, H, policy and ckpt_interval=50; a 64-trajectory batch (S = B)."""
-    cfg = _cfg("large_policy", B=64)
+def _full_size_case(name, n_sampled):
+    """The configuration at its full sizes, in the launch configuration bench.py times.  The oracle
+    cannot afford the whole batch, so `n_sampled` strided trajectories are checked:
+      (a) as a batch of their own (S = B = n_sampled, full N, L, H, policy): everything incl. grad_theta;
+      (b) inside the full batch: their states, per-trajectory losses and d loss / d s0 (a per-trajectory
+          quantity that exercises the whole backward sweep) must match the oracle, and the other
+          trajectories run on v from the library's own prepare."""
+    import torch
+    from paper_2202_13638_amd import binding
+    cfg = _cfg(name)
     inp = synth.make_inputs(cfg)
-    ref = harness.oracle_reference(cfg, inp)
-    got = harness.gpu_rollout(cfg, inp, ref["v32"])
-    harness.assert_parity(ref, got, label="large_policy/B64/ckpt50")
-    plain = harness.gpu_rollout(cfg, inp, ref["v32"], ckpt_interval=0)
+    idx = np.arange(n_sampled) * (cfg.B // n_sampled) + 3
+    sub_cfg, sub_inp = synth.subset_trajectories(cfg, inp, idx)
+    ref = harness.oracle_reference(sub_cfg, sub_inp)                      # oracle prepare + rollout on the sample
+    got = harness.gpu_rollout(sub_cfg, sub_inp, ref["v32"])
+    harness.assert_parity(ref, got, label=f"{name}/sampled-batch")
+
+    ctx = binding.Bagel(binding.dims_from_config(cfg))
+    g = harness.to_gpu(inp)
+    v_all = torch.empty((cfg.B, cfg.M, cfg.N), dtype=torch.float32, device="cuda")
+    ctx.bagel_prepare_samples(g["X"], g["y"], g["lengthscale"], g["signal_var"], g["noise_var"], g["omega"],
+                              g["phase"], g["w"], g["eps"], v_all)
+    torch.cuda.synchronize()
+    v_lib = v_all[torch.from_numpy(idx).cuda()].cpu().numpy().astype(np.float64)
+    err = np.abs(v_lib - ref["v64"]).max() / np.abs(ref["v64"]).max()
+    print(f"[prepare {name} full size] max|dv|/max|v| on the sampled rows = {err:.3e}", flush=True)
+    assert err <= 5e-7
+    v_all[torch.from_numpy(idx).cuda()] = torch.from_numpy(ref["v32"]).cuda()
+    ctx.bagel_set_samples(g["X"], g["lengthscale"], g["signal_var"], g["omega"], g["phase"], g["w"], v_all)
+    del v_all
+    B, H, ds = cfg.B, cfg.H, cfg.d_s
+    loss = torch.zeros(1, device="cuda")
+    lpt = torch.zeros(B, device="cuda")
+    states = torch.zeros((H + 1, B, ds), device="cuda")
+    gth = torch.zeros(ctx.P, device="cuda")
+    gs0 = torch.zeros((B, ds), device="cuda")
+    ctx.bagel_rollout_loss_grad(g["theta"], g["s0"], g["goals"], loss, gth, lpt, states, gs0)
+    torch.cuda.synchronize()
+    st = states[:, torch.from_numpy(idx).cuda()].cpu().numpy().astype(np.float64)
+    d_state = np.abs(st - ref["states"]).max() / np.abs(ref["states"]).max()
+    lp = lpt.cpu().numpy().astype(np.float64)
+    d_lpt = np.abs(lp[idx] - ref["loss_per_traj"]).max() / np.abs(ref["loss_per_traj"]).max()
+    gs = gs0.cpu().numpy().astype(np.float64)[idx] * (B / n_sampled)      # 1/B normalisation of the loss
+    d_gs0 = np.abs(gs - ref["grad_s0"]).max() / np.abs(ref["grad_s0"]).max()
+    print(f"[parity {name}/full-size sampled] state={d_state:.3e} loss_per_traj={d_lpt:.3e} grad_s0={d_gs0:.3e}",
+          flush=True)
+    assert d_state <= harness.TOL_STATE and d_lpt <= 10 * harness.TOL_LOSS and d_gs0 <= harness.TOL_GRAD
+    # properties that hold at any size
+    assert abs(float(loss.item()) - lp.mean()) <= 1e-5 * abs(lp.mean())
+    assert bool(torch.isfinite(gth).all()) and bool(torch.isfinite(states).all())
+    # the same trajectories give (up to the summation order of a different work split) the same
+    # numbers whether they run alone or inside the full batch
+    np.testing.assert_allclose(st, got["states"], rtol=0, atol=2e-5 * np.abs(got["states"]).max())
+    ctx.close()
+    return got
+
+
+@pytest.mark.timeout(900)
+def test_large_policy_full_size_with_checkpointing():
+    """N=4096, L=2048, B=4096, H=500, policy 5-256-256-1, ckpt_interval=50."""
+    cfg = _cfg("large_policy")
+    got = _full_size_case("large_policy", 64)
+    # the same sampled batch without checkpointing: identical states, same gradient
+    idx = np.arange(64) * (cfg.B // 64) + 3
+    sub_cfg, sub_inp = synth.subset_trajectories(cfg, synth.make_inputs(cfg), idx)
+    ref = harness.oracle_reference(sub_cfg, sub_inp, grad=False)
+    plain = harness.gpu_rollout(sub_cfg, sub_inp, ref["v32"], ckpt_interval=0)
     np.testing.assert_array_equal(plain["states"], got["states"])
-    np.testing.assert_allclose(plain["grad_theta"], got["grad_theta"], rtol=1e-5, atol=1e-6 * np.abs(got["grad_theta"]).max())
+    np.testing.assert_allclose(plain["grad_theta"], got["grad_theta"], rtol=1e-5,
+                               atol=1e-6 * np.abs(got["grad_theta"]).max())
+
+
+@pytest.mark.timeout(1500)
+def test_stress_full_size():
+    """N=8192, D=8, M=6, L=4096, B=S=8192, H=1000, policy 8-256-256-2 with bounded actions: the
+    workload bench.py times."""
+    _full_size_case("stress", 32)
 
 
 # ------------------------------------------------------------------ one evaluation of the samples
