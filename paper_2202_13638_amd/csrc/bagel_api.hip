@@ -111,7 +111,9 @@ extern "C" int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_s
     const int target = env_int("BAGEL_TARGET_WGS", 4096);
     int chunk = 1024;
     while (chunk > 32 && items / chunk < target) chunk /= 2;
-    c->CK = env_int("BAGEL_CK", chunk);
+    // fewer, longer units for the training points when there are plenty of them: the kernel's speed does
+    // not depend on the split, the size of the partial-sum array does
+    c->CK = env_int("BAGEL_CK", (N / chunk >= 16) ? 2 * chunk : chunk);
     c->CL = env_int("BAGEL_CL", chunk);
     c->CK = (c->CK + 3) & ~3;
     c->CL = (c->CL + 3) & ~3;
@@ -133,9 +135,9 @@ extern "C" int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_s
     int wf_total = 0, wb_total = 0;
     for (int l = 0; l < c->n_layers; ++l) {
         const int no = c->width[l + 1], ni = c->width[l];
-        c->wpf_off[l] = wf_total; c->wpf_rp[l] = (no + 31) / 32 * 32; c->wpf_kp[l] = (ni + 7) / 8 * 8;
+        c->wpf_off[l] = wf_total; c->wpf_rp[l] = (no + 31) / 32 * 32; c->wpf_kp[l] = (ni + 31) / 32 * 32;
         wf_total += c->wpf_rp[l] * c->wpf_kp[l];
-        c->wpb_off[l] = wb_total; c->wpb_rp[l] = (ni + 31) / 32 * 32; c->wpb_kp[l] = (no + 7) / 8 * 8;
+        c->wpb_off[l] = wb_total; c->wpb_rp[l] = (ni + 31) / 32 * 32; c->wpb_kp[l] = (no + 31) / 32 * 32;
         wb_total += c->wpb_rp[l] * c->wpb_kp[l];
     }
     const size_t Bz = (size_t)B, T = (size_t)c->T_tape;
@@ -152,8 +154,8 @@ extern "C" int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_s
     ALLOC(c->xbuf, (size_t)D * Bz);
     ALLOC(c->part, (size_t)c->units * (1 + D) * Bz);
     ALLOC(c->lpt, Bz);
-    ALLOC(c->lam, (size_t)dims->d_s * Bz);
-    ALLOC(c->us, (size_t)dims->d_s * Bz);
+    ALLOC(c->lam, (size_t)2 * dims->d_s * Bz);
+    ALLOC(c->us, (size_t)2 * dims->d_s * Bz);
     ALLOC(c->dh0, (size_t)c->d_in * Bz);
     ALLOC(c->fbuf, (size_t)M * Bz);
     ALLOC(c->tape_s, (size_t)(H + 1) * dims->d_s * Bz);

@@ -37,8 +37,8 @@ struct bagel_ctx {
     double *xbuf;                // [D][B]   GP input of the current step; rows 0..d_s-1 are the state (float64)
     double *part;                // [units][1+D][B] partial sums of one step
     double *lpt;                 // [B] running cost per trajectory
-    double *lam;                 // [d_s][B] adjoint of the state
-    double *us;                  // [d_s][B] J_s^T lam of the step being swept
+    double *lam;                 // [2][d_s][B] adjoint of the state, double-buffered over t
+    double *us;                  // [2][d_s][B] J_s^T lam of the step being swept, double-buffered over t
     float *dh0;                  // [d_in][B] adjoint of the policy input
     double *fbuf;                // [M][B] sample values of the current step, summed over work units
 
@@ -52,7 +52,7 @@ struct bagel_ctx {
     double *ckpt_s;              // [n_seg][d_s][B] state at the start of each segment
 
     // ---- parameters and gradient -----------------------------------------------------------
-    float *wpad_f, *wpad_b;      // zero-padded weights: forward [out pad 32][in pad 8], backward [in pad 32][out pad 8]
+    float *wpad_f, *wpad_b;      // zero-padded weights: forward [out pad 32][in pad 32], backward [in pad 32][out pad 32]
     int wpf_off[3], wpf_rp[3], wpf_kp[3];
     int wpb_off[3], wpb_rp[3], wpb_kp[3];
     float *gsplit;               // [ksplit][P] split-contraction partial weight gradients

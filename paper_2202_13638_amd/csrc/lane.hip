@@ -164,59 +164,82 @@ __global__ __launch_bounds__(1024) void finish_loss_kernel(const double *__restr
     if (threadIdx.x == 0) loss[0] = (float)(sh[0] / (double)B);
 }
 
-// Backward sweep, trajectory part.  Called with t = H, H-1, ..., 0:
+// Backward sweep, trajectory part.  Called with t = H, H-1, ..., 0; one thread per (trajectory,
+// input dimension d), every thread re-deriving the small adjoint vector lam_t it needs:
 //   t == H : lam = (1/B) dc/ds(s_H, g_{H-1})
-//   t <  H : lam += J_s(x_t)^T lam_{t+1} (kept in us) + (d a_t/d s_t)^T u_a (dh0 from the policy
-//            backward) + [t >= 1] (1/B) dc/ds(s_t, g_{t-1})
-//   then, for t >= 1, the quantities step t-1 needs: u = J(x_{t-1})^T lam; us = u[:ds];
+//   t <  H : lam = lam_{t+1} + J_s(x_t)^T lam_{t+1} (kept in us) + (d a_t/d s_t)^T u_a (dh0 from the
+//            policy backward) + [t >= 1] (1/B) dc/ds(s_t, g_{t-1})
+//   then, for t >= 1, what step t-1 needs: u_d = sum_m J(x_{t-1})[m][d] lam[m]; us = u[:ds];
 //   delta_out = u[ds:] * d a / d z_out.
+// lam and us are double-buffered over t (read *_in, write *_out) because threads of different d
+// read the old values while the thread with d == 0 publishes the new ones.
 __global__ __launch_bounds__(BAGEL_BLOCK) void adjoint_lane_kernel(lane_args a, int t,
                                                                    const float *__restrict__ goals_prev,
                                                                    const float *__restrict__ dh0,
                                                                    const float *__restrict__ tape_J_slot,
                                                                    const float *__restrict__ tape_a_slot,
+                                                                   const double *__restrict__ lam_in,
+                                                                   double *__restrict__ lam_out,
+                                                                   const double *__restrict__ us_in,
+                                                                   double *__restrict__ us_out,
                                                                    float *__restrict__ dout_slot,
                                                                    float *__restrict__ grad_s0)
 {
     const int b = blockIdx.x * BAGEL_BLOCK + threadIdx.x;
+    const int d = blockIdx.y;
     if (b >= a.B) return;
     double lam[8];
-    if (t == a.H) {
-        for (int i = 0; i < a.ds; ++i) lam[i] = 0.0;
-    } else {
-        for (int i = 0; i < a.ds; ++i)
-            lam[i] = a.lam[(size_t)i * a.B + b] + a.us[(size_t)i * a.B + b] + (double)dh0[(size_t)i * a.B + b];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        lam[i] = 0.0;
+        if (i < a.ds && t < a.H)
+            lam[i] = lam_in[(size_t)i * a.B + b] + us_in[(size_t)i * a.B + b] + (double)dh0[(size_t)i * a.B + b];
     }
     if (t >= 1) {
-        double s[8], dc[8];
-        float g[8];
-        for (int i = 0; i < a.ds; ++i) {
-            s[i] = (double)a.tape_s[((size_t)t * a.ds + i) * a.B + b];
-            dc[i] = 0.0;
-        }
-        for (int j = 0; j < a.dg; ++j) g[j] = goals_prev[(size_t)b * a.dg + j];
-        step_cost(a, s, g, dc);
-        for (int i = 0; i < a.ds; ++i) lam[i] += dc[i] / (double)a.B;
-    }
-    for (int i = 0; i < a.ds; ++i) a.lam[(size_t)i * a.B + b] = lam[i];
-    if (t == 0) {
-        if (grad_s0)
-            for (int i = 0; i < a.ds; ++i) grad_s0[(size_t)b * a.ds + i] = (float)lam[i];
-        return;
-    }
-    for (int d = 0; d < a.D; ++d) {
-        double acc = 0.0;
-        for (int m = 0; m < a.M; ++m) acc += (double)tape_J_slot[((size_t)m * a.D + d) * a.B + b] * lam[m];
-        if (d < a.ds) {
-            a.us[(size_t)d * a.B + b] = acc;
-        } else {
-            const int o = d - a.ds;
-            if (a.act_bound > 0.0f) {
-                const double th = (double)tape_a_slot[(size_t)o * a.B + b];
-                acc *= (double)a.act_bound * (1.0 - th * th);
+        // d cost / d s at s_t against g_{t-1}
+        double r[8], e = 0.0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            r[j] = 0.0;
+            if (j < a.dg) {
+                r[j] = (double)a.tape_s[((size_t)t * a.ds + a.tracked[j]) * a.B + b] - (double)goals_prev[(size_t)b * a.dg + j];
+                e += (double)a.q[j] * r[j] * r[j];
             }
-            dout_slot[(size_t)o * a.B + b] = (float)acc;
         }
+        double factor = 2.0;
+        if (a.cost_kind == 1) {
+            const double sr2 = (double)a.sigma_r * (double)a.sigma_r;
+            factor = exp(-e / (2.0 * sr2)) / sr2;
+        }
+        factor /= (double)a.B;
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (j < a.dg && a.tracked[j] == i) lam[i] += factor * (double)a.q[j] * r[j];
+    }
+    if (d == 0) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (i < a.ds) {
+                lam_out[(size_t)i * a.B + b] = lam[i];
+                if (t == 0 && grad_s0) grad_s0[(size_t)b * a.ds + i] = (float)lam[i];
+            }
+    }
+    if (t == 0) return;
+    double acc = 0.0;
+#pragma unroll
+    for (int m = 0; m < 8; ++m)
+        if (m < a.M) acc += (double)tape_J_slot[((size_t)m * a.D + d) * a.B + b] * lam[m];
+    if (d < a.ds) {
+        us_out[(size_t)d * a.B + b] = acc;
+    } else {
+        const int o = d - a.ds;
+        if (a.act_bound > 0.0f) {
+            const double th = (double)tape_a_slot[(size_t)o * a.B + b];
+            acc *= (double)a.act_bound * (1.0 - th * th);
+        }
+        dout_slot[(size_t)o * a.B + b] = (float)acc;
     }
 }
 
@@ -302,10 +325,17 @@ hipError_t bagel_launch_adjoint_lane(bagel_ctx *c, int t, int prev_slot, const f
     a.tape_s = c->tape_s;
     const size_t B = c->dm.B;
     const int last = c->n_layers - 1;
-    hipLaunchKernelGGL(adjoint_lane_kernel, lane_grid(c), dim3(BAGEL_BLOCK), 0, c->stream, a, t,
+    const size_t half = (size_t)c->dm.d_s * B;      // lam and us hold two buffers each, alternating with t
+    const double *lam_in = c->lam + ((t + 1) & 1) * half;
+    double *lam_out = c->lam + (t & 1) * half;
+    const double *us_in = c->us + ((t + 1) & 1) * half;
+    double *us_out = c->us + (t & 1) * half;
+    dim3 grid((c->dm.B + BAGEL_BLOCK - 1) / BAGEL_BLOCK, t >= 1 ? c->D : 1);
+    hipLaunchKernelGGL(adjoint_lane_kernel, grid, dim3(BAGEL_BLOCK), 0, c->stream, a, t,
                        t >= 1 ? goals + (size_t)(t - 1) * B * c->dm.d_g : nullptr, c->dh0,
                        t >= 1 ? slot_ptr(c->tape_J, prev_slot, c->M * c->D, c->dm.B) : nullptr,
-                       t >= 1 ? slot_ptr(c->tape_a, prev_slot, c->dm.d_a, c->dm.B) : nullptr,
+                       t >= 1 ? slot_ptr(c->tape_a, prev_slot, c->dm.d_a, c->dm.B) : nullptr, lam_in, lam_out,
+                       us_in, us_out,
                        t >= 1 ? slot_ptr(c->tape_d[last], prev_slot, c->dm.d_a, c->dm.B) : nullptr, grad_s0);
     return hipGetLastError();
 }

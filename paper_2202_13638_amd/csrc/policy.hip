@@ -6,7 +6,7 @@
 // Forward / backward of one step.  A workgroup holds 32 trajectories and 8 waves; a wave owns the
 // 32x32 output tile of units [32 rt, 32 rt + 32) x the 32 trajectories (and, when a layer has fewer
 // than 8 row tiles, one slice of the contraction; slices are added through LDS in a fixed order).
-//   A operand = weights, zero-padded to [rows % 32 == 0][K % 8 == 0] and re-ordered once per call
+//   A operand = weights, zero-padded to [rows % 32 == 0][K % 32 == 0] and re-ordered once per call
 //               so that a wave reads the operands of four MFMAs as 1 KB of contiguous memory;
 //   B operand = the layer's input activations, kept in LDS as [K/4][trajectory][4] so a lane
 //               reads the matching four K values of its trajectory with one 16-byte load.
@@ -60,36 +60,52 @@ __device__ __forceinline__ wave_plan plan_layer(int rows, int kp, int wave)
     p.nrt = (rows + 31) >> 5;
     p.ksplit = PW / p.nrt;
     if (p.ksplit < 1) p.ksplit = 1;
-    const int k8 = kp >> 3;                       // contraction length in groups of 8
-    if (p.ksplit > k8) p.ksplit = k8;
+    const int k32 = kp >> 5;                      // contraction length in batches of 32 (kp % 32 == 0)
+    if (p.ksplit > k32) p.ksplit = k32;
     p.rt = wave % p.nrt;
     p.ks = wave / p.nrt;
     p.active = p.ks < p.ksplit;
-    const int per = (k8 + p.ksplit - 1) / p.ksplit;
-    p.k_begin = p.ks * per;
-    p.k_end = p.k_begin + per < k8 ? p.k_begin + per : k8;
+    const int per = (k32 + p.ksplit - 1) / p.ksplit;
+    p.k_begin = 4 * p.ks * per;                   // in groups of 8, always a multiple of 4
+    p.k_end = p.k_begin + 4 * per < 4 * k32 ? p.k_begin + 4 * per : 4 * k32;
     return p;
 }
 
 // acc = W[32 rt .. +32][8 k_begin .. 8 k_end) * act[same K][32 trajectories].
 // Packed weights: element W[32 rt + c][8 k8 + 4 hf + e] sits at ((rt * kp/8 + k8) * 64 + c + 32 hf) * 4 + e,
-// so a wave reads 1 KB contiguous per 8 values of K.
+// so a wave reads 1 KB contiguous per 8 values of K.  The contraction is consumed in batches of 32
+// (16 MFMAs); the weight fragments of the next batch are requested before the MFMAs of the current
+// one issue.  All loads are unconditional (kp is padded to a multiple of 32 with zero weights; the
+// look-ahead past the end re-reads the last batch).
 __device__ __forceinline__ f16v tile_contract(const float *__restrict__ W, int kp, const wave_plan &p, int lane,
                                               const float4 *__restrict__ act4)
 {
     f16v acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+    if (p.k_begin >= p.k_end) return acc;
     const int c = lane & 31, hf = lane >> 5;
     const float4 *wfrag = reinterpret_cast<const float4 *>(W) + (size_t)p.rt * (kp >> 3) * 64 + lane;
     const float4 *bcol = act4 + hf * PL + c;
-    for (int k8 = p.k_begin; k8 < p.k_end; ++k8) {
-        const float4 av = wfrag[(size_t)k8 * 64];
-        const float4 bv = bcol[(k8 * 2) * PL];
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av.x, bv.x, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av.y, bv.y, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av.z, bv.z, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av.w, bv.w, acc, 0, 0, 0);
+    const int k_last = p.k_end - 4;
+    float4 av[4], an[4], bv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) av[u] = wfrag[(size_t)(p.k_begin + u) * 64];
+    for (int k8 = p.k_begin; k8 < p.k_end; k8 += 4) {
+        const int kn = k8 + 4 <= k_last ? k8 + 4 : k_last;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) an[u] = wfrag[(size_t)(kn + u) * 64];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) bv[u] = bcol[((k8 + u) * 2) * PL];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u].x, bv[u].x, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u].y, bv[u].y, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u].z, bv[u].z, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u].w, bv[u].w, acc, 0, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) av[u] = an[u];
     }
     return acc;
 }
@@ -265,31 +281,22 @@ __global__ void pack_theta_kernel(const float *__restrict__ theta, float *__rest
 
 // ---- weight gradient GEMM ------------------------------------------------------------------
 // C[o][i] = sum_kk Dl[o][kk] * Hl[i][kk], kk = (slot, b); db[o] = sum_kk Dl[o][kk].
-// Wave (wr, wc) of the 4x4 wave grid owns rows [64 wr, +64) x columns [64 wc, +64) as 2x2 MFMA tiles.
-__device__ __forceinline__ float4 load4_guard(const float *__restrict__ row, int bb, int B, bool row_ok, bool fast)
-{
-    if (!row_ok) return make_float4(0.f, 0.f, 0.f, 0.f);
-    if (fast && bb + 3 < B) return *reinterpret_cast<const float4 *>(row + bb);
-    float t[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) t[e] = (bb + e < B) ? row[bb + e] : 0.0f;
-    return make_float4(t[0], t[1], t[2], t[3]);
-}
-
+// Wave (wr, wc) of a wrows x wcols wave grid (at most 4x4, sized to the layer so that no wave idles)
+// owns rows [64 wr, +64) x columns [64 wc, +64) as 2x2 MFMA tiles.
+template <bool FAST>
 __global__ __launch_bounds__(1024) void weight_grad_kernel(const float *__restrict__ Dl, const float *__restrict__ Hl,
                                                            float *__restrict__ gsplit, int no, int ni, int B,
                                                            int n_slots, int chunks_per_slot, int chunks_per_split,
-                                                           int w_off, int b_off, int P)
+                                                           int w_off, int b_off, int P, int wcols)
 {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int wr = wave >> 2, wc = wave & 3;
+    const int wr = wave / wcols, wc = wave - wr * wcols;   // the workgroup has wrows x wcols waves
     const int cl = lane & 31, hf = lane >> 5;
     const int o_base = blockIdx.y * 256 + wr * 64, i_base = blockIdx.z * 256 + wc * 64;
     if (o_base >= no || i_base >= ni) return;   // whole wave has nothing to do (no barriers in this kernel)
     const bool fa_on[2] = {true, o_base + 32 < no};
     const bool fb_on[2] = {true, i_base + 32 < ni};
-    const bool fast = (B & 3) == 0;
     const int total_chunks = n_slots * chunks_per_slot;
     const int c_begin = blockIdx.x * chunks_per_split;
     const int c_end = min(total_chunks, c_begin + chunks_per_split);
@@ -304,17 +311,13 @@ __global__ __launch_bounds__(1024) void weight_grad_kernel(const float *__restri
     float bsum[2] = {0.0f, 0.0f};
     const int orow[2] = {o_base + cl, o_base + 32 + cl};
     const int irow[2] = {i_base + cl, i_base + 32 + cl};
+    // rows past the end are clamped: they feed accumulator rows / columns that are never stored
+    const int oc[2] = {min(orow[0], no - 1), min(orow[1], no - 1)};
+    const int ic[2] = {min(irow[0], ni - 1), min(irow[1], ni - 1)};
 
-    for (int c = c_begin; c < c_end; ++c) {
-        const int slot = c / chunks_per_slot;
-        const int bb = (c - slot * chunks_per_slot) * 8 + 4 * hf;
-        float4 a4[2], b4[2];
+    auto mfma_chunk = [&](const float4 *a4, const float4 *b4) {
 #pragma unroll
-        for (int f = 0; f < 2; ++f) {
-            a4[f] = load4_guard(Dl + ((size_t)slot * no + min(orow[f], no - 1)) * B, bb, B, orow[f] < no, fast);
-            b4[f] = load4_guard(Hl + ((size_t)slot * ni + min(irow[f], ni - 1)) * B, bb, B, irow[f] < ni, fast);
-            bsum[f] += (a4[f].x + a4[f].y) + (a4[f].z + a4[f].w);
-        }
+        for (int f = 0; f < 2; ++f) bsum[f] += (a4[f].x + a4[f].y) + (a4[f].z + a4[f].w);
 #pragma unroll
         for (int x = 0; x < 2; ++x) {
             if (!fa_on[x]) continue;
@@ -326,6 +329,49 @@ __global__ __launch_bounds__(1024) void weight_grad_kernel(const float *__restri
                 acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[x].z, b4[y].z, acc[x][y], 0, 0, 0);
                 acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[x].w, b4[y].w, acc[x][y], 0, 0, 0);
             }
+        }
+    };
+
+    if (FAST) {
+        // B % 8 == 0: every chunk is full and 16-byte aligned; loads are unconditional and the operands
+        // of chunk c+1 are requested before the MFMAs of chunk c issue
+        auto load_chunk = [&](int c, float4 *a4, float4 *b4) {
+            const int slot = c / chunks_per_slot;
+            const int bb = (c - slot * chunks_per_slot) * 8 + 4 * hf;
+#pragma unroll
+            for (int f = 0; f < 2; ++f) {
+                a4[f] = *reinterpret_cast<const float4 *>(Dl + ((size_t)slot * no + oc[f]) * B + bb);
+                b4[f] = *reinterpret_cast<const float4 *>(Hl + ((size_t)slot * ni + ic[f]) * B + bb);
+            }
+        };
+        float4 a4[2], b4[2], an[2], bn[2];
+        if (c_begin < c_end) load_chunk(c_begin, a4, b4);
+        for (int c = c_begin; c < c_end; ++c) {
+            load_chunk(c + 1 < c_end ? c + 1 : c, an, bn);
+            mfma_chunk(a4, b4);
+#pragma unroll
+            for (int f = 0; f < 2; ++f) { a4[f] = an[f]; b4[f] = bn[f]; }
+        }
+    } else {
+        for (int c = c_begin; c < c_end; ++c) {
+            const int slot = c / chunks_per_slot;
+            const int bb = (c - slot * chunks_per_slot) * 8 + 4 * hf;
+            float4 a4[2], b4[2];
+#pragma unroll
+            for (int f = 0; f < 2; ++f) {
+                const float *ar = Dl + ((size_t)slot * no + oc[f]) * B;
+                const float *br = Hl + ((size_t)slot * ni + ic[f]) * B;
+                float ta[4], tb[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const bool ok = bb + e < B;
+                    ta[e] = ok ? ar[bb + e] : 0.0f;
+                    tb[e] = ok ? br[bb + e] : 0.0f;
+                }
+                a4[f] = make_float4(ta[0], ta[1], ta[2], ta[3]);
+                b4[f] = make_float4(tb[0], tb[1], tb[2], tb[3]);
+            }
+            mfma_chunk(a4, b4);
         }
     }
     float *g = gsplit + (size_t)blockIdx.x * P;
@@ -427,8 +473,15 @@ hipError_t bagel_launch_weight_grad(bagel_ctx *c, int n_slots, bool accumulate, 
     for (int l = 0; l < c->n_layers; ++l) {
         const int no = c->width[l + 1], ni = c->width[l];
         dim3 grid(nz, (no + 255) / 256, (ni + 255) / 256);
-        hipLaunchKernelGGL(weight_grad_kernel, grid, dim3(1024), 0, c->stream, c->tape_d[l], c->tape_h[l], c->gsplit,
-                           no, ni, B, n_slots, chunks_per_slot, per, c->w_off[l], c->b_off[l], c->P);
+        const int wrows = no >= 256 ? 4 : (no + 63) / 64, wcols = ni >= 256 ? 4 : (ni + 63) / 64;
+        if (B % 8 == 0)
+            hipLaunchKernelGGL(weight_grad_kernel<true>, grid, dim3(64 * wrows * wcols), 0, c->stream, c->tape_d[l],
+                               c->tape_h[l], c->gsplit, no, ni, B, n_slots, chunks_per_slot, per, c->w_off[l],
+                               c->b_off[l], c->P, wcols);
+        else
+            hipLaunchKernelGGL(weight_grad_kernel<false>, grid, dim3(64 * wrows * wcols), 0, c->stream, c->tape_d[l],
+                               c->tape_h[l], c->gsplit, no, ni, B, n_slots, chunks_per_slot, per, c->w_off[l],
+                               c->b_off[l], c->P, wcols);
     }
     hipLaunchKernelGGL(grad_reduce_kernel, dim3((c->P + 255) / 256), dim3(256), 0, c->stream, c->gsplit, c->gacc, c->P,
                        nz, accumulate, grad_theta);
