@@ -31,6 +31,8 @@
 
 namespace {
 
+typedef float v4f __attribute__((ext_vector_type(4)));
+
 // 2^t for t <= log2(alpha^2): split off the integer part, evaluate 2^(f/2) for |f| <= 1/2 with a
 // degree-7 polynomial and square it (relative error 4e-13), scale with ldexp.  Very negative t
 // underflows to zero in ldexp.
@@ -81,7 +83,7 @@ __global__ __launch_bounds__(BAGEL_BLOCK) void gp_step_kernel(
 #pragma unroll
         for (int d = 0; d < D; ++d) G[d] = 0.0;
         for (int n4 = 0; n4 < CK / 4; ++n4) {
-            const float4 vv = vp[(size_t)n4 * S];
+            const v4f vv = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(vp + (size_t)n4 * S));   // read-once stream
             const float vj[4] = {vv.x, vv.y, vv.z, vv.w};
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -116,7 +118,7 @@ __global__ __launch_bounds__(BAGEL_BLOCK) void gp_step_kernel(
 #pragma unroll
         for (int d = 0; d < D; ++d) G[d] = 0.0;
         for (int l4 = 0; l4 < CL / 4; ++l4) {
-            const float4 ww = wp[(size_t)l4 * S];
+            const v4f ww = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(wp + (size_t)l4 * S));
             const float wj[4] = {ww.x, ww.y, ww.z, ww.w};
 #pragma unroll
             for (int j = 0; j < 4; ++j) {

@@ -77,6 +77,35 @@ __device__ __forceinline__ wave_plan plan_layer(int rows, int kp, int wave)
 // (16 MFMAs); the weight fragments of the next batch are requested before the MFMAs of the current
 // one issue.  All loads are unconditional (kp is padded to a multiple of 32 with zero weights; the
 // look-ahead past the end re-reads the last batch).
+// 16-byte read that the optimiser will not move across loop iterations (two relaxed wave-scope
+// atomic loads: an ordinary load instruction, but one the compiler keeps where it is written).
+// Used to keep the look-ahead operand loads of the MFMA loops ahead of the MFMAs; plain loads of
+// read-only memory are sunk back next to their use, which exposes the full memory latency.
+__device__ __forceinline__ float4 load16_pinned(const float4 *p)
+{
+    const unsigned long long *q = reinterpret_cast<const unsigned long long *>(p);
+    const unsigned long long lo = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+    const unsigned long long hi = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+    float4 r;
+    r.x = __uint_as_float((unsigned)lo);
+    r.y = __uint_as_float((unsigned)(lo >> 32));
+    r.z = __uint_as_float((unsigned)hi);
+    r.w = __uint_as_float((unsigned)(hi >> 32));
+    return r;
+}
+
+__device__ __forceinline__ f16v mfma_batch(f16v acc, const float4 *av, const float4 *bv)
+{
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u].x, bv[u].x, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u].y, bv[u].y, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u].z, bv[u].z, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u].w, bv[u].w, acc, 0, 0, 0);
+    }
+    return acc;
+}
+
 __device__ __forceinline__ f16v tile_contract(const float *__restrict__ W, int kp, const wave_plan &p, int lane,
                                               const float4 *__restrict__ act4)
 {
@@ -88,24 +117,23 @@ __device__ __forceinline__ f16v tile_contract(const float *__restrict__ W, int k
     const float4 *wfrag = reinterpret_cast<const float4 *>(W) + (size_t)p.rt * (kp >> 3) * 64 + lane;
     const float4 *bcol = act4 + hf * PL + c;
     const int k_last = p.k_end - 4;
-    float4 av[4], an[4], bv[4];
+    float4 a0[4], a1[4], bv[4];      // two weight batches in turn: one feeding MFMAs, one in flight
 #pragma unroll
-    for (int u = 0; u < 4; ++u) av[u] = wfrag[(size_t)(p.k_begin + u) * 64];
-    for (int k8 = p.k_begin; k8 < p.k_end; k8 += 4) {
-        const int kn = k8 + 4 <= k_last ? k8 + 4 : k_last;
+    for (int u = 0; u < 4; ++u) a0[u] = load16_pinned(wfrag + (size_t)(p.k_begin + u) * 64);
+    for (int k8 = p.k_begin; k8 < p.k_end; k8 += 8) {
+        const int k1 = k8 + 4 <= k_last ? k8 + 4 : k_last;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) an[u] = wfrag[(size_t)(kn + u) * 64];
+        for (int u = 0; u < 4; ++u) a1[u] = load16_pinned(wfrag + (size_t)(k1 + u) * 64);
 #pragma unroll
         for (int u = 0; u < 4; ++u) bv[u] = bcol[((k8 + u) * 2) * PL];
+        acc = mfma_batch(acc, a0, bv);
+        if (k8 + 4 >= p.k_end) break;
+        const int k2 = k8 + 8 <= k_last ? k8 + 8 : k_last;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u].x, bv[u].x, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u].y, bv[u].y, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u].z, bv[u].z, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u].w, bv[u].w, acc, 0, 0, 0);
-        }
+        for (int u = 0; u < 4; ++u) a0[u] = load16_pinned(wfrag + (size_t)(k2 + u) * 64);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) av[u] = an[u];
+        for (int u = 0; u < 4; ++u) bv[u] = bcol[((k8 + 4 + u) * 2) * PL];
+        acc = mfma_batch(acc, a1, bv);
     }
     return acc;
 }
