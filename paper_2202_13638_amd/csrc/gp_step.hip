@@ -36,12 +36,14 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 // 2^t for t <= log2(alpha^2): split off the integer part, evaluate 2^(f/2) for |f| <= 1/2 with a
 // degree-7 polynomial and square it (relative error 4e-13), scale with ldexp.  Very negative t
 // underflows to zero in ldexp.
-__device__ __forceinline__ double exp2_poly(double t)
+// The two highest coefficients come in from the caller, c7 in a scalar and c6 in a vector register:
+// the first Horner step is then a single three-operand FMA (an FMA takes at most one scalar operand;
+// with both as literals the compiler spends an extra register move per evaluation).
+__device__ __forceinline__ double exp2_poly(double t, double c7, double c6)
 {
     const double n = rint(t);
     const double f = t - n;                       // exact, |f| <= 1/2
-    double p = 1.192611307487823e-07;
-    p = fma(p, f, 2.409383341728244e-06);
+    double p = fma(c7, f, c6);
     p = fma(p, f, 4.1667353769980764e-05);
     p = fma(p, f, 0.0006011326659205452);
     p = fma(p, f, 0.006938013583872582);
@@ -82,6 +84,8 @@ __global__ __launch_bounds__(BAGEL_BLOCK) void gp_step_kernel(
         double G[D];
 #pragma unroll
         for (int d = 0; d < D; ++d) G[d] = 0.0;
+        double c7 = 1.192611307487823e-07, c6 = 2.409383341728244e-06;
+        asm volatile("" : "+s"(c7), "+v"(c6));    // pin the register classes (see exp2_poly)
         for (int n4 = 0; n4 < CK / 4; ++n4) {
             const v4f vv = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(vp + (size_t)n4 * S));   // read-once stream
             const float vj[4] = {vv.x, vv.y, vv.z, vv.w};
@@ -91,7 +95,7 @@ __global__ __launch_bounds__(BAGEL_BLOCK) void gp_step_kernel(
                 double t = q + r[D];
 #pragma unroll
                 for (int d = 0; d < D; ++d) t = fma(x[d], r[d], t);
-                const double k = exp2_poly(t);
+                const double k = exp2_poly(t, c7, c6);
                 const double vk = (double)vj[j] * k;
                 u += vk;
                 if (JAC) {
@@ -123,9 +127,11 @@ __global__ __launch_bounds__(BAGEL_BLOCK) void gp_step_kernel(
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const double *__restrict__ r = Or + (size_t)(l4 * 4 + j) * (D + 1);
-                double z = r[D];
+                // product first, phase offset last: both are scalar operands, and an FMA takes only one
+                double z = x[0] * r[0];
 #pragma unroll
-                for (int d = 0; d < D; ++d) z = fma(x[d], r[d], z);
+                for (int d = 1; d < D; ++d) z = fma(x[d], r[d], z);
+                z += r[D];
                 // z is the phase in revolutions; its fractional part is exact in float64 and the
                 // hardware sin / cos take revolutions (absolute error about one float32 ulp)
                 const float y = (float)__builtin_amdgcn_fract(z);
