@@ -73,7 +73,7 @@ static hipError_t dev_alloc(bagel_ctx *c, T **p, size_t count)
 
 static void free_all(bagel_ctx *c)
 {
-    void *ptrs[] = {c->Xs, c->Os, c->A, c->amp, c->v4, c->w4, c->xbuf, c->part, c->lpt, c->lam, c->us, c->dh0,
+    void *ptrs[] = {c->Xs, c->Os, c->A, c->amp, c->v4, c->w4, c->xbuf, c->part, c->lpt, c->lam,
                     c->tape_s, c->tape_J, c->tape_h[0], c->tape_h[1], c->tape_h[2], c->tape_a, c->tape_d[0],
                     c->tape_d[1], c->tape_d[2], c->ckpt_s, c->wpad_f, c->wpad_b, c->gsplit, c->gacc, c->fbuf};
     for (void *p : ptrs)
@@ -154,9 +154,7 @@ extern "C" int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_s
     ALLOC(c->xbuf, (size_t)D * Bz);
     ALLOC(c->part, (size_t)c->units * (1 + D) * Bz);
     ALLOC(c->lpt, Bz);
-    ALLOC(c->lam, (size_t)2 * dims->d_s * Bz);
-    ALLOC(c->us, (size_t)2 * dims->d_s * Bz);
-    ALLOC(c->dh0, (size_t)c->d_in * Bz);
+    ALLOC(c->lam, (size_t)dims->d_s * Bz);
     ALLOC(c->fbuf, (size_t)M * Bz);
     ALLOC(c->tape_s, (size_t)(H + 1) * dims->d_s * Bz);
     ALLOC(c->tape_J, T * M * D * Bz);
@@ -333,16 +331,6 @@ extern "C" int bagel_rollout_loss(bagel_ctx *c, const float *theta, const float 
     return BAGEL_OK;
 }
 
-// backward sweep over steps t1-1 .. t0 whose tape sits in slots 0 .. t1-t0-1
-static int run_backward(bagel_ctx *c, int t0, int t1, const float *theta, const float *goals)
-{
-    for (int t = t1; t > t0; --t) {
-        BAGEL_HIP(c, bagel_launch_adjoint_lane(c, t, t - 1 - t0, goals, nullptr));
-        BAGEL_HIP(c, bagel_launch_policy_backward(c, t - 1 - t0, theta));
-    }
-    return BAGEL_OK;
-}
-
 extern "C" int bagel_rollout_loss_grad(bagel_ctx *c, const float *theta, const float *s0, const float *goals,
                                        float *loss, float *grad_theta, float *loss_per_traj, float *states,
                                        float *grad_s0)
@@ -361,9 +349,7 @@ extern "C" int bagel_rollout_loss_grad(bagel_ctx *c, const float *theta, const f
         rc = run_forward(c, 0, H, 0, true, true, true, false, theta, goals, states);
         if (rc != BAGEL_OK) return rc;
         BAGEL_HIP(c, bagel_launch_finish_loss(c, loss, loss_per_traj));
-        rc = run_backward(c, 0, H, theta, goals);
-        if (rc != BAGEL_OK) return rc;
-        BAGEL_HIP(c, bagel_launch_adjoint_lane(c, 0, 0, goals, grad_s0));
+        BAGEL_HIP(c, bagel_launch_backward_sweep(c, 0, H, goals, grad_s0));
         BAGEL_HIP(c, bagel_launch_weight_grad(c, H, false, grad_theta));
         return BAGEL_OK;
     }
@@ -378,9 +364,7 @@ extern "C" int bagel_rollout_loss_grad(bagel_ctx *c, const float *theta, const f
         BAGEL_HIP(c, bagel_launch_restore(c, seg, t0, goals));
         rc = run_forward(c, t0, t1, t0, true, false, false, false, theta, goals, nullptr);
         if (rc != BAGEL_OK) return rc;
-        rc = run_backward(c, t0, t1, theta, goals);
-        if (rc != BAGEL_OK) return rc;
-        if (seg == 0) BAGEL_HIP(c, bagel_launch_adjoint_lane(c, 0, 0, goals, grad_s0));
+        BAGEL_HIP(c, bagel_launch_backward_sweep(c, t0, t1, goals, grad_s0));
         BAGEL_HIP(c, bagel_launch_weight_grad(c, t1 - t0, seg != n_seg - 1, seg == 0 ? grad_theta : nullptr));
     }
     return BAGEL_OK;

@@ -37,9 +37,7 @@ struct bagel_ctx {
     double *xbuf;                // [D][B]   GP input of the current step; rows 0..d_s-1 are the state (float64)
     double *part;                // [units][1+D][B] partial sums of one step
     double *lpt;                 // [B] running cost per trajectory
-    double *lam;                 // [2][d_s][B] adjoint of the state, double-buffered over t
-    double *us;                  // [2][d_s][B] J_s^T lam of the step being swept, double-buffered over t
-    float *dh0;                  // [d_in][B] adjoint of the policy input
+    double *lam;                 // [d_s][B] adjoint of the state between the segments of a checkpointed sweep
     double *fbuf;                // [M][B] sample values of the current step, summed over work units
 
     // ---- tape (T_tape slots: H, or ckpt_interval when checkpointing) ----------------------
@@ -95,7 +93,6 @@ hipError_t bagel_launch_restore(bagel_ctx *ctx, int seg, int t, const float *goa
 hipError_t bagel_launch_advance(bagel_ctx *ctx, int t, int slot, int next_slot, bool jac, bool add_cost,
                                 bool write_tape_s, int ckpt_index, const float *goals, float *states_out);
 hipError_t bagel_launch_finish_loss(bagel_ctx *ctx, float *loss, float *loss_per_traj);
-hipError_t bagel_launch_adjoint_lane(bagel_ctx *ctx, int t, int prev_slot, const float *goals, float *grad_s0);
 hipError_t bagel_launch_eval_io(bagel_ctx *ctx, int phase, const float *x, float *f);
 // add up the per-unit partial sums: value into fbuf, Jacobian into tape slot `slot` (or jac_out if slot < 0)
 hipError_t bagel_launch_finalize(bagel_ctx *ctx, bool jac, int slot, float *jac_out);
@@ -103,7 +100,8 @@ hipError_t bagel_launch_finalize(bagel_ctx *ctx, bool jac, int slot, float *jac_
 // ---- policy.hip --------------------------------------------------------------------------
 hipError_t bagel_launch_pack_theta(bagel_ctx *ctx, const float *theta);
 hipError_t bagel_launch_policy_forward(bagel_ctx *ctx, int slot, const float *theta);
-hipError_t bagel_launch_policy_backward(bagel_ctx *ctx, int slot, const float *theta);
+// backward sweep over steps t_hi-1 .. t_lo (tape slot of step k is k - t_lo); grad_s0 is written when t_lo == 0
+hipError_t bagel_launch_backward_sweep(bagel_ctx *ctx, int t_lo, int t_hi, const float *goals, float *grad_s0);
 hipError_t bagel_launch_weight_grad(bagel_ctx *ctx, int n_slots, bool accumulate, float *grad_theta);
 
 // ---- prepare.hip -------------------------------------------------------------------------

@@ -1,7 +1,6 @@
 // Lane-per-trajectory kernels around the sample evaluation: reduction of the per-unit partial
 // sums, the state update s_{t+1} = s_t + f(x_t) (state increments as GP targets, Sec. III-A), the
-// running cost (Algorithm 1, return accumulation; eq. (8) or the quadratic cost), and the
-// trajectory part of the backward sweep (adjoint of the state through the transition Jacobian).
+// running cost (Algorithm 1, return accumulation; eq. (8) or the quadratic cost).
 // All per-trajectory arrays are laid out [component][B] so that a wave reads consecutive
 // trajectories.
 #include "bagel_internal.h"
@@ -19,7 +18,7 @@ struct lane_args {
     int tracked[8];
     float q[8];
     const double *A, *amp, *part;
-    double *xbuf, *lpt, *lam, *us;
+    double *xbuf, *lpt;
     float *tape_s;
     double *ckpt_s;
 };
@@ -58,25 +57,17 @@ __global__ __launch_bounds__(BAGEL_BLOCK) void finalize_kernel(lane_args a, int 
     }
 }
 
-// cost at state s against goal g (float goals), optionally d cost / d s accumulated into dc[ds]
-__device__ __forceinline__ double step_cost(const lane_args &a, const double *s, const float *g, double *dc)
+// cost at state s against goal g (float goals): quadratic, or the saturating reward of eq. (8) negated
+__device__ __forceinline__ double step_cost(const lane_args &a, const double *s, const float *g)
 {
     double e = 0.0;
     for (int j = 0; j < a.dg; ++j) {
         const double r = s[a.tracked[j]] - (double)g[j];
         e += (double)a.q[j] * r * r;
     }
-    if (a.cost_kind == 0) {
-        if (dc)
-            for (int j = 0; j < a.dg; ++j) dc[a.tracked[j]] += 2.0 * (double)a.q[j] * (s[a.tracked[j]] - (double)g[j]);
-        return e;
-    }
+    if (a.cost_kind == 0) return e;
     const double sr2 = (double)a.sigma_r * (double)a.sigma_r;
-    const double c = -exp(-e / (2.0 * sr2));
-    if (dc)
-        for (int j = 0; j < a.dg; ++j)
-            dc[a.tracked[j]] += -c * (double)a.q[j] * (s[a.tracked[j]] - (double)g[j]) / sr2;
-    return c;
+    return -exp(-e / (2.0 * sr2));
 }
 
 __global__ __launch_bounds__(BAGEL_BLOCK) void init_state_kernel(lane_args a, const float *__restrict__ s0,
@@ -137,7 +128,7 @@ __global__ __launch_bounds__(BAGEL_BLOCK) void advance_kernel(lane_args a, int t
     if (add_cost) {
         float g[8];
         for (int j = 0; j < a.dg; ++j) g[j] = goals_t[(size_t)b * a.dg + j];
-        a.lpt[b] += step_cost(a, s, g, nullptr);
+        a.lpt[b] += step_cost(a, s, g);
     }
     if (h0_next)
         for (int j = 0; j < a.dg; ++j) h0_next[(size_t)(a.ds + j) * a.B + b] = goals_next[(size_t)b * a.dg + j];
@@ -164,85 +155,6 @@ __global__ __launch_bounds__(1024) void finish_loss_kernel(const double *__restr
     if (threadIdx.x == 0) loss[0] = (float)(sh[0] / (double)B);
 }
 
-// Backward sweep, trajectory part.  Called with t = H, H-1, ..., 0; one thread per (trajectory,
-// input dimension d), every thread re-deriving the small adjoint vector lam_t it needs:
-//   t == H : lam = (1/B) dc/ds(s_H, g_{H-1})
-//   t <  H : lam = lam_{t+1} + J_s(x_t)^T lam_{t+1} (kept in us) + (d a_t/d s_t)^T u_a (dh0 from the
-//            policy backward) + [t >= 1] (1/B) dc/ds(s_t, g_{t-1})
-//   then, for t >= 1, what step t-1 needs: u_d = sum_m J(x_{t-1})[m][d] lam[m]; us = u[:ds];
-//   delta_out = u[ds:] * d a / d z_out.
-// lam and us are double-buffered over t (read *_in, write *_out) because threads of different d
-// read the old values while the thread with d == 0 publishes the new ones.
-__global__ __launch_bounds__(BAGEL_BLOCK) void adjoint_lane_kernel(lane_args a, int t,
-                                                                   const float *__restrict__ goals_prev,
-                                                                   const float *__restrict__ dh0,
-                                                                   const float *__restrict__ tape_J_slot,
-                                                                   const float *__restrict__ tape_a_slot,
-                                                                   const double *__restrict__ lam_in,
-                                                                   double *__restrict__ lam_out,
-                                                                   const double *__restrict__ us_in,
-                                                                   double *__restrict__ us_out,
-                                                                   float *__restrict__ dout_slot,
-                                                                   float *__restrict__ grad_s0)
-{
-    const int b = blockIdx.x * BAGEL_BLOCK + threadIdx.x;
-    const int d = blockIdx.y;
-    if (b >= a.B) return;
-    double lam[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        lam[i] = 0.0;
-        if (i < a.ds && t < a.H)
-            lam[i] = lam_in[(size_t)i * a.B + b] + us_in[(size_t)i * a.B + b] + (double)dh0[(size_t)i * a.B + b];
-    }
-    if (t >= 1) {
-        // d cost / d s at s_t against g_{t-1}
-        double r[8], e = 0.0;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            r[j] = 0.0;
-            if (j < a.dg) {
-                r[j] = (double)a.tape_s[((size_t)t * a.ds + a.tracked[j]) * a.B + b] - (double)goals_prev[(size_t)b * a.dg + j];
-                e += (double)a.q[j] * r[j] * r[j];
-            }
-        }
-        double factor = 2.0;
-        if (a.cost_kind == 1) {
-            const double sr2 = (double)a.sigma_r * (double)a.sigma_r;
-            factor = exp(-e / (2.0 * sr2)) / sr2;
-        }
-        factor /= (double)a.B;
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                if (j < a.dg && a.tracked[j] == i) lam[i] += factor * (double)a.q[j] * r[j];
-    }
-    if (d == 0) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-            if (i < a.ds) {
-                lam_out[(size_t)i * a.B + b] = lam[i];
-                if (t == 0 && grad_s0) grad_s0[(size_t)b * a.ds + i] = (float)lam[i];
-            }
-    }
-    if (t == 0) return;
-    double acc = 0.0;
-#pragma unroll
-    for (int m = 0; m < 8; ++m)
-        if (m < a.M) acc += (double)tape_J_slot[((size_t)m * a.D + d) * a.B + b] * lam[m];
-    if (d < a.ds) {
-        us_out[(size_t)d * a.B + b] = acc;
-    } else {
-        const int o = d - a.ds;
-        if (a.act_bound > 0.0f) {
-            const double th = (double)tape_a_slot[(size_t)o * a.B + b];
-            acc *= (double)a.act_bound * (1.0 - th * th);
-        }
-        dout_slot[(size_t)o * a.B + b] = (float)acc;
-    }
-}
-
 // bagel_sample_eval plumbing: phase 0 loads x[B][D] into xbuf; phase 1 writes f[B][M] from fbuf.
 __global__ __launch_bounds__(BAGEL_BLOCK) void eval_io_kernel(lane_args a, int phase, const float *__restrict__ xin,
                                                               const double *__restrict__ fbuf,
@@ -265,7 +177,7 @@ lane_args make_args(const bagel_ctx *c)
     a.cost_kind = c->dm.cost_kind; a.sigma_r = c->dm.sigma_r; a.act_bound = c->dm.act_bound;
     for (int j = 0; j < 8; ++j) { a.tracked[j] = c->dm.tracked[j]; a.q[j] = c->dm.q[j]; }
     a.A = c->A; a.amp = c->amp; a.part = c->part;
-    a.xbuf = c->xbuf; a.lpt = c->lpt; a.lam = c->lam; a.us = c->us;
+    a.xbuf = c->xbuf; a.lpt = c->lpt;
     a.tape_s = nullptr; a.ckpt_s = nullptr;
     return a;
 }
@@ -316,27 +228,6 @@ hipError_t bagel_launch_advance(bagel_ctx *c, int t, int slot, int next_slot, bo
 hipError_t bagel_launch_finish_loss(bagel_ctx *c, float *loss, float *loss_per_traj)
 {
     hipLaunchKernelGGL(finish_loss_kernel, dim3(1), dim3(1024), 0, c->stream, c->lpt, c->dm.B, loss, loss_per_traj);
-    return hipGetLastError();
-}
-
-hipError_t bagel_launch_adjoint_lane(bagel_ctx *c, int t, int prev_slot, const float *goals, float *grad_s0)
-{
-    lane_args a = make_args(c);
-    a.tape_s = c->tape_s;
-    const size_t B = c->dm.B;
-    const int last = c->n_layers - 1;
-    const size_t half = (size_t)c->dm.d_s * B;      // lam and us hold two buffers each, alternating with t
-    const double *lam_in = c->lam + ((t + 1) & 1) * half;
-    double *lam_out = c->lam + (t & 1) * half;
-    const double *us_in = c->us + ((t + 1) & 1) * half;
-    double *us_out = c->us + (t & 1) * half;
-    dim3 grid((c->dm.B + BAGEL_BLOCK - 1) / BAGEL_BLOCK, t >= 1 ? c->D : 1);
-    hipLaunchKernelGGL(adjoint_lane_kernel, grid, dim3(BAGEL_BLOCK), 0, c->stream, a, t,
-                       t >= 1 ? goals + (size_t)(t - 1) * B * c->dm.d_g : nullptr, c->dh0,
-                       t >= 1 ? slot_ptr(c->tape_J, prev_slot, c->M * c->D, c->dm.B) : nullptr,
-                       t >= 1 ? slot_ptr(c->tape_a, prev_slot, c->dm.d_a, c->dm.B) : nullptr, lam_in, lam_out,
-                       us_in, us_out,
-                       t >= 1 ? slot_ptr(c->tape_d[last], prev_slot, c->dm.d_a, c->dm.B) : nullptr, grad_s0);
     return hipGetLastError();
 }
 

@@ -38,11 +38,9 @@ struct policy_args {
     int kp[3], rp[3];     // padded contraction length and row count per layer
     float act_bound;
     const float *theta;
-    const float *Wp;      // packed weights: forward rows = outputs, backward rows = inputs
+    const float *Wp;      // packed forward weights (rows = outputs)
     float *h[3];          // tape slots of the layer inputs
-    float *d[3];          // tape slots of the pre-activation adjoints
     float *a_slot;        // [d_a][B]
-    float *dh0;           // [d_in][B]
     double *xbuf;         // [D][B]
 };
 
@@ -231,52 +229,187 @@ __global__ __launch_bounds__(PW * 64) void policy_forward_kernel(policy_args a)
     }
 }
 
-__global__ __launch_bounds__(PW * 64) void policy_backward_kernel(policy_args a)
+// ---- backward sweep ------------------------------------------------------------------------
+// Reverse-mode pass of Algorithm 1 over the steps t_hi-1, ..., t_lo of every trajectory in ONE
+// launch.  Trajectories do not interact in the sweep, so a workgroup keeps its 32 trajectories for
+// the whole range and walks the tape backwards on its own; the adjoint of the state (lam) lives in
+// LDS in float64.  For step k = t-1 (tape slot k - t_lo), with lam = lam_t = dL/ds_t:
+//   u      = J_f(x_k)^T lam                         (J_f from the tape, [M][D])
+//   us     = u[:d_s];  delta_out = u[d_s:] * d a / d z_out   -> tape_d[last], input of the policy backward
+//   policy backward through W^T (matrix cores): tape_d[l-1] for the weight-gradient GEMM, and the
+//   adjoint dh0 of the policy input, whose first d_s rows are (d a_k / d s_k)^T u_a
+//   lam_{t-1} = lam + us + dh0[:d_s] + [t-1 >= 1] (1/B) d cost / d s (s_{t-1}, g_{t-2})
+// lam_{t_hi} is the cost gradient at s_H when t_hi == H and is read from `lam` otherwise (the sweep
+// of a checkpointed rollout is split into segments); lam_{t_lo} is written back to `lam`, and to
+// grad_s0 when t_lo == 0.
+struct sweep_args {
+    int B, nl, ds, da, dg, D, M, H;
+    int t_hi, t_lo;
+    int width[4];
+    int wp_off[3], kp[3];
+    float act_bound;
+    int cost_kind;
+    float sigma_r;
+    int tracked[8];
+    float q[8];
+    const float *Wp;          // packed backward weights
+    const float *tape_h[3];   // slot 0 of each tape
+    float *tape_d[3];
+    const float *tape_a, *tape_J, *tape_s;
+    const float *goals;       // [H][B][d_g]
+    double *lam;              // [d_s][B]
+    float *grad_s0;           // [B][d_s] or null
+};
+
+// lam += (1/B) d cost / d s_i at state s_t (t >= 1) against g_{t-1}, for trajectory b
+__device__ __forceinline__ double add_cost_gradient(const sweep_args &a, double lam, int t, int i, int b)
+{
+    double r[8], e = 0.0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        r[j] = 0.0;
+        if (j < a.dg) {
+            r[j] = (double)a.tape_s[((size_t)t * a.ds + a.tracked[j]) * a.B + b] -
+                   (double)a.goals[((size_t)(t - 1) * a.B + b) * a.dg + j];
+            e += (double)a.q[j] * r[j] * r[j];
+        }
+    }
+    double factor = 2.0;
+    if (a.cost_kind == 1) {
+        const double sr2 = (double)a.sigma_r * (double)a.sigma_r;
+        factor = exp(-e / (2.0 * sr2)) / sr2;
+    }
+    factor /= (double)a.B;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+        if (j < a.dg && a.tracked[j] == i) lam += factor * (double)a.q[j] * r[j];
+    return lam;
+}
+
+__global__ __launch_bounds__(PW * 64) void backward_sweep_kernel(sweep_args a)
 {
     __shared__ float4 act4[(BAGEL_MAX_HIDDEN / 4) * PL];
     __shared__ float4 red4[PW * 4 * 64];
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    __shared__ double lamS[8][PL], usS[8][PL];
+    __shared__ float dh0S[16][PL];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 31, hf = lane >> 5;
     const int b0 = blockIdx.x * PL;
     const int b = b0 + c;
     const bool live = b < a.B;
+    const int bc = live ? b : a.B - 1;            // clamped trajectory of the MFMA lanes
     const int last = a.nl - 1;
+    // the lane-per-(row, trajectory) phases see the workgroup as 16 rows x 32 trajectories
+    const int bl = tid & (PL - 1), row = tid >> 5;
+    const bool liveq = b0 + bl < a.B;
+    const int bq = liveq ? b0 + bl : a.B - 1;
 
-    stage_input(a.d[last], a.width[a.nl], a.kp[last], a.B, b0, act4);
+    if (row < a.ds) {
+        double v = 0.0;
+        if (a.t_hi == a.H) v = add_cost_gradient(a, 0.0, a.H, row, bq);
+        else v = a.lam[(size_t)row * a.B + bq];
+        lamS[row][bl] = v;
+    }
     __syncthreads();
 
-    for (int l = last; l >= 0; --l) {
-        const int ni = a.width[l];       // result rows: inputs of layer l; contraction over its outputs
-        const wave_plan p = plan_layer(ni, a.kp[l], wave);
-        f16v acc;
-        if (p.active) acc = tile_contract(a.Wp + a.wp_off[l], a.kp[l], p, lane, act4);
-        combine_slices(acc, p, wave, lane, red4);
-        if (p.active && p.ks == 0) {
+    for (int t = a.t_hi; t > a.t_lo; --t) {
+        const size_t slot = (size_t)(t - 1 - a.t_lo);
+        const float *Jt = a.tape_J + slot * a.M * a.D * a.B;
+        // ---- u = J^T lam: rows 0-7 build the policy-backward input (4 outputs each, zero padded up
+        //      to the 32 rows one MFMA batch consumes), rows 8-15 the state part
+        if (row < 8) {
+            float out[4];
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int ib = p.rt * 32 + 8 * g + 4 * hf;
-                float out[4];
+            for (int e = 0; e < 4; ++e) {
+                const int o = row * 4 + e;
+                out[e] = 0.0f;
+                if (o < a.da) {
+                    double acc = 0.0;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int i = ib + e;
-                    float dv = 0.0f;
-                    if (i < ni) {
-                        dv = acc[4 * g + e];
-                        if (l > 0) {
-                            const float hv = a.h[l][(size_t)i * a.B + (live ? b : a.B - 1)];
-                            dv *= (1.0f - hv * hv);
-                            if (live) a.d[l - 1][(size_t)i * a.B + b] = dv;
-                        } else if (live) {
-                            a.dh0[(size_t)i * a.B + b] = dv;
-                        }
+                    for (int m = 0; m < 8; ++m)
+                        if (m < a.M) acc += (double)Jt[((size_t)m * a.D + a.ds + o) * a.B + bq] * lamS[m][bl];
+                    if (a.act_bound > 0.0f) {
+                        const double th = (double)a.tape_a[(slot * a.da + o) * a.B + bq];
+                        acc *= (double)a.act_bound * (1.0 - th * th);
                     }
-                    out[e] = dv;
+                    out[e] = (float)acc;
+                    if (liveq) a.tape_d[last][(slot * a.da + o) * a.B + bq] = out[e];
                 }
-                if (l > 0) act4[(ib >> 2) * PL + c] = make_float4(out[0], out[1], out[2], out[3]);
             }
+            act4[row * PL + bl] = make_float4(out[0], out[1], out[2], out[3]);
+        } else if (row - 8 < a.ds) {
+            const int i = row - 8;
+            double acc = 0.0;
+#pragma unroll
+            for (int m = 0; m < 8; ++m)
+                if (m < a.M) acc += (double)Jt[((size_t)m * a.D + i) * a.B + bq] * lamS[m][bl];
+            usS[i][bl] = acc;
         }
         __syncthreads();
+
+        // ---- policy backward: delta_{l-1} = (W_l^T delta_l) * (1 - h_l^2)
+        for (int l = last; l >= 0; --l) {
+            const int ni = a.width[l];
+            const wave_plan p = plan_layer(ni, a.kp[l], wave);
+            const bool owner = p.active && p.ks == 0;
+            // tanh outputs of the layer below, requested before the contraction so that they arrive under it
+            float hv[16];
+            if (l > 0 && owner) {
+                const float *hl = a.tape_h[l] + slot * ni * a.B + bc;
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int i = p.rt * 32 + 8 * g + 4 * hf + e;
+                        hv[4 * g + e] = __hip_atomic_load(hl + (size_t)(i < ni ? i : ni - 1) * a.B, __ATOMIC_RELAXED,
+                                                          __HIP_MEMORY_SCOPE_WAVEFRONT);
+                    }
+            }
+            f16v acc;
+            if (p.active) acc = tile_contract(a.Wp + a.wp_off[l], a.kp[l], p, lane, act4);
+            combine_slices(acc, p, wave, lane, red4);
+            if (owner) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int ib = p.rt * 32 + 8 * g + 4 * hf;
+                    float out[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int i = ib + e;
+                        float dv = 0.0f;
+                        if (i < ni) {
+                            dv = acc[4 * g + e];
+                            if (l > 0) {
+                                const float h = hv[4 * g + e];
+                                dv *= (1.0f - h * h);
+                                if (live) a.tape_d[l - 1][(slot * ni + i) * a.B + b] = dv;
+                            } else if (i < 16) {
+                                dh0S[i][c] = dv;
+                            }
+                        }
+                        out[e] = dv;
+                    }
+                    if (l > 0) act4[(ib >> 2) * PL + c] = make_float4(out[0], out[1], out[2], out[3]);
+                }
+            }
+            __syncthreads();
+        }
+
+        // ---- lam_{t-1}
+        if (row < a.ds) {
+            double v = lamS[row][bl] + usS[row][bl] + (double)dh0S[row][bl];
+            if (t - 1 >= 1) v = add_cost_gradient(a, v, t - 1, row, bq);
+            lamS[row][bl] = v;
+        }
+        __syncthreads();
+    }
+
+    if (row < a.ds && liveq) {
+        const double v = lamS[row][bl];
+        a.lam[(size_t)row * a.B + bq] = v;
+        if (a.t_lo == 0 && a.grad_s0) a.grad_s0[(size_t)bq * a.ds + row] = (float)v;
     }
 }
 
@@ -434,28 +567,24 @@ __global__ void grad_reduce_kernel(const float *__restrict__ gsplit, double *__r
     if (grad_theta) grad_theta[p] = (float)s;
 }
 
-policy_args make_pargs(const bagel_ctx *c, int slot, bool backward)
+policy_args make_pargs(const bagel_ctx *c, int slot)
 {
     policy_args a;
     a.B = c->dm.B; a.nl = c->n_layers; a.ds = c->dm.d_s;
     for (int i = 0; i < 4; ++i) a.width[i] = c->width[i];
     for (int i = 0; i < 3; ++i) {
         a.b_off[i] = c->b_off[i];
-        a.wp_off[i] = backward ? c->wpb_off[i] : c->wpf_off[i];
-        a.kp[i] = backward ? c->wpb_kp[i] : c->wpf_kp[i];
-        a.rp[i] = backward ? c->wpb_rp[i] : c->wpf_rp[i];
+        a.wp_off[i] = c->wpf_off[i];
+        a.kp[i] = c->wpf_kp[i];
+        a.rp[i] = c->wpf_rp[i];
     }
     a.act_bound = c->dm.act_bound;
     const size_t B = c->dm.B;
-    for (int l = 0; l < 3; ++l) {
-        a.h[l] = (l < c->n_layers) ? c->tape_h[l] + (size_t)slot * c->width[l] * B : nullptr;
-        a.d[l] = (l < c->n_layers && c->tape_d[l]) ? c->tape_d[l] + (size_t)slot * c->width[l + 1] * B : nullptr;
-    }
+    for (int l = 0; l < 3; ++l) a.h[l] = (l < c->n_layers) ? c->tape_h[l] + (size_t)slot * c->width[l] * B : nullptr;
     a.a_slot = c->tape_a + (size_t)slot * c->dm.d_a * B;
-    a.dh0 = c->dh0;
     a.xbuf = c->xbuf;
     a.theta = nullptr;
-    a.Wp = backward ? c->wpad_b : c->wpad_f;
+    a.Wp = c->wpad_f;
     return a;
 }
 
@@ -476,17 +605,30 @@ hipError_t bagel_launch_pack_theta(bagel_ctx *c, const float *theta)
 
 hipError_t bagel_launch_policy_forward(bagel_ctx *c, int slot, const float *theta)
 {
-    policy_args a = make_pargs(c, slot, false);
+    policy_args a = make_pargs(c, slot);
     a.theta = theta;
     hipLaunchKernelGGL(policy_forward_kernel, dim3((c->dm.B + PL - 1) / PL), dim3(PW * 64), 0, c->stream, a);
     return hipGetLastError();
 }
 
-hipError_t bagel_launch_policy_backward(bagel_ctx *c, int slot, const float *theta)
+hipError_t bagel_launch_backward_sweep(bagel_ctx *c, int t_lo, int t_hi, const float *goals, float *grad_s0)
 {
-    policy_args a = make_pargs(c, slot, true);
-    a.theta = theta;
-    hipLaunchKernelGGL(policy_backward_kernel, dim3((c->dm.B + PL - 1) / PL), dim3(PW * 64), 0, c->stream, a);
+    sweep_args a;
+    a.B = c->dm.B; a.nl = c->n_layers; a.ds = c->dm.d_s; a.da = c->dm.d_a; a.dg = c->dm.d_g; a.D = c->D; a.M = c->M;
+    a.H = c->dm.H; a.t_hi = t_hi; a.t_lo = t_lo;
+    for (int i = 0; i < 4; ++i) a.width[i] = c->width[i];
+    for (int l = 0; l < 3; ++l) {
+        a.wp_off[l] = c->wpb_off[l];
+        a.kp[l] = c->wpb_kp[l];
+        a.tape_h[l] = l < c->n_layers ? c->tape_h[l] : nullptr;
+        a.tape_d[l] = l < c->n_layers ? c->tape_d[l] : nullptr;
+    }
+    a.act_bound = c->dm.act_bound; a.cost_kind = c->dm.cost_kind; a.sigma_r = c->dm.sigma_r;
+    for (int j = 0; j < 8; ++j) { a.tracked[j] = c->dm.tracked[j]; a.q[j] = c->dm.q[j]; }
+    a.Wp = c->wpad_b;
+    a.tape_a = c->tape_a; a.tape_J = c->tape_J; a.tape_s = c->tape_s;
+    a.goals = goals; a.lam = c->lam; a.grad_s0 = grad_s0;
+    hipLaunchKernelGGL(backward_sweep_kernel, dim3((c->dm.B + PL - 1) / PL), dim3(PW * 64), 0, c->stream, a);
     return hipGetLastError();
 }
 
