@@ -122,6 +122,7 @@ extern "C" int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_s
     c->Np = c->nck * c->CK;
     c->Lp = c->ncl * c->CL;
     c->units = M * (c->nck + c->ncl);
+    c->groups = M * ((c->nck + 3) / 4 + (c->ncl + 3) / 4);
     if (c->units > 65535) {
         delete c;
         CREATE_FAIL(BAGEL_EINVAL, "bagel_create: too many work units (%d)", M * (int)((N + 31) / 32 + (L + 31) / 32));
@@ -152,7 +153,7 @@ extern "C" int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_s
     ALLOC(c->v4, (size_t)M * (c->Np / 4) * dims->S);
     ALLOC(c->w4, (size_t)M * (c->Lp / 4) * dims->S);
     ALLOC(c->xbuf, (size_t)D * Bz);
-    ALLOC(c->part, (size_t)c->units * (1 + D) * Bz);
+    ALLOC(c->part, (size_t)c->groups * (1 + D) * Bz);
     ALLOC(c->lpt, Bz);
     ALLOC(c->lam, (size_t)dims->d_s * Bz);
     ALLOC(c->fbuf, (size_t)M * Bz);

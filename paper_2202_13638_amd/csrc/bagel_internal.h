@@ -26,6 +26,7 @@ struct bagel_ctx {
     int CK, CL;                  // training points / features per work unit (multiples of 4)
     int nck, ncl;                // chunks per output
     int units;                   // M * (nck + ncl)
+    int groups;                  // M * (ceil(nck/4) + ceil(ncl/4)): four units per workgroup and partial sum
     double *Xs;                  // [M][Np][D+1]: log2(e)/l_md^2 * X_nd, then log2(alpha_m^2) - 1/2 sum_d log2(e)/l_md^2 X_nd^2
     double *Os;                  // [M][Lp][D+1]: omega_mld / (2 pi) (revolutions per unit x_d), then phase / (2 pi)
     double *A;                   // [M][D]: log2(e) / l_md^2
@@ -35,7 +36,7 @@ struct bagel_ctx {
 
     // ---- per-step workspace (lane = trajectory, arrays are [component][B]) ---------------
     double *xbuf;                // [D][B]   GP input of the current step; rows 0..d_s-1 are the state (float64)
-    double *part;                // [units][1+D][B] partial sums of one step
+    double *part;                // [groups][1+D][B] partial sums of one step
     double *lpt;                 // [B] running cost per trajectory
     double *lam;                 // [d_s][B] adjoint of the state between the segments of a checkpointed sweep
     double *fbuf;                // [M][B] sample values of the current step, summed over work units

@@ -2,14 +2,16 @@
 //   f_sm(x) = phi_m(x)^T w_sm + k_m(x, X)^T v_sm      and, optionally, d f_sm / d x.
 // This is the dominant kernel of a rollout step (Algorithm 1, the sampled transition).
 //
-// Mapping.  Lane = trajectory.  A workgroup holds 256 consecutive trajectories and one
-// work unit: either CK training points or CL random features of one GP output m.  The
-// operands that all trajectories share (scaled training inputs, frequencies) are read
-// through wave-uniform addresses, so they travel through the scalar cache into SGPRs and
-// feed the vector FMAs as scalar operands; the per-sample streams v and w are read as
-// one float4 (four consecutive points / features) per lane, coalesced across lanes.
-// Each unit writes its partial sums [1+D][B]; a later kernel adds the units up in a fixed
-// order, so results do not depend on scheduling.
+// Mapping.  Lane = trajectory.  A wave holds 64 consecutive trajectories and one work unit:
+// either CK training points or CL random features of one GP output m.  The operands that
+// all trajectories share (scaled training inputs, frequencies) are read through
+// wave-uniform addresses, so they travel through the scalar cache into SGPRs and feed the
+// vector FMAs as scalar operands; the per-sample streams v and w are read as one float4
+// (four consecutive points / features) per lane, coalesced across lanes.  The four waves
+// of a workgroup take four consecutive units of the same output and kind for the same 64
+// trajectories and add their sums through LDS in wave order; the workgroup writes one
+// partial sum [1+D][B] per group of four units, and a later kernel adds the groups up in
+// a fixed order, so results do not depend on scheduling.
 //
 // Arithmetic.  The kernel row is evaluated in float64: with noise variance far below the
 // signal variance the representer weights v are large with alternating signs, the sum
@@ -60,33 +62,38 @@ __global__ __launch_bounds__(BAGEL_BLOCK) void gp_step_kernel(
     double *__restrict__ part, int B, int S, int per_sample, int Np, int Lp, int CK, int CL, int nck,
     int ncl, int M)
 {
-    const int b_raw = blockIdx.x * BAGEL_BLOCK + threadIdx.x;
+    __shared__ double red[3][1 + D][64];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int b_raw = blockIdx.x * 64 + lane;
     const bool live = b_raw < B;
     const int b = live ? b_raw : B - 1;
     const int sidx = b / per_sample;
-    const int unit = blockIdx.y;
+    const int group = blockIdx.y;                  // four consecutive units of one output and kind
+    const int ngk = (nck + 3) >> 2, ngl = (ncl + 3) >> 2;
 
     double x[D];
 #pragma unroll
     for (int d = 0; d < D; ++d) x[d] = xbuf[(size_t)d * B + b];
 
-    double *out = part + (size_t)unit * (1 + D) * B + b;
+    double *out = part + (size_t)group * (1 + D) * B + b;
+    double u = 0.0;                                // this wave's sums: value, then the D Jacobian sums
+    double G[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) G[d] = 0.0;
 
-    if (unit < M * nck) {
+    if (group < M * ngk) {
         // ---------------- kernel-row unit: CK training points of output m ----------------
-        const int m = unit / nck, c = unit - m * nck;
+        const int m = group / ngk, c = 4 * (group - m * ngk) + wave;
+        const int n_iter = c < nck ? CK / 4 : 0;   // a wave past the last chunk adds nothing
         double q = 0.0;
 #pragma unroll
         for (int d = 0; d < D; ++d) q = fma(-0.5 * A[m * D + d] * x[d], x[d], q);
         const double *__restrict__ Xr = Xs + ((size_t)m * Np + (size_t)c * CK) * (D + 1);
         const float4 *__restrict__ vp = v4 + ((size_t)m * (Np / 4) + (size_t)c * (CK / 4)) * S + sidx;
-        double u = 0.0;
-        double G[D];
-#pragma unroll
-        for (int d = 0; d < D; ++d) G[d] = 0.0;
         double c7 = 1.192611307487823e-07, c6 = 2.409383341728244e-06;
         asm volatile("" : "+s"(c7), "+v"(c6));    // pin the register classes (see exp2_poly)
-        for (int n4 = 0; n4 < CK / 4; ++n4) {
+        for (int n4 = 0; n4 < n_iter; ++n4) {
             const v4f vv = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(vp + (size_t)n4 * S));   // read-once stream
             const float vj[4] = {vv.x, vv.y, vv.z, vv.w};
 #pragma unroll
@@ -104,24 +111,15 @@ __global__ __launch_bounds__(BAGEL_BLOCK) void gp_step_kernel(
                 }
             }
         }
-        if (live) {
-            out[0] = u;
-            if (JAC) {
-#pragma unroll
-                for (int d = 0; d < D; ++d) out[(size_t)(1 + d) * B] = G[d];
-            }
-        }
     } else {
         // ---------------- random-feature unit: CL features of output m -------------------
-        const int uu = unit - M * nck;
-        const int m = uu / ncl, c = uu - m * ncl;
+        const int gg = group - M * ngk;
+        const int m = gg / ngl, c = 4 * (gg - m * ngl) + wave;
+        const int n_iter = c < ncl ? CL / 4 : 0;
         const double *__restrict__ Or = Os + ((size_t)m * Lp + (size_t)c * CL) * (D + 1);
         const float4 *__restrict__ wp = w4 + ((size_t)m * (Lp / 4) + (size_t)c * (CL / 4)) * S + sidx;
         float p = 0.0f;
-        double G[D];
-#pragma unroll
-        for (int d = 0; d < D; ++d) G[d] = 0.0;
-        for (int l4 = 0; l4 < CL / 4; ++l4) {
+        for (int l4 = 0; l4 < n_iter; ++l4) {
             const v4f ww = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(wp + (size_t)l4 * S));
             const float wj[4] = {ww.x, ww.y, ww.z, ww.w};
 #pragma unroll
@@ -145,8 +143,29 @@ __global__ __launch_bounds__(BAGEL_BLOCK) void gp_step_kernel(
                 }
             }
         }
+        u = (double)p;
+    }
+
+    // waves 1-3 hand their sums to wave 0, which adds them in wave order and writes the group's partial
+    if (wave > 0) {
+        red[wave - 1][0][lane] = u;
+        if (JAC) {
+#pragma unroll
+            for (int d = 0; d < D; ++d) red[wave - 1][1 + d][lane] = G[d];
+        }
+    }
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+        for (int w = 0; w < 3; ++w) {
+            u += red[w][0][lane];
+            if (JAC) {
+#pragma unroll
+                for (int d = 0; d < D; ++d) G[d] += red[w][1 + d][lane];
+            }
+        }
         if (live) {
-            out[0] = (double)p;
+            out[0] = u;
             if (JAC) {
 #pragma unroll
                 for (int d = 0; d < D; ++d) out[(size_t)(1 + d) * B] = G[d];
@@ -158,7 +177,7 @@ __global__ __launch_bounds__(BAGEL_BLOCK) void gp_step_kernel(
 template <int D>
 hipError_t launch_d(bagel_ctx *c, bool jac)
 {
-    dim3 grid((c->dm.B + BAGEL_BLOCK - 1) / BAGEL_BLOCK, c->units);
+    dim3 grid((c->dm.B + 63) / 64, c->groups);
     const int per_sample = c->dm.B / c->dm.S;
     if (jac)
         hipLaunchKernelGGL((gp_step_kernel<D, true>), grid, dim3(BAGEL_BLOCK), 0, c->stream, c->Xs, c->Os, c->A,

@@ -12,7 +12,7 @@ constexpr double TWO_PI = 6.28318530717958647693;
 
 struct lane_args {
     int B, D, M, ds, da, dg, H;
-    int nck, ncl;
+    int nck, ncl;                // groups of work units per output: training points, features
     int cost_kind;
     float sigma_r, act_bound;
     int tracked[8];
@@ -173,7 +173,7 @@ lane_args make_args(const bagel_ctx *c)
 {
     lane_args a;
     a.B = c->dm.B; a.D = c->D; a.M = c->M; a.ds = c->dm.d_s; a.da = c->dm.d_a; a.dg = c->dm.d_g; a.H = c->dm.H;
-    a.nck = c->nck; a.ncl = c->ncl;
+    a.nck = (c->nck + 3) / 4; a.ncl = (c->ncl + 3) / 4;
     a.cost_kind = c->dm.cost_kind; a.sigma_r = c->dm.sigma_r; a.act_bound = c->dm.act_bound;
     for (int j = 0; j < 8; ++j) { a.tracked[j] = c->dm.tracked[j]; a.q[j] = c->dm.q[j]; }
     a.A = c->A; a.amp = c->amp; a.part = c->part;

@@ -136,6 +136,58 @@ __device__ __forceinline__ f16v tile_contract(const float *__restrict__ W, int k
     return acc;
 }
 
+// The weights a wave multiplies with are read once per launch and stay in its registers.
+// Packed weights: element W[32 rt + c][8 k8 + 4 hf + e] sits at ((rt * kp/8 + k8) * 64 + c + 32 hf) * 4 + e,
+// so a "group" (8 contraction indices) is one float4 per lane and a wave reads it as 1 KB of
+// contiguous memory.  A wave's slice of a layer, groups [k_begin, k_end), is a whole number of
+// batches of 4 groups (kp is a multiple of 32) and at most 8 batches (a 32 x 256 block).
+template <int NBMAX>
+__device__ __forceinline__ void load_wave_weights(float4 (&w)[4 * NBMAX], const float *__restrict__ W, int kp,
+                                                  const wave_plan &p, int lane)
+{
+    if (!p.active) return;
+    const float4 *wfrag = reinterpret_cast<const float4 *>(W) + ((size_t)p.rt * (kp >> 3) + p.k_begin) * 64 + lane;
+    const int nb = (p.k_end - p.k_begin) >> 2;
+#pragma unroll
+    for (int ub = 0; ub < NBMAX; ++ub)
+        if (ub < nb) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) w[4 * ub + u] = wfrag[(size_t)(4 * ub + u) * 64];
+        }
+}
+
+__device__ __forceinline__ f16v mfma_group(f16v acc, const float4 av, const float4 bv)
+{
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av.x, bv.x, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av.y, bv.y, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av.z, bv.z, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av.w, bv.w, acc, 0, 0, 0);
+    return acc;
+}
+
+// acc = W[wave's rows][its slice of the contraction] * act[same K][32 trajectories]: weights from
+// registers, activations from LDS as [K/4][trajectory][4], one batch (4 groups, 16 MFMAs) at a time.
+template <int NBMAX>
+__device__ __forceinline__ f16v contract_batches(const float4 (&w)[4 * NBMAX], const wave_plan &p, int lane,
+                                                 const float4 *__restrict__ act4)
+{
+    f16v acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+    const float4 *bcol = act4 + ((size_t)p.k_begin * 2 + (lane >> 5)) * PL + (lane & 31);
+    const int nb = (p.k_end - p.k_begin) >> 2;
+#pragma unroll
+    for (int ub = 0; ub < NBMAX; ++ub)
+        if (ub < nb) {
+            float4 bv[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) bv[u] = bcol[(4 * ub + u) * 2 * PL];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc = mfma_group(acc, w[4 * ub + u], bv[u]);
+        }
+    return acc;
+}
+
 // Add the partial tiles of the other contraction slices (through LDS, fixed order).  Contains the
 // barrier that also separates the reads of the layer input from the writes of the next one.
 __device__ __forceinline__ void combine_slices(f16v &acc, const wave_plan &p, int wave, int lane, float4 *red4)
@@ -156,6 +208,24 @@ __device__ __forceinline__ void combine_slices(f16v &acc, const wave_plan &p, in
             }
         }
     }
+}
+
+// tanh in float32 from the hardware exp2 and reciprocal: 1 - 2 / (e^{2|z|} + 1) with the sign of z,
+// and the odd Taylor polynomial up to z^9 below |z| = 1/4, where the first form loses relative
+// accuracy.  Absolute error about 1e-7, relative error below 1e-6; a fraction of the instructions of
+// the library routine, which matters because a layer's epilogue evaluates 8192 of them per workgroup.
+__device__ __forceinline__ float tanh_fast(float z)
+{
+    const float az = fabsf(z);
+    const float t = __builtin_amdgcn_exp2f(az * 2.8853900817779268f);          // e^{2|z|}; +inf for large |z|
+    const float big = copysignf(1.0f - 2.0f * __builtin_amdgcn_rcpf(t + 1.0f), z);
+    const float z2 = z * z;
+    float p = 62.0f / 2835.0f;
+    p = fmaf(p, z2, -17.0f / 315.0f);
+    p = fmaf(p, z2, 2.0f / 15.0f);
+    p = fmaf(p, z2, -1.0f / 3.0f);
+    const float small = fmaf(z * z2, p, z);
+    return az < 0.25f ? small : big;
 }
 
 // rows of a [n][B] array -> LDS [k/4][trajectory][4], zero-filled up to kp rows
@@ -180,6 +250,7 @@ __global__ __launch_bounds__(PW * 64) void policy_forward_kernel(policy_args a)
 {
     __shared__ float4 act4[(BAGEL_MAX_HIDDEN / 4) * PL];   // layer input  [K/4][trajectory]
     __shared__ float4 red4[PW * 4 * 64];                   // partial tiles of split contractions
+    __shared__ float biasS[3][BAGEL_MAX_HIDDEN];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int c = lane & 31, hf = lane >> 5;
@@ -187,17 +258,34 @@ __global__ __launch_bounds__(PW * 64) void policy_forward_kernel(policy_args a)
     const int b = b0 + c;
     const bool live = b < a.B;
 
+    // every wave first requests its share of all weight matrices; they arrive while the input is staged
+    float4 w_first[4], w_last[4], w_wide[32];
+    const wave_plan p_first = plan_layer(a.width[1], a.kp[0], wave);
+    const wave_plan p_last = plan_layer(a.width[a.nl], a.kp[a.nl - 1], wave);
+    wave_plan p_wide = p_first;
+    load_wave_weights<1>(w_first, a.Wp + a.wp_off[0], a.kp[0], p_first, lane);
+    if (a.nl == 3) {
+        p_wide = plan_layer(a.width[2], a.kp[1], wave);
+        load_wave_weights<8>(w_wide, a.Wp + a.wp_off[1], a.kp[1], p_wide, lane);
+    }
+    load_wave_weights<1>(w_last, a.Wp + a.wp_off[a.nl - 1], a.kp[a.nl - 1], p_last, lane);
+    for (int l = 0; l < a.nl; ++l)
+        for (int j = threadIdx.x; j < a.width[l + 1]; j += PW * 64) biasS[l][j] = a.theta[a.b_off[l] + j];
     stage_input(a.h[0], a.width[0], a.kp[0], a.B, b0, act4);
     __syncthreads();
 
     for (int l = 0; l < a.nl; ++l) {
         const int nj = a.width[l + 1];
-        const wave_plan p = plan_layer(nj, a.kp[l], wave);
+        const wave_plan p = l == 0 ? p_first : (l == a.nl - 1 ? p_last : p_wide);
         f16v acc;
-        if (p.active) acc = tile_contract(a.Wp + a.wp_off[l], a.kp[l], p, lane, act4);
+        if (p.active) {
+            if (l == 0) acc = contract_batches<1>(w_first, p, lane, act4);
+            else if (l == a.nl - 1) acc = contract_batches<1>(w_last, p, lane, act4);
+            else acc = contract_batches<8>(w_wide, p, lane, act4);
+        }
         combine_slices(acc, p, wave, lane, red4);
         if (p.active && p.ks == 0) {
-            const float *bias = a.theta + a.b_off[l];
+            const float *bias = biasS[l];
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int jb = p.rt * 32 + 8 * g + 4 * hf;
@@ -209,13 +297,13 @@ __global__ __launch_bounds__(PW * 64) void policy_forward_kernel(policy_args a)
                     if (j < nj) z = acc[4 * g + e] + bias[j];
                     out[e] = 0.0f;
                     if (l < a.nl - 1) {
-                        const float hv = j < nj ? tanhf(z) : 0.0f;
+                        const float hv = j < nj ? tanh_fast(z) : 0.0f;
                         out[e] = hv;
                         if (live && j < nj) a.h[l + 1][(size_t)j * a.B + b] = hv;
                     } else if (live && j < nj) {
                         float act_v = z, act_out = z;
                         if (a.act_bound > 0.0f) {
-                            act_v = tanhf(z);
+                            act_v = tanh_fast(z);
                             act_out = a.act_bound * act_v;
                         }
                         a.a_slot[(size_t)j * a.B + b] = act_v;
@@ -261,16 +349,52 @@ struct sweep_args {
     float *grad_s0;           // [B][d_s] or null
 };
 
-// lam += (1/B) d cost / d s_i at state s_t (t >= 1) against g_{t-1}, for trajectory b
-__device__ __forceinline__ double add_cost_gradient(const sweep_args &a, double lam, int t, int i, int b)
+// 4-byte read that the optimiser keeps where it is written (see load16_pinned).  Used for the tape
+// values a later phase needs, requested a phase early so that they arrive under the matrix work.
+__device__ __forceinline__ float load_pinned(const float *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+}
+
+// What thread (row, trajectory) reads from the tape for one step of the sweep: row d < D owns
+// component d of u = J^T lam.
+struct sweep_tape {
+    float J[8];           // J[m][row]
+    float th;             // rows d_s .. D-1: tanh output of the bounded action row - d_s
+    float sv[8], gv[8];   // rows < d_s: tracked states of s_{t-1} and the goals they are compared with
+};
+
+// step k = t-1 (tape slot k - t_lo) and the cost data of state t-1
+__device__ __forceinline__ void sweep_tape_load(const sweep_args &a, int t, int row, int bq, sweep_tape &r)
+{
+    const size_t slot = (size_t)(t - 1 - a.t_lo);
+    if (row < a.D) {
+        const float *Jt = a.tape_J + (slot * a.M * a.D + row) * a.B + bq;
+#pragma unroll
+        for (int m = 0; m < 8; ++m)
+            if (m < a.M) r.J[m] = load_pinned(Jt + (size_t)m * a.D * a.B);
+        if (row >= a.ds && a.act_bound > 0.0f) r.th = load_pinned(a.tape_a + (slot * a.da + (row - a.ds)) * a.B + bq);
+    }
+    if (row < a.ds && t - 1 >= 1) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if (j < a.dg) {
+                r.sv[j] = load_pinned(a.tape_s + ((size_t)(t - 1) * a.ds + a.tracked[j]) * a.B + bq);
+                r.gv[j] = load_pinned(a.goals + ((size_t)(t - 2) * a.B + bq) * a.dg + j);
+            }
+    }
+}
+
+// lam + (1/B) d cost / d s_i, the cost of tracked states sv against goals gv
+__device__ __forceinline__ double add_cost_gradient(const sweep_args &a, double lam, int i, const float *sv,
+                                                    const float *gv)
 {
     double r[8], e = 0.0;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         r[j] = 0.0;
         if (j < a.dg) {
-            r[j] = (double)a.tape_s[((size_t)t * a.ds + a.tracked[j]) * a.B + b] -
-                   (double)a.goals[((size_t)(t - 1) * a.B + b) * a.dg + j];
+            r[j] = (double)sv[j] - (double)gv[j];
             e += (double)a.q[j] * r[j] * r[j];
         }
     }
@@ -284,6 +408,19 @@ __device__ __forceinline__ double add_cost_gradient(const sweep_args &a, double 
     for (int j = 0; j < 8; ++j)
         if (j < a.dg && a.tracked[j] == i) lam += factor * (double)a.q[j] * r[j];
     return lam;
+}
+
+// tanh outputs h_l of the units a wave owns (the rows of its output tile), for the tanh derivative
+__device__ __forceinline__ void load_tanh_outputs(const float *hl, int ni, int B, const wave_plan &p, int hf,
+                                                  float *hv)
+{
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int i = p.rt * 32 + 8 * g + 4 * hf + e;
+            hv[4 * g + e] = load_pinned(hl + (size_t)(i < ni ? i : ni - 1) * B);
+        }
 }
 
 __global__ __launch_bounds__(PW * 64) void backward_sweep_kernel(sweep_args a)
@@ -305,68 +442,78 @@ __global__ __launch_bounds__(PW * 64) void backward_sweep_kernel(sweep_args a)
     const int bl = tid & (PL - 1), row = tid >> 5;
     const bool liveq = b0 + bl < a.B;
     const int bq = liveq ? b0 + bl : a.B - 1;
+    // the wave's share of the top layer (input width[last], contraction over the d_a outputs)
+    const wave_plan p_top = plan_layer(a.width[last], a.kp[last], wave);
+    const bool top_owner = last > 0 && p_top.active && p_top.ks == 0;
 
     if (row < a.ds) {
         double v = 0.0;
-        if (a.t_hi == a.H) v = add_cost_gradient(a, 0.0, a.H, row, bq);
-        else v = a.lam[(size_t)row * a.B + bq];
+        if (a.t_hi == a.H) {
+            float sv[8], gv[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (j < a.dg) {
+                    sv[j] = a.tape_s[((size_t)a.H * a.ds + a.tracked[j]) * a.B + bq];
+                    gv[j] = a.goals[((size_t)(a.H - 1) * a.B + bq) * a.dg + j];
+                }
+            v = add_cost_gradient(a, 0.0, row, sv, gv);
+        } else {
+            v = a.lam[(size_t)row * a.B + bq];
+        }
         lamS[row][bl] = v;
     }
+    sweep_tape cur = {}, nxt = {};
+    float hv_top[16] = {}, hv_top_next[16] = {};
+    sweep_tape_load(a, a.t_hi, row, bq, cur);
+    if (top_owner)
+        load_tanh_outputs(a.tape_h[last] + (size_t)(a.t_hi - 1 - a.t_lo) * a.width[last] * a.B + bc, a.width[last], a.B,
+                          p_top, hf, hv_top);
     __syncthreads();
 
     for (int t = a.t_hi; t > a.t_lo; --t) {
         const size_t slot = (size_t)(t - 1 - a.t_lo);
-        const float *Jt = a.tape_J + slot * a.M * a.D * a.B;
-        // ---- u = J^T lam: rows 0-7 build the policy-backward input (4 outputs each, zero padded up
-        //      to the 32 rows one MFMA batch consumes), rows 8-15 the state part
-        if (row < 8) {
-            float out[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int o = row * 4 + e;
-                out[e] = 0.0f;
-                if (o < a.da) {
-                    double acc = 0.0;
-#pragma unroll
-                    for (int m = 0; m < 8; ++m)
-                        if (m < a.M) acc += (double)Jt[((size_t)m * a.D + a.ds + o) * a.B + bq] * lamS[m][bl];
-                    if (a.act_bound > 0.0f) {
-                        const double th = (double)a.tape_a[(slot * a.da + o) * a.B + bq];
-                        acc *= (double)a.act_bound * (1.0 - th * th);
-                    }
-                    out[e] = (float)acc;
-                    if (liveq) a.tape_d[last][(slot * a.da + o) * a.B + bq] = out[e];
-                }
-            }
-            act4[row * PL + bl] = make_float4(out[0], out[1], out[2], out[3]);
-        } else if (row - 8 < a.ds) {
-            const int i = row - 8;
+        // ---- u = J^T lam, one component per row: the state part goes to usS, the action part times
+        //      d a / d z_out is the input of the policy backward (rows d_a .. 31 of it are zero: one MFMA
+        //      batch consumes 32 rows)
+        float *act1 = reinterpret_cast<float *>(act4);
+        if (tid < 6 * PL) act4[(2 + row) * PL + bl] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (row < a.D) {
             double acc = 0.0;
 #pragma unroll
             for (int m = 0; m < 8; ++m)
-                if (m < a.M) acc += (double)Jt[((size_t)m * a.D + i) * a.B + bq] * lamS[m][bl];
-            usS[i][bl] = acc;
+                if (m < a.M) acc += (double)cur.J[m] * lamS[m][bl];
+            if (row < a.ds) {
+                usS[row][bl] = acc;
+            } else {
+                const int o = row - a.ds;
+                if (a.act_bound > 0.0f) {
+                    const double th = (double)cur.th;
+                    acc *= (double)a.act_bound * (1.0 - th * th);
+                }
+                const float dv = (float)acc;
+                if (liveq) a.tape_d[last][(slot * a.da + o) * a.B + bq] = dv;
+                act1[((o >> 2) * PL + bl) * 4 + (o & 3)] = dv;
+            }
+        } else if (row - a.ds < 8) {
+            const int o = row - a.ds;
+            act1[((o >> 2) * PL + bl) * 4 + (o & 3)] = 0.0f;
         }
         __syncthreads();
+        // the tape of the next step of the sweep is requested now and arrives under the matrix work
+        if (t - 1 > a.t_lo) {
+            sweep_tape_load(a, t - 1, row, bq, nxt);
+            if (top_owner)
+                load_tanh_outputs(a.tape_h[last] + (slot - 1) * a.width[last] * a.B + bc, a.width[last], a.B, p_top, hf,
+                                  hv_top_next);
+        }
 
         // ---- policy backward: delta_{l-1} = (W_l^T delta_l) * (1 - h_l^2)
         for (int l = last; l >= 0; --l) {
             const int ni = a.width[l];
             const wave_plan p = plan_layer(ni, a.kp[l], wave);
             const bool owner = p.active && p.ks == 0;
-            // tanh outputs of the layer below, requested before the contraction so that they arrive under it
             float hv[16];
-            if (l > 0 && owner) {
-                const float *hl = a.tape_h[l] + slot * ni * a.B + bc;
-#pragma unroll
-                for (int g = 0; g < 4; ++g)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int i = p.rt * 32 + 8 * g + 4 * hf + e;
-                        hv[4 * g + e] = __hip_atomic_load(hl + (size_t)(i < ni ? i : ni - 1) * a.B, __ATOMIC_RELAXED,
-                                                          __HIP_MEMORY_SCOPE_WAVEFRONT);
-                    }
-            }
+            if (l > 0 && l < last && owner) load_tanh_outputs(a.tape_h[l] + slot * ni * a.B + bc, ni, a.B, p, hf, hv);
             f16v acc;
             if (p.active) acc = tile_contract(a.Wp + a.wp_off[l], a.kp[l], p, lane, act4);
             combine_slices(acc, p, wave, lane, red4);
@@ -382,7 +529,7 @@ __global__ __launch_bounds__(PW * 64) void backward_sweep_kernel(sweep_args a)
                         if (i < ni) {
                             dv = acc[4 * g + e];
                             if (l > 0) {
-                                const float h = hv[4 * g + e];
+                                const float h = l == last ? hv_top[4 * g + e] : hv[4 * g + e];
                                 dv *= (1.0f - h * h);
                                 if (live) a.tape_d[l - 1][(slot * ni + i) * a.B + b] = dv;
                             } else if (i < 16) {
@@ -400,9 +547,12 @@ __global__ __launch_bounds__(PW * 64) void backward_sweep_kernel(sweep_args a)
         // ---- lam_{t-1}
         if (row < a.ds) {
             double v = lamS[row][bl] + usS[row][bl] + (double)dh0S[row][bl];
-            if (t - 1 >= 1) v = add_cost_gradient(a, v, t - 1, row, bq);
+            if (t - 1 >= 1) v = add_cost_gradient(a, v, row, cur.sv, cur.gv);
             lamS[row][bl] = v;
         }
+        cur = nxt;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) hv_top[r] = hv_top_next[r];
         __syncthreads();
     }
 
@@ -414,7 +564,7 @@ __global__ __launch_bounds__(PW * 64) void backward_sweep_kernel(sweep_args a)
 }
 
 // theta -> packed, zero-padded forward (rows = outputs, K = inputs) and backward (rows = inputs,
-// K = outputs) matrices in the fragment order tile_contract reads
+// K = outputs) matrices in the fragment order tile_contract and load_wave_weights read
 __device__ __forceinline__ void unpack_index(int idx, int kp, int &row, int &k)
 {
     const int e = idx & 3, lane = (idx >> 2) & 63, blk = idx >> 8;     // blk = rt * (kp/8) + k8
