@@ -87,6 +87,8 @@ def lib():
         L.oracle_policy.argtypes = [C.POINTER(Dims), _DP, _DP, _DP]
         L.oracle_rollout.restype = C.c_int
         L.oracle_rollout.argtypes = [C.POINTER(Dims)] + [_DP] * 15
+        L.oracle_adam_step.restype = None
+        L.oracle_adam_step.argtypes = [C.c_int, _DP, _DP, _DP, _DP, C.c_int] + [C.c_double] * 4
         _lib = L
     return _lib
 
@@ -176,3 +178,31 @@ def rollout(dm: Dims, m: Dict[str, np.ndarray], v, theta=None, s0=None, goals=No
     if rc != 0:
         raise RuntimeError(f"oracle_rollout failed with code {rc}")
     return {"loss": float(loss[0]), "loss_per_traj": lpt, "states": states, "grad_theta": g, "grad_s0": gs0}
+
+
+ADAM_DEFAULTS = dict(lr=1e-2, beta1=0.9, beta2=0.999, eps=1e-8)   # lr: Sec. IV-A; the rest: Adam's own defaults
+
+
+def adam_step(theta, grad, m, v, t: int, *, lr=1e-2, beta1=0.9, beta2=0.999, eps=1e-8) -> None:
+    """In-place Adam update of float64 arrays theta, m, v (step counter t >= 1)."""
+    for a in (theta, m, v):
+        assert a.dtype == np.float64 and a.flags.c_contiguous
+    grad = _d(grad)
+    lib().oracle_adam_step(len(theta), _p(theta), _p(grad), _p(m), _p(v), int(t), float(lr), float(beta1),
+                           float(beta2), float(eps))
+
+
+def optimize(dm: Dims, m: Dict[str, np.ndarray], v, theta0, s0_sets, goal_sets, n_iters: int, *,
+             first_step: int = 1, adam_m=None, adam_v=None, **adam):
+    """Inner loop of Algorithm 1: iteration i rolls out from s0_sets[i % n_sets] towards goal_sets[i % n_sets],
+    takes the gradient of the loss and updates theta with Adam.  Returns (theta, adam_m, adam_v, losses)."""
+    theta = _d(theta0).copy()
+    am = np.zeros_like(theta) if adam_m is None else _d(adam_m).copy()
+    av = np.zeros_like(theta) if adam_v is None else _d(adam_v).copy()
+    losses = np.empty(n_iters)
+    n_sets = len(s0_sets)
+    for i in range(n_iters):
+        r = rollout(dm, m, v, theta=theta, s0=s0_sets[i % n_sets], goals=goal_sets[i % n_sets], want_states=False)
+        losses[i] = r["loss"]
+        adam_step(theta, r["grad_theta"], am, av, first_step + i, **adam)
+    return theta, am, av, losses

@@ -22,12 +22,19 @@
  *                           running cost) and loss = (1/b) * sum as in eq. (10),
  *                           (11); backward pass = the adjoint of exactly those
  *                           steps, summed over trajectories and time.
+ *   oracle_adam_step        Algorithm 1, the parameter update: Sec. III-C names
+ *                           Adam (Kingma & Ba) as the gradient-descent rule; the
+ *                           update is that paper's Algorithm 1 with bias-corrected
+ *                           moment estimates.  The inner loop of Algorithm 1
+ *                           (oracle.optimize in the Python wrapper) alternates
+ *                           oracle_rollout and oracle_adam_step.
  *
  * Pins (tests/test_oracle_pins.py): with w = 0 and eps = 0 a sample is the
  * textbook posterior mean of eq. (2); sample mean / covariance over many draws
  * against eq. (2), (3); feature inner products against eq. (4); central finite
  * differences and an independent autodiff graph for the gradient; H = 1 closed
- * form; additivity over trajectories.  The numerical values of a rollout on the
+ * form; additivity over trajectories; the Adam step against its closed form for a
+ * constant gradient and against torch.optim.Adam.  The numerical values of a rollout on the
  * synthetic workloads themselves are not printed anywhere in the paper.
  *
  * Conventions: row-major arrays; X[N][D]; per output m: ell[M][D], sf2[M]
@@ -460,4 +467,23 @@ int oracle_rollout(const oracle_dims *dm, const double *X, const double *ell, co
     free(gpart);
     free(lpt);
     return err;
+}
+
+/*
+ * One Adam update (Sec. III-C: the policy parameters are updated with Adam), step counter t >= 1:
+ *   m <- beta1 m + (1 - beta1) g;  v <- beta2 v + (1 - beta2) g^2;
+ *   theta <- theta - lr * (m / (1 - beta1^t)) / (sqrt(v / (1 - beta2^t)) + eps).
+ * theta, m, v are updated in place.
+ */
+void oracle_adam_step(int P, double *theta, const double *grad, double *m, double *v, int t,
+                      double lr, double beta1, double beta2, double eps)
+{
+    const double c1 = 1.0 - pow(beta1, (double)t), c2 = 1.0 - pow(beta2, (double)t);
+    for (int p = 0; p < P; ++p) {
+        const double g = grad[p];
+        m[p] = beta1 * m[p] + (1.0 - beta1) * g;
+        v[p] = beta2 * v[p] + (1.0 - beta2) * g * g;
+        const double mhat = m[p] / c1, vhat = v[p] / c2;
+        theta[p] -= lr * mhat / (sqrt(vhat) + eps);
+    }
 }

@@ -340,3 +340,67 @@ def test_config_table():
     for name, cfg in synth.CONFIGS.items():
         assert cfg.P == P[name]
         assert cfg.M == cfg.d_s and cfg.d_in == cfg.d_s + cfg.d_g
+
+
+# ------------------------------------------------------------------ Adam step and the inner loop
+def test_adam_constant_gradient_closed_form():
+    """With a constant gradient the bias-corrected moments are exactly g and g^2 at every step, so each
+    step moves theta by -lr g / (|g| + eps) (Adam, Kingma & Ba, Algorithm 1)."""
+    rng = np.random.default_rng(5)
+    P = 37
+    g = rng.standard_normal(P) * 10.0 ** rng.integers(-6, 3, P)
+    theta0 = rng.standard_normal(P)
+    theta, m, v = theta0.copy(), np.zeros(P), np.zeros(P)
+    lr, eps = 3e-3, 1e-8
+    for t in range(1, 8):
+        oracle.adam_step(theta, g, m, v, t, lr=lr, eps=eps)
+        np.testing.assert_allclose(theta, theta0 - t * lr * g / (np.abs(g) + eps), rtol=1e-12, atol=1e-15)
+    # a sign flip of the gradient flips the step; a zero gradient leaves theta alone
+    theta, m, v = np.zeros(3), np.zeros(3), np.zeros(3)
+    oracle.adam_step(theta, np.array([2.0, -2.0, 0.0]), m, v, 1, lr=0.1)
+    np.testing.assert_allclose(theta, [-0.1, 0.1, 0.0], atol=1e-9)
+
+
+def test_adam_matches_library_routine():
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(6)
+    P = 53
+    theta0 = rng.standard_normal(P)
+    grads = rng.standard_normal((12, P)) * np.linspace(0.1, 3.0, 12)[:, None]
+    kw = dict(lr=1e-2, beta1=0.85, beta2=0.97, eps=1e-7)
+    theta, m, v = theta0.copy(), np.zeros(P), np.zeros(P)
+    tt = torch.tensor(theta0, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.Adam([tt], lr=kw["lr"], betas=(kw["beta1"], kw["beta2"]), eps=kw["eps"])
+    for t, g in enumerate(grads, start=1):
+        oracle.adam_step(theta, g, m, v, t, **kw)
+        tt.grad = torch.tensor(g, dtype=torch.float64)
+        opt.step()
+        np.testing.assert_allclose(theta, tt.detach().numpy(), rtol=1e-10, atol=1e-13)
+
+
+def test_inner_loop_is_rollout_gradient_then_adam_and_lowers_the_loss():
+    """oracle.optimize against the same loop spelt out with torch.optim.Adam on the oracle's gradients;
+    with fixed initial states and goals (the single-goal setting of Sec. IV-A) the loss goes down."""
+    torch = pytest.importorskip("torch")
+    cfg = synth.scaled(synth.CONFIGS["tiny"], B=8, H=10)
+    inp = synth.make_inputs(cfg)
+    dm = oracle.dims_from_config(cfg)
+    v = oracle.prepare_samples(dm, inp)
+    sets_s0 = [inp["s0"], synth.make_inputs(cfg, trial=1)["s0"]]
+    sets_g = [inp["goals"], synth.make_inputs(cfg, trial=1)["goals"]]
+    n = 6
+    theta, am, av, losses = oracle.optimize(dm, inp, v, inp["theta"], sets_s0, sets_g, n, lr=1e-2)
+    tt = torch.tensor(np.asarray(inp["theta"], dtype=np.float64), requires_grad=True)
+    opt = torch.optim.Adam([tt], lr=1e-2)
+    for i in range(n):
+        r = oracle.rollout(dm, inp, v, theta=tt.detach().numpy(), s0=sets_s0[i % 2], goals=sets_g[i % 2])
+        assert abs(r["loss"] - losses[i]) <= 1e-12 * abs(losses[i])
+        tt.grad = torch.tensor(r["grad_theta"])
+        opt.step()
+    np.testing.assert_allclose(theta, tt.detach().numpy(), rtol=1e-9, atol=1e-12)
+    # split into two calls with the moments carried over: identical
+    th1, m1, v1, _ = oracle.optimize(dm, inp, v, inp["theta"], sets_s0, sets_g, 2, lr=1e-2)
+    th2, _, _, _ = oracle.optimize(dm, inp, v, th1, sets_s0, sets_g, 4, first_step=3, adam_m=m1, adam_v=v1, lr=1e-2)
+    np.testing.assert_allclose(th2, theta, rtol=1e-13, atol=1e-15)
+    fixed = oracle.optimize(dm, inp, v, inp["theta"], sets_s0[:1], sets_g[:1], 25, lr=1e-2)[3]
+    assert fixed[-1] < fixed[0]
