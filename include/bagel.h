@@ -138,6 +138,35 @@ int bagel_rollout_loss_grad(bagel_ctx *ctx, const float *theta, const float *s0,
                             float *grad_s0);
 
 /*
+ * One Adam update of the policy parameters on the device (Sec. III-C: the parameters are updated
+ * with Adam; Algorithm 1, "update theta via gradient descent").  step >= 1 is the update counter:
+ *   m <- beta1 m + (1 - beta1) g;  v <- beta2 v + (1 - beta2) g^2;
+ *   theta <- theta - lr (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps).
+ * theta[P], adam_m[P], adam_v[P] are device arrays owned by the caller and updated in place
+ * (start the moments at zero); grad[P] is read.  Stored in float32, arithmetic in float64.
+ * The paper fixes lr = 1e-2 (Sec. IV-A); beta1 = 0.9, beta2 = 0.999, eps = 1e-8 are Adam's defaults.
+ * Errors: EINVAL (null pointer, step < 1, betas outside [0, 1), lr or eps not positive), EHIP.
+ */
+int bagel_adam_step(bagel_ctx *ctx, float *theta, const float *grad, float *adam_m, float *adam_v,
+                    int step, float lr, float beta1, float beta2, float eps);
+
+/*
+ * Inner loop of Algorithm 1 (forward pass, backward pass, parameter update), n_iters times,
+ * enqueued on the context's stream without any host synchronisation.  Iteration i (0-based)
+ * rolls out from s0_sets[i % n_sets] towards goal_sets[i % n_sets], writes its loss to
+ * loss_history[i] and applies Adam update number first_step + i.
+ *   s0_sets[n_sets][B][d_s], goal_sets[n_sets][H][B][d_g]: n_sets = 1 is the fixed start and goal of
+ *   Sec. IV-A, several sets are batches of starts and goals drawn by the caller (Sec. IV-B); the
+ *   library draws no random numbers.  theta, adam_m, adam_v as in bagel_adam_step; loss_history[n_iters].
+ * The function samples stay as installed; to redraw them between iterations call the loop with
+ * n_iters = 1 and bagel_prepare_samples in between (the optimiser state lives with the caller).
+ * Errors: EINVAL, ENOTPREPARED, EHIP.
+ */
+int bagel_optimize(bagel_ctx *ctx, float *theta, float *adam_m, float *adam_v, const float *s0_sets,
+                   const float *goal_sets, int n_sets, int n_iters, int first_step, float lr,
+                   float beta1, float beta2, float eps, float *loss_history);
+
+/*
  * One evaluation of the function samples (the transition model alone): for every trajectory b,
  * f[b][m] = f_{s(b),m}(x[b]) and, if jac != NULL, jac[b][m][d] = d f / d x_d.   x[B][D].
  * Runs the same kernels as one rollout step.  Errors: EINVAL, ENOTPREPARED, EHIP.

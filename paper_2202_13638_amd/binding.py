@@ -20,7 +20,7 @@ _NAMES = {EINVAL: "BAGEL_EINVAL", ENOTPREPARED: "BAGEL_ENOTPREPARED", ENOMEM: "B
 
 EXPORTS = ["bagel_num_params", "bagel_create", "bagel_destroy", "bagel_workspace_bytes",
            "bagel_prepare_samples", "bagel_set_samples", "bagel_rollout_loss",
-           "bagel_rollout_loss_grad", "bagel_sample_eval", "bagel_last_error",
+           "bagel_rollout_loss_grad", "bagel_sample_eval", "bagel_last_error", "bagel_adam_step", "bagel_optimize",
            "bagel_profile_enable", "bagel_profile_read"]
 
 
@@ -102,6 +102,10 @@ def load():
         L.bagel_profile_enable.argtypes = [vp, C.c_int]
         L.bagel_profile_read.restype = C.c_int
         L.bagel_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int)]
+        L.bagel_adam_step.restype = C.c_int
+        L.bagel_adam_step.argtypes = [vp] + [fp] * 4 + [C.c_int] + [C.c_float] * 4
+        L.bagel_optimize.restype = C.c_int
+        L.bagel_optimize.argtypes = [vp] + [fp] * 5 + [C.c_int] * 3 + [C.c_float] * 4 + [fp]
         L.bagel_last_error.restype = C.c_char_p
         L.bagel_last_error.argtypes = [vp]
         _lib = L
@@ -198,6 +202,22 @@ class Bagel:
             _ptr(loss_per_traj, (d.B,), "loss_per_traj", optional=True),
             _ptr(states, (d.H + 1, d.B, d.d_s), "states", optional=True),
             _ptr(grad_s0, (d.B, d.d_s), "grad_s0", optional=True)))
+
+    def bagel_adam_step(self, theta, grad, adam_m, adam_v, step, lr=1e-2, beta1=0.9, beta2=0.999, eps=1e-8):
+        P = (self.P,)
+        self._check(self._lib.bagel_adam_step(
+            self._h, _ptr(theta, P, "theta"), _ptr(grad, P, "grad"), _ptr(adam_m, P, "adam_m"),
+            _ptr(adam_v, P, "adam_v"), int(step), lr, beta1, beta2, eps))
+
+    def bagel_optimize(self, theta, adam_m, adam_v, s0_sets, goal_sets, n_iters, loss_history, first_step=1,
+                       lr=1e-2, beta1=0.9, beta2=0.999, eps=1e-8):
+        d, P = self.dims, (self.P,)
+        n_sets = int(s0_sets.shape[0]) if hasattr(s0_sets, "shape") and len(s0_sets.shape) == 3 else 0
+        self._check(self._lib.bagel_optimize(
+            self._h, _ptr(theta, P, "theta"), _ptr(adam_m, P, "adam_m"), _ptr(adam_v, P, "adam_v"),
+            _ptr(s0_sets, (n_sets, d.B, d.d_s), "s0_sets"), _ptr(goal_sets, (n_sets, d.H, d.B, d.d_g), "goal_sets"),
+            n_sets, int(n_iters), int(first_step), lr, beta1, beta2, eps,
+            _ptr(loss_history, (int(n_iters),), "loss_history")))
 
     def bagel_profile_enable(self, every: int):
         self._check(self._lib.bagel_profile_enable(self._h, int(every)))

@@ -3,6 +3,7 @@
 // enqueues, per step, the policy kernel, the sample-evaluation kernel and the state-advance kernel
 // on the context's stream (Algorithm 1, forward pass); the gradient call then sweeps the tape
 // backwards (Algorithm 1, backward pass) and finishes with one weight-gradient GEMM per layer.
+#include <math.h>
 #include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
@@ -75,7 +76,7 @@ static void free_all(bagel_ctx *c)
 {
     void *ptrs[] = {c->Xs, c->Os, c->A, c->amp, c->v4, c->w4, c->xbuf, c->part, c->lpt, c->lam,
                     c->tape_s, c->tape_J, c->tape_h[0], c->tape_h[1], c->tape_h[2], c->tape_a, c->tape_d[0],
-                    c->tape_d[1], c->tape_d[2], c->ckpt_s, c->wpad_f, c->wpad_b, c->gsplit, c->gacc, c->fbuf};
+                    c->tape_d[1], c->tape_d[2], c->ckpt_s, c->wpad_f, c->wpad_b, c->gsplit, c->gacc, c->fbuf, c->gtheta};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
 }
@@ -169,6 +170,7 @@ extern "C" int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_s
     ALLOC(c->wpad_b, (size_t)wb_total);
     ALLOC(c->gsplit, (size_t)c->ksplit * c->P);
     ALLOC(c->gacc, (size_t)c->P);
+    ALLOC(c->gtheta, (size_t)c->P);
 #undef ALLOC
     if (e != hipSuccess) {
         const int64_t want = c->bytes;
@@ -367,6 +369,55 @@ extern "C" int bagel_rollout_loss_grad(bagel_ctx *c, const float *theta, const f
         if (rc != BAGEL_OK) return rc;
         BAGEL_HIP(c, bagel_launch_backward_sweep(c, t0, t1, goals, grad_s0));
         BAGEL_HIP(c, bagel_launch_weight_grad(c, t1 - t0, seg != n_seg - 1, seg == 0 ? grad_theta : nullptr));
+    }
+    return BAGEL_OK;
+}
+
+static const char *check_adam(int step, float lr, float beta1, float beta2, float eps)
+{
+    if (step < 1) return "step must be >= 1";
+    if (!(lr > 0.0f) || !(eps > 0.0f)) return "lr and eps must be positive";
+    if (!(beta1 >= 0.0f && beta1 < 1.0f) || !(beta2 >= 0.0f && beta2 < 1.0f)) return "betas must lie in [0, 1)";
+    return nullptr;
+}
+
+static hipError_t adam_update(bagel_ctx *c, float *theta, const float *grad, float *m, float *v, int step,
+                              float lr, float beta1, float beta2, float eps)
+{
+    const double b1 = (double)beta1, b2 = (double)beta2;
+    return bagel_launch_adam(c, theta, grad, m, v, (double)lr, b1, b2, (double)eps, 1.0 - pow(b1, (double)step),
+                             1.0 - pow(b2, (double)step));
+}
+
+extern "C" int bagel_adam_step(bagel_ctx *c, float *theta, const float *grad, float *adam_m, float *adam_v,
+                               int step, float lr, float beta1, float beta2, float eps)
+{
+    if (!c) return BAGEL_EINVAL;
+    c->err[0] = 0;
+    if (!theta || !grad || !adam_m || !adam_v) BAGEL_FAIL(c, BAGEL_EINVAL, "bagel_adam_step: null argument");
+    if (const char *msg = check_adam(step, lr, beta1, beta2, eps)) BAGEL_FAIL(c, BAGEL_EINVAL, "bagel_adam_step: %s", msg);
+    BAGEL_HIP(c, adam_update(c, theta, grad, adam_m, adam_v, step, lr, beta1, beta2, eps));
+    return BAGEL_OK;
+}
+
+extern "C" int bagel_optimize(bagel_ctx *c, float *theta, float *adam_m, float *adam_v, const float *s0_sets,
+                              const float *goal_sets, int n_sets, int n_iters, int first_step, float lr,
+                              float beta1, float beta2, float eps, float *loss_history)
+{
+    if (!c) return BAGEL_EINVAL;
+    c->err[0] = 0;
+    if (!theta || !adam_m || !adam_v || !s0_sets || !goal_sets || !loss_history)
+        BAGEL_FAIL(c, BAGEL_EINVAL, "bagel_optimize: null argument");
+    if (n_sets < 1 || n_iters < 0) BAGEL_FAIL(c, BAGEL_EINVAL, "bagel_optimize: n_sets must be >= 1 and n_iters >= 0");
+    if (const char *msg = check_adam(first_step, lr, beta1, beta2, eps)) BAGEL_FAIL(c, BAGEL_EINVAL, "bagel_optimize: %s", msg);
+    if (!c->prepared) BAGEL_FAIL(c, BAGEL_ENOTPREPARED, "bagel_optimize: no samples installed");
+    const size_t s0_sz = (size_t)c->dm.B * c->dm.d_s, g_sz = (size_t)c->dm.H * c->dm.B * c->dm.d_g;
+    for (int i = 0; i < n_iters; ++i) {
+        const int set = i % n_sets;
+        const int rc = bagel_rollout_loss_grad(c, theta, s0_sets + set * s0_sz, goal_sets + set * g_sz, loss_history + i,
+                                               c->gtheta, nullptr, nullptr, nullptr);
+        if (rc != BAGEL_OK) return rc;
+        BAGEL_HIP(c, adam_update(c, theta, c->gtheta, adam_m, adam_v, first_step + i, lr, beta1, beta2, eps));
     }
     return BAGEL_OK;
 }

@@ -56,6 +56,7 @@ struct bagel_ctx {
     int wpb_off[3], wpb_rp[3], wpb_kp[3];
     float *gsplit;               // [ksplit][P] split-contraction partial weight gradients
     double *gacc;                // [P] gradient accumulated over segments
+    float *gtheta;               // [P] gradient of the current iteration of bagel_optimize
     int ksplit;
 
     // ---- measurement hooks -------------------------------------------------------------------
@@ -104,6 +105,8 @@ hipError_t bagel_launch_policy_forward(bagel_ctx *ctx, int slot, const float *th
 // backward sweep over steps t_hi-1 .. t_lo (tape slot of step k is k - t_lo); grad_s0 is written when t_lo == 0
 hipError_t bagel_launch_backward_sweep(bagel_ctx *ctx, int t_lo, int t_hi, const float *goals, float *grad_s0);
 hipError_t bagel_launch_weight_grad(bagel_ctx *ctx, int n_slots, bool accumulate, float *grad_theta);
+hipError_t bagel_launch_adam(bagel_ctx *ctx, float *theta, const float *grad, float *m, float *v, double lr,
+                             double beta1, double beta2, double eps, double corr1, double corr2);
 
 // ---- prepare.hip -------------------------------------------------------------------------
 // v = (K + noise I)^-1 (y - Phi w - eps) for every sample, float64 inside; packs v into ctx->v4

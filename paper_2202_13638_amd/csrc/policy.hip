@@ -717,6 +717,21 @@ __global__ void grad_reduce_kernel(const float *__restrict__ gsplit, double *__r
     if (grad_theta) grad_theta[p] = (float)s;
 }
 
+// Adam update (Kingma & Ba, Algorithm 1) of theta, m, v in place; corr1 = 1 - beta1^step, corr2 = 1 - beta2^step
+__global__ void adam_kernel(float *__restrict__ theta, const float *__restrict__ grad, float *__restrict__ m,
+                            float *__restrict__ v, int P, double lr, double beta1, double beta2, double eps,
+                            double corr1, double corr2)
+{
+    const int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= P) return;
+    const double g = (double)grad[p];
+    const double mn = beta1 * (double)m[p] + (1.0 - beta1) * g;
+    const double vn = beta2 * (double)v[p] + (1.0 - beta2) * g * g;
+    m[p] = (float)mn;
+    v[p] = (float)vn;
+    theta[p] = (float)((double)theta[p] - lr * (mn / corr1) / (sqrt(vn / corr2) + eps));
+}
+
 policy_args make_pargs(const bagel_ctx *c, int slot)
 {
     policy_args a;
@@ -779,6 +794,14 @@ hipError_t bagel_launch_backward_sweep(bagel_ctx *c, int t_lo, int t_hi, const f
     a.tape_a = c->tape_a; a.tape_J = c->tape_J; a.tape_s = c->tape_s;
     a.goals = goals; a.lam = c->lam; a.grad_s0 = grad_s0;
     hipLaunchKernelGGL(backward_sweep_kernel, dim3((c->dm.B + PL - 1) / PL), dim3(PW * 64), 0, c->stream, a);
+    return hipGetLastError();
+}
+
+hipError_t bagel_launch_adam(bagel_ctx *c, float *theta, const float *grad, float *m, float *v, double lr,
+                             double beta1, double beta2, double eps, double corr1, double corr2)
+{
+    hipLaunchKernelGGL(adam_kernel, dim3((c->P + 255) / 256), dim3(256), 0, c->stream, theta, grad, m, v, c->P, lr,
+                       beta1, beta2, eps, corr1, corr2);
     return hipGetLastError();
 }
 

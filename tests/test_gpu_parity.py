@@ -246,3 +246,115 @@ def test_prepare_reports_non_positive_definite():
         ctx.bagel_rollout_loss(g["theta"], g["s0"], g["goals"], loss)
     assert e.value.code == binding.ENOTPREPARED
     ctx.close()
+
+
+# ------------------------------------------------------------------ parameter update and inner loop
+def test_adam_step_against_oracle_and_argument_checks():
+    """bagel_adam_step on float32 arrays against the float64 oracle on the same values, over several
+    updates with changing gradients (state stored in float32, so the bound is float32 rounding)."""
+    import torch
+    from paper_2202_13638_amd import binding
+    cfg = _cfg("tiny")
+    ctx = binding.Bagel(binding.dims_from_config(cfg))
+    P = ctx.P
+    rng = np.random.default_rng(11)
+    theta = rng.standard_normal(P).astype(np.float32)
+    th_o, m_o, v_o = theta.astype(np.float64), np.zeros(P), np.zeros(P)
+    th_g = torch.from_numpy(theta).cuda()
+    m_g, v_g = torch.zeros(P, device="cuda"), torch.zeros(P, device="cuda")
+    # the interface takes the hyper-parameters as float32: the oracle gets exactly those values
+    kw = {k: float(np.float32(x)) for k, x in dict(lr=1e-2, beta1=0.9, beta2=0.999, eps=1e-8).items()}
+    m_scale, v_scale = np.zeros(P), np.zeros(P)      # largest value each stored moment went through
+    for t in range(1, 9):
+        g = (rng.standard_normal(P) * 10.0 ** rng.integers(-5, 2, P)).astype(np.float32)
+        oracle.adam_step(th_o, g, m_o, v_o, t, **kw)
+        ctx.bagel_adam_step(th_g, torch.from_numpy(g).cuda(), m_g, v_g, t, **kw)
+        m_scale, v_scale = np.maximum(m_scale, np.abs(m_o)), np.maximum(v_scale, v_o)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(th_g.cpu().numpy(), th_o, rtol=0, atol=8 * 6e-8 * np.abs(th_o).max() + 8 * 1e-2 * 1e-5)
+    assert (np.abs(m_g.cpu().numpy() - m_o) <= 8 * 6e-8 * m_scale + 1e-30).all()
+    assert (np.abs(v_g.cpu().numpy() - v_o) <= 8 * 6e-8 * v_scale + 1e-30).all()
+    for bad in (dict(step=0), dict(lr=0.0), dict(beta1=1.0), dict(beta2=-0.1), dict(eps=0.0)):
+        args = dict(step=1, **kw)
+        args.update(bad)
+        with pytest.raises(binding.BagelError) as e:
+            ctx.bagel_adam_step(th_g, m_g, m_g, v_g, args.pop("step"), **args)
+        assert e.value.code == binding.EINVAL
+    ctx.close()
+
+
+def test_inner_loop_against_oracle():
+    """bagel_optimize (rollout, gradient, Adam; two alternating sets of initial states and goals) against
+    the oracle's loop, one iteration at a time from the same float32 state (parameters and moments): Adam
+    divides the gradient by its own scale, so a gradient entry that is small against the gradient error
+    moves by up to lr in either direction, and a free-running comparison drifts apart on exactly those
+    entries.  Per iteration: loss to the loss tolerance; parameters with a clear gradient
+    (|g| >= 1e-2 max|g|) to 2e-3 lr (the gradient tolerance, 1e-3 of max|g|, would allow a relative error
+    of 0.1 on such an entry and hence 0.1 lr; the measured gradient error is about 1e-5 max|g|), all others
+    within the largest step Adam can take.  The n-iteration
+    call must then equal n one-iteration calls bit for bit."""
+    import torch
+    from paper_2202_13638_amd import binding
+    cfg = _cfg("small", B=64, H=30)
+    inp = synth.make_inputs(cfg)
+    other = synth.make_inputs(cfg, trial=1)
+    dm = oracle.dims_from_config(cfg)
+    v32 = oracle.prepare_samples(dm, inp).astype(np.float32)
+    s0_sets = np.stack([inp["s0"], other["s0"]])
+    goal_sets = np.stack([inp["goals"], other["goals"]])
+    n = 6
+    hp = {k: float(np.float32(x)) for k, x in dict(lr=1e-2, beta1=0.9, beta2=0.999, eps=1e-8).items()}  # as the interface sees them
+    lr = hp["lr"]
+
+    ctx = binding.Bagel(binding.dims_from_config(cfg))
+    g_in = harness.to_gpu(inp)
+    ctx.bagel_set_samples(g_in["X"], g_in["lengthscale"], g_in["signal_var"], g_in["omega"], g_in["phase"], g_in["w"],
+                          torch.from_numpy(v32).cuda())
+    ss, gs = torch.from_numpy(s0_sets).cuda(), torch.from_numpy(goal_sets).cuda()
+    th = np.asarray(inp["theta"], dtype=np.float32)
+    am, av = np.zeros_like(th), np.zeros_like(th)
+    worst = dict(loss=0.0, clear=0.0, rest=0.0)
+    for i in range(n):
+        # both sides start the iteration from the same float32 parameters and moments
+        th_g, am_g, av_g = (torch.from_numpy(a.copy()).cuda() for a in (th, am, av))
+        hist = torch.zeros(1, device="cuda")
+        # iteration i uses set i % 2: present the sets rotated so that a one-iteration call picks it
+        order = [i % 2, (i + 1) % 2]
+        ctx.bagel_optimize(th_g, am_g, av_g, ss[order].contiguous(), gs[order].contiguous(), 1, hist, first_step=i + 1, **hp)
+        torch.cuda.synchronize()
+        th_o, am_o, av_o = th.astype(np.float64), am.astype(np.float64), av.astype(np.float64)
+        r = oracle.rollout(dm, inp, v32, theta=th_o, s0=s0_sets[i % 2], goals=goal_sets[i % 2], want_states=False)
+        oracle.adam_step(th_o, r["grad_theta"], am_o, av_o, i + 1, **hp)
+        clear = np.abs(r["grad_theta"]) >= 1e-2 * np.abs(r["grad_theta"]).max()
+        assert clear.sum() > 50
+        d = np.abs(th_g.cpu().numpy().astype(np.float64) - th_o)
+        worst["loss"] = max(worst["loss"], abs(float(hist.item()) - r["loss"]) / abs(r["loss"]))
+        worst["clear"] = max(worst["clear"], d[clear].max())
+        worst["rest"] = max(worst["rest"], d.max())
+        # carry the oracle's state on, rounded to what the interface can hold
+        th, am, av = th_o.astype(np.float32), am_o.astype(np.float32), av_o.astype(np.float32)
+    print(f"[parity inner loop] per iteration: loss rel {worst['loss']:.3e}; theta: clear entries "
+          f"{worst['clear']:.3e}, all {worst['rest']:.3e} (lr {lr:.3g})", flush=True)
+    assert worst["loss"] <= harness.TOL_LOSS
+    assert worst["clear"] <= 2e-3 * lr
+    assert worst["rest"] <= 2.1 * lr
+
+    # free-running: n iterations in one call == split calls with the state carried by the caller
+    def run(chunks):
+        theta = g_in["theta"].clone()
+        m, v = torch.zeros_like(theta), torch.zeros_like(theta)
+        hist = torch.zeros(n, device="cuda")
+        done = 0
+        for k in chunks:
+            # a later call starts at iteration `done`: rotate the sets so that its first iteration uses set done % 2
+            order = [done % 2, (done + 1) % 2]
+            ctx.bagel_optimize(theta, m, v, ss[order].contiguous(), gs[order].contiguous(), k, hist[done:done + k],
+                               first_step=done + 1, **hp)
+            done += k
+        torch.cuda.synchronize()
+        return theta, hist
+    t1, h1 = run([n])
+    t2, h2 = run([2, 1, 3])
+    assert torch.equal(t1, t2) and torch.equal(h1, h2)
+    assert bool(torch.isfinite(t1).all()) and float(h1[0]) > 0.0
+    ctx.close()
