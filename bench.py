@@ -13,6 +13,8 @@ Prints ONE JSON line, with
                algorithmic flops per launch / average launch duration measured with HIP events on
                the library's stream during the timed steps, against the float64 vector peak.
   cpu_baseline the float64 oracle timed on this host's cores on a bounded sample of the workload.
+  forward_only, inner_loop   one bagel_rollout_loss call, and two iterations of bagel_optimize (rollout,
+               gradient, Adam update), both outside the timed region.
 """
 from __future__ import annotations
 
@@ -32,7 +34,7 @@ from paper_2202_13638_amd import synth  # noqa: E402
 PEAK_FP64_VECTOR_TFLOPS = 78.6   # MI355X vector float64 (= unpacked float32) peak
 # HBM bytes per launch of gp_step_kernel<8,true> on the stress workload from rocprofv3 --pmc
 # (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, factors from a plain 1 GiB copy): profiles/gp_step_stress_pmc.md
-STRESS_GP_STEP_TRAFFIC_BYTES = 2.508e9 + 8.49e7
+STRESS_GP_STEP_TRAFFIC_BYTES = 2.5015e9 + 1.416e7
 
 
 def algorithmic_flops_per_traj_step(cfg, jac=True):
@@ -80,6 +82,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="stress", choices=list(synth.CONFIGS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the forward-only and inner-loop figures")
     ap.add_argument("--profile-every", type=int, default=8, help="time every n-th sample-evaluation launch")
     ap.add_argument("--ckpt", type=int, default=None, help="override ckpt_interval")
     ap.add_argument("--horizon", type=int, default=None,
@@ -172,6 +175,24 @@ def main():
                      "flops_per_launch": flops_launch,
                      "share_of_step": (avg_ms * cfg.H * (2 if ckpt else 1)) / (1e3 * elapsed / args.steps)},
     }
+    if not args.no_extras:
+        # reported alongside, outside the timed region: the forward pass alone, and the inner loop of
+        # Algorithm 1 (rollout, gradient, Adam update per iteration) on fixed initial states and goals
+        def timed(fn):
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            fn()
+            torch.cuda.synchronize()
+            return time.perf_counter() - t
+        t_fwd = timed(lambda: ctx.bagel_rollout_loss(g["theta"], g["s0"], g["goals"], loss))
+        out["forward_only"] = {"value": traj_steps / t_fwd, "unit": "trajectory-steps/s", "ms_per_call": 1e3 * t_fwd}
+        n_it = 2
+        theta = g["theta"].clone()
+        am, av = torch.zeros_like(theta), torch.zeros_like(theta)
+        hist = torch.zeros(n_it, device="cuda")
+        t_opt = timed(lambda: ctx.bagel_optimize(theta, am, av, g["s0"][None], g["goals"][None], n_it, hist))
+        out["inner_loop"] = {"value": traj_steps * n_it / t_opt, "unit": "trajectory-steps/s", "iterations": n_it,
+                             "ms_per_iteration": 1e3 * t_opt / n_it, "loss": [float(x) for x in hist.cpu()]}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, inp)
     ctx.close()
