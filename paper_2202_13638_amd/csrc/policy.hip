@@ -705,6 +705,122 @@ __global__ __launch_bounds__(1024) void weight_grad_kernel(const float *__restri
     }
 }
 
+// The same GEMM for a wide layer (128 < rows, columns <= 256; B a multiple of 32), with both
+// operands staged through LDS.  The direct kernel above has every wave fetch its own operand rows
+// from global memory, 16 bytes per row and chunk, which re-fetches every cache line four times and
+// caps it at the L2-to-CU bandwidth.  Here the 16 waves of a workgroup load one tile of 32
+// contraction indices (32 trajectories of one tape slot) for all rows of both operands with
+// 128-byte row segments, write it to LDS with rows padded to 36 floats (a lane's 16-byte reads of
+// consecutive rows then fall into different banks), and every wave reads its 64 x 64 block's
+// operands from there.  Tiles are double-buffered: the global loads of tile k+1 are in flight while
+// the 64 MFMAs per wave of tile k run; one barrier per tile.
+constexpr int WG_KC = 32;              // contraction indices per tile
+constexpr int WG_LD = WG_KC + 4;       // padded row length in LDS (floats)
+
+__global__ __launch_bounds__(1024) void weight_grad_tiled_kernel(const float *__restrict__ Dl, const float *__restrict__ Hl,
+                                                                 float *__restrict__ gsplit, int no, int ni, int B,
+                                                                 int n_slots, int tiles_per_split, int w_off, int b_off,
+                                                                 int P)
+{
+    extern __shared__ float lds[];     // [2 stages][A: 256 x WG_LD | B: 256 x WG_LD]
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wr = wave >> 2, wc = wave & 3;
+    const int cl = lane & 31, hf = lane >> 5;
+    const int tiles_per_slot = B / WG_KC;
+    const int total = n_slots * tiles_per_slot;
+    const int t_begin = blockIdx.x * tiles_per_split;
+    const int t_end = min(total, t_begin + tiles_per_split);
+
+    // global -> register staging: thread handles rows r0 and r0 + 128 of both operands, 16 bytes each
+    const int r0 = tid >> 3, kq = tid & 7;
+    const int ra[2] = {min(r0, no - 1), min(r0 + 128, no - 1)};       // rows past the end are clamped: they
+    const int rb[2] = {min(r0, ni - 1), min(r0 + 128, ni - 1)};       // feed accumulators that are never stored
+    float4 ga[2], gb[2];
+    auto load_tile = [&](int t) {
+        const int slot = t / tiles_per_slot;
+        const int bb = (t - slot * tiles_per_slot) * WG_KC + 4 * kq;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            ga[j] = *reinterpret_cast<const float4 *>(Dl + ((size_t)slot * no + ra[j]) * B + bb);
+            gb[j] = *reinterpret_cast<const float4 *>(Hl + ((size_t)slot * ni + rb[j]) * B + bb);
+        }
+    };
+    auto store_tile = [&](int stage) {
+        float *As = lds + stage * (2 * 256 * WG_LD), *Bs = As + 256 * WG_LD;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            *reinterpret_cast<float4 *>(As + (r0 + 128 * j) * WG_LD + 4 * kq) = ga[j];
+            *reinterpret_cast<float4 *>(Bs + (r0 + 128 * j) * WG_LD + 4 * kq) = gb[j];
+        }
+    };
+
+    f16v acc[2][2];
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+#pragma unroll
+        for (int y = 0; y < 2; ++y)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.0f;
+    float bsum[2] = {0.0f, 0.0f};
+
+    if (t_begin < t_end) {
+        load_tile(t_begin);
+        store_tile(0);
+    }
+    __syncthreads();
+    for (int t = t_begin; t < t_end; ++t) {
+        const int stage = (t - t_begin) & 1;
+        if (t + 1 < t_end) load_tile(t + 1);
+        const float *As = lds + stage * (2 * 256 * WG_LD) + (64 * wr + cl) * WG_LD + 4 * hf;
+        const float *Bs = lds + stage * (2 * 256 * WG_LD) + 256 * WG_LD + (64 * wc + cl) * WG_LD + 4 * hf;
+#pragma unroll
+        for (int k8 = 0; k8 < WG_KC / 8; ++k8) {
+            float4 a4[2], b4[2];
+#pragma unroll
+            for (int f = 0; f < 2; ++f) {
+                a4[f] = *reinterpret_cast<const float4 *>(As + 32 * f * WG_LD + 8 * k8);
+                b4[f] = *reinterpret_cast<const float4 *>(Bs + 32 * f * WG_LD + 8 * k8);
+            }
+#pragma unroll
+            for (int f = 0; f < 2; ++f) bsum[f] += (a4[f].x + a4[f].y) + (a4[f].z + a4[f].w);
+#pragma unroll
+            for (int x = 0; x < 2; ++x)
+#pragma unroll
+                for (int y = 0; y < 2; ++y) {
+                    acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[x].x, b4[y].x, acc[x][y], 0, 0, 0);
+                    acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[x].y, b4[y].y, acc[x][y], 0, 0, 0);
+                    acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[x].z, b4[y].z, acc[x][y], 0, 0, 0);
+                    acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[x].w, b4[y].w, acc[x][y], 0, 0, 0);
+                }
+        }
+        if (t + 1 < t_end) store_tile(stage ^ 1);
+        __syncthreads();
+    }
+
+    float *g = gsplit + (size_t)blockIdx.x * P;
+    const int o_base = 64 * wr, i_base = 64 * wc;
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+#pragma unroll
+        for (int y = 0; y < 2; ++y)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int o = o_base + x * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
+                const int i = i_base + y * 32 + cl;
+                if (o < no && i < ni) g[w_off + (size_t)o * ni + i] = acc[x][y][r];
+            }
+    if (wc == 0) {
+#pragma unroll
+        for (int f = 0; f < 2; ++f) {
+            const float tot = bsum[f] + __shfl_xor(bsum[f], 32);
+            const int o = o_base + 32 * f + cl;
+            if (hf == 0 && o < no) g[b_off + o] = tot;
+        }
+    }
+}
+
 // gacc[p] (+)= sum_z gsplit[z][p] in z order; optionally emit grad_theta = (float) gacc
 __global__ void grad_reduce_kernel(const float *__restrict__ gsplit, double *__restrict__ gacc, int P, int ksplit,
                                    bool accumulate, float *__restrict__ grad_theta)
@@ -815,6 +931,22 @@ hipError_t bagel_launch_weight_grad(bagel_ctx *c, int n_slots, bool accumulate, 
     const int nz = (total + per - 1) / per;
     for (int l = 0; l < c->n_layers; ++l) {
         const int no = c->width[l + 1], ni = c->width[l];
+        if (no > 128 && ni > 128 && no <= 256 && ni <= 256 && B % WG_KC == 0) {
+            // wide layer: operands staged through LDS (147 KB of dynamic LDS, raised once per process)
+            const int tiles = n_slots * (B / WG_KC);
+            const int per_t = (tiles + nz - 1) / nz;
+            const size_t lds_bytes = (size_t)2 * 2 * 256 * WG_LD * sizeof(float);
+            static bool raised = false;
+            if (!raised) {
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(weight_grad_tiled_kernel),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+                if (e != hipSuccess) return e;
+                raised = true;
+            }
+            hipLaunchKernelGGL(weight_grad_tiled_kernel, dim3(nz), dim3(1024), lds_bytes, c->stream, c->tape_d[l],
+                               c->tape_h[l], c->gsplit, no, ni, B, n_slots, per_t, c->w_off[l], c->b_off[l], c->P);
+            continue;
+        }
         dim3 grid(nz, (no + 255) / 256, (ni + 255) / 256);
         const int wrows = no >= 256 ? 4 : (no + 63) / 64, wcols = ni >= 256 ? 4 : (ni + 63) / 64;
         if (B % 8 == 0)
