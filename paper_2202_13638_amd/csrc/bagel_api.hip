@@ -309,12 +309,13 @@ static int run_forward(bagel_ctx *c, int t0, int t1, int slot_base, bool jac, bo
     const int K = c->T_tape;
     for (int t = t0; t < t1; ++t) {
         const int slot = jac ? t - slot_base : 0;
-        const int next_slot = jac ? (t + 1 < t1 ? slot + 1 : -1) : 0;
-        BAGEL_HIP(c, bagel_launch_policy_forward(c, slot, theta));
+        const int next_slot = t + 1 < t1 ? (jac ? slot + 1 : 0) : -1;
+        // the policy of the first step runs on its own; every later one is part of the previous step's tail
+        if (t == t0) BAGEL_HIP(c, bagel_launch_policy_forward(c, slot, theta));
         BAGEL_HIP(c, gp_step_timed(c, jac));
-        BAGEL_HIP(c, bagel_launch_finalize(c, jac, slot, nullptr));
         const int ck = (write_ckpt && (t + 1) % K == 0 && t + 1 < c->dm.H) ? (t + 1) / K : -1;
-        BAGEL_HIP(c, bagel_launch_advance(c, t, slot, next_slot, jac, add_cost, write_tape_s, ck, goals, states_out));
+        BAGEL_HIP(c, bagel_launch_step_tail(c, t, slot, next_slot, jac, add_cost, write_tape_s, ck, theta, goals,
+                                            states_out));
     }
     return BAGEL_OK;
 }

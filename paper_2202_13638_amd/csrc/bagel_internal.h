@@ -91,9 +91,6 @@ hipError_t bagel_launch_pack_samples(bagel_ctx *ctx, const float *w, const float
 hipError_t bagel_launch_init_state(bagel_ctx *ctx, const float *s0, const float *goals, float *states_out,
                                    bool tape, bool ckpt);
 hipError_t bagel_launch_restore(bagel_ctx *ctx, int seg, int t, const float *goals);
-// finish step t (reduce partial sums, advance the state, cost, tapes, policy input of step t+1)
-hipError_t bagel_launch_advance(bagel_ctx *ctx, int t, int slot, int next_slot, bool jac, bool add_cost,
-                                bool write_tape_s, int ckpt_index, const float *goals, float *states_out);
 hipError_t bagel_launch_finish_loss(bagel_ctx *ctx, float *loss, float *loss_per_traj);
 hipError_t bagel_launch_eval_io(bagel_ctx *ctx, int phase, const float *x, float *f);
 // add up the per-unit partial sums: value into fbuf, Jacobian into tape slot `slot` (or jac_out if slot < 0)
@@ -102,6 +99,12 @@ hipError_t bagel_launch_finalize(bagel_ctx *ctx, bool jac, int slot, float *jac_
 // ---- policy.hip --------------------------------------------------------------------------
 hipError_t bagel_launch_pack_theta(bagel_ctx *ctx, const float *theta);
 hipError_t bagel_launch_policy_forward(bagel_ctx *ctx, int slot, const float *theta);
+// after the sample evaluation of step t: reduce its partial sums (Jacobian into tape slot `slot` if jac),
+// advance the state, cost against goals[t], tapes, and the policy of step t+1 into tape slot next_slot
+// (no policy if t is the last step or next_slot < 0)
+hipError_t bagel_launch_step_tail(bagel_ctx *ctx, int t, int slot, int next_slot, bool jac, bool add_cost,
+                                  bool write_tape_s, int ckpt_index, const float *theta, const float *goals,
+                                  float *states_out);
 // backward sweep over steps t_hi-1 .. t_lo (tape slot of step k is k - t_lo); grad_s0 is written when t_lo == 0
 hipError_t bagel_launch_backward_sweep(bagel_ctx *ctx, int t_lo, int t_hi, const float *goals, float *grad_s0);
 hipError_t bagel_launch_weight_grad(bagel_ctx *ctx, int n_slots, bool accumulate, float *grad_theta);

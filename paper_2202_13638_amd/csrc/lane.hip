@@ -57,19 +57,6 @@ __global__ __launch_bounds__(BAGEL_BLOCK) void finalize_kernel(lane_args a, int 
     }
 }
 
-// cost at state s against goal g (float goals): quadratic, or the saturating reward of eq. (8) negated
-__device__ __forceinline__ double step_cost(const lane_args &a, const double *s, const float *g)
-{
-    double e = 0.0;
-    for (int j = 0; j < a.dg; ++j) {
-        const double r = s[a.tracked[j]] - (double)g[j];
-        e += (double)a.q[j] * r * r;
-    }
-    if (a.cost_kind == 0) return e;
-    const double sr2 = (double)a.sigma_r * (double)a.sigma_r;
-    return -exp(-e / (2.0 * sr2));
-}
-
 __global__ __launch_bounds__(BAGEL_BLOCK) void init_state_kernel(lane_args a, const float *__restrict__ s0,
                                                                  const float *__restrict__ goals0,
                                                                  float *__restrict__ states_out,
@@ -102,36 +89,6 @@ __global__ __launch_bounds__(BAGEL_BLOCK) void restore_kernel(lane_args a, const
         h0_slot[(size_t)i * a.B + b] = (float)v;
     }
     for (int j = 0; j < a.dg; ++j) h0_slot[(size_t)(a.ds + j) * a.B + b] = goals_t[(size_t)b * a.dg + j];
-}
-
-// Finish step t: s_{t+1} = s_t + f (f from finalize_kernel), cost against goals[t], tapes, and the
-// policy input of step t+1.
-__global__ __launch_bounds__(BAGEL_BLOCK) void advance_kernel(lane_args a, int t, bool jac, bool add_cost,
-                                                              const float *__restrict__ goals_t,
-                                                              const float *__restrict__ goals_next,
-                                                              const double *__restrict__ fbuf,
-                                                              float *__restrict__ states_out_next,
-                                                              float *__restrict__ h0_next,
-                                                              double *__restrict__ ckpt_next)
-{
-    const int b = blockIdx.x * BAGEL_BLOCK + threadIdx.x;
-    if (b >= a.B) return;
-    double s[8];
-    for (int i = 0; i < a.ds; ++i) {
-        s[i] = a.xbuf[(size_t)i * a.B + b] + fbuf[(size_t)i * a.B + b];
-        a.xbuf[(size_t)i * a.B + b] = s[i];
-        if (a.tape_s) a.tape_s[((size_t)(t + 1) * a.ds + i) * a.B + b] = (float)s[i];
-        if (states_out_next) states_out_next[(size_t)b * a.ds + i] = (float)s[i];
-        if (ckpt_next) ckpt_next[(size_t)i * a.B + b] = s[i];
-        if (h0_next) h0_next[(size_t)i * a.B + b] = (float)s[i];
-    }
-    if (add_cost) {
-        float g[8];
-        for (int j = 0; j < a.dg; ++j) g[j] = goals_t[(size_t)b * a.dg + j];
-        a.lpt[b] += step_cost(a, s, g);
-    }
-    if (h0_next)
-        for (int j = 0; j < a.dg; ++j) h0_next[(size_t)(a.ds + j) * a.B + b] = goals_next[(size_t)b * a.dg + j];
 }
 
 // loss = (1/B) sum_b lpt[b], summed in a fixed tree order by one workgroup
@@ -206,22 +163,6 @@ hipError_t bagel_launch_restore(bagel_ctx *c, int seg, int t, const float *goals
     hipLaunchKernelGGL(restore_kernel, lane_grid(c), dim3(BAGEL_BLOCK), 0, c->stream, a,
                        c->ckpt_s + (size_t)seg * c->dm.d_s * B, goals + (size_t)t * B * c->dm.d_g,
                        slot_ptr(c->tape_h[0], 0, c->d_in, c->dm.B));
-    return hipGetLastError();
-}
-
-hipError_t bagel_launch_advance(bagel_ctx *c, int t, int slot, int next_slot, bool jac, bool add_cost,
-                                bool write_tape_s, int ckpt_index, const float *goals, float *states_out)
-{
-    lane_args a = make_args(c);
-    const size_t B = c->dm.B;
-    a.tape_s = write_tape_s ? c->tape_s : nullptr;
-    const bool has_next = t + 1 < c->dm.H;
-    hipLaunchKernelGGL(advance_kernel, lane_grid(c), dim3(BAGEL_BLOCK), 0, c->stream, a, t, jac, add_cost,
-                       goals + (size_t)t * B * c->dm.d_g, has_next ? goals + (size_t)(t + 1) * B * c->dm.d_g : nullptr,
-                       c->fbuf,
-                       states_out ? states_out + (size_t)(t + 1) * B * c->dm.d_s : nullptr,
-                       (has_next && next_slot >= 0) ? slot_ptr(c->tape_h[0], next_slot, c->d_in, c->dm.B) : nullptr,
-                       ckpt_index >= 0 ? c->ckpt_s + (size_t)ckpt_index * c->dm.d_s * B : nullptr);
     return hipGetLastError();
 }
 

@@ -246,23 +246,21 @@ __device__ __forceinline__ void stage_input(const float *__restrict__ src, int n
     }
 }
 
-__global__ __launch_bounds__(PW * 64) void policy_forward_kernel(policy_args a)
-{
-    __shared__ float4 act4[(BAGEL_MAX_HIDDEN / 4) * PL];   // layer input  [K/4][trajectory]
-    __shared__ float4 red4[PW * 4 * 64];                   // partial tiles of split contractions
-    __shared__ float biasS[3][BAGEL_MAX_HIDDEN];
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int c = lane & 31, hf = lane >> 5;
-    const int b0 = blockIdx.x * PL;
-    const int b = b0 + c;
-    const bool live = b < a.B;
+// Per-wave register copy of the forward weights (requested first in a kernel: they arrive while the
+// layer-0 input is being produced), the share of each layer the wave works on, and the biases in LDS.
+// The three arrays are separate locals of the calling kernel so that they are promoted to registers.
+#define FORWARD_WEIGHTS_DECL                                   \
+    float4 w_first[4], w_last[4], w_wide[32];                  \
+    wave_plan p_first, p_last, p_wide
 
-    // every wave first requests its share of all weight matrices; they arrive while the input is staged
-    float4 w_first[4], w_last[4], w_wide[32];
-    const wave_plan p_first = plan_layer(a.width[1], a.kp[0], wave);
-    const wave_plan p_last = plan_layer(a.width[a.nl], a.kp[a.nl - 1], wave);
-    wave_plan p_wide = p_first;
+__device__ __forceinline__ void load_forward_weights(const policy_args &a, int wave, int lane, float4 (&w_first)[4],
+                                                     float4 (&w_last)[4], float4 (&w_wide)[32], wave_plan &p_first,
+                                                     wave_plan &p_last, wave_plan &p_wide,
+                                                     float (*biasS)[BAGEL_MAX_HIDDEN])
+{
+    p_first = plan_layer(a.width[1], a.kp[0], wave);
+    p_last = plan_layer(a.width[a.nl], a.kp[a.nl - 1], wave);
+    p_wide = p_first;
     load_wave_weights<1>(w_first, a.Wp + a.wp_off[0], a.kp[0], p_first, lane);
     if (a.nl == 3) {
         p_wide = plan_layer(a.width[2], a.kp[1], wave);
@@ -271,9 +269,20 @@ __global__ __launch_bounds__(PW * 64) void policy_forward_kernel(policy_args a)
     load_wave_weights<1>(w_last, a.Wp + a.wp_off[a.nl - 1], a.kp[a.nl - 1], p_last, lane);
     for (int l = 0; l < a.nl; ++l)
         for (int j = threadIdx.x; j < a.width[l + 1]; j += PW * 64) biasS[l][j] = a.theta[a.b_off[l] + j];
-    stage_input(a.h[0], a.width[0], a.kp[0], a.B, b0, act4);
-    __syncthreads();
+}
 
+// The layers of pi_theta for the 32 trajectories of a workgroup, input in act4 (all waves past a
+// barrier after it was written).  Writes the tape (h of the hidden layers, the action before
+// scaling) and the action into xbuf.
+__device__ __forceinline__ void policy_layers(const policy_args &a, const float4 (&w_first)[4],
+                                              const float4 (&w_last)[4], const float4 (&w_wide)[32],
+                                              const wave_plan &p_first, const wave_plan &p_last,
+                                              const wave_plan &p_wide, int wave, int lane, int b0, float4 *act4,
+                                              float4 *red4, const float (*biasS)[BAGEL_MAX_HIDDEN])
+{
+    const int c = lane & 31, hf = lane >> 5;
+    const int b = b0 + c;
+    const bool live = b < a.B;
     for (int l = 0; l < a.nl; ++l) {
         const int nj = a.width[l + 1];
         const wave_plan p = l == 0 ? p_first : (l == a.nl - 1 ? p_last : p_wide);
@@ -315,6 +324,126 @@ __global__ __launch_bounds__(PW * 64) void policy_forward_kernel(policy_args a)
         }
         __syncthreads();
     }
+}
+
+// Policy of one step on its own (first step of a rollout or of a replayed segment): input from tape slot h[0].
+__global__ __launch_bounds__(PW * 64) void policy_forward_kernel(policy_args a)
+{
+    __shared__ float4 act4[(BAGEL_MAX_HIDDEN / 4) * PL];   // layer input  [K/4][trajectory]
+    __shared__ float4 red4[PW * 4 * 64];                   // partial tiles of split contractions
+    __shared__ float biasS[3][BAGEL_MAX_HIDDEN];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int b0 = blockIdx.x * PL;
+    FORWARD_WEIGHTS_DECL;
+    load_forward_weights(a, wave, lane, w_first, w_last, w_wide, p_first, p_last, p_wide, biasS);
+    stage_input(a.h[0], a.width[0], a.kp[0], a.B, b0, act4);
+    __syncthreads();
+    policy_layers(a, w_first, w_last, w_wide, p_first, p_last, p_wide, wave, lane, b0, act4, red4, biasS);
+}
+
+// ---- end of step t and policy of step t+1 in one launch -------------------------------------
+// After the sample evaluation of step t: add up its partial sums (value f and Jacobian J_f, as in
+// finalize_kernel), advance the state s_{t+1} = s_t + f (state increments as GP targets, Sec. III-A),
+// add the cost of s_{t+1} against the goal of step t (Algorithm 1, return accumulation), write the
+// tapes, and - unless this was the last step - run pi_theta([s_{t+1} ; g_{t+1}]) for the same 32
+// trajectories straight from LDS.  The weights are requested before the reduction starts.
+struct tail_args {
+    int D, M, dg, ngk, ngl, ncomp;      // ncomp = 1 (value only) or 1 + D (with Jacobian)
+    int cost_kind, add_cost, do_policy;
+    float sigma_r;
+    int tracked[8];
+    float q[8];
+    const double *A, *amp, *part;       // part: [groups][1+D][B]
+    double *lpt;                        // [B]
+    float *tape_s_next;                 // [d_s][B] slot of s_{t+1}, or null
+    float *states_out_next;             // [B][d_s] or null
+    double *ckpt_next;                  // [d_s][B] or null
+    const float *goals_t, *goals_next;  // [B][d_g]; goals_next null at the last step
+    float *jdst;                        // tape slot [M][D][B] of step t, or null
+};
+
+__global__ __launch_bounds__(PW * 64) void step_tail_kernel(tail_args r, policy_args a)
+{
+    __shared__ float4 act4[(BAGEL_MAX_HIDDEN / 4) * PL];
+    __shared__ float4 red4[PW * 4 * 64];
+    __shared__ float biasS[3][BAGEL_MAX_HIDDEN];
+    __shared__ double fS[8][PL], sS[8][PL];
+    constexpr double LN2 = 0.69314718055994530942, TWO_PI = 6.28318530717958647693;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int b0 = blockIdx.x * PL;
+    const int bl = tid & (PL - 1), row = tid >> 5;      // 16 rows x 32 trajectories
+    const bool liveq = b0 + bl < a.B;
+    const int bq = liveq ? b0 + bl : a.B - 1;
+    const int B = a.B, ds = a.ds;
+
+    FORWARD_WEIGHTS_DECL;
+    if (r.do_policy) load_forward_weights(a, wave, lane, w_first, w_last, w_wide, p_first, p_last, p_wide, biasS);
+
+    // ---- partial sums -> f (LDS) and J_f (tape): one (output m, component) pair per thread and pass
+    const size_t stride = (size_t)(1 + r.D) * B;
+    for (int qi = row; qi < r.M * r.ncomp; qi += 16) {
+        const int m = qi / r.ncomp, comp = qi - m * r.ncomp;
+        const double *pk = r.part + (size_t)(m * r.ngk) * stride + bq;
+        const double *pr = r.part + (size_t)(r.M * r.ngk + m * r.ngl) * stride + bq;
+        double u = 0.0;
+        for (int c = 0; c < r.ngk; ++c) u += pk[c * stride];
+        const double amp = r.amp[m];
+        if (comp == 0) {
+            double p = 0.0;
+            for (int c = 0; c < r.ngl; ++c) p += pr[c * stride];
+            fS[m][bl] = amp * p + u;
+        } else {
+            const int d = comp - 1;
+            double gk = 0.0, gr = 0.0;
+            for (int c = 0; c < r.ngk; ++c) gk += pk[c * stride + (size_t)comp * B];
+            for (int c = 0; c < r.ngl; ++c) gr += pr[c * stride + (size_t)comp * B];
+            const double x = a.xbuf[(size_t)d * B + bq];
+            const double J = -amp * TWO_PI * gr + LN2 * (gk - r.A[m * r.D + d] * x * u);
+            if (liveq) r.jdst[(size_t)(m * r.D + d) * B + bq] = (float)J;
+        }
+    }
+    __syncthreads();
+
+    // ---- s_{t+1}, tapes, and the policy input [s_{t+1} ; g_{t+1}] (rows up to 32 zero) in act4
+    float *act1 = reinterpret_cast<float *>(act4);
+    const int d_in = a.width[0];
+    for (int k = row; k < 32; k += 16) {
+        float hin = 0.0f;
+        if (k < ds) {
+            const double s = a.xbuf[(size_t)k * B + bq] + fS[k][bl];
+            sS[k][bl] = s;
+            hin = (float)s;
+            if (liveq) {
+                a.xbuf[(size_t)k * B + bq] = s;
+                if (r.tape_s_next) r.tape_s_next[(size_t)k * B + bq] = hin;
+                if (r.states_out_next) r.states_out_next[(size_t)bq * ds + k] = hin;
+                if (r.ckpt_next) r.ckpt_next[(size_t)k * B + bq] = s;
+            }
+        } else if (k < d_in && r.goals_next) {
+            hin = r.goals_next[(size_t)bq * r.dg + (k - ds)];
+        }
+        if (r.do_policy) {
+            act1[((k >> 2) * PL + bl) * 4 + (k & 3)] = hin;
+            if (liveq && k < d_in) a.h[0][(size_t)k * B + bq] = hin;
+        }
+    }
+    __syncthreads();
+    if (r.add_cost && row == 0 && liveq) {
+        double e = 0.0;
+        for (int j = 0; j < r.dg; ++j) {
+            const double dlt = sS[r.tracked[j]][bl] - (double)r.goals_t[(size_t)bq * r.dg + j];
+            e += (double)r.q[j] * dlt * dlt;
+        }
+        if (r.cost_kind == 1) {
+            const double sr2 = (double)r.sigma_r * (double)r.sigma_r;
+            e = -exp(-e / (2.0 * sr2));
+        }
+        r.lpt[bq] += e;
+    }
+    if (r.do_policy) policy_layers(a, w_first, w_last, w_wide, p_first, p_last, p_wide, wave, lane, b0, act4, red4, biasS);
 }
 
 // ---- backward sweep ------------------------------------------------------------------------
@@ -889,6 +1018,32 @@ hipError_t bagel_launch_policy_forward(bagel_ctx *c, int slot, const float *thet
     policy_args a = make_pargs(c, slot);
     a.theta = theta;
     hipLaunchKernelGGL(policy_forward_kernel, dim3((c->dm.B + PL - 1) / PL), dim3(PW * 64), 0, c->stream, a);
+    return hipGetLastError();
+}
+
+hipError_t bagel_launch_step_tail(bagel_ctx *c, int t, int slot, int next_slot, bool jac, bool add_cost,
+                                  bool write_tape_s, int ckpt_index, const float *theta, const float *goals,
+                                  float *states_out)
+{
+    const size_t B = c->dm.B;
+    const bool has_next = t + 1 < c->dm.H && next_slot >= 0;
+    tail_args r;
+    r.D = c->D; r.M = c->M; r.dg = c->dm.d_g;
+    r.ngk = (c->nck + 3) / 4; r.ngl = (c->ncl + 3) / 4;
+    r.ncomp = jac ? 1 + c->D : 1;
+    r.cost_kind = c->dm.cost_kind; r.add_cost = add_cost ? 1 : 0; r.do_policy = has_next ? 1 : 0;
+    r.sigma_r = c->dm.sigma_r;
+    for (int j = 0; j < 8; ++j) { r.tracked[j] = c->dm.tracked[j]; r.q[j] = c->dm.q[j]; }
+    r.A = c->A; r.amp = c->amp; r.part = c->part; r.lpt = c->lpt;
+    r.tape_s_next = write_tape_s ? c->tape_s + (size_t)(t + 1) * c->dm.d_s * B : nullptr;
+    r.states_out_next = states_out ? states_out + (size_t)(t + 1) * B * c->dm.d_s : nullptr;
+    r.ckpt_next = ckpt_index >= 0 ? c->ckpt_s + (size_t)ckpt_index * c->dm.d_s * B : nullptr;
+    r.goals_t = goals + (size_t)t * B * c->dm.d_g;
+    r.goals_next = has_next ? goals + (size_t)(t + 1) * B * c->dm.d_g : nullptr;
+    r.jdst = jac ? c->tape_J + (size_t)slot * c->M * c->D * B : nullptr;
+    policy_args a = make_pargs(c, has_next ? next_slot : 0);
+    a.theta = theta;
+    hipLaunchKernelGGL(step_tail_kernel, dim3((c->dm.B + PL - 1) / PL), dim3(PW * 64), 0, c->stream, r, a);
     return hipGetLastError();
 }
 
