@@ -85,6 +85,8 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="skip the forward-only and inner-loop figures")
     ap.add_argument("--profile-every", type=int, default=8, help="time every n-th sample-evaluation launch")
     ap.add_argument("--ckpt", type=int, default=None, help="override ckpt_interval")
+    ap.add_argument("--trajectories-per-sample", type=int, default=1,
+                    help="supplementary runs: G trajectories share one function sample (S = B / G)")
     ap.add_argument("--horizon", type=int, default=None,
                     help="profiling runs only: shorter horizon (per-launch figures do not depend on it)")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -103,10 +105,12 @@ def main():
     if args.horizon is not None:
         cfg = synth.scaled(cfg, H=args.horizon)
     t0 = time.perf_counter()
-    inp = synth.make_inputs(cfg)
+    S = cfg.B // args.trajectories_per_sample
+    inp = synth.make_inputs(cfg, S=S)
     t_gen = time.perf_counter() - t0
 
-    dims = binding.dims_from_config(cfg) if args.ckpt is None else binding.dims_from_config(cfg, ckpt_interval=args.ckpt)
+    kw = {} if args.ckpt is None else {"ckpt_interval": args.ckpt}
+    dims = binding.dims_from_config(cfg, S=S, **kw)
     ctx = binding.Bagel(dims)
     g = {k: torch.from_numpy(a).cuda() for k, a in inp.items()}
     torch.cuda.synchronize()
@@ -163,7 +167,7 @@ def main():
         "vs_baseline": None,
         "dtype": "f64",
         "data": "synthetic",
-        "config": {"workload": cfg.name, "N": cfg.N, "D": cfg.D, "M": cfg.M, "L": cfg.L, "B": cfg.B, "S": cfg.B,
+        "config": {"workload": cfg.name, "N": cfg.N, "D": cfg.D, "M": cfg.M, "L": cfg.L, "B": cfg.B, "S": S,
                    "H": cfg.H, "policy": [cfg.d_in, *cfg.hidden, cfg.d_a], "ckpt_interval": ckpt,
                    "arithmetic": "kernel row and feature phase in f64, policy and sin/cos in f32, f32 interface",
                    "prepare_s": round(t_prep, 3), "input_generation_s": round(t_gen, 1),
@@ -193,7 +197,7 @@ def main():
         t_opt = timed(lambda: ctx.bagel_optimize(theta, am, av, g["s0"][None], g["goals"][None], n_it, hist))
         out["inner_loop"] = {"value": traj_steps * n_it / t_opt, "unit": "trajectory-steps/s", "iterations": n_it,
                              "ms_per_iteration": 1e3 * t_opt / n_it, "loss": [float(x) for x in hist.cpu()]}
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.trajectories_per_sample == 1:
         out["cpu_baseline"] = cpu_baseline(cfg, inp)
     ctx.close()
     print(json.dumps(out))

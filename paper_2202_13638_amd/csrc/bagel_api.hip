@@ -112,10 +112,15 @@ extern "C" int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_s
     const int target = env_int("BAGEL_TARGET_WGS", 4096);
     int chunk = 1024;
     while (chunk > 32 && items / chunk < target) chunk /= 2;
-    // fewer, longer units for the training points when there are plenty of them: the kernel's speed does
-    // not depend on the split, the size of the partial-sum array does
-    c->CK = env_int("BAGEL_CK", (N / chunk >= 16) ? 2 * chunk : chunk);
-    c->CL = env_int("BAGEL_CL", chunk);
+    // Longer units for the training points when there are plenty of them (fewer partial sums), shorter
+    // ones for the features of a large problem: workgroups are dispatched in grid order, training-point
+    // units first, so short feature units at the end fill the tail of the launch.  Measured on MI355X:
+    // stress 0.650 ms per launch at (CK, CL) = (1024, 512), 0.628 ms at (1024, 256); the large-policy
+    // step 140.6 ms at (128, 64), 136.8 ms at (256, 64).
+    const int ck_default = N / chunk >= 32 ? 4 * chunk : (N / chunk >= 16 ? 2 * chunk : chunk);
+    const int cl_default = (chunk >= 512 && L / chunk >= 8) ? chunk / 2 : chunk;
+    c->CK = env_int("BAGEL_CK", ck_default);
+    c->CL = env_int("BAGEL_CL", cl_default);
     c->CK = (c->CK + 3) & ~3;
     c->CL = (c->CL + 3) & ~3;
     c->nck = (N + c->CK - 1) / c->CK;
