@@ -34,7 +34,7 @@ from paper_2202_13638_amd import synth  # noqa: E402
 PEAK_FP64_VECTOR_TFLOPS = 78.6   # MI355X vector float64 (= unpacked float32) peak
 # HBM bytes per launch of gp_step_kernel<8,true> on the stress workload from rocprofv3 --pmc
 # (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, factors from a plain 1 GiB copy): profiles/gp_step_stress_pmc.md
-STRESS_GP_STEP_TRAFFIC_BYTES = 2.5015e9 + 1.416e7
+STRESS_GP_STEP_TRAFFIC_BYTES = 2.5015e9 + 2.123e7
 
 
 def algorithmic_flops_per_traj_step(cfg, jac=True):
