@@ -87,6 +87,12 @@ def lib():
         L.oracle_policy.argtypes = [C.POINTER(Dims), _DP, _DP, _DP]
         L.oracle_rollout.restype = C.c_int
         L.oracle_rollout.argtypes = [C.POINTER(Dims)] + [_DP] * 15
+        L.oracle_posterior_prepare.restype = C.c_int
+        L.oracle_posterior_prepare.argtypes = [C.POINTER(Dims)] + [_DP] * 7
+        L.oracle_posterior_moments.restype = None
+        L.oracle_posterior_moments.argtypes = [C.POINTER(Dims)] + [_DP] * 11
+        L.oracle_posterior_rollout.restype = C.c_int
+        L.oracle_posterior_rollout.argtypes = [C.POINTER(Dims)] + [_DP] * 14
         L.oracle_adam_step.restype = None
         L.oracle_adam_step.argtypes = [C.c_int, _DP, _DP, _DP, _DP, C.c_int] + [C.c_double] * 4
         _lib = L
@@ -206,3 +212,56 @@ def optimize(dm: Dims, m: Dict[str, np.ndarray], v, theta0, s0_sets, goal_sets, 
         losses[i] = r["loss"]
         adam_step(theta, r["grad_theta"], am, av, first_step + i, **adam)
     return theta, am, av, losses
+
+
+def posterior_prepare(dm: Dims, m: Dict[str, np.ndarray]):
+    """alpha[M,N] = K_hat^-1 y and Kinv[M,N,N] = K_hat^-1 (eq. (2), (3)) from X y lengthscale signal_var noise_var."""
+    a = {k: _d(m[k]) for k in ("X", "y", "lengthscale", "signal_var", "noise_var")}
+    M = dm.d_s
+    alpha = np.empty((M, dm.N))
+    Kinv = np.empty((M, dm.N, dm.N))
+    rc = lib().oracle_posterior_prepare(C.byref(dm), _p(a["X"]), _p(a["y"]), _p(a["lengthscale"]), _p(a["signal_var"]),
+                                        _p(a["noise_var"]), _p(alpha), _p(Kinv))
+    if rc != 0:
+        raise FloatingPointError(f"oracle_posterior_prepare failed with code {rc}")
+    return alpha, Kinv
+
+
+def posterior_moments(dm: Dims, m: Dict[str, np.ndarray], alpha, Kinv, x, jac: bool = True):
+    """mu[M], var[M] (and dmu[M,D], dvar[M,D]) of the predictive posterior at x[D]."""
+    a = {k: _d(m[k]) for k in ("X", "lengthscale", "signal_var")}
+    alpha, Kinv, x = _d(alpha), _d(Kinv), _d(x)
+    M, D = dm.d_s, dm.d_s + dm.d_a
+    mu, var = np.empty(M), np.empty(M)
+    dmu = np.empty((M, D)) if jac else None
+    dvar = np.empty((M, D))
+    work = np.empty(2 * dm.N)
+    lib().oracle_posterior_moments(C.byref(dm), _p(a["X"]), _p(a["lengthscale"]), _p(a["signal_var"]), _p(alpha),
+                                   _p(Kinv), _p(x), _p(mu), _p(var), _p(dmu), _p(dvar), _p(work))
+    return (mu, var, dmu, dvar) if jac else (mu, var)
+
+
+def posterior_rollout(dm: Dims, m: Dict[str, np.ndarray], alpha, Kinv, xi, theta=None, s0=None, goals=None, *,
+                      grad: bool = True, want_states: bool = True):
+    """Algorithm 1 with per-step posterior draws f = mu + sqrt(var) xi, xi[H,B,M].  Returns the dict of rollout()."""
+    a = {k: _d(m[k]) for k in ("X", "lengthscale", "signal_var")}
+    alpha, Kinv, xi = _d(alpha), _d(Kinv), _d(xi)
+    theta = _d(m["theta"] if theta is None else theta)
+    s0 = _d(m["s0"] if s0 is None else s0)
+    goals = _d(m["goals"] if goals is None else goals)
+    M = dm.d_s
+    assert alpha.shape == (M, dm.N) and Kinv.shape == (M, dm.N, dm.N) and xi.shape == (dm.H, dm.B, M)
+    assert s0.shape == (dm.B, dm.d_s) and goals.shape == (dm.H, dm.B, dm.d_g)
+    P = num_params(dm)
+    assert theta.shape == (P,)
+    loss = np.zeros(1)
+    lpt = np.empty(dm.B)
+    states = np.empty((dm.H + 1, dm.B, dm.d_s)) if want_states else None
+    g = np.zeros(P) if grad else None
+    gs0 = np.zeros((dm.B, dm.d_s)) if grad else None
+    rc = lib().oracle_posterior_rollout(C.byref(dm), _p(a["X"]), _p(a["lengthscale"]), _p(a["signal_var"]), _p(alpha),
+                                        _p(Kinv), _p(xi), _p(theta), _p(s0), _p(goals), _p(loss), _p(lpt), _p(states),
+                                        _p(g), _p(gs0))
+    if rc != 0:
+        raise RuntimeError(f"oracle_posterior_rollout failed with code {rc}")
+    return {"loss": float(loss[0]), "loss_per_traj": lpt, "states": states, "grad_theta": g, "grad_s0": gs0}

@@ -22,6 +22,15 @@
  *                           running cost) and loss = (1/b) * sum as in eq. (10),
  *                           (11); backward pass = the adjoint of exactly those
  *                           steps, summed over trajectories and time.
+ *   oracle_posterior_*      the sampler of Algorithm 1 as printed: at every step the next
+ *                           state is drawn from the predictive posterior, eq. (9), with the
+ *                           moments of eq. (2) (zero prior mean) and eq. (3), one independent
+ *                           GP per state (Sec. III-A).  The draw is reparameterised,
+ *                           f = mu(x) + sqrt(var(x)) * xi with xi ~ N(0,1) handed in, so that
+ *                           the loss is differentiable in theta (Sec. III-B differentiates
+ *                           through the sampled transitions).  Exact moments from K_hat^-1;
+ *                           the Lanczos variance estimates the paper uses to speed this up are
+ *                           an approximation of the same quantity and are not reproduced.
  *   oracle_adam_step        Algorithm 1, the parameter update: Sec. III-C names
  *                           Adam (Kingma & Ba) as the gradient-descent rule; the
  *                           update is that paper's Algorithm 1 with bias-corrected
@@ -34,7 +43,9 @@
  * against eq. (2), (3); feature inner products against eq. (4); central finite
  * differences and an independent autodiff graph for the gradient; H = 1 closed
  * form; additivity over trajectories; the Adam step against its closed form for a
- * constant gradient and against torch.optim.Adam.  The numerical values of a rollout on the
+ * constant gradient and against torch.optim.Adam; the posterior moments against scipy's
+ * Cholesky solve, the N = 1 closed form, finite differences, and (xi = 0) the pathwise rollout
+ * with a zero draw.  The numerical values of a rollout on the
  * synthetic workloads themselves are not printed anywhere in the paper.
  *
  * Conventions: row-major arrays; X[N][D]; per output m: ell[M][D], sf2[M]
@@ -304,6 +315,33 @@ static double step_cost(const oracle_dims *dm, const double *s, const double *g,
     return c;
 }
 
+/* The sampled transition of one trajectory at one step: f[M] = sampled state increment at x[D]
+ * and, if J != NULL, J[M][D] = d f / d x.  Two samplers implement it (pathwise function samples,
+ * per-step posterior draws); the rollout below is the same for both. */
+typedef struct transition {
+    void (*eval)(const struct transition *self, int b, int t, const double *x, double *f, double *J);
+} transition;
+
+typedef struct {
+    transition base;
+    const oracle_dims *dm;
+    const double *X, *ell, *sf2, *omega, *phase, *w, *v;
+    int per_sample;
+} pathwise_transition;
+
+static void pathwise_eval(const transition *self, int b, int t, const double *x, double *f, double *J)
+{
+    const pathwise_transition *p = (const pathwise_transition *)self;
+    const int M = p->dm->d_s, sidx = b / p->per_sample;
+    (void)t;
+    oracle_sample_eval(p->dm, p->X, p->ell, p->sf2, p->omega, p->phase, p->w + (size_t)sidx * M * p->dm->L,
+                       p->v + (size_t)sidx * M * p->dm->N, x, f, J);
+}
+
+static int rollout_core(const oracle_dims *dm, const transition *tr, const double *theta, const double *s0,
+                        const double *goals, double *loss, double *loss_per_traj, double *states,
+                        double *grad_theta, double *grad_s0);
+
 /*
  * Algorithm 1, forward and backward pass.
  *   s0[B][d_s], goals[H][B][d_g]; the cost at s_{t+1} uses goals[t] (the goal the policy saw).
@@ -317,10 +355,21 @@ int oracle_rollout(const oracle_dims *dm, const double *X, const double *ell, co
                    double *loss, double *loss_per_traj, double *states,
                    double *grad_theta, double *grad_s0)
 {
+    if (dm->S < 1 || dm->B % dm->S != 0) return -1;
+    pathwise_transition p;
+    p.base.eval = pathwise_eval;
+    p.dm = dm; p.X = X; p.ell = ell; p.sf2 = sf2; p.omega = omega; p.phase = phase; p.w = w; p.v = v;
+    p.per_sample = dm->B / dm->S;
+    return rollout_core(dm, &p.base, theta, s0, goals, loss, loss_per_traj, states, grad_theta, grad_s0);
+}
+
+static int rollout_core(const oracle_dims *dm, const transition *tr, const double *theta, const double *s0,
+                        const double *goals, double *loss, double *loss_per_traj, double *states,
+                        double *grad_theta, double *grad_s0)
+{
     const int ds = dm->d_s, da = dm->d_a, dg = dm->d_g, D = ds + da, M = ds;
-    const int N = dm->N, L = dm->L, S = dm->S, B = dm->B, H = dm->H;
-    if (S < 1 || B % S != 0 || ds > 8 || dg > 8 || D > 16) return -1;
-    const int per_sample = B / S;
+    const int B = dm->B, H = dm->H;
+    if (ds > 8 || dg > 8 || D > 16) return -1;
     const int P = oracle_num_params(dm);
     const int nl = n_layers(dm);
     int wd[4];
@@ -357,9 +406,6 @@ int oracle_rollout(const oracle_dims *dm, const double *X, const double *ell, co
         } else {
 #pragma omp for schedule(static)
             for (int b = 0; b < B; ++b) {
-                const int sidx = b / per_sample;
-                const double *w_s = w + (size_t)sidx * M * L;
-                const double *v_s = v + (size_t)sidx * M * N;
                 double x[16], f[8], a[8], h0[16];
                 for (int i = 0; i < ds; ++i) S_tape[i] = s0[(size_t)b * ds + i];
                 double total = 0.0;
@@ -372,8 +418,7 @@ int oracle_rollout(const oracle_dims *dm, const double *X, const double *ell, co
                     policy_forward(dm, theta, h0, A_tape + (size_t)t * act_sz, a);
                     for (int i = 0; i < ds; ++i) x[i] = s[i];
                     for (int i = 0; i < da; ++i) x[ds + i] = a[i];
-                    oracle_sample_eval(dm, X, ell, sf2, omega, phase, w_s, v_s, x, f,
-                                       want_grad ? J_tape + (size_t)t * M * D : NULL);
+                    tr->eval(tr, b, t, x, f, want_grad ? J_tape + (size_t)t * M * D : NULL);
                     double *sn = S_tape + (size_t)(t + 1) * ds;
                     for (int i = 0; i < ds; ++i) sn[i] = s[i] + f[i];
                     total += step_cost(dm, sn, g, NULL);
@@ -467,6 +512,116 @@ int oracle_rollout(const oracle_dims *dm, const double *X, const double *ell, co
     free(gpart);
     free(lpt);
     return err;
+}
+
+/*
+ * Exact GP posterior, eq. (2) and (3), per output m:
+ *   alpha_m = K_hat_m^-1 y_m,   Kinv_m = K_hat_m^-1   (K_hat = K + sigma_n^2 I, kernel of eq. (4)).
+ * alpha[M][N], Kinv[M][N][N].  Returns 0, or 1 + m if K_hat_m is not positive definite.
+ */
+int oracle_posterior_prepare(const oracle_dims *dm, const double *X, const double *y, const double *ell,
+                             const double *sf2, const double *sn2, double *alpha, double *Kinv)
+{
+    const int N = dm->N, M = dm->d_s, D = dm->d_s + dm->d_a;
+    double *K = (double *)malloc((size_t)N * N * sizeof(double));
+    double *col = (double *)malloc((size_t)N * sizeof(double));
+    if (!K || !col) { free(K); free(col); return -2; }
+    int rc = 0;
+    for (int m = 0; m < M && !rc; ++m) {
+        for (int i = 0; i < N; ++i)
+            for (int j = 0; j < N; ++j)
+                K[(size_t)i * N + j] = oracle_kernel(D, ell + (size_t)m * D, sf2[m], X + (size_t)i * D, X + (size_t)j * D) +
+                                       (i == j ? sn2[m] : 0.0);
+        if (cholesky_lower(K, N)) { rc = 1 + m; break; }
+        for (int i = 0; i < N; ++i) alpha[(size_t)m * N + i] = y[(size_t)m * N + i];
+        cholesky_solve(K, N, alpha + (size_t)m * N);
+        for (int j = 0; j < N; ++j) {                      /* column j of the inverse */
+            for (int i = 0; i < N; ++i) col[i] = (i == j) ? 1.0 : 0.0;
+            cholesky_solve(K, N, col);
+            for (int i = 0; i < N; ++i) Kinv[((size_t)m * N + i) * N + j] = col[i];
+        }
+    }
+    free(K); free(col);
+    return rc;
+}
+
+#define ORACLE_VAR_FLOOR 1e-12   /* variance below this is held there (and its derivative is zero) */
+
+/*
+ * Posterior moments at x[D] for every output: mu[M] (eq. (2), zero prior mean), var[M] (eq. (3),
+ * latent function: no observation noise added), and optionally their derivatives dmu[M][D],
+ * dvar[M][D] with respect to x.  work: 2 N doubles.
+ */
+void oracle_posterior_moments(const oracle_dims *dm, const double *X, const double *ell, const double *sf2,
+                              const double *alpha, const double *Kinv, const double *x, double *mu, double *var,
+                              double *dmu, double *dvar, double *work)
+{
+    const int N = dm->N, M = dm->d_s, D = dm->d_s + dm->d_a;
+    double *k = work, *q = work + N;
+    for (int m = 0; m < M; ++m) {
+        const double *l = ell + (size_t)m * D;
+        for (int n = 0; n < N; ++n) k[n] = oracle_kernel(D, l, sf2[m], x, X + (size_t)n * D);
+        double mean = 0.0, quad = 0.0;
+        for (int i = 0; i < N; ++i) {
+            double acc = 0.0;
+            const double *row = Kinv + ((size_t)m * N + i) * N;
+            for (int j = 0; j < N; ++j) acc += row[j] * k[j];
+            q[i] = acc;
+            mean += alpha[(size_t)m * N + i] * k[i];
+            quad += k[i] * acc;
+        }
+        mu[m] = mean;
+        double vv = sf2[m] - quad;                     /* k(x,x) = alpha^2 */
+        const int floored = vv < ORACLE_VAR_FLOOR;
+        var[m] = floored ? ORACLE_VAR_FLOOR : vv;
+        if (dmu) {
+            for (int d = 0; d < D; ++d) {
+                double a = 0.0, b = 0.0;
+                for (int n = 0; n < N; ++n) {
+                    const double dk = k[n] * (X[(size_t)n * D + d] - x[d]) / (l[d] * l[d]);   /* d k_n / d x_d */
+                    a += alpha[(size_t)m * N + n] * dk;
+                    b += q[n] * dk;
+                }
+                dmu[(size_t)m * D + d] = a;
+                dvar[(size_t)m * D + d] = floored ? 0.0 : -2.0 * b;
+            }
+        }
+    }
+}
+
+typedef struct {
+    transition base;
+    const oracle_dims *dm;
+    const double *X, *ell, *sf2, *alpha, *Kinv, *xi;     /* xi[H][B][M] standard normal draws */
+} posterior_transition;
+
+static void posterior_eval(const transition *self, int b, int t, const double *x, double *f, double *J)
+{
+    const posterior_transition *p = (const posterior_transition *)self;
+    const int M = p->dm->d_s, D = p->dm->d_s + p->dm->d_a, N = p->dm->N;
+    double mu[8], var[8], dmu[8 * 16], dvar[8 * 16];
+    double *work = (double *)malloc((size_t)2 * N * sizeof(double));
+    oracle_posterior_moments(p->dm, p->X, p->ell, p->sf2, p->alpha, p->Kinv, x, mu, var, J ? dmu : NULL, dvar, work);
+    free(work);
+    for (int m = 0; m < M; ++m) {
+        const double z = p->xi[((size_t)t * p->dm->B + b) * M + m];
+        const double sd = sqrt(var[m]);
+        f[m] = mu[m] + sd * z;                          /* eq. (9), reparameterised */
+        if (J)
+            for (int d = 0; d < D; ++d) J[(size_t)m * D + d] = dmu[(size_t)m * D + d] + z * dvar[(size_t)m * D + d] / (2.0 * sd);
+    }
+}
+
+/* Algorithm 1 with the per-step posterior sampler; arguments as oracle_rollout, xi[H][B][M]. */
+int oracle_posterior_rollout(const oracle_dims *dm, const double *X, const double *ell, const double *sf2,
+                             const double *alpha, const double *Kinv, const double *xi, const double *theta,
+                             const double *s0, const double *goals, double *loss, double *loss_per_traj,
+                             double *states, double *grad_theta, double *grad_s0)
+{
+    posterior_transition p;
+    p.base.eval = posterior_eval;
+    p.dm = dm; p.X = X; p.ell = ell; p.sf2 = sf2; p.alpha = alpha; p.Kinv = Kinv; p.xi = xi;
+    return rollout_core(dm, &p.base, theta, s0, goals, loss, loss_per_traj, states, grad_theta, grad_s0);
 }
 
 /*

@@ -196,3 +196,10 @@ def subset_trajectories(cfg: Config, inp: Dict[str, np.ndarray], idx) -> Tuple[C
         out[k] = np.ascontiguousarray(inp[k][idx])
     out["goals"] = np.ascontiguousarray(inp["goals"][:, idx])
     return scaled(cfg, B=len(idx)), out
+
+
+def make_normal_draws(cfg: Config, trial: int = 0) -> np.ndarray:
+    """xi[H, B, M] ~ N(0, 1), float32: the draws of the per-step posterior sampler (its own stream,
+    independent of make_inputs)."""
+    rng = np.random.default_rng([1000 * cfg.index + trial, 77])
+    return rng.standard_normal((cfg.H, cfg.B, cfg.M)).astype(np.float32)

@@ -404,3 +404,122 @@ def test_inner_loop_is_rollout_gradient_then_adam_and_lowers_the_loss():
     np.testing.assert_allclose(th2, theta, rtol=1e-13, atol=1e-15)
     fixed = oracle.optimize(dm, inp, v, inp["theta"], sets_s0[:1], sets_g[:1], 25, lr=1e-2)[3]
     assert fixed[-1] < fixed[0]
+
+
+# ------------------------------------------------------------------ per-step posterior sampler (eq. (2), (3), (9))
+def _posterior_problem(**kw):
+    cfg, inp, dm = small_problem(**kw)
+    alpha, Kinv = oracle.posterior_prepare(dm, inp)
+    return cfg, inp, dm, alpha, Kinv
+
+
+def test_posterior_moments_match_textbook_solve():
+    """mu = k^T K_hat^-1 y and var = k(x,x) - k^T K_hat^-1 k with scipy's Cholesky routines."""
+    cfg, inp, dm, alpha, Kinv = _posterior_problem(seed=3, N=40, noise_var=1e-3)
+    X = inp["X"].astype(np.float64)
+    rng = np.random.default_rng(0)
+    for m in range(cfg.M):
+        ell, sf2, sn2 = inp["lengthscale"][m].astype(np.float64), float(inp["signal_var"][m]), float(inp["noise_var"][m])
+        Khat = np_kernel(ell, sf2, X, X) + sn2 * np.eye(cfg.N)
+        cf = sla.cho_factor(Khat, lower=True)
+        np.testing.assert_allclose(alpha[m], sla.cho_solve(cf, inp["y"][m].astype(np.float64)), rtol=1e-8, atol=1e-10)
+        np.testing.assert_allclose(Kinv[m] @ Khat, np.eye(cfg.N), atol=1e-7)
+        for _ in range(5):
+            x = rng.uniform(-1.2, 1.2, cfg.D)
+            k = np_kernel(ell, sf2, x[None, :], X)[0]
+            mu, var = oracle.posterior_moments(dm, inp, alpha, Kinv, x, jac=False)
+            assert abs(mu[m] - k @ sla.cho_solve(cf, inp["y"][m].astype(np.float64))) < 1e-9
+            assert abs(var[m] - (sf2 - k @ sla.cho_solve(cf, k))) < 1e-9
+            assert 0.0 < var[m] <= sf2
+
+
+def test_posterior_single_point_closed_form_and_far_field():
+    cfg = synth.Config("p1", 9, 1, 1, 1, 1, 4, 2, 2, (3,), 0.0, "sinusoid", "const", 0, 0.8, 1e-2)
+    inp = synth.make_inputs(cfg)
+    dm = oracle.dims_from_config(cfg)
+    alpha, Kinv = oracle.posterior_prepare(dm, inp)
+    sf2, sn2 = float(inp["signal_var"][0]), float(inp["noise_var"][0])
+    ell = inp["lengthscale"][0].astype(np.float64)
+    X1, y1 = inp["X"][0].astype(np.float64), float(inp["y"][0, 0])
+    x = X1 + np.array([0.3, -0.2])
+    k = sf2 * math.exp(-0.5 * (((x - X1) / ell) ** 2).sum())
+    mu, var = oracle.posterior_moments(dm, inp, alpha, Kinv, x, jac=False)
+    assert abs(mu[0] - k * y1 / (sf2 + sn2)) < 1e-12
+    assert abs(var[0] - (sf2 - k * k / (sf2 + sn2))) < 1e-12
+    # far from the data the posterior returns to the prior: mean 0, variance alpha^2
+    mu, var = oracle.posterior_moments(dm, inp, alpha, Kinv, X1 + 50.0, jac=False)
+    assert abs(mu[0]) < 1e-12 and abs(var[0] - sf2) < 1e-12
+
+
+def test_posterior_moment_derivatives_by_finite_differences():
+    cfg, inp, dm, alpha, Kinv = _posterior_problem(seed=4, N=30, d_s=3, d_a=2, noise_var=1e-3)
+    x = np.random.default_rng(1).uniform(-0.8, 0.8, cfg.D)
+    mu, var, dmu, dvar = oracle.posterior_moments(dm, inp, alpha, Kinv, x)
+    h = 1e-6
+    for d in range(cfg.D):
+        e = np.zeros(cfg.D); e[d] = h
+        mp, vp = oracle.posterior_moments(dm, inp, alpha, Kinv, x + e, jac=False)
+        mm, vm = oracle.posterior_moments(dm, inp, alpha, Kinv, x - e, jac=False)
+        np.testing.assert_allclose(dmu[:, d], (mp - mm) / (2 * h), rtol=1e-6, atol=1e-8)
+        np.testing.assert_allclose(dvar[:, d], (vp - vm) / (2 * h), rtol=1e-6, atol=1e-8)
+
+
+def test_posterior_rollout_with_zero_draws_is_the_mean_rollout():
+    """xi = 0: every transition is the posterior mean, which is also the pathwise sample with w = 0 and
+    eps = 0 (pinned above against eq. (2)); states, loss and gradient must agree."""
+    cfg, inp, dm, alpha, Kinv = _posterior_problem(seed=5, N=24, L=16, S=4, B=8, H=6)
+    zero = dict(inp)
+    zero["w"] = np.zeros_like(inp["w"]); zero["eps"] = np.zeros_like(inp["eps"])
+    v = oracle.prepare_samples(dm, zero)
+    ref = oracle.rollout(dm, zero, v)
+    got = oracle.posterior_rollout(dm, inp, alpha, Kinv, np.zeros((cfg.H, cfg.B, cfg.M)))
+    np.testing.assert_allclose(got["states"], ref["states"], rtol=0, atol=1e-9)
+    assert abs(got["loss"] - ref["loss"]) < 1e-9 * abs(ref["loss"])
+    np.testing.assert_allclose(got["grad_theta"], ref["grad_theta"], rtol=1e-6, atol=1e-9 * np.abs(ref["grad_theta"]).max())
+
+
+def test_posterior_rollout_one_step_moments_and_gradient():
+    """H = 1: the next state is s0 + mu + sqrt(var) xi by direct evaluation; over many draws its mean and
+    variance are eq. (2) and (3); the gradient matches central differences on every parameter."""
+    cfg, inp, dm, alpha, Kinv = _posterior_problem(seed=6, N=20, B=4, S=4, H=1, hidden=(4,))
+    xi = synth.make_normal_draws(cfg).astype(np.float64)
+    out = oracle.posterior_rollout(dm, inp, alpha, Kinv, xi)
+    for b in range(cfg.B):
+        h0 = np.concatenate([inp["s0"][b], inp["goals"][0, b]]).astype(np.float64)
+        x = np.concatenate([inp["s0"][b].astype(np.float64), oracle.policy(dm, inp["theta"], h0)])
+        mu, var = oracle.posterior_moments(dm, inp, alpha, Kinv, x, jac=False)
+        np.testing.assert_allclose(out["states"][1, b], inp["s0"][b] + mu + np.sqrt(var) * xi[0, b], rtol=0, atol=1e-12)
+    draws = np.random.default_rng(2).standard_normal((4000, 1, cfg.B, cfg.M))
+    nxt = np.stack([oracle.posterior_rollout(dm, inp, alpha, Kinv, z, grad=False)["states"][1] for z in draws])
+    h0 = np.concatenate([inp["s0"][0], inp["goals"][0, 0]]).astype(np.float64)
+    x = np.concatenate([inp["s0"][0].astype(np.float64), oracle.policy(dm, inp["theta"], h0)])
+    mu, var = oracle.posterior_moments(dm, inp, alpha, Kinv, x, jac=False)
+    inc = nxt[:, 0, :] - inp["s0"][0]
+    assert np.all(np.abs(inc.mean(0) - mu) < 4 * np.sqrt(var / 4000))
+    np.testing.assert_allclose(inc.var(0), var, rtol=0.15)
+
+
+@pytest.mark.parametrize("kw", [dict(), dict(act_bound=0.7, d_a=2, d_g=2, d_s=3, hidden=(4, 3)), dict(cost_kind=1)])
+def test_posterior_rollout_gradient_by_finite_differences(kw):
+    cfg, inp, dm, alpha, Kinv = _posterior_problem(seed=7, N=16, L=8, B=3, S=3, H=5, noise_var=1e-2, **kw)
+    xi = synth.make_normal_draws(cfg).astype(np.float64)
+    out = oracle.posterior_rollout(dm, inp, alpha, Kinv, xi)
+    theta = inp["theta"].astype(np.float64)
+    # var = alpha^2 - k^T K_hat^-1 k cancels, so the loss carries a round-off of ~1e-13: a step of 1e-4
+    # keeps it out of the difference quotient (measured: error 2e-9 at 1e-4, 5e-8 at 1e-6, growing as 1/h)
+    h = 1e-4
+    fd = np.zeros_like(theta)
+    for p in range(theta.size):
+        tp, tm = theta.copy(), theta.copy()
+        tp[p] += h; tm[p] -= h
+        fd[p] = (oracle.posterior_rollout(dm, inp, alpha, Kinv, xi, theta=tp, grad=False, want_states=False)["loss"] -
+                 oracle.posterior_rollout(dm, inp, alpha, Kinv, xi, theta=tm, grad=False, want_states=False)["loss"]) / (2 * h)
+    np.testing.assert_allclose(out["grad_theta"], fd, rtol=1e-5, atol=1e-7 * np.abs(fd).max() + 1e-10)
+    s0 = inp["s0"].astype(np.float64)
+    fd0 = np.zeros_like(s0)
+    for idx in np.ndindex(*s0.shape):
+        sp, sm = s0.copy(), s0.copy()
+        sp[idx] += h; sm[idx] -= h
+        fd0[idx] = (oracle.posterior_rollout(dm, inp, alpha, Kinv, xi, s0=sp, grad=False, want_states=False)["loss"] -
+                    oracle.posterior_rollout(dm, inp, alpha, Kinv, xi, s0=sm, grad=False, want_states=False)["loss"]) / (2 * h)
+    np.testing.assert_allclose(out["grad_s0"], fd0, rtol=1e-5, atol=1e-7 * np.abs(fd0).max() + 1e-10)
