@@ -138,6 +138,31 @@ int bagel_rollout_loss_grad(bagel_ctx *ctx, const float *theta, const float *s0,
                             float *grad_s0);
 
 /*
+ * Per-step posterior sampler: Algorithm 1 as printed draws the next state at every step from the
+ * predictive posterior (eq. (9)) with the moments of eq. (2) (zero prior mean) and eq. (3), one
+ * independent GP per state.  Here the draw is reparameterised with standard normal numbers the
+ * caller supplies, f_m = mu_m(x) + sqrt(var_m(x)) xi, and the moments are exact (K_hat^-1 is kept;
+ * the Lanczos variance estimates the paper uses are an approximation of the same quantity and are not
+ * part of this library).  Cost per trajectory, step and output: 2 N^2 flop in float64, so this
+ * sampler is meant for N of a few thousand; the pathwise calls above cost 2 N (D+1).
+ *
+ * bagel_prepare_posterior: alpha_m = K_hat_m^-1 y_m and K_hat_m^-1 for every output, float64, kept in
+ * the context (the first call allocates 8 (M Np^2 + 2 Np B) bytes, Np = N rounded up to 64).
+ * Arrays as in bagel_prepare_samples.  Synchronises the stream.  Errors: EINVAL, ENOMEM, ENOTPD, EHIP.
+ *
+ * bagel_posterior_rollout_loss / _grad: as bagel_rollout_loss / bagel_rollout_loss_grad, with
+ * xi[H][B][M] (M = d_s): the draw used for output m of trajectory b at step t.  A variance below
+ * 1e-12 is held at 1e-12 and its derivative taken as zero.  Errors: EINVAL, ENOTPREPARED, EHIP.
+ */
+int bagel_prepare_posterior(bagel_ctx *ctx, const float *X, const float *y, const float *lengthscale,
+                            const float *signal_var, const float *noise_var);
+int bagel_posterior_rollout_loss(bagel_ctx *ctx, const float *theta, const float *s0, const float *goals,
+                                 const float *xi, float *loss, float *loss_per_traj, float *states);
+int bagel_posterior_rollout_loss_grad(bagel_ctx *ctx, const float *theta, const float *s0, const float *goals,
+                                      const float *xi, float *loss, float *grad_theta, float *loss_per_traj,
+                                      float *states, float *grad_s0);
+
+/*
  * One Adam update of the policy parameters on the device (Sec. III-C: the parameters are updated
  * with Adam; Algorithm 1, "update theta via gradient descent").  step >= 1 is the update counter:
  *   m <- beta1 m + (1 - beta1) g;  v <- beta2 v + (1 - beta2) g^2;

@@ -21,6 +21,7 @@ _NAMES = {EINVAL: "BAGEL_EINVAL", ENOTPREPARED: "BAGEL_ENOTPREPARED", ENOMEM: "B
 EXPORTS = ["bagel_num_params", "bagel_create", "bagel_destroy", "bagel_workspace_bytes",
            "bagel_prepare_samples", "bagel_set_samples", "bagel_rollout_loss",
            "bagel_rollout_loss_grad", "bagel_sample_eval", "bagel_last_error", "bagel_adam_step", "bagel_optimize",
+           "bagel_prepare_posterior", "bagel_posterior_rollout_loss", "bagel_posterior_rollout_loss_grad",
            "bagel_profile_enable", "bagel_profile_read"]
 
 
@@ -102,6 +103,12 @@ def load():
         L.bagel_profile_enable.argtypes = [vp, C.c_int]
         L.bagel_profile_read.restype = C.c_int
         L.bagel_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int)]
+        L.bagel_prepare_posterior.restype = C.c_int
+        L.bagel_prepare_posterior.argtypes = [vp] + [fp] * 5
+        L.bagel_posterior_rollout_loss.restype = C.c_int
+        L.bagel_posterior_rollout_loss.argtypes = [vp] + [fp] * 7
+        L.bagel_posterior_rollout_loss_grad.restype = C.c_int
+        L.bagel_posterior_rollout_loss_grad.argtypes = [vp] + [fp] * 9
         L.bagel_adam_step.restype = C.c_int
         L.bagel_adam_step.argtypes = [vp] + [fp] * 4 + [C.c_int] + [C.c_float] * 4
         L.bagel_optimize.restype = C.c_int
@@ -198,6 +205,31 @@ class Bagel:
         self._check(self._lib.bagel_rollout_loss_grad(
             self._h, _ptr(theta, (self.P,), "theta"), _ptr(s0, (d.B, d.d_s), "s0"),
             _ptr(goals, (d.H, d.B, d.d_g), "goals"), _ptr(loss, (1,), "loss"),
+            _ptr(grad_theta, (self.P,), "grad_theta"),
+            _ptr(loss_per_traj, (d.B,), "loss_per_traj", optional=True),
+            _ptr(states, (d.H + 1, d.B, d.d_s), "states", optional=True),
+            _ptr(grad_s0, (d.B, d.d_s), "grad_s0", optional=True)))
+
+    def bagel_prepare_posterior(self, X, y, lengthscale, signal_var, noise_var):
+        d, M, D = self.dims, self.M, self.D
+        self._check(self._lib.bagel_prepare_posterior(
+            self._h, _ptr(X, (d.N, D), "X"), _ptr(y, (M, d.N), "y"), _ptr(lengthscale, (M, D), "lengthscale"),
+            _ptr(signal_var, (M,), "signal_var"), _ptr(noise_var, (M,), "noise_var")))
+
+    def bagel_posterior_rollout_loss(self, theta, s0, goals, xi, loss, loss_per_traj=None, states=None):
+        d = self.dims
+        self._check(self._lib.bagel_posterior_rollout_loss(
+            self._h, _ptr(theta, (self.P,), "theta"), _ptr(s0, (d.B, d.d_s), "s0"),
+            _ptr(goals, (d.H, d.B, d.d_g), "goals"), _ptr(xi, (d.H, d.B, self.M), "xi"), _ptr(loss, (1,), "loss"),
+            _ptr(loss_per_traj, (d.B,), "loss_per_traj", optional=True),
+            _ptr(states, (d.H + 1, d.B, d.d_s), "states", optional=True)))
+
+    def bagel_posterior_rollout_loss_grad(self, theta, s0, goals, xi, loss, grad_theta, loss_per_traj=None,
+                                          states=None, grad_s0=None):
+        d = self.dims
+        self._check(self._lib.bagel_posterior_rollout_loss_grad(
+            self._h, _ptr(theta, (self.P,), "theta"), _ptr(s0, (d.B, d.d_s), "s0"),
+            _ptr(goals, (d.H, d.B, d.d_g), "goals"), _ptr(xi, (d.H, d.B, self.M), "xi"), _ptr(loss, (1,), "loss"),
             _ptr(grad_theta, (self.P,), "grad_theta"),
             _ptr(loss_per_traj, (d.B,), "loss_per_traj", optional=True),
             _ptr(states, (d.H + 1, d.B, d.d_s), "states", optional=True),

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libbagel.so")
-SOURCES = ["bagel_api.hip", "gp_step.hip", "lane.hip", "model.hip", "policy.hip", "prepare.hip"]
+SOURCES = ["bagel_api.hip", "gp_step.hip", "lane.hip", "model.hip", "policy.hip", "posterior.hip", "prepare.hip"]
 # -packed-fp32-ops is switched off on purpose: no packed float32 VALU instructions in this library
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

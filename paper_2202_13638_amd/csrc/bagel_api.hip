@@ -76,7 +76,7 @@ static void free_all(bagel_ctx *c)
 {
     void *ptrs[] = {c->Xs, c->Os, c->A, c->amp, c->v4, c->w4, c->xbuf, c->part, c->lpt, c->lam,
                     c->tape_s, c->tape_J, c->tape_h[0], c->tape_h[1], c->tape_h[2], c->tape_a, c->tape_d[0],
-                    c->tape_d[1], c->tape_d[2], c->ckpt_s, c->wpad_f, c->wpad_b, c->gsplit, c->gacc, c->fbuf, c->gtheta};
+                    c->tape_d[1], c->tape_d[2], c->ckpt_s, c->wpad_f, c->wpad_b, c->gsplit, c->gacc, c->fbuf, c->gtheta, c->post_alpha, c->post_Kinv, c->post_Kx, c->post_Q};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
 }
@@ -317,21 +317,27 @@ static int run_forward(bagel_ctx *c, int t0, int t1, int slot_base, bool jac, bo
         const int next_slot = t + 1 < t1 ? (jac ? slot + 1 : 0) : -1;
         // the policy of the first step runs on its own; every later one is part of the previous step's tail
         if (t == t0) BAGEL_HIP(c, bagel_launch_policy_forward(c, slot, theta));
-        BAGEL_HIP(c, gp_step_timed(c, jac));
+        if (c->cur_xi)
+            BAGEL_HIP(c, bagel_launch_posterior_step(c, jac, c->cur_xi + (size_t)t * c->dm.B * c->M));
+        else
+            BAGEL_HIP(c, gp_step_timed(c, jac));
         const int ck = (write_ckpt && (t + 1) % K == 0 && t + 1 < c->dm.H) ? (t + 1) / K : -1;
         BAGEL_HIP(c, bagel_launch_step_tail(c, t, slot, next_slot, jac, add_cost, write_tape_s, ck, theta, goals,
-                                            states_out));
+                                            states_out, c->cur_xi != nullptr));
     }
     return BAGEL_OK;
 }
 
-extern "C" int bagel_rollout_loss(bagel_ctx *c, const float *theta, const float *s0, const float *goals,
-                                  float *loss, float *loss_per_traj, float *states)
+// Forward pass and loss; xi == null: pathwise function samples, else per-step posterior draws xi[H][B][M]
+static int rollout_loss_impl(bagel_ctx *c, const char *who, const float *theta, const float *s0, const float *goals,
+                             const float *xi, bool posterior, float *loss, float *loss_per_traj, float *states)
 {
     if (!c) return BAGEL_EINVAL;
     c->err[0] = 0;
-    if (!theta || !s0 || !goals || !loss) BAGEL_FAIL(c, BAGEL_EINVAL, "bagel_rollout_loss: null argument");
-    if (!c->prepared) BAGEL_FAIL(c, BAGEL_ENOTPREPARED, "bagel_rollout_loss: no samples installed");
+    if (!theta || !s0 || !goals || !loss || (posterior && !xi)) BAGEL_FAIL(c, BAGEL_EINVAL, "%s: null argument", who);
+    if (posterior ? !c->post_prepared : !c->prepared)
+        BAGEL_FAIL(c, BAGEL_ENOTPREPARED, "%s: %s", who, posterior ? "no posterior cache installed" : "no samples installed");
+    c->cur_xi = posterior ? xi : nullptr;
     BAGEL_HIP(c, bagel_launch_pack_theta(c, theta));
     BAGEL_HIP(c, bagel_launch_init_state(c, s0, goals, states, false, false));
     const int rc = run_forward(c, 0, c->dm.H, 0, false, true, false, false, theta, goals, states);
@@ -340,15 +346,29 @@ extern "C" int bagel_rollout_loss(bagel_ctx *c, const float *theta, const float 
     return BAGEL_OK;
 }
 
-extern "C" int bagel_rollout_loss_grad(bagel_ctx *c, const float *theta, const float *s0, const float *goals,
-                                       float *loss, float *grad_theta, float *loss_per_traj, float *states,
-                                       float *grad_s0)
+extern "C" int bagel_rollout_loss(bagel_ctx *c, const float *theta, const float *s0, const float *goals,
+                                  float *loss, float *loss_per_traj, float *states)
+{
+    return rollout_loss_impl(c, "bagel_rollout_loss", theta, s0, goals, nullptr, false, loss, loss_per_traj, states);
+}
+
+extern "C" int bagel_posterior_rollout_loss(bagel_ctx *c, const float *theta, const float *s0, const float *goals,
+                                            const float *xi, float *loss, float *loss_per_traj, float *states)
+{
+    return rollout_loss_impl(c, "bagel_posterior_rollout_loss", theta, s0, goals, xi, true, loss, loss_per_traj, states);
+}
+
+static int rollout_loss_grad_impl(bagel_ctx *c, const char *who, const float *theta, const float *s0,
+                                  const float *goals, const float *xi, bool posterior, float *loss, float *grad_theta,
+                                  float *loss_per_traj, float *states, float *grad_s0)
 {
     if (!c) return BAGEL_EINVAL;
     c->err[0] = 0;
-    if (!theta || !s0 || !goals || !loss || !grad_theta)
-        BAGEL_FAIL(c, BAGEL_EINVAL, "bagel_rollout_loss_grad: null argument");
-    if (!c->prepared) BAGEL_FAIL(c, BAGEL_ENOTPREPARED, "bagel_rollout_loss_grad: no samples installed");
+    if (!theta || !s0 || !goals || !loss || !grad_theta || (posterior && !xi))
+        BAGEL_FAIL(c, BAGEL_EINVAL, "%s: null argument", who);
+    if (posterior ? !c->post_prepared : !c->prepared)
+        BAGEL_FAIL(c, BAGEL_ENOTPREPARED, "%s: %s", who, posterior ? "no posterior cache installed" : "no samples installed");
+    c->cur_xi = posterior ? xi : nullptr;
     const int H = c->dm.H, K = c->T_tape;
     const bool ckpt = K < H;
     int rc;
@@ -376,6 +396,56 @@ extern "C" int bagel_rollout_loss_grad(bagel_ctx *c, const float *theta, const f
         BAGEL_HIP(c, bagel_launch_backward_sweep(c, t0, t1, goals, grad_s0));
         BAGEL_HIP(c, bagel_launch_weight_grad(c, t1 - t0, seg != n_seg - 1, seg == 0 ? grad_theta : nullptr));
     }
+    return BAGEL_OK;
+}
+
+extern "C" int bagel_rollout_loss_grad(bagel_ctx *c, const float *theta, const float *s0, const float *goals,
+                                       float *loss, float *grad_theta, float *loss_per_traj, float *states,
+                                       float *grad_s0)
+{
+    return rollout_loss_grad_impl(c, "bagel_rollout_loss_grad", theta, s0, goals, nullptr, false, loss, grad_theta,
+                                  loss_per_traj, states, grad_s0);
+}
+
+extern "C" int bagel_posterior_rollout_loss_grad(bagel_ctx *c, const float *theta, const float *s0, const float *goals,
+                                                 const float *xi, float *loss, float *grad_theta,
+                                                 float *loss_per_traj, float *states, float *grad_s0)
+{
+    return rollout_loss_grad_impl(c, "bagel_posterior_rollout_loss_grad", theta, s0, goals, xi, true, loss, grad_theta,
+                                  loss_per_traj, states, grad_s0);
+}
+
+// Exact posterior cache for the per-step sampler.  The first call allocates it.
+extern "C" int bagel_prepare_posterior(bagel_ctx *c, const float *X, const float *y, const float *lengthscale,
+                                       const float *signal_var, const float *noise_var)
+{
+    if (!c) return BAGEL_EINVAL;
+    c->err[0] = 0;
+    if (!X || !y || !lengthscale || !signal_var || !noise_var)
+        BAGEL_FAIL(c, BAGEL_EINVAL, "bagel_prepare_posterior: null argument");
+    c->post_prepared = false;
+    if (!c->post_Kinv) {
+        c->post_Np = (c->dm.N + 63) / 64 * 64;
+        const size_t Np = (size_t)c->post_Np, B = (size_t)c->dm.B, M = (size_t)c->M;
+        hipError_t e = dev_alloc(c, &c->post_alpha, M * Np);
+        if (e == hipSuccess) e = dev_alloc(c, &c->post_Kinv, M * Np * Np);
+        if (e == hipSuccess) e = dev_alloc(c, &c->post_Kx, Np * B);
+        if (e == hipSuccess) e = dev_alloc(c, &c->post_Q, Np * B);
+        if (e != hipSuccess) {
+            void *ptrs[] = {c->post_alpha, c->post_Kinv, c->post_Kx, c->post_Q};
+            for (void *p : ptrs)
+                if (p) (void)hipFree(p);
+            c->post_alpha = c->post_Kinv = c->post_Kx = c->post_Q = nullptr;
+            (void)hipGetLastError();
+            BAGEL_FAIL(c, BAGEL_ENOMEM, "bagel_prepare_posterior: device allocation failed (%zu bytes for K_hat^-1)",
+                       M * Np * Np * sizeof(double));
+        }
+    }
+    // the scaled training inputs the kernel rows are computed from (the feature tables are left alone)
+    BAGEL_HIP(c, bagel_launch_build_model(c, X, lengthscale, signal_var, nullptr, nullptr));
+    const int rc = bagel_prepare_posterior_impl(c, X, y, lengthscale, signal_var, noise_var);
+    if (rc != BAGEL_OK) return rc;
+    c->post_prepared = true;
     return BAGEL_OK;
 }
 

@@ -59,6 +59,15 @@ struct bagel_ctx {
     float *gtheta;               // [P] gradient of the current iteration of bagel_optimize
     int ksplit;
 
+    // ---- per-step posterior sampler (buffers allocated by the first bagel_prepare_posterior) -----
+    bool post_prepared;
+    int post_Np;                 // N rounded up to a multiple of 64
+    double post_sf2[8];          // alpha_m^2
+    double *post_alpha;          // [M][post_Np]           K_hat^-1 y, zero on the padding
+    double *post_Kinv;           // [M][post_Np][post_Np]  K_hat^-1
+    double *post_Kx, *post_Q;    // [post_Np][B]: kernel rows of one output at the current inputs; K_hat^-1 Kx
+    const float *cur_xi;         // draws of the rollout in progress (null: pathwise sampler)
+
     // ---- measurement hooks -------------------------------------------------------------------
     int prof_every, prof_seen, prof_used;
     hipEvent_t *prof_ev;         // 2 * BAGEL_PROF_MAX events, created on enable
@@ -101,15 +110,20 @@ hipError_t bagel_launch_pack_theta(bagel_ctx *ctx, const float *theta);
 hipError_t bagel_launch_policy_forward(bagel_ctx *ctx, int slot, const float *theta);
 // after the sample evaluation of step t: reduce its partial sums (Jacobian into tape slot `slot` if jac),
 // advance the state, cost against goals[t], tapes, and the policy of step t+1 into tape slot next_slot
-// (no policy if t is the last step or next_slot < 0)
+// (no policy if t is the last step or next_slot < 0); direct: ctx->part holds final values [m][1+D][B]
 hipError_t bagel_launch_step_tail(bagel_ctx *ctx, int t, int slot, int next_slot, bool jac, bool add_cost,
                                   bool write_tape_s, int ckpt_index, const float *theta, const float *goals,
-                                  float *states_out);
+                                  float *states_out, bool direct);
 // backward sweep over steps t_hi-1 .. t_lo (tape slot of step k is k - t_lo); grad_s0 is written when t_lo == 0
 hipError_t bagel_launch_backward_sweep(bagel_ctx *ctx, int t_lo, int t_hi, const float *goals, float *grad_s0);
 hipError_t bagel_launch_weight_grad(bagel_ctx *ctx, int n_slots, bool accumulate, float *grad_theta);
 hipError_t bagel_launch_adam(bagel_ctx *ctx, float *theta, const float *grad, float *m, float *v, double lr,
                              double beta1, double beta2, double eps, double corr1, double corr2);
+
+// ---- posterior.hip ------------------------------------------------------------------------
+// mu + sqrt(var) xi and its Jacobian for every trajectory and output at xbuf, into ctx->part as
+// [m][1+D][B] (final values, not partial sums)
+hipError_t bagel_launch_posterior_step(bagel_ctx *ctx, bool jac, const float *xi_t);
 
 // ---- prepare.hip -------------------------------------------------------------------------
 // v = (K + noise I)^-1 (y - Phi w - eps) for every sample, float64 inside; packs v into ctx->v4
@@ -117,3 +131,10 @@ hipError_t bagel_launch_adam(bagel_ctx *ctx, float *theta, const float *grad, fl
 int bagel_prepare_impl(bagel_ctx *ctx, const float *X, const float *y, const float *ell, const float *sf2,
                        const float *sn2, const float *omega, const float *phase, const float *w,
                        const float *eps, float *v_out);
+
+// K_hat^-1 and K_hat^-1 y of every output into ctx->post_Kinv / post_alpha (float64)
+int bagel_prepare_posterior_impl(bagel_ctx *ctx, const float *X, const float *y, const float *ell, const float *sf2,
+                                 const float *sn2);
+// C (+)= alpha * A * B in float64 with element strides (see dgemm_kernel); overwrite: C = alpha * A * B
+void bagel_dgemm(hipStream_t st, int Mr, int Nc, int Kd, double alpha, const double *A, long sai, long sak,
+                 const double *Bm, long sbk, long sbj, double *Cm, long ldc, bool overwrite);

@@ -37,7 +37,7 @@ __global__ void build_model_kernel(const float *__restrict__ X, const float *__r
             row[D] = -2000.0;
         }
     }
-    if (i < Lp) {
+    if (omega && i < Lp) {
         double *row = Os + ((size_t)m * Lp + i) * (D + 1);
         if (i < L) {
             for (int d = 0; d < D; ++d) row[d] = INV_TWO_PI * (double)omega[((size_t)m * L + i) * D + d];

@@ -351,6 +351,7 @@ __global__ __launch_bounds__(PW * 64) void policy_forward_kernel(policy_args a)
 struct tail_args {
     int D, M, dg, ngk, ngl, ncomp;      // ncomp = 1 (value only) or 1 + D (with Jacobian)
     int cost_kind, add_cost, do_policy;
+    int direct;                         // part holds f and J_f themselves, [m][1+D][B] (per-step posterior sampler)
     float sigma_r;
     int tracked[8];
     float q[8];
@@ -386,6 +387,12 @@ __global__ __launch_bounds__(PW * 64) void step_tail_kernel(tail_args r, policy_
     const size_t stride = (size_t)(1 + r.D) * B;
     for (int qi = row; qi < r.M * r.ncomp; qi += 16) {
         const int m = qi / r.ncomp, comp = qi - m * r.ncomp;
+        if (r.direct) {
+            const double val = r.part[(size_t)m * stride + (size_t)comp * B + bq];
+            if (comp == 0) fS[m][bl] = val;
+            else if (liveq) r.jdst[(size_t)(m * r.D + comp - 1) * B + bq] = (float)val;
+            continue;
+        }
         const double *pk = r.part + (size_t)(m * r.ngk) * stride + bq;
         const double *pr = r.part + (size_t)(r.M * r.ngk + m * r.ngl) * stride + bq;
         double u = 0.0;
@@ -1023,7 +1030,7 @@ hipError_t bagel_launch_policy_forward(bagel_ctx *c, int slot, const float *thet
 
 hipError_t bagel_launch_step_tail(bagel_ctx *c, int t, int slot, int next_slot, bool jac, bool add_cost,
                                   bool write_tape_s, int ckpt_index, const float *theta, const float *goals,
-                                  float *states_out)
+                                  float *states_out, bool direct)
 {
     const size_t B = c->dm.B;
     const bool has_next = t + 1 < c->dm.H && next_slot >= 0;
@@ -1032,6 +1039,7 @@ hipError_t bagel_launch_step_tail(bagel_ctx *c, int t, int slot, int next_slot, 
     r.ngk = (c->nck + 3) / 4; r.ngl = (c->ncl + 3) / 4;
     r.ncomp = jac ? 1 + c->D : 1;
     r.cost_kind = c->dm.cost_kind; r.add_cost = add_cost ? 1 : 0; r.do_policy = has_next ? 1 : 0;
+    r.direct = direct ? 1 : 0;
     r.sigma_r = c->dm.sigma_r;
     for (int j = 0; j < 8; ++j) { r.tracked[j] = c->dm.tracked[j]; r.q[j] = c->dm.q[j]; }
     r.A = c->A; r.amp = c->amp; r.part = c->part; r.lpt = c->lpt;

@@ -79,12 +79,13 @@ __global__ void convert_w_kernel(const float *__restrict__ w, double *__restrict
     if (l < L) Wd[(size_t)s * L + l] = (double)w[((size_t)s * M + m) * L + l];
 }
 
-// C[i][j] (ldc) += alpha * sum_k A(i,k) * B(k,j), A(i,k) = A[i*sai + k*sak], B(k,j) = B[k*sbk + j*sbj].
-// lower_only: skip tiles entirely above the diagonal (used for the symmetric trailing update).
+// C[i][j] (ldc) += alpha * sum_k A(i,k) * B(k,j), A(i,k) = A[i*sai + k*sak], B(k,j) = B[k*sbk + j*sbj]
+// (C = alpha * ... with overwrite).  lower_only: skip tiles entirely above the diagonal (used for the
+// symmetric trailing update).
 __global__ __launch_bounds__(256) void dgemm_kernel(int Mr, int Nc, int Kd, double alpha,
                                                     const double *__restrict__ A, long sai, long sak,
                                                     const double *__restrict__ Bm, long sbk, long sbj,
-                                                    double *__restrict__ Cm, long ldc, int lower_only)
+                                                    double *__restrict__ Cm, long ldc, int lower_only, int overwrite)
 {
     const int i0 = blockIdx.y * TM, j0 = blockIdx.x * TN;
     if (lower_only && j0 > i0 + TM - 1) return;
@@ -135,7 +136,7 @@ __global__ __launch_bounds__(256) void dgemm_kernel(int Mr, int Nc, int Kd, doub
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const int gj = j0 + tx * 4 + c;
-            if (gj < Nc) Cm[(long)gi * ldc + gj] += alpha * acc[r][c];
+            if (gj < Nc) Cm[(long)gi * ldc + gj] = (overwrite ? 0.0 : Cm[(long)gi * ldc + gj]) + alpha * acc[r][c];
         }
     }
 }
@@ -254,15 +255,72 @@ __global__ void emit_v_kernel(const double *__restrict__ V, float *__restrict__ 
 }
 
 void gemm(hipStream_t st, int Mr, int Nc, int Kd, double alpha, const double *A, long sai, long sak,
-          const double *Bm, long sbk, long sbj, double *Cm, long ldc, bool lower_only)
+          const double *Bm, long sbk, long sbj, double *Cm, long ldc, bool lower_only, bool overwrite = false)
 {
     if (Mr <= 0 || Nc <= 0 || Kd <= 0) return;
     dim3 grid((Nc + TN - 1) / TN, (Mr + TM - 1) / TM);
     hipLaunchKernelGGL(dgemm_kernel, grid, dim3(256), 0, st, Mr, Nc, Kd, alpha, A, sai, sak, Bm, sbk, sbj, Cm, ldc,
-                       lower_only ? 1 : 0);
+                       lower_only ? 1 : 0, overwrite ? 1 : 0);
+}
+
+// In-place blocked Cholesky of K [Np][Np] (lower; Np a multiple of NB), then K_hat^-1 applied to the S
+// right-hand sides R [Np][S] in place.  A pivot that is not positive is reported through *flag.
+void factor_and_solve(hipStream_t st, double *K, int Np, double *R, int S, int flag_base, int *flag)
+{
+    for (int k = 0; k < Np; k += NB) {
+        hipLaunchKernelGGL(potrf_diag_kernel, dim3(1), dim3(NB), 0, st, K, Np, k, flag_base, flag);
+        const int rest = Np - k - NB;
+        if (rest > 0) {
+            hipLaunchKernelGGL(trsm_panel_kernel, dim3((rest + 255) / 256), dim3(256), 0, st, K, Np, k);
+            const double *Pn = K + (size_t)(k + NB) * Np + k;
+            // trailing[i][j] -= sum_c P[i][c] P[j][c]
+            gemm(st, rest, rest, NB, -1.0, Pn, Np, 1, Pn, 1, Np, K + (size_t)(k + NB) * Np + (k + NB), Np, true);
+        }
+    }
+    // forward substitution  L Z = R
+    for (int k = 0; k < Np; k += NB) {
+        hipLaunchKernelGGL(trsv_fwd_kernel, dim3((S + 255) / 256), dim3(256), 0, st, K, Np, k, R, S);
+        const int rest = Np - k - NB;
+        if (rest > 0)
+            gemm(st, rest, S, NB, -1.0, K + (size_t)(k + NB) * Np + k, Np, 1, R + (size_t)k * S, S, 1,
+                 R + (size_t)(k + NB) * S, S, false);
+    }
+    // backward substitution  L^T V = Z
+    for (int k = Np - NB; k >= 0; k -= NB) {
+        hipLaunchKernelGGL(trsv_bwd_kernel, dim3((S + 255) / 256), dim3(256), 0, st, K, Np, k, R, S);
+        if (k > 0)   // R[0:k] -= L[k:k+NB, 0:k]^T V_k : A(i, c) = K[(k+c)*Np + i]
+            gemm(st, k, S, NB, -1.0, K + (size_t)k * Np, 1, Np, R + (size_t)k * S, S, 1, R, S, false);
+    }
+}
+
+// R[n][j] = [n == j] for j < Np, and R[n][Np] = y[n] (zero on the padding): right-hand sides for K_hat^-1 and alpha
+__global__ void posterior_rhs_kernel(const float *__restrict__ y_m, double *__restrict__ R, int N, int Np)
+{
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    const int n = blockIdx.y;
+    if (j > Np) return;
+    R[(size_t)n * (Np + 1) + j] = (j < Np) ? (j == n ? 1.0 : 0.0) : (n < N ? (double)y_m[n] : 0.0);
+}
+
+// split the solved right-hand sides into Kinv[Np][Np] and alpha[Np]
+__global__ void posterior_emit_kernel(const double *__restrict__ R, double *__restrict__ Kinv, double *__restrict__ alpha,
+                                      int Np)
+{
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    const int n = blockIdx.y;
+    if (j > Np) return;
+    const double v = R[(size_t)n * (Np + 1) + j];
+    if (j < Np) Kinv[(size_t)n * Np + j] = v;
+    else alpha[n] = v;
 }
 
 }  // namespace
+
+void bagel_dgemm(hipStream_t st, int Mr, int Nc, int Kd, double alpha, const double *A, long sai, long sak,
+                 const double *Bm, long sbk, long sbj, double *Cm, long ldc, bool overwrite)
+{
+    gemm(st, Mr, Nc, Kd, alpha, A, sai, sak, Bm, sbk, sbj, Cm, ldc, false, overwrite);
+}
 
 int bagel_prepare_impl(bagel_ctx *c, const float *X, const float *y, const float *ell, const float *sf2,
                        const float *sn2, const float *omega, const float *phase, const float *w,
@@ -310,31 +368,7 @@ int bagel_prepare_impl(bagel_ctx *c, const float *X, const float *y, const float
         // R -= Phi W^T : A = Phi [Np][L] (k fast), B(k=l, j=s) = Wd[s][l]
         gemm(st, Np, S, L, -1.0, Phi, L, 1, Wd, 1, L, R, S, false);
 
-        // Cholesky
-        for (int k = 0; k < Np; k += NB) {
-            hipLaunchKernelGGL(potrf_diag_kernel, dim3(1), dim3(NB), 0, st, K, Np, k, m * Np, flag);
-            const int rest = Np - k - NB;
-            if (rest > 0) {
-                hipLaunchKernelGGL(trsm_panel_kernel, dim3((rest + 255) / 256), dim3(256), 0, st, K, Np, k);
-                const double *Pn = K + (size_t)(k + NB) * Np + k;
-                // trailing[i][j] -= sum_c P[i][c] P[j][c]
-                gemm(st, rest, rest, NB, -1.0, Pn, Np, 1, Pn, 1, Np, K + (size_t)(k + NB) * Np + (k + NB), Np, true);
-            }
-        }
-        // forward substitution  L Z = R
-        for (int k = 0; k < Np; k += NB) {
-            hipLaunchKernelGGL(trsv_fwd_kernel, dim3((S + 255) / 256), dim3(256), 0, st, K, Np, k, R, S);
-            const int rest = Np - k - NB;
-            if (rest > 0)
-                gemm(st, rest, S, NB, -1.0, K + (size_t)(k + NB) * Np + k, Np, 1, R + (size_t)k * S, S, 1,
-                     R + (size_t)(k + NB) * S, S, false);
-        }
-        // backward substitution  L^T V = Z
-        for (int k = Np - NB; k >= 0; k -= NB) {
-            hipLaunchKernelGGL(trsv_bwd_kernel, dim3((S + 255) / 256), dim3(256), 0, st, K, Np, k, R, S);
-            if (k > 0)   // R[0:k] -= L[k:k+NB, 0:k]^T V_k : A(i, c) = K[(k+c)*Np + i]
-                gemm(st, k, S, NB, -1.0, K + (size_t)k * Np, 1, Np, R + (size_t)k * S, S, 1, R, S, false);
-        }
+        factor_and_solve(st, K, Np, R, S, m * Np, flag);
         hipLaunchKernelGGL(emit_v_kernel, dim3((S + 255) / 256, c->Np / 4), dim3(256), 0, st, R, v_out, c->v4, N, c->Np,
                            S, M, m);
         P_HIP(hipGetLastError());
@@ -353,6 +387,65 @@ done:
     if (Phi) (void)hipFree(Phi);
     if (R) (void)hipFree(R);
     if (Wd) (void)hipFree(Wd);
+    if (flag) (void)hipFree(flag);
+    return rc;
+#undef P_HIP
+}
+
+// Exact posterior cache of the per-step sampler (eq. (2), (3)): for every output alpha = K_hat^-1 y and
+// K_hat^-1 itself, float64, padded to Np = multiple of 64 (the padding rows and columns of K_hat are an
+// identity block, so they do not couple to the data; padded alpha entries are zero).
+int bagel_prepare_posterior_impl(bagel_ctx *c, const float *X, const float *y, const float *ell, const float *sf2,
+                                 const float *sn2)
+{
+    const int N = c->dm.N, M = c->M, D = c->D;
+    const int Np = c->post_Np;
+    hipStream_t st = c->stream;
+    double *K = nullptr, *R = nullptr;
+    int *flag = nullptr;
+    float h_sf2[8], h_sn2[8];
+    int rc = BAGEL_OK;
+    int h_flag = 0;
+#define P_HIP(call)                                                                              \
+    do {                                                                                         \
+        hipError_t e__ = (call);                                                                 \
+        if (e__ != hipSuccess) {                                                                 \
+            snprintf(c->err, sizeof(c->err), "bagel_prepare_posterior: %s failed: %s", #call,    \
+                     hipGetErrorString(e__));                                                    \
+            rc = (e__ == hipErrorOutOfMemory) ? BAGEL_ENOMEM : BAGEL_EHIP;                       \
+            goto done;                                                                           \
+        }                                                                                        \
+    } while (0)
+    P_HIP(hipMalloc((void **)&K, (size_t)Np * Np * sizeof(double)));
+    P_HIP(hipMalloc((void **)&R, (size_t)Np * (Np + 1) * sizeof(double)));
+    P_HIP(hipMalloc((void **)&flag, sizeof(int)));
+    P_HIP(hipMemsetAsync(flag, 0, sizeof(int), st));
+    P_HIP(hipMemcpyAsync(h_sf2, sf2, M * sizeof(float), hipMemcpyDeviceToHost, st));
+    P_HIP(hipMemcpyAsync(h_sn2, sn2, M * sizeof(float), hipMemcpyDeviceToHost, st));
+    P_HIP(hipStreamSynchronize(st));
+    for (int m = 0; m < M; ++m) {
+        c->post_sf2[m] = (double)h_sf2[m];
+        hipLaunchKernelGGL(build_khat_kernel, dim3((Np + 255) / 256, Np), dim3(256), 0, st, X, ell + (size_t)m * D,
+                           h_sf2[m], h_sn2[m], K, N, Np, D);
+        hipLaunchKernelGGL(posterior_rhs_kernel, dim3((Np + 1 + 255) / 256, Np), dim3(256), 0, st, y + (size_t)m * N, R,
+                           N, Np);
+        factor_and_solve(st, K, Np, R, Np + 1, m * Np, flag);
+        hipLaunchKernelGGL(posterior_emit_kernel, dim3((Np + 1 + 255) / 256, Np), dim3(256), 0, st, R,
+                           c->post_Kinv + (size_t)m * Np * Np, c->post_alpha + (size_t)m * Np, Np);
+        P_HIP(hipGetLastError());
+    }
+    P_HIP(hipMemcpyAsync(&h_flag, flag, sizeof(int), hipMemcpyDeviceToHost, st));
+    P_HIP(hipStreamSynchronize(st));
+    if (h_flag != 0) {
+        snprintf(c->err, sizeof(c->err),
+                 "bagel_prepare_posterior: K + noise_var I is not positive definite (output %d, pivot %d)",
+                 (h_flag - 1) / Np, (h_flag - 1) % Np);
+        rc = BAGEL_ENOTPD;
+    }
+done:
+    (void)hipStreamSynchronize(st);
+    if (K) (void)hipFree(K);
+    if (R) (void)hipFree(R);
     if (flag) (void)hipFree(flag);
     return rc;
 #undef P_HIP

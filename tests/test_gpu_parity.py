@@ -358,3 +358,62 @@ def test_inner_loop_against_oracle():
     assert torch.equal(t1, t2) and torch.equal(h1, h2)
     assert bool(torch.isfinite(t1).all()) and float(h1[0]) > 0.0
     ctx.close()
+
+
+# ------------------------------------------------------------------ per-step posterior sampler
+def _posterior_case(cfg, label, S=None, **dims_kw):
+    """Oracle (exact eq. (2), (3) moments, reparameterised draws) against bagel_prepare_posterior +
+    bagel_posterior_rollout_loss(_grad) on the same float32 inputs and draws."""
+    import torch
+    from paper_2202_13638_amd import binding
+    inp = synth.make_inputs(cfg, S=S)
+    xi = synth.make_normal_draws(cfg)
+    dm = oracle.dims_from_config(cfg, S=S, **{k: v for k, v in dims_kw.items() if k != "ckpt_interval"})
+    alpha, Kinv = oracle.posterior_prepare(dm, inp)
+    ref = oracle.posterior_rollout(dm, inp, alpha, Kinv, xi)
+    ctx = binding.Bagel(binding.dims_from_config(cfg, S=S, **dims_kw))
+    g = harness.to_gpu(inp)
+    B, H, ds = cfg.B, cfg.H, cfg.d_s
+    loss = torch.full((1,), float("nan"), device="cuda")
+    lpt = torch.full((B,), float("nan"), device="cuda")
+    states = torch.full((H + 1, B, ds), float("nan"), device="cuda")
+    gth = torch.full((ctx.P,), float("nan"), device="cuda")
+    gs0 = torch.full((B, ds), float("nan"), device="cuda")
+    xi_g = torch.from_numpy(xi).cuda()
+    with pytest.raises(binding.BagelError) as e:
+        ctx.bagel_posterior_rollout_loss(g["theta"], g["s0"], g["goals"], xi_g, loss)
+    assert e.value.code == binding.ENOTPREPARED
+    ctx.bagel_prepare_posterior(g["X"], g["y"], g["lengthscale"], g["signal_var"], g["noise_var"])
+    ctx.bagel_posterior_rollout_loss(g["theta"], g["s0"], g["goals"], xi_g, loss, lpt, states)
+    torch.cuda.synchronize()
+    fwd = dict(loss=float(loss.item()), loss_per_traj=lpt.cpu().numpy().astype(np.float64),
+               states=states.cpu().numpy().astype(np.float64))
+    harness.assert_parity(ref, fwd, grad=False, label=f"{label}/fwd")
+    ctx.bagel_posterior_rollout_loss_grad(g["theta"], g["s0"], g["goals"], xi_g, loss, gth, lpt, states, gs0)
+    torch.cuda.synchronize()
+    got = dict(loss=float(loss.item()), loss_per_traj=lpt.cpu().numpy().astype(np.float64),
+               states=states.cpu().numpy().astype(np.float64), grad_theta=gth.cpu().numpy().astype(np.float64),
+               grad_s0=gs0.cpu().numpy().astype(np.float64))
+    harness.assert_parity(ref, got, label=f"{label}/grad")
+    ctx.close()
+    return got
+
+
+def test_posterior_sampler_small_ragged():
+    # N, B not multiples of the tile sizes; one hidden layer
+    cfg = synth.Config("pp", 21, 3, 2, 2, 200, 16, 37, 12, (16,), 0.0, "sinusoid", "steps", 0, 0.6, 1e-3)
+    _posterior_case(cfg, "posterior-ragged")
+
+
+def test_posterior_sampler_bounded_saturating_checkpointed():
+    cfg = synth.Config("pq", 22, 2, 1, 1, 130, 16, 64, 23, (32, 16), 0.8, "sinusoid", "const", 0, 0.5, 1e-3)
+    plain = _posterior_case(cfg, "posterior-bounded", cost_kind=1, sigma_r=0.6)
+    ck = _posterior_case(cfg, "posterior-bounded-ckpt", cost_kind=1, sigma_r=0.6, ckpt_interval=5)
+    np.testing.assert_array_equal(plain["states"], ck["states"])
+    np.testing.assert_allclose(plain["grad_theta"], ck["grad_theta"], rtol=1e-5, atol=1e-6 * np.abs(plain["grad_theta"]).max())
+
+
+@pytest.mark.timeout(600)
+def test_posterior_sampler_small_config_size():
+    """The Small configuration's model (N=512, 4 outputs, policy 5-64-64-1) with a shorter batch and horizon."""
+    _posterior_case(_cfg("small", B=64, H=20), "posterior-small")
