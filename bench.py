@@ -81,6 +81,9 @@ def main():
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="stress", choices=list(synth.CONFIGS))
+    ap.add_argument("--sampler", default="pathwise", choices=["pathwise", "posterior"],
+                    help="pathwise: one function sample per trajectory (the headline path); posterior: per-step "
+                         "draws from the exact predictive posterior (2 N^2 flop per trajectory, step and output)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the forward-only and inner-loop figures")
     ap.add_argument("--profile-every", type=int, default=8, help="time every n-th sample-evaluation launch")
@@ -115,8 +118,13 @@ def main():
     g = {k: torch.from_numpy(a).cuda() for k, a in inp.items()}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    ctx.bagel_prepare_samples(g["X"], g["y"], g["lengthscale"], g["signal_var"], g["noise_var"], g["omega"],
-                              g["phase"], g["w"], g["eps"], None)
+    posterior = args.sampler == "posterior"
+    if posterior:
+        ctx.bagel_prepare_posterior(g["X"], g["y"], g["lengthscale"], g["signal_var"], g["noise_var"])
+        g["xi"] = torch.from_numpy(synth.make_normal_draws(cfg)).cuda()
+    else:
+        ctx.bagel_prepare_samples(g["X"], g["y"], g["lengthscale"], g["signal_var"], g["noise_var"], g["omega"],
+                                  g["phase"], g["w"], g["eps"], None)
     torch.cuda.synchronize()
     t_prep = time.perf_counter() - t0
     for k in ("w", "eps", "y"):
@@ -133,7 +141,10 @@ def main():
         del src, dst
 
     def step():
-        ctx.bagel_rollout_loss_grad(g["theta"], g["s0"], g["goals"], loss, grad)
+        if posterior:
+            ctx.bagel_posterior_rollout_loss_grad(g["theta"], g["s0"], g["goals"], g["xi"], loss, grad)
+        else:
+            ctx.bagel_rollout_loss_grad(g["theta"], g["s0"], g["goals"], loss, grad)
 
     for _ in range(args.warmup):
         step()
@@ -151,7 +162,12 @@ def main():
     traj_steps = cfg.B * cfg.H
     value = traj_steps * args.steps / elapsed
     ckpt = dims.ckpt_interval if 0 < dims.ckpt_interval < cfg.H else 0
-    flops_launch = algorithmic_flops_per_traj_step(cfg, jac=True) * cfg.B
+    if posterior:
+        # per step: the float64 GEMM with K_hat^-1 (2 N^2 flop per trajectory and output) plus kernel rows and
+        # the moment / derivative sums (about 2 N (3 D + 8))
+        flops_launch = cfg.M * cfg.B * (2 * cfg.N * cfg.N + 2 * cfg.N * (3 * cfg.D + 8))
+    else:
+        flops_launch = algorithmic_flops_per_traj_step(cfg, jac=True) * cfg.B
     avg_ms = k_ms / max(k_n, 1)
     achieved = flops_launch / (avg_ms * 1e-3) / 1e12 if k_n else float("nan")
     out = {
@@ -167,19 +183,21 @@ def main():
         "vs_baseline": None,
         "dtype": "f64",
         "data": "synthetic",
-        "config": {"workload": cfg.name, "N": cfg.N, "D": cfg.D, "M": cfg.M, "L": cfg.L, "B": cfg.B, "S": S,
+        "config": {"workload": cfg.name, "sampler": args.sampler, "N": cfg.N, "D": cfg.D, "M": cfg.M, "L": cfg.L, "B": cfg.B, "S": S,
                    "H": cfg.H, "policy": [cfg.d_in, *cfg.hidden, cfg.d_a], "ckpt_interval": ckpt,
                    "arithmetic": "kernel row and feature phase in f64, policy and sin/cos in f32, f32 interface",
                    "prepare_s": round(t_prep, 3), "input_generation_s": round(t_gen, 1),
                    "workspace_GB": round(ctx.workspace_bytes() / 1e9, 2)},
-        "roofline": {"bound": "alu", "kernel": "gp_step_kernel<D,jac>", "achieved": achieved,
+        "roofline": {"bound": "alu", "kernel": "posterior step: rows + dgemm_kernel + reduce, all outputs" if posterior
+                     else "gp_step_kernel<D,jac>", "achieved": achieved,
                      "peak": PEAK_FP64_VECTOR_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP64_VECTOR_TFLOPS,
-                     "traffic": STRESS_GP_STEP_TRAFFIC_BYTES if (cfg.name == "stress" and args.horizon is None) else None,
+                     "traffic": STRESS_GP_STEP_TRAFFIC_BYTES if (cfg.name == "stress" and args.horizon is None
+                                                                  and not posterior and S == cfg.B) else None,
                      "avg_launch_ms": avg_ms, "timed_launches": k_n,
                      "flops_per_launch": flops_launch,
                      "share_of_step": (avg_ms * cfg.H * (2 if ckpt else 1)) / (1e3 * elapsed / args.steps)},
     }
-    if not args.no_extras:
+    if not args.no_extras and not posterior:
         # reported alongside, outside the timed region: the forward pass alone, and the inner loop of
         # Algorithm 1 (rollout, gradient, Adam update per iteration) on fixed initial states and goals
         def timed(fn):
@@ -197,7 +215,7 @@ def main():
         t_opt = timed(lambda: ctx.bagel_optimize(theta, am, av, g["s0"][None], g["goals"][None], n_it, hist))
         out["inner_loop"] = {"value": traj_steps * n_it / t_opt, "unit": "trajectory-steps/s", "iterations": n_it,
                              "ms_per_iteration": 1e3 * t_opt / n_it, "loss": [float(x) for x in hist.cpu()]}
-    if not args.no_cpu_baseline and args.trajectories_per_sample == 1:
+    if not args.no_cpu_baseline and args.trajectories_per_sample == 1 and not posterior:
         out["cpu_baseline"] = cpu_baseline(cfg, inp)
     ctx.close()
     print(json.dumps(out))

@@ -200,7 +200,8 @@ int bagel_sample_eval(bagel_ctx *ctx, const float *x, float *f, float *jac);
 
 /*
  * Measurement hooks (used by bench.py; not part of the method).  With every > 0, every
- * `every`-th launch of the sample-evaluation kernel inside the rollout calls is bracketed by
+ * `every`-th launch of the sample-evaluation kernel inside the rollout calls (for the posterior
+ * sampler: the launches of one step, all outputs) is bracketed by
  * HIP events on the context's stream (at most 4096 timed launches between two reads; further
  * ones are skipped).  bagel_profile_read synchronises the stream, returns the summed elapsed
  * milliseconds and the number of timed launches since the last read, and resets both.

@@ -240,7 +240,7 @@ extern "C" int bagel_prepare_samples(bagel_ctx *c, const float *X, const float *
     return BAGEL_OK;
 }
 
-static hipError_t gp_step_timed(bagel_ctx *c, bool jac);
+static hipError_t gp_step_timed(bagel_ctx *c, bool jac, const float *xi_t = nullptr);
 
 extern "C" int bagel_sample_eval(bagel_ctx *c, const float *x, float *f, float *jac)
 {
@@ -255,8 +255,9 @@ extern "C" int bagel_sample_eval(bagel_ctx *c, const float *x, float *f, float *
     return BAGEL_OK;
 }
 
-// the sample-evaluation launch, optionally bracketed by events
-static hipError_t gp_step_timed(bagel_ctx *c, bool jac)
+// the sample-evaluation launch (pathwise samples, or with xi_t the launches of one posterior step),
+// optionally bracketed by events
+static hipError_t gp_step_timed(bagel_ctx *c, bool jac, const float *xi_t)
 {
     bool timed = false;
     if (c->prof_every > 0) {
@@ -266,7 +267,7 @@ static hipError_t gp_step_timed(bagel_ctx *c, bool jac)
             if (e != hipSuccess) return e;
         }
     }
-    hipError_t e = bagel_launch_gp_step(c, jac);
+    hipError_t e = xi_t ? bagel_launch_posterior_step(c, jac, xi_t) : bagel_launch_gp_step(c, jac);
     if (timed && e == hipSuccess) {
         e = hipEventRecord(c->prof_ev[2 * c->prof_used + 1], c->stream);
         c->prof_used++;
@@ -317,10 +318,7 @@ static int run_forward(bagel_ctx *c, int t0, int t1, int slot_base, bool jac, bo
         const int next_slot = t + 1 < t1 ? (jac ? slot + 1 : 0) : -1;
         // the policy of the first step runs on its own; every later one is part of the previous step's tail
         if (t == t0) BAGEL_HIP(c, bagel_launch_policy_forward(c, slot, theta));
-        if (c->cur_xi)
-            BAGEL_HIP(c, bagel_launch_posterior_step(c, jac, c->cur_xi + (size_t)t * c->dm.B * c->M));
-        else
-            BAGEL_HIP(c, gp_step_timed(c, jac));
+        BAGEL_HIP(c, gp_step_timed(c, jac, c->cur_xi ? c->cur_xi + (size_t)t * c->dm.B * c->M : nullptr));
         const int ck = (write_ckpt && (t + 1) % K == 0 && t + 1 < c->dm.H) ? (t + 1) / K : -1;
         BAGEL_HIP(c, bagel_launch_step_tail(c, t, slot, next_slot, jac, add_cost, write_tape_s, ck, theta, goals,
                                             states_out, c->cur_xi != nullptr));

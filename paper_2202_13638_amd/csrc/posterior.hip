@@ -68,21 +68,29 @@ __global__ __launch_bounds__(256) void posterior_rows_kernel(const double *__res
     }
 }
 
-// thread (b, comp): comp 0 -> f, comp 1 + d -> J[d]; out[(comp) * B + b] of output m
+// Workgroup = 64 trajectories x 16 slices of the training points, one component (comp 0 -> f,
+// comp 1 + d -> J[d]) per blockIdx.y; the slices' sums are added through LDS in slice order, then
+// slice 0 finishes the moments.  out[comp * B + b] of output m.
 template <int D>
-__global__ __launch_bounds__(256) void posterior_reduce_kernel(const double *__restrict__ Xs_m, const double *__restrict__ A_m,
-                                                               const double *__restrict__ alpha_m,
-                                                               const double *__restrict__ Kx, const double *__restrict__ Q,
-                                                               const double *__restrict__ xbuf,
-                                                               const float *__restrict__ xi_t, double sf2,
-                                                               double *__restrict__ out, int B, int N, int M, int m)
+__global__ __launch_bounds__(1024) void posterior_reduce_kernel(const double *__restrict__ Xs_m, const double *__restrict__ A_m,
+                                                                const double *__restrict__ alpha_m,
+                                                                const double *__restrict__ Kx, const double *__restrict__ Q,
+                                                                const double *__restrict__ xbuf,
+                                                                const float *__restrict__ xi_t, double sf2,
+                                                                double *__restrict__ out, int B, int N, int M, int m)
 {
-    const int b = blockIdx.x * 256 + threadIdx.x;
+    __shared__ double red[15][4][64];
+    const int lane = threadIdx.x & 63;
+    const int slice = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int b_raw = blockIdx.x * 64 + lane;
+    const bool live = b_raw < B;
+    const int b = live ? b_raw : B - 1;
     const int comp = blockIdx.y;
-    if (b >= B) return;
-    double mu = 0.0, quad = 0.0, gmu = 0.0, gq = 0.0;
     const int d = comp - 1;
-    for (int n = 0; n < N; ++n) {
+    const int per = (N + 15) / 16;
+    const int n_begin = slice * per, n_end = min(N, n_begin + per);
+    double mu = 0.0, quad = 0.0, gmu = 0.0, gq = 0.0;
+    for (int n = n_begin; n < n_end; ++n) {
         const double k = Kx[(size_t)n * B + b];
         const double ak = alpha_m[n] * k, qk = Q[(size_t)n * B + b] * k;
         mu += ak;
@@ -92,6 +100,15 @@ __global__ __launch_bounds__(256) void posterior_reduce_kernel(const double *__r
             gmu = fma(ak, xs, gmu);
             gq = fma(qk, xs, gq);
         }
+    }
+    if (slice > 0) {
+        red[slice - 1][0][lane] = mu; red[slice - 1][1][lane] = quad;
+        red[slice - 1][2][lane] = gmu; red[slice - 1][3][lane] = gq;
+    }
+    __syncthreads();
+    if (slice > 0 || !live) return;
+    for (int s = 0; s < 15; ++s) {
+        mu += red[s][0][lane]; quad += red[s][1][lane]; gmu += red[s][2][lane]; gq += red[s][3][lane];
     }
     double var = sf2 - quad;
     const bool floored = var < VAR_FLOOR;
@@ -118,7 +135,7 @@ hipError_t step_d(bagel_ctx *c, bool jac, const float *xi_t)
         hipLaunchKernelGGL((posterior_rows_kernel<D>), dim3((B + 255) / 256, (Np + 31) / 32), dim3(256), 0, c->stream, Xs_m,
                            A_m, c->xbuf, c->post_Kx, B, N, Np);
         bagel_dgemm(c->stream, Np, B, Np, 1.0, c->post_Kinv + (size_t)m * Np * Np, Np, 1, c->post_Kx, B, 1, c->post_Q, B, true);
-        hipLaunchKernelGGL((posterior_reduce_kernel<D>), dim3((B + 255) / 256, jac ? 1 + D : 1), dim3(256), 0, c->stream,
+        hipLaunchKernelGGL((posterior_reduce_kernel<D>), dim3((B + 63) / 64, jac ? 1 + D : 1), dim3(1024), 0, c->stream,
                            Xs_m, A_m, c->post_alpha + (size_t)m * Np, c->post_Kx, c->post_Q, c->xbuf, xi_t, c->post_sf2[m],
                            c->part + (size_t)m * (1 + D) * B, B, N, M, m);
     }

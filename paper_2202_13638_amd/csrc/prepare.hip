@@ -82,6 +82,17 @@ __global__ void convert_w_kernel(const float *__restrict__ w, double *__restrict
 // C[i][j] (ldc) += alpha * sum_k A(i,k) * B(k,j), A(i,k) = A[i*sai + k*sak], B(k,j) = B[k*sbk + j*sbj]
 // (C = alpha * ... with overwrite).  lower_only: skip tiles entirely above the diagonal (used for the
 // symmetric trailing update).
+// A workgroup owns a 64 x 64 tile of C; its four waves own 32 x 32 quarters as 2 x 2 tiles of
+// v_mfma_f64_16x16x4 (D[16x16] += A[16x4] B[4x16]; lane l feeds A[i = l % 16][k = l / 16] and
+// B[k = l / 16][j = l % 16]; register r of lane l holds D[row = l / 16 + 4 r][col = l % 16]).
+// Operand tiles of 16 contraction indices go through LDS as [k][i] with rows padded by one element,
+// so the 16 lanes of a k-row read consecutive addresses.  The float64 matrix pipe has the rate of the
+// vector pipe on this chip, but it needs one LDS read per 512 FMAs where a vector-FMA micro-tile
+// needs one per 2.  (A 128 x 128 tile with register prefetch was measured too: no faster on the
+// [2048 x 2048] x [2048 x 1024] products of the posterior sampler, where it leaves half the compute
+// units without a tile, and slower on the 64-deep updates of the blocked factorisation.)
+typedef double d4v __attribute__((ext_vector_type(4)));
+
 __global__ __launch_bounds__(256) void dgemm_kernel(int Mr, int Nc, int Kd, double alpha,
                                                     const double *__restrict__ A, long sai, long sak,
                                                     const double *__restrict__ Bm, long sbk, long sbj,
@@ -92,12 +103,14 @@ __global__ __launch_bounds__(256) void dgemm_kernel(int Mr, int Nc, int Kd, doub
     __shared__ double As[TK][TM + 1];
     __shared__ double Bs[TK][TN + 1];
     const int tid = threadIdx.x;
-    const int tx = tid & 15, ty = tid >> 4;
-    double acc[4][4];
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wi = (wave >> 1) * 32, wj = (wave & 1) * 32;     // the wave's quarter of the tile
+    const int lr = lane & 15, lk = lane >> 4;
+    d4v acc[2][2];
 #pragma unroll
-    for (int r = 0; r < 4; ++r)
+    for (int x = 0; x < 2; ++x)
 #pragma unroll
-        for (int c = 0; c < 4; ++c) acc[r][c] = 0.0;
+        for (int y = 0; y < 2; ++y) acc[x][y] = d4v{0.0, 0.0, 0.0, 0.0};
     // loaders: pick the thread->element map that walks the unit-stride direction fastest
     const bool a_k_fast = (sak == 1);
     const bool b_j_fast = (sbj == 1);
@@ -116,29 +129,33 @@ __global__ __launch_bounds__(256) void dgemm_kernel(int Mr, int Nc, int Kd, doub
         }
         __syncthreads();
 #pragma unroll
-        for (int k = 0; k < TK; ++k) {
-            double av[4], bv[4];
+        for (int ks = 0; ks < TK; ks += 4) {
+            double av[2], bv[2];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) av[r] = As[k][ty * 4 + r];
+            for (int x = 0; x < 2; ++x) av[x] = As[ks + lk][wi + 16 * x + lr];
 #pragma unroll
-            for (int c = 0; c < 4; ++c) bv[c] = Bs[k][tx * 4 + c];
+            for (int y = 0; y < 2; ++y) bv[y] = Bs[ks + lk][wj + 16 * y + lr];
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
+            for (int x = 0; x < 2; ++x)
 #pragma unroll
-                for (int c = 0; c < 4; ++c) acc[r][c] = fma(av[r], bv[c], acc[r][c]);
+                for (int y = 0; y < 2; ++y)
+                    acc[x][y] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[x], bv[y], acc[x][y], 0, 0, 0);
         }
         __syncthreads();
     }
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int gi = i0 + ty * 4 + r;
-        if (gi >= Mr) continue;
+    for (int x = 0; x < 2; ++x)
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const int gj = j0 + tx * 4 + c;
-            if (gj < Nc) Cm[(long)gi * ldc + gj] = (overwrite ? 0.0 : Cm[(long)gi * ldc + gj]) + alpha * acc[r][c];
-        }
-    }
+        for (int y = 0; y < 2; ++y)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int gi = i0 + wi + 16 * x + lk + 4 * r;
+                const int gj = j0 + wj + 16 * y + lr;
+                if (gi < Mr && gj < Nc) {
+                    double *dst = Cm + (long)gi * ldc + gj;
+                    *dst = (overwrite ? 0.0 : *dst) + alpha * acc[x][y][r];
+                }
+            }
 }
 
 // Factor the NB x NB diagonal block at (k,k) in place (lower).  One workgroup of NB threads,
