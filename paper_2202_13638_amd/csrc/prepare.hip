@@ -114,20 +114,40 @@ __global__ __launch_bounds__(256) void dgemm_kernel(int Mr, int Nc, int Kd, doub
     // loaders: pick the thread->element map that walks the unit-stride direction fastest
     const bool a_k_fast = (sak == 1);
     const bool b_j_fast = (sbj == 1);
-    for (int k0 = 0; k0 < Kd; k0 += TK) {
+    constexpr int PER = TM * TK / 256;                // elements of each operand tile per thread
+    double ra[PER], rb[PER];
+    auto fetch = [&](int k0) {                        // global -> registers (zero outside the matrices)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int idx = tid + e * 256;            // 0..1023 = TM*TK
+        for (int e = 0; e < PER; ++e) {
+            const int idx = tid + e * 256;
             int ii, kk;
             if (a_k_fast) { kk = idx % TK; ii = idx / TK; } else { ii = idx % TM; kk = idx / TM; }
             const int gi = i0 + ii, gk = k0 + kk;
-            As[kk][ii] = (gi < Mr && gk < Kd) ? A[(long)gi * sai + (long)gk * sak] : 0.0;
+            ra[e] = (gi < Mr && gk < Kd) ? A[(long)gi * sai + (long)gk * sak] : 0.0;
             int jj, kb;
             if (b_j_fast) { jj = idx % TN; kb = idx / TN; } else { kb = idx % TK; jj = idx / TK; }
             const int gj = j0 + jj, gkb = k0 + kb;
-            Bs[kb][jj] = (gj < Nc && gkb < Kd) ? Bm[(long)gkb * sbk + (long)gj * sbj] : 0.0;
+            rb[e] = (gj < Nc && gkb < Kd) ? Bm[(long)gkb * sbk + (long)gj * sbj] : 0.0;
         }
-        __syncthreads();
+    };
+    auto stash = [&]() {                              // registers -> LDS
+#pragma unroll
+        for (int e = 0; e < PER; ++e) {
+            const int idx = tid + e * 256;
+            int ii, kk;
+            if (a_k_fast) { kk = idx % TK; ii = idx / TK; } else { ii = idx % TM; kk = idx / TM; }
+            As[kk][ii] = ra[e];
+            int jj, kb;
+            if (b_j_fast) { jj = idx % TN; kb = idx / TN; } else { kb = idx % TK; jj = idx / TK; }
+            Bs[kb][jj] = rb[e];
+        }
+    };
+    fetch(0);
+    stash();
+    __syncthreads();
+    for (int k0 = 0; k0 < Kd; k0 += TK) {
+        const bool more = k0 + TK < Kd;
+        if (more) fetch(k0 + TK);                     // in flight under the MFMAs below
 #pragma unroll
         for (int ks = 0; ks < TK; ks += 4) {
             double av[2], bv[2];
@@ -141,6 +161,8 @@ __global__ __launch_bounds__(256) void dgemm_kernel(int Mr, int Nc, int Kd, doub
                 for (int y = 0; y < 2; ++y)
                     acc[x][y] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[x], bv[y], acc[x][y], 0, 0, 0);
         }
+        __syncthreads();
+        if (more) stash();
         __syncthreads();
     }
 #pragma unroll
