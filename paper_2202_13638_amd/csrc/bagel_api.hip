@@ -1,8 +1,10 @@
 // C ABI of libbagel.so (declared in include/bagel.h): argument checks, the context and its
 // buffers, and the per-call schedule of kernels.  A rollout is a host loop over the horizon that
-// enqueues, per step, the policy kernel, the sample-evaluation kernel and the state-advance kernel
-// on the context's stream (Algorithm 1, forward pass); the gradient call then sweeps the tape
-// backwards (Algorithm 1, backward pass) and finishes with one weight-gradient GEMM per layer.
+// enqueues, per step, the sample evaluation (pathwise function samples, or the per-step posterior
+// draw) and the end-of-step kernel, which also runs the policy of the next step, on the context's
+// stream (Algorithm 1, forward pass); the gradient call then sweeps the tape backwards in one launch
+// per tape segment (Algorithm 1, backward pass) and finishes with one weight-gradient GEMM per layer.
+// bagel_optimize wraps that in the inner loop of Algorithm 1 with an Adam update per iteration.
 #include <math.h>
 #include <stdio.h>
 #include <stdlib.h>

@@ -1,6 +1,7 @@
-// Lane-per-trajectory kernels around the sample evaluation: reduction of the per-unit partial
-// sums, the state update s_{t+1} = s_t + f(x_t) (state increments as GP targets, Sec. III-A), the
-// running cost (Algorithm 1, return accumulation; eq. (8) or the quadratic cost).
+// Lane-per-trajectory kernels at the edges of a rollout: initial state and checkpoint restore,
+// the final loss reduction (Algorithm 1: loss = mean over trajectories of the summed cost), and the
+// plumbing of bagel_sample_eval (reduction of the partial sums of one sample evaluation on its own;
+// inside a rollout that reduction is part of the end-of-step kernel).
 // All per-trajectory arrays are laid out [component][B] so that a wave reads consecutive
 // trajectories.
 #include "bagel_internal.h"

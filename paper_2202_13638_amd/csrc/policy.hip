@@ -1,13 +1,15 @@
 // Policy network pi_theta([s ; g]): tanh MLP with a linear or saturating output (Sec. III-B and
-// IV-A: feed-forward policy, bounded action), its backward pass, and the weight gradients.
-// All three are dense float32 contractions and run on the matrix cores
-// (v_mfma_f32_32x32x2_f32: D[32x32] += A[32x2] B[2x32]).
+// IV-A: feed-forward policy, bounded action), the end of a rollout step around it, the backward
+// sweep of Algorithm 1, the weight gradients and the Adam update.  The layers are dense float32
+// contractions and run on the matrix cores (v_mfma_f32_32x32x2_f32: D[32x32] += A[32x2] B[2x32]).
 //
-// Forward / backward of one step.  A workgroup holds 32 trajectories and 8 waves; a wave owns the
+// Layers, forward and backward.  A workgroup holds 32 trajectories and 8 waves; a wave owns the
 // 32x32 output tile of units [32 rt, 32 rt + 32) x the 32 trajectories (and, when a layer has fewer
 // than 8 row tiles, one slice of the contraction; slices are added through LDS in a fixed order).
 //   A operand = weights, zero-padded to [rows % 32 == 0][K % 32 == 0] and re-ordered once per call
-//               so that a wave reads the operands of four MFMAs as 1 KB of contiguous memory;
+//               so that a wave reads the operands of four MFMAs as 1 KB of contiguous memory; the
+//               forward kernels keep the wave's share of all layers in registers, the backward
+//               sweep streams its share from L2 one batch of 16 MFMAs ahead;
 //   B operand = the layer's input activations, kept in LDS as [K/4][trajectory][4] so a lane
 //               reads the matching four K values of its trajectory with one 16-byte load.
 // Lanes 0-31 feed K = k0..k0+3 and lanes 32-63 feed K = k0+4..k0+7 over four MFMAs; the order in
@@ -15,12 +17,16 @@
 // tanh derivative in the backward pass) writes the next layer's input back to LDS in the same
 // layout and to the tape in HBM as [unit][B].
 //
+// Kernels: policy_forward_kernel (first step of a rollout or segment), step_tail_kernel (everything
+// between two sample evaluations: reduction of the partial sums, state update, cost, tapes, policy
+// of the next step), backward_sweep_kernel (all backward steps of a tape segment in one launch).
+//
 // Weight gradients are not accumulated inside the sweep.  For each layer
 //   dW[o][i] = sum_{t,b} delta[t][o][b] * h[t][i][b],   db[o] = sum_{t,b} delta[t][o][b]
-// is one GEMM over the taped arrays with the contraction over (step, trajectory).  Both operands
-// are contiguous along the contraction, so lanes load their MFMA operands straight from HBM/L2;
-// the contraction range is split over workgroups in a fixed way and the partial results are
-// added in a fixed order, so the gradient is bitwise reproducible.
+// is one GEMM over the taped arrays with the contraction over (step, trajectory): operands staged
+// through LDS for the wide layer (weight_grad_tiled_kernel), read straight from the tape for the
+// narrow ones (weight_grad_kernel).  The contraction range is split over workgroups in a fixed way
+// and the partial results are added in a fixed order, so the gradient is bitwise reproducible.
 #include "bagel_internal.h"
 
 namespace {
