@@ -265,3 +265,56 @@ def posterior_rollout(dm: Dims, m: Dict[str, np.ndarray], alpha, Kinv, xi, theta
     if rc != 0:
         raise RuntimeError(f"oracle_posterior_rollout failed with code {rc}")
     return {"loss": float(loss[0]), "loss_per_traj": lpt, "states": states, "grad_theta": g, "grad_s0": gs0}
+
+
+# ---------------------------------------------------------------------------------------------
+# GP hyper-parameter learning (the step before the rollouts in Algorithm 1: "learn GP transition
+# dynamics").  Plain numpy, float64.
+
+def hyper_lml_grad(X, y_m, log_hyp_m):
+    """Log marginal likelihood of one output's GP and its gradient (eq. (5), (6); eq. (6) as printed has
+    K_hat and its inverse exchanged, the standard form is used):
+        lml = -1/2 y^T K_hat^-1 y - 1/2 log|K_hat| - n/2 log(2 pi),
+        d lml / d phi = 1/2 tr((a a^T - K_hat^-1) dK_hat/dphi),  a = K_hat^-1 y,
+    with the kernel of eq. (4), K_hat = K + sigma_n^2 I, and phi = log_hyp_m = (log l_1 .. log l_D,
+    log alpha^2, log sigma_n^2).  Returns (lml, grad[D+2])."""
+    X, y_m, lh = _d(X), _d(y_m), _d(log_hyp_m)
+    n, D = X.shape
+    ell, sf2, sn2 = np.exp(lh[:D]), np.exp(lh[D]), np.exp(lh[D + 1])
+    diff2 = ((X[:, None, :] - X[None, :, :]) / ell) ** 2               # [n, n, D]
+    K = sf2 * np.exp(-0.5 * diff2.sum(-1))
+    Khat = K + sn2 * np.eye(n)
+    Lc = np.linalg.cholesky(Khat)
+    Kinv = np.linalg.inv(Khat)
+    a = Kinv @ y_m
+    lml = -0.5 * y_m @ a - np.log(np.diag(Lc)).sum() - 0.5 * n * np.log(2.0 * np.pi)
+    W = np.outer(a, a) - Kinv
+    grad = np.empty(D + 2)
+    for d in range(D):
+        grad[d] = 0.5 * np.sum(W * K * diff2[:, :, d])                  # dK/d log l_d = K (x_d - x'_d)^2 / l_d^2
+    grad[D] = 0.5 * np.sum(W * K)                                        # dK/d log alpha^2 = K
+    grad[D + 1] = 0.5 * sn2 * np.trace(W)                                # dK_hat/d log sigma_n^2 = sigma_n^2 I
+    return float(lml), grad
+
+
+def hyper_fit(X, y, log_hyp0, n_iters: int, *, first_step: int = 1, adam_m=None, adam_v=None, lr=1e-2, beta1=0.9,
+              beta2=0.999, eps=1e-8):
+    """Adam on -lml / n of every output (hyper-parameters, moments and the Adam constants held in float32
+    between iterations, as the device interface holds them; arithmetic in float64).  y[M, n],
+    log_hyp0[M, D+2].  Returns (log_hyp, adam_m, adam_v, lml_history[n_iters, M])."""
+    X, y = _d(X), _d(y)
+    n = X.shape[0]
+    lh = np.asarray(log_hyp0, dtype=np.float32).copy()
+    am = np.zeros_like(lh) if adam_m is None else np.asarray(adam_m, dtype=np.float32).copy()
+    av = np.zeros_like(lh) if adam_v is None else np.asarray(adam_v, dtype=np.float32).copy()
+    hp = [float(np.float32(v)) for v in (lr, beta1, beta2, eps)]
+    hist = np.empty((n_iters, lh.shape[0]))
+    for it in range(n_iters):
+        g = np.empty(lh.shape)
+        for m in range(lh.shape[0]):
+            hist[it, m], gm = hyper_lml_grad(X, y[m], lh[m])
+            g[m] = -gm / n
+        th, mm, vv = (a.astype(np.float64).ravel().copy() for a in (lh, am, av))
+        adam_step(th, g.ravel(), mm, vv, first_step + it, lr=hp[0], beta1=hp[1], beta2=hp[2], eps=hp[3])
+        lh, am, av = (a.reshape(lh.shape).astype(np.float32) for a in (th, mm, vv))
+    return lh, am, av, hist

@@ -38,6 +38,9 @@
  *                           (oracle.optimize in the Python wrapper) alternates
  *                           oracle_rollout and oracle_adam_step.
  *
+ * (GP hyper-parameter learning by the marginal likelihood, eq. (5), (6), is the plain numpy
+ * function hyper_lml_grad in the Python wrapper; pinned against scikit-learn and finite differences.)
+ *
  * Pins (tests/test_oracle_pins.py): with w = 0 and eps = 0 a sample is the
  * textbook posterior mean of eq. (2); sample mean / covariance over many draws
  * against eq. (2), (3); feature inner products against eq. (4); central finite

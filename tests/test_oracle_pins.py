@@ -523,3 +523,57 @@ def test_posterior_rollout_gradient_by_finite_differences(kw):
         fd0[idx] = (oracle.posterior_rollout(dm, inp, alpha, Kinv, xi, s0=sp, grad=False, want_states=False)["loss"] -
                     oracle.posterior_rollout(dm, inp, alpha, Kinv, xi, s0=sm, grad=False, want_states=False)["loss"]) / (2 * h)
     np.testing.assert_allclose(out["grad_s0"], fd0, rtol=1e-5, atol=1e-7 * np.abs(fd0).max() + 1e-10)
+
+
+# ------------------------------------------------------------------ hyper-parameter learning (eq. (5), (6))
+def _hyper_problem(n=30, D=3, seed=0):
+    rng = np.random.default_rng(seed)
+    X = rng.uniform(-1, 1, (n, D))
+    y = np.sin(2.0 * X[:, 0]) + 0.3 * X[:, 1] + 0.05 * rng.standard_normal(n)
+    lh = np.concatenate([np.log(rng.uniform(0.5, 2.0, D)), [np.log(0.7)], [np.log(0.02)]])
+    return X, y, lh
+
+
+def test_marginal_likelihood_matches_library_routine():
+    """lml and its gradient against scikit-learn's GaussianProcessRegressor with the same kernel
+    (constant * RBF with per-dimension length scales + white noise); sklearn's theta is
+    (log alpha^2, log l_1 .. log l_D, log sigma_n^2)."""
+    gp = pytest.importorskip("sklearn.gaussian_process")
+    from sklearn.gaussian_process.kernels import RBF, ConstantKernel, WhiteKernel
+    X, y, lh = _hyper_problem()
+    D = X.shape[1]
+    kern = ConstantKernel(np.exp(lh[D])) * RBF(length_scale=np.exp(lh[:D])) + WhiteKernel(np.exp(lh[D + 1]))
+    model = gp.GaussianProcessRegressor(kernel=kern, optimizer=None, alpha=0.0).fit(X, y)
+    theta = np.concatenate([[lh[D]], lh[:D], [lh[D + 1]]])
+    ref, ref_g = model.log_marginal_likelihood(theta, eval_gradient=True)
+    lml, g = oracle.hyper_lml_grad(X, y, lh)
+    assert abs(lml - ref) <= 1e-9 * abs(ref)
+    np.testing.assert_allclose(np.concatenate([[g[D]], g[:D], [g[D + 1]]]), ref_g, rtol=1e-7, atol=1e-9)
+
+
+def test_marginal_likelihood_closed_form_and_finite_differences():
+    # one training point: lml = -1/2 y^2 / (a2 + s2) - 1/2 log(a2 + s2) - 1/2 log 2 pi
+    lml, g = oracle.hyper_lml_grad(np.array([[0.3, -0.1]]), np.array([0.8]), np.log([1.0, 2.0, 0.5, 0.1]))
+    c = 0.6
+    assert abs(lml - (-0.5 * 0.64 / c - 0.5 * math.log(c) - 0.5 * math.log(2 * math.pi))) < 1e-12
+    dl_dc = 0.5 * 0.64 / c ** 2 - 0.5 / c
+    np.testing.assert_allclose(g, [0.0, 0.0, dl_dc * 0.5, dl_dc * 0.1], atol=1e-12)
+    X, y, lh = _hyper_problem(n=25, D=4, seed=3)
+    _, g = oracle.hyper_lml_grad(X, y, lh)
+    h = 1e-6
+    for j in range(lh.size):
+        e = np.zeros_like(lh); e[j] = h
+        fd = (oracle.hyper_lml_grad(X, y, lh + e)[0] - oracle.hyper_lml_grad(X, y, lh - e)[0]) / (2 * h)
+        assert abs(g[j] - fd) <= 1e-6 * max(1.0, abs(fd))
+
+
+def test_hyper_fit_raises_the_marginal_likelihood():
+    X, y, lh = _hyper_problem(n=40, D=2, seed=5)
+    Y = np.stack([y, 0.5 * y + 0.1 * X[:, 1]])
+    lh0 = np.tile(np.log([1.0, 1.0, 1.0, 0.1]), (2, 1))
+    out, am, av, hist = oracle.hyper_fit(X, Y, lh0, 30, lr=5e-2)
+    assert np.all(hist[-1] > hist[0])
+    # split runs with the state carried over reproduce the single run
+    o1, m1, v1, _ = oracle.hyper_fit(X, Y, lh0, 10, lr=5e-2)
+    o2, _, _, _ = oracle.hyper_fit(X, Y, o1, 20, first_step=11, adam_m=m1, adam_v=v1, lr=5e-2)
+    np.testing.assert_array_equal(o2, out)
