@@ -84,6 +84,9 @@ def main():
     ap.add_argument("--sampler", default="pathwise", choices=["pathwise", "posterior"],
                     help="pathwise: one function sample per trajectory (the headline path); posterior: per-step "
                          "draws from the exact predictive posterior (2 N^2 flop per trajectory, step and output)")
+    ap.add_argument("--hyper-iters", type=int, default=0,
+                    help="also time this many iterations of bagel_hyper_fit (marginal-likelihood learning of the GP "
+                         "hyper-parameters) on the workload's training set, outside the timed region")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the forward-only and inner-loop figures")
     ap.add_argument("--profile-every", type=int, default=8, help="time every n-th sample-evaluation launch")
@@ -215,6 +218,21 @@ def main():
         t_opt = timed(lambda: ctx.bagel_optimize(theta, am, av, g["s0"][None], g["goals"][None], n_it, hist))
         out["inner_loop"] = {"value": traj_steps * n_it / t_opt, "unit": "trajectory-steps/s", "iterations": n_it,
                              "ms_per_iteration": 1e3 * t_opt / n_it, "loss": [float(x) for x in hist.cpu()]}
+    if args.hyper_iters > 0:
+        lh = torch.cat([g["lengthscale"].log(), g["signal_var"].log()[:, None], g["noise_var"].log()[:, None]], dim=1).contiguous()
+        am, av = torch.zeros_like(lh), torch.zeros_like(lh)
+        hist = torch.zeros((args.hyper_iters, cfg.M), device="cuda")
+        yy = torch.from_numpy(inp["y"]).cuda()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ctx.bagel_hyper_fit(g["X"], yy, lh, am, av, args.hyper_iters, hist)
+        torch.cuda.synchronize()
+        t_h = time.perf_counter() - t0
+        Np = (cfg.N + 63) // 64 * 64
+        flop = 2.0 * cfg.M * args.hyper_iters * (Np ** 3 / 3 + 2.0 * Np ** 3)     # Cholesky + K_hat^-1 by substitution
+        out["hyper_fit"] = {"iterations": args.hyper_iters, "ms_per_iteration": 1e3 * t_h / args.hyper_iters,
+                            "TFLOP/s": flop / t_h / 1e12, "frac_of_f64_peak": flop / t_h / 1e12 / PEAK_FP64_VECTOR_TFLOPS,
+                            "lml_first": [float(x) for x in hist[0].cpu()], "lml_last": [float(x) for x in hist[-1].cpu()]}
     if not args.no_cpu_baseline and args.trajectories_per_sample == 1 and not posterior:
         out["cpu_baseline"] = cpu_baseline(cfg, inp)
     ctx.close()

@@ -192,6 +192,28 @@ int bagel_optimize(bagel_ctx *ctx, float *theta, float *adam_m, float *adam_v, c
                    float beta1, float beta2, float eps, float *loss_history);
 
 /*
+ * GP hyper-parameter learning (Algorithm 1, "learn GP transition dynamics"): the log marginal
+ * likelihood of eq. (5) for every output,
+ *   lml_m = -1/2 y_m^T K_hat^-1 y_m - 1/2 log|K_hat| - N/2 log(2 pi),
+ * and its gradient (eq. (6) in its standard form, 1/2 tr((a a^T - K_hat^-1) dK_hat/dphi), a = K_hat^-1 y)
+ * with respect to the logarithms of the hyper-parameters of eq. (4):
+ *   log_hyp[M][D+2] = (log l_1 .. log l_D, log alpha^2, log sigma_n^2) per output.
+ * X[N][D], y[M][N] as in bagel_prepare_samples; lml[M]; grad[M][D+2] or NULL.  Float64 inside.
+ * Set-up work: allocates its N x N buffers for the duration of the call and synchronises the stream.
+ * Errors: EINVAL, ENOMEM, ENOTPD, EHIP.
+ *
+ * bagel_hyper_fit: n_iters Adam updates of log_hyp (in place) that raise lml / N of every output;
+ * adam_m, adam_v [M][D+2] are the caller's optimiser state (start at zero), first_step >= 1 the
+ * number of the first update; lml_history[n_iters][M] receives the lml before each update.
+ * The paper does not state the optimiser settings of this step; they are arguments.
+ */
+int bagel_hyper_lml_grad(bagel_ctx *ctx, const float *X, const float *y, const float *log_hyp, float *lml,
+                         float *grad);
+int bagel_hyper_fit(bagel_ctx *ctx, const float *X, const float *y, float *log_hyp, float *adam_m, float *adam_v,
+                    int n_iters, int first_step, float lr, float beta1, float beta2, float eps,
+                    float *lml_history);
+
+/*
  * One evaluation of the function samples (the transition model alone): for every trajectory b,
  * f[b][m] = f_{s(b),m}(x[b]) and, if jac != NULL, jac[b][m][d] = d f / d x_d.   x[B][D].
  * Runs the same kernels as one rollout step.  Errors: EINVAL, ENOTPREPARED, EHIP.

@@ -21,7 +21,7 @@ _NAMES = {EINVAL: "BAGEL_EINVAL", ENOTPREPARED: "BAGEL_ENOTPREPARED", ENOMEM: "B
 EXPORTS = ["bagel_num_params", "bagel_create", "bagel_destroy", "bagel_workspace_bytes",
            "bagel_prepare_samples", "bagel_set_samples", "bagel_rollout_loss",
            "bagel_rollout_loss_grad", "bagel_sample_eval", "bagel_last_error", "bagel_adam_step", "bagel_optimize",
-           "bagel_prepare_posterior", "bagel_posterior_rollout_loss", "bagel_posterior_rollout_loss_grad",
+           "bagel_hyper_lml_grad", "bagel_hyper_fit", "bagel_prepare_posterior", "bagel_posterior_rollout_loss", "bagel_posterior_rollout_loss_grad",
            "bagel_profile_enable", "bagel_profile_read"]
 
 
@@ -109,6 +109,10 @@ def load():
         L.bagel_posterior_rollout_loss.argtypes = [vp] + [fp] * 7
         L.bagel_posterior_rollout_loss_grad.restype = C.c_int
         L.bagel_posterior_rollout_loss_grad.argtypes = [vp] + [fp] * 9
+        L.bagel_hyper_lml_grad.restype = C.c_int
+        L.bagel_hyper_lml_grad.argtypes = [vp] + [fp] * 5
+        L.bagel_hyper_fit.restype = C.c_int
+        L.bagel_hyper_fit.argtypes = [vp] + [fp] * 5 + [C.c_int] * 2 + [C.c_float] * 4 + [fp]
         L.bagel_adam_step.restype = C.c_int
         L.bagel_adam_step.argtypes = [vp] + [fp] * 4 + [C.c_int] + [C.c_float] * 4
         L.bagel_optimize.restype = C.c_int
@@ -234,6 +238,20 @@ class Bagel:
             _ptr(loss_per_traj, (d.B,), "loss_per_traj", optional=True),
             _ptr(states, (d.H + 1, d.B, d.d_s), "states", optional=True),
             _ptr(grad_s0, (d.B, d.d_s), "grad_s0", optional=True)))
+
+    def bagel_hyper_lml_grad(self, X, y, log_hyp, lml, grad=None):
+        d, M, D = self.dims, self.M, self.D
+        self._check(self._lib.bagel_hyper_lml_grad(
+            self._h, _ptr(X, (d.N, D), "X"), _ptr(y, (M, d.N), "y"), _ptr(log_hyp, (M, D + 2), "log_hyp"),
+            _ptr(lml, (M,), "lml"), _ptr(grad, (M, D + 2), "grad", optional=True)))
+
+    def bagel_hyper_fit(self, X, y, log_hyp, adam_m, adam_v, n_iters, lml_history, first_step=1, lr=1e-2, beta1=0.9,
+                        beta2=0.999, eps=1e-8):
+        d, M, D = self.dims, self.M, self.D
+        self._check(self._lib.bagel_hyper_fit(
+            self._h, _ptr(X, (d.N, D), "X"), _ptr(y, (M, d.N), "y"), _ptr(log_hyp, (M, D + 2), "log_hyp"),
+            _ptr(adam_m, (M, D + 2), "adam_m"), _ptr(adam_v, (M, D + 2), "adam_v"), int(n_iters), int(first_step),
+            lr, beta1, beta2, eps, _ptr(lml_history, (int(n_iters), M), "lml_history")))
 
     def bagel_adam_step(self, theta, grad, adam_m, adam_v, step, lr=1e-2, beta1=0.9, beta2=0.999, eps=1e-8):
         P = (self.P,)

@@ -461,7 +461,7 @@ static hipError_t adam_update(bagel_ctx *c, float *theta, const float *grad, flo
                               float lr, float beta1, float beta2, float eps)
 {
     const double b1 = (double)beta1, b2 = (double)beta2;
-    return bagel_launch_adam(c, theta, grad, m, v, (double)lr, b1, b2, (double)eps, 1.0 - pow(b1, (double)step),
+    return bagel_launch_adam(c, theta, grad, m, v, c->P, (double)lr, b1, b2, (double)eps, 1.0 - pow(b1, (double)step),
                              1.0 - pow(b2, (double)step));
 }
 
@@ -496,4 +496,27 @@ extern "C" int bagel_optimize(bagel_ctx *c, float *theta, float *adam_m, float *
         BAGEL_HIP(c, adam_update(c, theta, c->gtheta, adam_m, adam_v, first_step + i, lr, beta1, beta2, eps));
     }
     return BAGEL_OK;
+}
+
+extern "C" int bagel_hyper_lml_grad(bagel_ctx *c, const float *X, const float *y, const float *log_hyp, float *lml,
+                                    float *grad)
+{
+    if (!c) return BAGEL_EINVAL;
+    c->err[0] = 0;
+    if (!X || !y || !log_hyp || !lml) BAGEL_FAIL(c, BAGEL_EINVAL, "bagel_hyper_lml_grad: null argument");
+    return bagel_hyper_impl(c, X, y, const_cast<float *>(log_hyp), lml, grad, nullptr, nullptr, 0, 1, 0.0, 0.0, 0.0, 0.0);
+}
+
+extern "C" int bagel_hyper_fit(bagel_ctx *c, const float *X, const float *y, float *log_hyp, float *adam_m,
+                               float *adam_v, int n_iters, int first_step, float lr, float beta1, float beta2,
+                               float eps, float *lml_history)
+{
+    if (!c) return BAGEL_EINVAL;
+    c->err[0] = 0;
+    if (!X || !y || !log_hyp || !adam_m || !adam_v || !lml_history)
+        BAGEL_FAIL(c, BAGEL_EINVAL, "bagel_hyper_fit: null argument");
+    if (n_iters < 1) BAGEL_FAIL(c, BAGEL_EINVAL, "bagel_hyper_fit: n_iters must be >= 1");
+    if (const char *msg = check_adam(first_step, lr, beta1, beta2, eps)) BAGEL_FAIL(c, BAGEL_EINVAL, "bagel_hyper_fit: %s", msg);
+    return bagel_hyper_impl(c, X, y, log_hyp, lml_history, nullptr, adam_m, adam_v, n_iters, first_step, (double)lr,
+                            (double)beta1, (double)beta2, (double)eps);
 }

@@ -117,7 +117,7 @@ hipError_t bagel_launch_step_tail(bagel_ctx *ctx, int t, int slot, int next_slot
 // backward sweep over steps t_hi-1 .. t_lo (tape slot of step k is k - t_lo); grad_s0 is written when t_lo == 0
 hipError_t bagel_launch_backward_sweep(bagel_ctx *ctx, int t_lo, int t_hi, const float *goals, float *grad_s0);
 hipError_t bagel_launch_weight_grad(bagel_ctx *ctx, int n_slots, bool accumulate, float *grad_theta);
-hipError_t bagel_launch_adam(bagel_ctx *ctx, float *theta, const float *grad, float *m, float *v, double lr,
+hipError_t bagel_launch_adam(bagel_ctx *ctx, float *theta, const float *grad, float *m, float *v, int count, double lr,
                              double beta1, double beta2, double eps, double corr1, double corr2);
 
 // ---- posterior.hip ------------------------------------------------------------------------
@@ -138,3 +138,7 @@ int bagel_prepare_posterior_impl(bagel_ctx *ctx, const float *X, const float *y,
 // C (+)= alpha * A * B in float64 with element strides (see dgemm_kernel); overwrite: C = alpha * A * B
 void bagel_dgemm(hipStream_t st, int Mr, int Nc, int Kd, double alpha, const double *A, long sai, long sak,
                  const double *Bm, long sbk, long sbj, double *Cm, long ldc, bool overwrite);
+// lml[iters][M] and grad[M][D+2] of the log hyper-parameters log_hyp[M][D+2]; n_iters > 0: Adam fit in place
+int bagel_hyper_impl(bagel_ctx *ctx, const float *X, const float *y, float *log_hyp, float *lml, float *grad,
+                     float *adam_m, float *adam_v, int n_iters, int first_step, double lr, double beta1, double beta2,
+                     double eps);

@@ -1082,10 +1082,10 @@ hipError_t bagel_launch_backward_sweep(bagel_ctx *c, int t_lo, int t_hi, const f
     return hipGetLastError();
 }
 
-hipError_t bagel_launch_adam(bagel_ctx *c, float *theta, const float *grad, float *m, float *v, double lr,
+hipError_t bagel_launch_adam(bagel_ctx *c, float *theta, const float *grad, float *m, float *v, int count, double lr,
                              double beta1, double beta2, double eps, double corr1, double corr2)
 {
-    hipLaunchKernelGGL(adam_kernel, dim3((c->P + 255) / 256), dim3(256), 0, c->stream, theta, grad, m, v, c->P, lr,
+    hipLaunchKernelGGL(adam_kernel, dim3((count + 255) / 256), dim3(256), 0, c->stream, theta, grad, m, v, count, lr,
                        beta1, beta2, eps, corr1, corr2);
     return hipGetLastError();
 }

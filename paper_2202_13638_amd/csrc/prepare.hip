@@ -11,6 +11,7 @@
 //      GEMM-dominated;
 //   5. v is rounded to float32 once, written to v_out[S][M][N] and packed for the step kernel.
 // This is set-up work outside the timed rollouts; buffers are allocated here and freed on return.
+#include <math.h>
 #include <stdio.h>
 
 #include "bagel_internal.h"
@@ -353,6 +354,101 @@ __global__ void posterior_emit_kernel(const double *__restrict__ R, double *__re
     else alpha[n] = v;
 }
 
+// ---- hyper-parameter learning: log marginal likelihood and its gradient (eq. (5), (6)) ----------
+// K_hat for hyper-parameters given as logarithms on the device: lh = (log l_1 .. log l_D, log alpha^2,
+// log sigma_n^2); identity on the padding
+__global__ void build_khat_log_kernel(const float *__restrict__ X, const float *__restrict__ lh, double *__restrict__ K,
+                                      int N, int Np, int D)
+{
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    const int i = blockIdx.y;
+    if (j >= Np) return;
+    double val;
+    if (i < N && j < N) {
+        double r = 0.0;
+        for (int d = 0; d < D; ++d) {
+            const double t = ((double)X[(size_t)i * D + d] - (double)X[(size_t)j * D + d]) / exp((double)lh[d]);
+            r += t * t;
+        }
+        val = exp((double)lh[D]) * exp(-0.5 * r);
+        if (i == j) val += exp((double)lh[D + 1]);
+    } else {
+        val = (i == j) ? 1.0 : 0.0;
+    }
+    K[(size_t)i * Np + j] = val;
+}
+
+// fixed-order sum of one value per thread over a workgroup of 256 (result valid in thread 0)
+__device__ __forceinline__ double block_sum_256(double v, double *sh)
+{
+    sh[threadIdx.x] = v;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) sh[threadIdx.x] += sh[threadIdx.x + s];
+        __syncthreads();
+    }
+    return sh[0];
+}
+
+// lml = -1/2 y^T a - sum_i log L_ii - N/2 log(2 pi); L = factor in K (diagonal), a = last column of R
+__global__ __launch_bounds__(256) void hyper_lml_kernel(const double *__restrict__ Lf, const double *__restrict__ R,
+                                                        const float *__restrict__ y_m, int N, int Np,
+                                                        float *__restrict__ lml_out)
+{
+    __shared__ double sh[256];
+    double ld = 0.0, quad = 0.0;
+    for (int i = threadIdx.x; i < Np; i += 256) ld += log(Lf[(size_t)i * Np + i]);
+    for (int n = threadIdx.x; n < N; n += 256) quad += (double)y_m[n] * R[(size_t)n * (Np + 1) + Np];
+    const double ld_tot = block_sum_256(ld, sh);
+    __syncthreads();
+    const double q_tot = block_sum_256(quad, sh);
+    if (threadIdx.x == 0) lml_out[0] = (float)(-0.5 * q_tot - ld_tot - 0.5 * (double)N * 1.8378770664093453);
+}
+
+// row i of sum_ij (a_i a_j - Kinv_ij) dK_hat_ij / dphi_c for c = 0 .. D+1 -> partial[i][D+2]
+__global__ __launch_bounds__(256) void hyper_grad_rows_kernel(const float *__restrict__ X, const float *__restrict__ lh,
+                                                              const double *__restrict__ R, double *__restrict__ partial,
+                                                              int N, int Np, int D)
+{
+    __shared__ double sh[256];
+    const int i = blockIdx.x;
+    double acc[BAGEL_MAX_D + 2];
+    for (int c = 0; c < D + 2; ++c) acc[c] = 0.0;
+    const double sf2 = exp((double)lh[D]), sn2 = exp((double)lh[D + 1]);
+    const double ai = R[(size_t)i * (Np + 1) + Np];
+    for (int j = threadIdx.x; j < N; j += 256) {
+        const double w = ai * R[(size_t)j * (Np + 1) + Np] - R[(size_t)i * (Np + 1) + j];
+        double r = 0.0, t2[BAGEL_MAX_D];
+        for (int d = 0; d < D; ++d) {
+            const double t = ((double)X[(size_t)i * D + d] - (double)X[(size_t)j * D + d]) / exp((double)lh[d]);
+            t2[d] = t * t;
+            r += t2[d];
+        }
+        const double wk = w * sf2 * exp(-0.5 * r);
+        for (int d = 0; d < D; ++d) acc[d] += wk * t2[d];
+        acc[D] += wk;
+        if (j == i) acc[D + 1] += w * sn2;
+    }
+    for (int c = 0; c < D + 2; ++c) {
+        const double tot = block_sum_256(acc[c], sh);
+        if (threadIdx.x == 0) partial[(size_t)i * (D + 2) + c] = tot;
+        __syncthreads();
+    }
+}
+
+// grad[c] = 1/2 sum_i partial[i][c] (in row order); neg_scaled[c] = -grad[c] / N for the Adam update
+__global__ void hyper_grad_final_kernel(const double *__restrict__ partial, int N, int D, float *__restrict__ grad,
+                                        float *__restrict__ neg_scaled)
+{
+    const int c = threadIdx.x;
+    if (c >= D + 2) return;
+    double s = 0.0;
+    for (int i = 0; i < N; ++i) s += partial[(size_t)i * (D + 2) + c];
+    s *= 0.5;
+    if (grad) grad[c] = (float)s;
+    if (neg_scaled) neg_scaled[c] = (float)(-s / (double)N);
+}
+
 }  // namespace
 
 void bagel_dgemm(hipStream_t st, int Mr, int Nc, int Kd, double alpha, const double *A, long sai, long sak,
@@ -485,6 +581,73 @@ done:
     (void)hipStreamSynchronize(st);
     if (K) (void)hipFree(K);
     if (R) (void)hipFree(R);
+    if (flag) (void)hipFree(flag);
+    return rc;
+#undef P_HIP
+}
+
+// Log marginal likelihood of every output's GP and its gradient in the log hyper-parameters
+// (eq. (5), (6)), n_iters > 0: Adam ascent on lml / N for n_iters iterations (Algorithm 1, "learn GP
+// transition dynamics").  Buffers are allocated here and freed on return (set-up work).
+int bagel_hyper_impl(bagel_ctx *c, const float *X, const float *y, float *log_hyp, float *lml, float *grad,
+                     float *adam_m, float *adam_v, int n_iters, int first_step, double lr, double beta1, double beta2,
+                     double eps)
+{
+    const int N = c->dm.N, M = c->M, D = c->D, H2 = c->D + 2;
+    const int Np = (N + NB - 1) / NB * NB;
+    hipStream_t st = c->stream;
+    double *K = nullptr, *R = nullptr, *partial = nullptr;
+    float *gneg = nullptr;
+    int *flag = nullptr;
+    int rc = BAGEL_OK, h_flag = 0;
+#define P_HIP(call)                                                                              \
+    do {                                                                                         \
+        hipError_t e__ = (call);                                                                 \
+        if (e__ != hipSuccess) {                                                                 \
+            snprintf(c->err, sizeof(c->err), "bagel_hyper: %s failed: %s", #call, hipGetErrorString(e__)); \
+            rc = (e__ == hipErrorOutOfMemory) ? BAGEL_ENOMEM : BAGEL_EHIP;                       \
+            goto done;                                                                           \
+        }                                                                                        \
+    } while (0)
+    P_HIP(hipMalloc((void **)&K, (size_t)Np * Np * sizeof(double)));
+    P_HIP(hipMalloc((void **)&R, (size_t)Np * (Np + 1) * sizeof(double)));
+    P_HIP(hipMalloc((void **)&partial, (size_t)N * H2 * sizeof(double)));
+    P_HIP(hipMalloc((void **)&gneg, (size_t)M * H2 * sizeof(float)));
+    P_HIP(hipMalloc((void **)&flag, sizeof(int)));
+    P_HIP(hipMemsetAsync(flag, 0, sizeof(int), st));
+    for (int it = 0; it < (n_iters > 0 ? n_iters : 1); ++it) {
+        for (int m = 0; m < M; ++m) {
+            const float *lh = log_hyp + (size_t)m * H2;
+            hipLaunchKernelGGL(build_khat_log_kernel, dim3((Np + 255) / 256, Np), dim3(256), 0, st, X, lh, K, N, Np, D);
+            hipLaunchKernelGGL(posterior_rhs_kernel, dim3((Np + 1 + 255) / 256, Np), dim3(256), 0, st, y + (size_t)m * N,
+                               R, N, Np);
+            factor_and_solve(st, K, Np, R, Np + 1, m * Np, flag);
+            hipLaunchKernelGGL(hyper_lml_kernel, dim3(1), dim3(256), 0, st, K, R, y + (size_t)m * N, N, Np,
+                               lml + (size_t)it * M + m);
+            hipLaunchKernelGGL(hyper_grad_rows_kernel, dim3(N), dim3(256), 0, st, X, lh, R, partial, N, Np, D);
+            hipLaunchKernelGGL(hyper_grad_final_kernel, dim3(1), dim3(64), 0, st, partial, N, D,
+                               grad ? grad + (size_t)m * H2 : nullptr, gneg + (size_t)m * H2);
+            P_HIP(hipGetLastError());
+        }
+        if (n_iters > 0) {
+            const int step = first_step + it;
+            P_HIP(bagel_launch_adam(c, log_hyp, gneg, adam_m, adam_v, M * H2, lr, beta1, beta2, eps,
+                                    1.0 - pow(beta1, (double)step), 1.0 - pow(beta2, (double)step)));
+        }
+    }
+    P_HIP(hipMemcpyAsync(&h_flag, flag, sizeof(int), hipMemcpyDeviceToHost, st));
+    P_HIP(hipStreamSynchronize(st));
+    if (h_flag != 0) {
+        snprintf(c->err, sizeof(c->err), "bagel_hyper: K + noise_var I is not positive definite (output %d, pivot %d)",
+                 (h_flag - 1) / Np, (h_flag - 1) % Np);
+        rc = BAGEL_ENOTPD;
+    }
+done:
+    (void)hipStreamSynchronize(st);
+    if (K) (void)hipFree(K);
+    if (R) (void)hipFree(R);
+    if (partial) (void)hipFree(partial);
+    if (gneg) (void)hipFree(gneg);
     if (flag) (void)hipFree(flag);
     return rc;
 #undef P_HIP

@@ -61,6 +61,10 @@ def test_bad_hidden_tracked_and_null_arguments(lib):
     assert lib.bagel_rollout_loss(None, None, None, None, None, None, None) == binding.EINVAL
     assert lib.bagel_workspace_bytes(None) == 0
     assert lib.bagel_adam_step(None, None, None, None, None, 1, 1e-2, 0.9, 0.999, 1e-8) == binding.EINVAL
+    assert lib.bagel_hyper_lml_grad(None, None, None, None, None, None) == binding.EINVAL
+    assert lib.bagel_hyper_fit(None, None, None, None, None, None, 1, 1, 1e-2, 0.9, 0.999, 1e-8, None) == binding.EINVAL
+    assert lib.bagel_prepare_posterior(None, None, None, None, None, None) == binding.EINVAL
+    assert lib.bagel_posterior_rollout_loss(None, None, None, None, None, None, None, None) == binding.EINVAL
     assert lib.bagel_optimize(None, None, None, None, None, None, 1, 1, 1, 1e-2, 0.9, 0.999, 1e-8, None) == binding.EINVAL
 
 

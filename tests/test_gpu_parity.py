@@ -417,3 +417,44 @@ def test_posterior_sampler_bounded_saturating_checkpointed():
 def test_posterior_sampler_small_config_size():
     """The Small configuration's model (N=512, 4 outputs, policy 5-64-64-1) with a shorter batch and horizon."""
     _posterior_case(_cfg("small", B=64, H=20), "posterior-small")
+
+
+# ------------------------------------------------------------------ hyper-parameter learning
+def test_marginal_likelihood_and_fit_against_oracle():
+    """bagel_hyper_lml_grad against the numpy oracle (float64 on both sides, float32 interface), on a ragged
+    N; then bagel_hyper_fit against the oracle's fit loop, which keeps its state in float32 like the
+    interface does.  The gradient of the marginal likelihood has no entries that vanish against the
+    others, so the free-running comparison is meaningful here."""
+    import torch
+    from paper_2202_13638_amd import binding
+    cfg = synth.Config("hy", 31, 3, 1, 1, 150, 16, 8, 2, (4,), 0.0, "sinusoid", "const", 0, 0.5, 1e-3)
+    inp = synth.make_inputs(cfg)
+    M, D = cfg.M, cfg.D
+    lh0 = np.concatenate([np.log(inp["lengthscale"]), np.log(inp["signal_var"])[:, None],
+                          np.log(inp["noise_var"])[:, None]], axis=1).astype(np.float32)
+    ctx = binding.Bagel(binding.dims_from_config(cfg))
+    g = harness.to_gpu(inp)
+    lml = torch.zeros(M, device="cuda")
+    grad = torch.zeros((M, D + 2), device="cuda")
+    ctx.bagel_hyper_lml_grad(g["X"], g["y"], torch.from_numpy(lh0).cuda(), lml, grad)
+    torch.cuda.synchronize()
+    for m in range(M):
+        ref, ref_g = oracle.hyper_lml_grad(inp["X"], inp["y"][m], lh0[m])
+        assert abs(float(lml[m]) - ref) <= 2e-7 * abs(ref)
+        np.testing.assert_allclose(grad[m].cpu().numpy(), ref_g, rtol=2e-6, atol=2e-6 * np.abs(ref_g).max())
+    # fit
+    n, lr = 12, 5e-2
+    start = np.tile(np.log(np.array([1.0] * D + [1.0, 0.1], dtype=np.float32)), (M, 1)).astype(np.float32)
+    lh_o, m_o, v_o, hist_o = oracle.hyper_fit(inp["X"], inp["y"], start, n, lr=lr)
+    lh_g = torch.from_numpy(start.copy()).cuda()
+    am, av = torch.zeros_like(lh_g), torch.zeros_like(lh_g)
+    hist = torch.zeros((n, M), device="cuda")
+    ctx.bagel_hyper_fit(g["X"], g["y"], lh_g, am, av, n, hist, lr=lr)
+    torch.cuda.synchronize()
+    d_hist = np.abs(hist.cpu().numpy() - hist_o) / np.abs(hist_o)
+    d_lh = np.abs(lh_g.cpu().numpy().astype(np.float64) - lh_o)
+    print(f"[parity hyper fit] lml rel {d_hist.max():.3e}; log hyper-parameters abs {d_lh.max():.3e} after {n} updates",
+          flush=True)
+    assert d_hist.max() <= 1e-5 and d_lh.max() <= 1e-4
+    assert np.all(hist_o[-1] > hist_o[0]) and bool((hist[-1] > hist[0]).all())
+    ctx.close()
