@@ -604,6 +604,13 @@ __global__ __launch_bounds__(PW * 64) void backward_sweep_kernel(sweep_args a)
         }
         lamS[row][bl] = v;
     }
+    // The wave's share of the two narrow transposed weight matrices stays in registers for the whole
+    // sweep (top layer: one group, its contraction runs over the d_a <= 8 outputs); the wide middle
+    // layer is streamed from L2 every step.
+    const wave_plan p_first = plan_layer(a.width[0], a.kp[0], wave);
+    float4 w_first[4];
+    load_wave_weights<1>(w_first, a.Wp + a.wp_off[0], a.kp[0], p_first, lane);
+    const float4 w_top = reinterpret_cast<const float4 *>(a.Wp + a.wp_off[last])[(size_t)p_top.rt * (a.kp[last] >> 3) * 64 + lane];
     sweep_tape cur = {}, nxt = {};
     float hv_top[16] = {}, hv_top_next[16] = {};
     sweep_tape_load(a, a.t_hi, row, bq, cur);
@@ -652,12 +659,22 @@ __global__ __launch_bounds__(PW * 64) void backward_sweep_kernel(sweep_args a)
         // ---- policy backward: delta_{l-1} = (W_l^T delta_l) * (1 - h_l^2)
         for (int l = last; l >= 0; --l) {
             const int ni = a.width[l];
-            const wave_plan p = plan_layer(ni, a.kp[l], wave);
+            const wave_plan p = l == last ? p_top : (l == 0 ? p_first : plan_layer(ni, a.kp[l], wave));
             const bool owner = p.active && p.ks == 0;
             float hv[16];
             if (l > 0 && l < last && owner) load_tanh_outputs(a.tape_h[l] + slot * ni * a.B + bc, ni, a.B, p, hf, hv);
             f16v acc;
-            if (p.active) acc = tile_contract(a.Wp + a.wp_off[l], a.kp[l], p, lane, act4);
+            if (p.active) {
+                if (l == last) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+                    acc = mfma_group(acc, w_top, act4[hf * PL + c]);
+                } else if (l == 0) {
+                    acc = contract_batches<1>(w_first, p, lane, act4);
+                } else {
+                    acc = tile_contract(a.Wp + a.wp_off[l], a.kp[l], p, lane, act4);
+                }
+            }
             combine_slices(acc, p, wave, lane, red4);
             if (owner) {
 #pragma unroll
