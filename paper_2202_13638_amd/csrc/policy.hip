@@ -257,12 +257,12 @@ __device__ __forceinline__ void stage_input(const float *__restrict__ src, int n
 // The three arrays are separate locals of the calling kernel so that they are promoted to registers.
 #define FORWARD_WEIGHTS_DECL                                   \
     float4 w_first[4], w_last[4], w_wide[32];                  \
+    float bias_r[3];                                           \
     wave_plan p_first, p_last, p_wide
 
 __device__ __forceinline__ void load_forward_weights(const policy_args &a, int wave, int lane, float4 (&w_first)[4],
                                                      float4 (&w_last)[4], float4 (&w_wide)[32], wave_plan &p_first,
-                                                     wave_plan &p_last, wave_plan &p_wide,
-                                                     float (*biasS)[BAGEL_MAX_HIDDEN])
+                                                     wave_plan &p_last, wave_plan &p_wide, float (&bias_r)[3])
 {
     p_first = plan_layer(a.width[1], a.kp[0], wave);
     p_last = plan_layer(a.width[a.nl], a.kp[a.nl - 1], wave);
@@ -273,8 +273,20 @@ __device__ __forceinline__ void load_forward_weights(const policy_args &a, int w
         load_wave_weights<8>(w_wide, a.Wp + a.wp_off[1], a.kp[1], p_wide, lane);
     }
     load_wave_weights<1>(w_last, a.Wp + a.wp_off[a.nl - 1], a.kp[a.nl - 1], p_last, lane);
-    for (int l = 0; l < a.nl; ++l)
-        for (int j = threadIdx.x; j < a.width[l + 1]; j += PW * 64) biasS[l][j] = a.theta[a.b_off[l] + j];
+    // biases: one value per thread and layer (a layer is at most 256 wide), parked in registers; writing
+    // them to LDS right away would wait for every load requested above
+#pragma unroll
+    for (int l = 0; l < 3; ++l)
+        bias_r[l] = (l < a.nl && (int)threadIdx.x < a.width[l + 1]) ? a.theta[a.b_off[l] + threadIdx.x] : 0.0f;
+}
+
+// second half of load_forward_weights, to be called once the loads have had time to arrive
+__device__ __forceinline__ void stash_biases(const policy_args &a, const float (&bias_r)[3],
+                                             float (*biasS)[BAGEL_MAX_HIDDEN])
+{
+#pragma unroll
+    for (int l = 0; l < 3; ++l)
+        if (l < a.nl && (int)threadIdx.x < a.width[l + 1]) biasS[l][threadIdx.x] = bias_r[l];
 }
 
 // The layers of pi_theta for the 32 trajectories of a workgroup, input in act4 (all waves past a
@@ -342,8 +354,9 @@ __global__ __launch_bounds__(PW * 64) void policy_forward_kernel(policy_args a)
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int b0 = blockIdx.x * PL;
     FORWARD_WEIGHTS_DECL;
-    load_forward_weights(a, wave, lane, w_first, w_last, w_wide, p_first, p_last, p_wide, biasS);
+    load_forward_weights(a, wave, lane, w_first, w_last, w_wide, p_first, p_last, p_wide, bias_r);
     stage_input(a.h[0], a.width[0], a.kp[0], a.B, b0, act4);
+    stash_biases(a, bias_r, biasS);
     __syncthreads();
     policy_layers(a, w_first, w_last, w_wide, p_first, p_last, p_wide, wave, lane, b0, act4, red4, biasS);
 }
@@ -370,6 +383,21 @@ struct tail_args {
     float *jdst;                        // tape slot [M][D][B] of step t, or null
 };
 
+// p[0] + p[stride] + ... (n terms, added in that order); the loads go out four at a time so that
+// their latencies overlap
+__device__ __forceinline__ double sum_groups(const double *__restrict__ p, int n, size_t stride)
+{
+    double s = 0.0;
+    for (int c0 = 0; c0 < n; c0 += 4) {
+        double v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = (c0 + u < n) ? p[(size_t)(c0 + u) * stride] : 0.0;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) s += v[u];
+    }
+    return s;
+}
+
 __global__ __launch_bounds__(PW * 64) void step_tail_kernel(tail_args r, policy_args a)
 {
     __shared__ float4 act4[(BAGEL_MAX_HIDDEN / 4) * PL];
@@ -387,7 +415,7 @@ __global__ __launch_bounds__(PW * 64) void step_tail_kernel(tail_args r, policy_
     const int B = a.B, ds = a.ds;
 
     FORWARD_WEIGHTS_DECL;
-    if (r.do_policy) load_forward_weights(a, wave, lane, w_first, w_last, w_wide, p_first, p_last, p_wide, biasS);
+    if (r.do_policy) load_forward_weights(a, wave, lane, w_first, w_last, w_wide, p_first, p_last, p_wide, bias_r);
 
     // ---- partial sums -> f (LDS) and J_f (tape): one (output m, component) pair per thread and pass
     const size_t stride = (size_t)(1 + r.D) * B;
@@ -401,18 +429,15 @@ __global__ __launch_bounds__(PW * 64) void step_tail_kernel(tail_args r, policy_
         }
         const double *pk = r.part + (size_t)(m * r.ngk) * stride + bq;
         const double *pr = r.part + (size_t)(r.M * r.ngk + m * r.ngl) * stride + bq;
-        double u = 0.0;
-        for (int c = 0; c < r.ngk; ++c) u += pk[c * stride];
+        const double u = sum_groups(pk, r.ngk, stride);
         const double amp = r.amp[m];
         if (comp == 0) {
-            double p = 0.0;
-            for (int c = 0; c < r.ngl; ++c) p += pr[c * stride];
+            const double p = sum_groups(pr, r.ngl, stride);
             fS[m][bl] = amp * p + u;
         } else {
             const int d = comp - 1;
-            double gk = 0.0, gr = 0.0;
-            for (int c = 0; c < r.ngk; ++c) gk += pk[c * stride + (size_t)comp * B];
-            for (int c = 0; c < r.ngl; ++c) gr += pr[c * stride + (size_t)comp * B];
+            const double gk = sum_groups(pk + (size_t)comp * B, r.ngk, stride);
+            const double gr = sum_groups(pr + (size_t)comp * B, r.ngl, stride);
             const double x = a.xbuf[(size_t)d * B + bq];
             const double J = -amp * TWO_PI * gr + LN2 * (gk - r.A[m * r.D + d] * x * u);
             if (liveq) r.jdst[(size_t)(m * r.D + d) * B + bq] = (float)J;
@@ -443,6 +468,7 @@ __global__ __launch_bounds__(PW * 64) void step_tail_kernel(tail_args r, policy_
             if (liveq && k < d_in) a.h[0][(size_t)k * B + bq] = hin;
         }
     }
+    if (r.do_policy) stash_biases(a, bias_r, biasS);
     __syncthreads();
     if (r.add_cost && row == 0 && liveq) {
         double e = 0.0;
