@@ -4,8 +4,9 @@
 // K_hat is ~ signal/noise variance times N, far beyond float32.  Per output:
 //   1. K_hat (padded to a multiple of 64 with an identity block) and Phi are built from the
 //      float32 inputs;
-//   2. blocked right-looking Cholesky: 64x64 diagonal factorisation, panel solve, trailing
-//      update of the lower triangle with a tiled float64 GEMM;
+//   2. blocked right-looking Cholesky with two block sizes: 64x64 diagonal factorisation and panel
+//      solve inside panels of 256 columns, trailing update of the lower triangle once per panel with
+//      a tiled float64 GEMM that is 256 deep;
 //   3. R = y 1^T - Phi W^T - Eps^T as one GEMM over the L features (R is [N][S]);
 //   4. blocked forward and backward substitution on all S right-hand sides at once, again
 //      GEMM-dominated;
@@ -181,98 +182,240 @@ __global__ __launch_bounds__(256) void dgemm_kernel(int Mr, int Nc, int Kd, doub
             }
 }
 
-// Factor the NB x NB diagonal block at (k,k) in place (lower).  One workgroup of NB threads,
-// thread = row.  Sets *flag = 1 + global row index on a pivot that is not positive.
+// The kernels below work on 64 x 64 blocks with one wave, lane = row or column of the block, the
+// lane's vector in registers and the shared triangular block in LDS, read as broadcasts.  What bounds
+// them is the latency between an LDS read and the FMA that uses it, so every step requests the
+// triangular row it needs as one burst of reads one step ahead (scheduling barriers keep the burst
+// together) and then runs independent FMAs on values that have already arrived.
+constexpr int LDB = NB + 2;      // LDS row stride: rows stay 16-byte aligned for two-element reads
+
+// A 64 x 64 block of a row-major matrix <-> LDS, by one wave: lane = column, so every global access is
+// one contiguous row; all 64 loads are requested before the first one is used.
+template <bool TRANSPOSE>
+__device__ __forceinline__ void block_to_lds(const double *__restrict__ src, size_t ld, double (*dst)[LDB])
+{
+    const int r = threadIdx.x;
+    double t[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) t[i] = src[(size_t)i * ld + r];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        if (TRANSPOSE) dst[r][i] = t[i];
+        else dst[i][r] = t[i];
+    }
+}
+
+__device__ __forceinline__ void lds_to_block(double (*src)[LDB], double *__restrict__ dst, size_t ld)
+{
+    const int r = threadIdx.x;
+#pragma unroll
+    for (int i = 0; i < NB; ++i) dst[(size_t)i * ld + r] = src[i][r];
+}
+
+constexpr int CH = 16;           // entries of a triangular row requested per burst
+
+// entries [16 q, 16 q + 16) of a row of the shared block, as one burst of broadcast reads
+__device__ __forceinline__ void read_chunk(const double *row, int q, double (&dst)[CH])
+{
+#pragma unroll
+    for (int e = 0; e < CH; ++e) dst[e] = row[q * CH + e];
+}
+
+// x <- L^-1 x for the lane's vector x, L lower triangular, given as its transpose Lt[i][c] = L[c][i]
+// and the reciprocals of its diagonal: column by column, x[c] -= x[i] L[c][i] for c > i.
+// The lane's vector takes half of the directly addressable registers, so the rows of Lt come in
+// chunks of 16 entries, the next chunk in flight while the FMAs of the current one issue.
+// One template instance per (row I, chunk Q): every register index is a compile-time constant.
+template <int I, int Q, int IDX>
+__device__ __forceinline__ void lower_item(double (&x)[NB], double (*Lt)[LDB], const double *rinv,
+                                           double (&buf)[2][CH], double rc)
+{
+    constexpr int NQ = NB / CH;
+    if constexpr (Q == (I + 1) / CH) x[I] *= rc;                  // first chunk of the row: x[I] is final
+    constexpr bool same_row = Q + 1 < NQ;
+    constexpr bool next_row = !same_row && (I + 2) / CH < NQ;     // row I + 1 has entries right of its diagonal
+    double rn = rc;
+    if constexpr (same_row) {
+        read_chunk(Lt[I], Q + 1, buf[(IDX + 1) & 1]);
+    } else {
+        rn = rinv[I + 1];
+        if constexpr (next_row) read_chunk(Lt[I + 1], (I + 2) / CH, buf[(IDX + 1) & 1]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int e = 0; e < CH; ++e) {
+        const int c = Q * CH + e;
+        if (c > I) x[c] = fma(-x[I], buf[IDX & 1][e], x[c]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (same_row) lower_item<I, Q + 1, IDX + 1>(x, Lt, rinv, buf, rc);
+    else if constexpr (next_row) lower_item<I + 1, (I + 2) / CH, IDX + 1>(x, Lt, rinv, buf, rn);
+    else x[I + 1] *= rn;                                         // the last row has nothing right of its diagonal
+}
+
+__device__ __forceinline__ void solve_lower(double (&x)[NB], double (*Lt)[LDB], const double *rinv)
+{
+    double buf[2][CH];
+    read_chunk(Lt[0], 0, buf[0]);
+    lower_item<0, 0, 0>(x, Lt, rinv, buf, rinv[0]);
+}
+
+// x <- L^-T x, L given by rows: from the last entry up, x[c] -= x[i] L[i][c] for c < i.
+template <int I, int Q, int IDX>
+__device__ __forceinline__ void upper_item(double (&x)[NB], double (*Ls)[LDB], const double *rinv,
+                                           double (&buf)[2][CH], double rc)
+{
+    if constexpr (Q == 0) x[I] *= rc;
+    constexpr bool same_row = Q + 1 <= (I - 1) / CH;
+    constexpr bool next_row = !same_row && I - 1 >= 1;
+    double rn = rc;
+    if constexpr (same_row) {
+        read_chunk(Ls[I], Q + 1, buf[(IDX + 1) & 1]);
+    } else {
+        rn = rinv[I - 1];
+        if constexpr (next_row) read_chunk(Ls[I - 1], 0, buf[(IDX + 1) & 1]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int e = 0; e < CH; ++e) {
+        const int c = Q * CH + e;
+        if (c < I) x[c] = fma(-x[I], buf[IDX & 1][e], x[c]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (same_row) upper_item<I, Q + 1, IDX + 1>(x, Ls, rinv, buf, rc);
+    else if constexpr (next_row) upper_item<I - 1, 0, IDX + 1>(x, Ls, rinv, buf, rn);
+    else x[0] *= rn;
+}
+
+__device__ __forceinline__ void solve_lower_transposed(double (&x)[NB], double (*Ls)[LDB], const double *rinv)
+{
+    double buf[2][CH];
+    read_chunk(Ls[NB - 1], 0, buf[0]);
+    upper_item<NB - 1, 0, 0>(x, Ls, rinv, buf, rinv[NB - 1]);
+}
+
+// Step J of the factorisation of a diagonal block (see potrf_diag_kernel)
+template <int J>
+__device__ __forceinline__ void potrf_step(double (&a)[NB], double (*col)[NB], int r, int *__restrict__ flag,
+                                           int flag_value)
+{
+    constexpr int NQ = NB / CH;
+    const double d = __shfl(a[J], J);
+    if (!(d > 0.0) && r == 0) atomicCAS(flag, 0, flag_value + J);
+    // keep going with a harmless pivot so that the result stays finite
+    const double piv = (d > 0.0) ? sqrt(d) : 1.0;
+    const double l = (r == J) ? piv : a[J] / piv;
+    a[J] = l;
+    if constexpr (J + 1 < NB) {
+        col[J & 1][r] = l;
+        __syncthreads();
+        // the column comes back in chunks of 16, the next chunk in flight under the FMAs of this one
+        double buf[2][CH];
+        constexpr int Q0 = (J + 1) / CH;
+        read_chunk(col[J & 1], Q0, buf[Q0 & 1]);
+#pragma unroll
+        for (int q = Q0; q < NQ; ++q) {
+            if (q + 1 < NQ) read_chunk(col[J & 1], q + 1, buf[(q + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int e = 0; e < CH; ++e) {
+                const int c = q * CH + e;
+                if (c > J) a[c] = fma(-l, buf[q & 1][e], a[c]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        potrf_step<J + 1>(a, col, r, flag, flag_value);
+    }
+}
+
+// Factor the NB x NB diagonal block at (k,k) in place (lower).  Lane = row, the row lives in
+// registers; right-looking: at step j the pivot comes from lane j, every lane scales its entry of
+// column j, the column is broadcast through LDS and each lane updates the rest of its row with
+// independent FMAs.  Entries above the diagonal are kept at zero, so no lane needs a predicate.
+// Sets *flag = 1 + global row index on a pivot that is not positive.
 __global__ __launch_bounds__(NB) void potrf_diag_kernel(double *__restrict__ K, int Np, int k, int flag_base,
                                                         int *__restrict__ flag)
 {
-    __shared__ double Ls[NB][NB + 1];
+    __shared__ __align__(16) double Ls[NB][LDB];
+    __shared__ __align__(16) double col[2][NB];
     const int r = threadIdx.x;
-    for (int c = 0; c < NB; ++c) Ls[r][c] = K[(size_t)(k + r) * Np + k + c];
+    block_to_lds<false>(K + (size_t)k * Np + k, Np, Ls);
     __syncthreads();
-    for (int j = 0; j < NB; ++j) {
-        const double d = Ls[j][j];
-        if (!(d > 0.0)) {
-            if (r == 0) atomicCAS(flag, 0, 1 + flag_base + k + j);
-            // keep going with a harmless pivot so every thread leaves the loop together
-        }
-        const double piv = (d > 0.0) ? sqrt(d) : 1.0;
-        __syncthreads();
-        if (r == j) Ls[j][j] = piv;
-        if (r > j) Ls[r][j] = Ls[r][j] / piv;
-        __syncthreads();
-        if (r > j)
-            for (int c = j + 1; c <= r; ++c) Ls[r][c] -= Ls[r][j] * Ls[c][j];
-        __syncthreads();
-    }
-    for (int c = 0; c < NB; ++c) K[(size_t)(k + r) * Np + k + c] = (c <= r) ? Ls[r][c] : 0.0;
+    double a[NB];
+#pragma unroll
+    for (int c = 0; c < NB; ++c) a[c] = (c <= r) ? Ls[r][c] : 0.0;
+    potrf_step<0>(a, col, r, flag, 1 + flag_base + k);
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < NB; ++c) Ls[r][c] = a[c];
+    __syncthreads();
+    lds_to_block(Ls, K + (size_t)k * Np + k, Np);
 }
 
-// Panel solve: rows i >= k+NB of columns k..k+NB-1:  P <- P * L_kk^-T.  Thread = row.
-__global__ __launch_bounds__(256) void trsm_panel_kernel(double *__restrict__ K, int Np, int k)
+// Diagonal block L_kk into LDS (by rows, or transposed), with the reciprocals of its diagonal beside it
+template <bool TRANSPOSE>
+__device__ __forceinline__ void load_diag_block(const double *__restrict__ K, int Np, int k, double (*Ls)[LDB],
+                                                double *rinv)
 {
-    __shared__ double Ls[NB][NB + 1];
-    for (int idx = threadIdx.x; idx < NB * NB; idx += 256) Ls[idx / NB][idx % NB] = K[(size_t)(k + idx / NB) * Np + k + idx % NB];
+    block_to_lds<TRANSPOSE>(K + (size_t)k * Np + k, Np, Ls);
     __syncthreads();
-    const int i = k + NB + blockIdx.x * 256 + threadIdx.x;
-    if (i >= Np) return;
-    double *row = K + (size_t)i * Np + k;
+    rinv[threadIdx.x] = 1.0 / Ls[threadIdx.x][threadIdx.x];
+    __syncthreads();
+}
+
+// Panel solve: rows i >= k+NB of columns k..k+NB-1:  P <- P * L_kk^-T, which is a forward substitution
+// with L_kk on every row of P.  One wave per 64 rows, lane = row; the rows go through LDS so that
+// global accesses are coalesced.
+__global__ __launch_bounds__(NB) void trsm_panel_kernel(double *__restrict__ K, int Np, int k)
+{
+    __shared__ __align__(16) double Lt[NB][LDB];
+    __shared__ __align__(16) double Ps[NB][LDB];
+    __shared__ double rinv[NB];
+    load_diag_block<true>(K, Np, k, Lt, rinv);
+    const int r = threadIdx.x;
+    const int i0 = k + NB + blockIdx.x * NB;            // Np is a multiple of NB: the block of rows is whole
+    block_to_lds<false>(K + (size_t)i0 * Np + k, Np, Ps);
+    __syncthreads();
     double x[NB];
 #pragma unroll
-    for (int j = 0; j < NB; ++j) x[j] = row[j];
+    for (int j = 0; j < NB; ++j) x[j] = Ps[r][j];
+    solve_lower(x, Lt, rinv);
 #pragma unroll
-    for (int j = 0; j < NB; ++j) {
-        double s = x[j];
-#pragma unroll
-        for (int c = 0; c < j; ++c) s -= x[c] * Ls[j][c];
-        x[j] = s / Ls[j][j];
-    }
-#pragma unroll
-    for (int j = 0; j < NB; ++j) row[j] = x[j];
+    for (int j = 0; j < NB; ++j) Ps[r][j] = x[j];
+    __syncthreads();
+    lds_to_block(Ps, K + (size_t)i0 * Np + k, Np);
 }
 
-// Forward substitution on block k for all right-hand sides: Z_k = L_kk^-1 R_k.  Thread = column s.
-__global__ __launch_bounds__(256) void trsv_fwd_kernel(const double *__restrict__ K, int Np, int k,
-                                                       double *__restrict__ R, int S)
+// Forward substitution on block k for all right-hand sides: Z_k = L_kk^-1 R_k.  Lane = column s.
+__global__ __launch_bounds__(NB) void trsv_fwd_kernel(const double *__restrict__ K, int Np, int k,
+                                                      double *__restrict__ R, int S)
 {
-    __shared__ double Ls[NB][NB + 1];
-    for (int idx = threadIdx.x; idx < NB * NB; idx += 256) Ls[idx / NB][idx % NB] = K[(size_t)(k + idx / NB) * Np + k + idx % NB];
-    __syncthreads();
-    const int s = blockIdx.x * 256 + threadIdx.x;
+    __shared__ __align__(16) double Lt[NB][LDB];
+    __shared__ double rinv[NB];
+    load_diag_block<true>(K, Np, k, Lt, rinv);
+    const int s = blockIdx.x * NB + threadIdx.x;
     if (s >= S) return;
     double z[NB];
 #pragma unroll
     for (int i = 0; i < NB; ++i) z[i] = R[(size_t)(k + i) * S + s];
-#pragma unroll
-    for (int i = 0; i < NB; ++i) {
-        double acc = z[i];
-#pragma unroll
-        for (int j = 0; j < i; ++j) acc -= Ls[i][j] * z[j];
-        z[i] = acc / Ls[i][i];
-    }
+    solve_lower(z, Lt, rinv);
 #pragma unroll
     for (int i = 0; i < NB; ++i) R[(size_t)(k + i) * S + s] = z[i];
 }
 
 // Backward substitution on block k: V_k = L_kk^-T Z_k.
-__global__ __launch_bounds__(256) void trsv_bwd_kernel(const double *__restrict__ K, int Np, int k,
-                                                       double *__restrict__ R, int S)
+__global__ __launch_bounds__(NB) void trsv_bwd_kernel(const double *__restrict__ K, int Np, int k,
+                                                      double *__restrict__ R, int S)
 {
-    __shared__ double Ls[NB][NB + 1];
-    for (int idx = threadIdx.x; idx < NB * NB; idx += 256) Ls[idx / NB][idx % NB] = K[(size_t)(k + idx / NB) * Np + k + idx % NB];
-    __syncthreads();
-    const int s = blockIdx.x * 256 + threadIdx.x;
+    __shared__ __align__(16) double Ls[NB][LDB];
+    __shared__ double rinv[NB];
+    load_diag_block<false>(K, Np, k, Ls, rinv);
+    const int s = blockIdx.x * NB + threadIdx.x;
     if (s >= S) return;
     double z[NB];
 #pragma unroll
     for (int i = 0; i < NB; ++i) z[i] = R[(size_t)(k + i) * S + s];
-#pragma unroll
-    for (int i = NB - 1; i >= 0; --i) {
-        double acc = z[i];
-#pragma unroll
-        for (int j = i + 1; j < NB; ++j) acc -= Ls[j][i] * z[j];
-        z[i] = acc / Ls[i][i];
-    }
+    solve_lower_transposed(z, Ls, rinv);
 #pragma unroll
     for (int i = 0; i < NB; ++i) R[(size_t)(k + i) * S + s] = z[i];
 }
@@ -305,31 +448,59 @@ void gemm(hipStream_t st, int Mr, int Nc, int Kd, double alpha, const double *A,
 
 // In-place blocked Cholesky of K [Np][Np] (lower; Np a multiple of NB), then K_hat^-1 applied to the S
 // right-hand sides R [Np][S] in place.  A pivot that is not positive is reported through *flag.
+// Two block sizes: the factorisation and the substitutions advance in steps of NB columns, but only
+// inside a panel of OB columns; what lies outside the panel is updated once per panel by a product
+// that is OB deep.  A product only NB deep reads and writes every element of the trailing matrix for
+// NB multiply-adds on it, which is bound by memory traffic; OB deep it is bound by the matrix pipe.
+constexpr int OB = 256;
+
 void factor_and_solve(hipStream_t st, double *K, int Np, double *R, int S, int flag_base, int *flag)
 {
-    for (int k = 0; k < Np; k += NB) {
-        hipLaunchKernelGGL(potrf_diag_kernel, dim3(1), dim3(NB), 0, st, K, Np, k, flag_base, flag);
-        const int rest = Np - k - NB;
+    for (int k = 0; k < Np; k += OB) {
+        const int ob = Np - k < OB ? Np - k : OB;
+        for (int kk = k; kk < k + ob; kk += NB) {
+            hipLaunchKernelGGL(potrf_diag_kernel, dim3(1), dim3(NB), 0, st, K, Np, kk, flag_base, flag);
+            const int below = Np - kk - NB;
+            if (below <= 0) continue;
+            hipLaunchKernelGGL(trsm_panel_kernel, dim3(below / NB), dim3(NB), 0, st, K, Np, kk);
+            const int cols = k + ob - kk - NB;          // columns of the panel still to be factored
+            const double *Pn = K + (size_t)(kk + NB) * Np + kk;
+            // K[i][j] -= sum_c P[i][c] P[j][c] for the rest of the panel
+            if (cols > 0)
+                gemm(st, below, cols, NB, -1.0, Pn, Np, 1, Pn, 1, Np, K + (size_t)(kk + NB) * Np + (kk + NB), Np, true);
+        }
+        const int rest = Np - k - ob;
         if (rest > 0) {
-            hipLaunchKernelGGL(trsm_panel_kernel, dim3((rest + 255) / 256), dim3(256), 0, st, K, Np, k);
-            const double *Pn = K + (size_t)(k + NB) * Np + k;
-            // trailing[i][j] -= sum_c P[i][c] P[j][c]
-            gemm(st, rest, rest, NB, -1.0, Pn, Np, 1, Pn, 1, Np, K + (size_t)(k + NB) * Np + (k + NB), Np, true);
+            const double *Pn = K + (size_t)(k + ob) * Np + k;
+            gemm(st, rest, rest, ob, -1.0, Pn, Np, 1, Pn, 1, Np, K + (size_t)(k + ob) * Np + (k + ob), Np, true);
         }
     }
     // forward substitution  L Z = R
-    for (int k = 0; k < Np; k += NB) {
-        hipLaunchKernelGGL(trsv_fwd_kernel, dim3((S + 255) / 256), dim3(256), 0, st, K, Np, k, R, S);
-        const int rest = Np - k - NB;
+    for (int k = 0; k < Np; k += OB) {
+        const int ob = Np - k < OB ? Np - k : OB;
+        for (int kk = k; kk < k + ob; kk += NB) {
+            hipLaunchKernelGGL(trsv_fwd_kernel, dim3((S + NB - 1) / NB), dim3(NB), 0, st, K, Np, kk, R, S);
+            const int rows = k + ob - kk - NB;
+            if (rows > 0)
+                gemm(st, rows, S, NB, -1.0, K + (size_t)(kk + NB) * Np + kk, Np, 1, R + (size_t)kk * S, S, 1,
+                     R + (size_t)(kk + NB) * S, S, false);
+        }
+        const int rest = Np - k - ob;
         if (rest > 0)
-            gemm(st, rest, S, NB, -1.0, K + (size_t)(k + NB) * Np + k, Np, 1, R + (size_t)k * S, S, 1,
-                 R + (size_t)(k + NB) * S, S, false);
+            gemm(st, rest, S, ob, -1.0, K + (size_t)(k + ob) * Np + k, Np, 1, R + (size_t)k * S, S, 1,
+                 R + (size_t)(k + ob) * S, S, false);
     }
     // backward substitution  L^T V = Z
-    for (int k = Np - NB; k >= 0; k -= NB) {
-        hipLaunchKernelGGL(trsv_bwd_kernel, dim3((S + 255) / 256), dim3(256), 0, st, K, Np, k, R, S);
-        if (k > 0)   // R[0:k] -= L[k:k+NB, 0:k]^T V_k : A(i, c) = K[(k+c)*Np + i]
-            gemm(st, k, S, NB, -1.0, K + (size_t)k * Np, 1, Np, R + (size_t)k * S, S, 1, R, S, false);
+    for (int k = (Np - 1) / OB * OB; k >= 0; k -= OB) {
+        const int ob = Np - k < OB ? Np - k : OB;
+        for (int kk = k + ob - NB; kk >= k; kk -= NB) {
+            hipLaunchKernelGGL(trsv_bwd_kernel, dim3((S + NB - 1) / NB), dim3(NB), 0, st, K, Np, kk, R, S);
+            if (kk > k)   // R[k:kk] -= L[kk:kk+NB, k:kk]^T V_kk : A(i, c) = K[(kk+c)*Np + k + i]
+                gemm(st, kk - k, S, NB, -1.0, K + (size_t)kk * Np + k, 1, Np, R + (size_t)kk * S, S, 1,
+                     R + (size_t)k * S, S, false);
+        }
+        if (k > 0)        // R[0:k] -= L[k:k+ob, 0:k]^T V[k:k+ob] : A(i, c) = K[(k+c)*Np + i]
+            gemm(st, k, S, ob, -1.0, K + (size_t)k * Np, 1, Np, R + (size_t)k * S, S, 1, R, S, false);
     }
 }
 
@@ -436,17 +607,21 @@ __global__ __launch_bounds__(256) void hyper_grad_rows_kernel(const float *__res
     }
 }
 
-// grad[c] = 1/2 sum_i partial[i][c] (in row order); neg_scaled[c] = -grad[c] / N for the Adam update
-__global__ void hyper_grad_final_kernel(const double *__restrict__ partial, int N, int D, float *__restrict__ grad,
-                                        float *__restrict__ neg_scaled)
+// grad[c] = 1/2 sum_i partial[i][c]; neg_scaled[c] = -grad[c] / N for the Adam update.  One workgroup
+// per hyper-parameter c: thread t adds rows t, t + 256, ... in order, then a fixed tree over the threads.
+__global__ __launch_bounds__(256) void hyper_grad_final_kernel(const double *__restrict__ partial, int N, int D,
+                                                               float *__restrict__ grad,
+                                                               float *__restrict__ neg_scaled)
 {
-    const int c = threadIdx.x;
-    if (c >= D + 2) return;
+    __shared__ double sh[256];
+    const int c = blockIdx.x;
     double s = 0.0;
-    for (int i = 0; i < N; ++i) s += partial[(size_t)i * (D + 2) + c];
-    s *= 0.5;
-    if (grad) grad[c] = (float)s;
-    if (neg_scaled) neg_scaled[c] = (float)(-s / (double)N);
+    for (int i = threadIdx.x; i < N; i += 256) s += partial[(size_t)i * (D + 2) + c];
+    s = 0.5 * block_sum_256(s, sh);
+    if (threadIdx.x == 0) {
+        if (grad) grad[c] = (float)s;
+        if (neg_scaled) neg_scaled[c] = (float)(-s / (double)N);
+    }
 }
 
 }  // namespace
@@ -625,7 +800,7 @@ int bagel_hyper_impl(bagel_ctx *c, const float *X, const float *y, float *log_hy
             hipLaunchKernelGGL(hyper_lml_kernel, dim3(1), dim3(256), 0, st, K, R, y + (size_t)m * N, N, Np,
                                lml + (size_t)it * M + m);
             hipLaunchKernelGGL(hyper_grad_rows_kernel, dim3(N), dim3(256), 0, st, X, lh, R, partial, N, Np, D);
-            hipLaunchKernelGGL(hyper_grad_final_kernel, dim3(1), dim3(64), 0, st, partial, N, D,
+            hipLaunchKernelGGL(hyper_grad_final_kernel, dim3(H2), dim3(256), 0, st, partial, N, D,
                                grad ? grad + (size_t)m * H2 : nullptr, gneg + (size_t)m * H2);
             P_HIP(hipGetLastError());
         }
