@@ -21,7 +21,8 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=o
 def _compile(src: str, force: bool) -> str:
     obj = os.path.join(BUILD, src.replace(".hip", ".o"))
     path = os.path.join(CSRC, src)
-    deps = [path, os.path.join(CSRC, "bagel_internal.h"), os.path.join(ROOT, "include", "bagel.h"), __file__]
+    deps = [path, *(os.path.join(CSRC, h) for h in os.listdir(CSRC) if h.endswith(".h")),
+            os.path.join(ROOT, "include", "bagel.h"), __file__]
     if not force and os.path.exists(obj) and all(os.path.getmtime(obj) >= os.path.getmtime(d) for d in deps):
         return obj
     cmd = ["hipcc", *FLAGS, "-c", path, "-o", obj]

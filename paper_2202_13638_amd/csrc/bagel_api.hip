@@ -78,7 +78,7 @@ static void free_all(bagel_ctx *c)
 {
     void *ptrs[] = {c->Xs, c->Os, c->A, c->amp, c->v4, c->w4, c->xbuf, c->part, c->lpt, c->lam,
                     c->tape_s, c->tape_J, c->tape_h[0], c->tape_h[1], c->tape_h[2], c->tape_a, c->tape_d[0],
-                    c->tape_d[1], c->tape_d[2], c->ckpt_s, c->wpad_f, c->wpad_b, c->gsplit, c->gacc, c->fbuf, c->gtheta, c->post_alpha, c->post_Kinv, c->post_Kx, c->post_Q};
+                    c->tape_d[1], c->tape_d[2], c->ckpt_s, c->wpad_f, c->wpad_b, c->gsplit, c->gacc, c->fbuf, c->gtheta, c->post_alpha, c->post_Kinv, c->post_Kx, c->post_sums};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
 }
@@ -429,13 +429,13 @@ extern "C" int bagel_prepare_posterior(bagel_ctx *c, const float *X, const float
         const size_t Np = (size_t)c->post_Np, B = (size_t)c->dm.B, M = (size_t)c->M;
         hipError_t e = dev_alloc(c, &c->post_alpha, M * Np);
         if (e == hipSuccess) e = dev_alloc(c, &c->post_Kinv, M * Np * Np);
-        if (e == hipSuccess) e = dev_alloc(c, &c->post_Kx, Np * B);
-        if (e == hipSuccess) e = dev_alloc(c, &c->post_Q, Np * B);
+        if (e == hipSuccess) e = dev_alloc(c, &c->post_Kx, M * Np * B);
+        if (e == hipSuccess) e = dev_alloc(c, &c->post_sums, M * (Np / 64) * 2 * (1 + (size_t)c->D) * B);
         if (e != hipSuccess) {
-            void *ptrs[] = {c->post_alpha, c->post_Kinv, c->post_Kx, c->post_Q};
+            void *ptrs[] = {c->post_alpha, c->post_Kinv, c->post_Kx, c->post_sums};
             for (void *p : ptrs)
                 if (p) (void)hipFree(p);
-            c->post_alpha = c->post_Kinv = c->post_Kx = c->post_Q = nullptr;
+            c->post_alpha = c->post_Kinv = c->post_Kx = c->post_sums = nullptr;
             (void)hipGetLastError();
             BAGEL_FAIL(c, BAGEL_ENOMEM, "bagel_prepare_posterior: device allocation failed (%zu bytes for K_hat^-1)",
                        M * Np * Np * sizeof(double));

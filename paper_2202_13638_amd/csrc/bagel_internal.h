@@ -65,7 +65,8 @@ struct bagel_ctx {
     double post_sf2[8];          // alpha_m^2
     double *post_alpha;          // [M][post_Np]           K_hat^-1 y, zero on the padding
     double *post_Kinv;           // [M][post_Np][post_Np]  K_hat^-1
-    double *post_Kx, *post_Q;    // [post_Np][B]: kernel rows of one output at the current inputs; K_hat^-1 Kx
+    double *post_Kx;             // [M][post_Np][B]: kernel rows at the current inputs
+    double *post_sums;           // [M][post_Np/64][2(1+D)][B]: per-tile sums of the moments
     const float *cur_xi;         // draws of the rollout in progress (null: pathwise sampler)
 
     // ---- measurement hooks -------------------------------------------------------------------

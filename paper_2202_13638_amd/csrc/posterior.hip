@@ -6,23 +6,32 @@
 // with the exact K_hat^-1 from bagel_prepare_posterior (the paper speeds the variance up with Lanczos
 // estimates of the same quantity; that approximation is not reproduced here).
 //
-// One step, per output m, for all B trajectories at once:
-//   1. posterior_rows_kernel: Kx[n][b] = k_m(x_b, X_n) in float64 (lane = trajectory, training inputs as
+// One step, all outputs m and all B trajectories at once:
+//   1. posterior_rows_kernel: Kx[m][n][b] = k_m(x_b, X_n) in float64 (lane = trajectory, training inputs as
 //      scalar operands, the same expanded-distance form and software exp2 as the pathwise step kernel);
-//   2. Q = K_hat_m^-1 Kx: one float64 GEMM [Np x Np] x [Np x B], the dominant cost (2 N^2 flop per
-//      trajectory, step and output);
-//   3. posterior_reduce_kernel: mu, var and their derivatives from Kx, Q, alpha and the scaled inputs,
-//        d mu / d x_d  = ln2 (sum_n alpha_n k_n Xs_nd - A_d x_d sum_n alpha_n k_n),
+//   2. posterior_gemm_kernel: Q = K_hat_m^-1 Kx_m, a float64 product [Np x Np] x [Np x B] per output and
+//      the dominant cost (2 N^2 flop per trajectory, step and output).  Q is never written: the
+//      workgroup that finishes a 64 x 64 tile of it multiplies the tile with the kernel rows and adds
+//      up, over the tile's 64 training points, the sums the moments are made of,
+//        sum_n a_n k_n, sum_n q_n k_n, sum_n a_n k_n Xs_nd, sum_n q_n k_n Xs_nd     (a = alpha_m, q = Q column),
+//      one set per tile row and trajectory;
+//   3. posterior_final_kernel adds the tile rows in order and finishes mu, var and their derivatives,
+//        d mu / d x_d  = ln2 (sum_n a_n k_n Xs_nd - A_d x_d sum_n a_n k_n),
 //        d var / d x_d = -2 ln2 (sum_n q_n k_n Xs_nd - A_d x_d sum_n q_n k_n),
 //      then f and J = d mu + xi / (2 sqrt(var)) d var, written in the layout the end-of-step kernel reads.
 // A variance below 1e-12 is held there and its derivative set to zero.
 // Everything after that (state update, cost, tape, policy, backward sweep) is shared with the pathwise sampler.
 #include "bagel_internal.h"
+#include "dgemm_tile.h"
 
 namespace {
 
 constexpr double LN2 = 0.69314718055994530942;
 constexpr double VAR_FLOOR = 1e-12;
+
+struct bagel_post_sf2 {
+    double v[8];                 // signal variance of every output
+};
 
 __device__ __forceinline__ double exp2_f64(double t)
 {
@@ -39,12 +48,16 @@ __device__ __forceinline__ double exp2_f64(double t)
     return ldexp(p * p, (int)n);
 }
 
-// Kx[n][b] for n in [32 blockIdx.y, +32), b = lane; rows n >= N (padding) are zero
+// Kx[m][n][b] for m = blockIdx.z, n in [32 blockIdx.y, +32), b = lane; rows n >= N (padding) are zero
 template <int D>
-__global__ __launch_bounds__(256) void posterior_rows_kernel(const double *__restrict__ Xs_m, const double *__restrict__ A_m,
+__global__ __launch_bounds__(256) void posterior_rows_kernel(const double *__restrict__ Xs, const double *__restrict__ A,
                                                              const double *__restrict__ xbuf, double *__restrict__ Kx,
-                                                             int B, int N, int Np)
+                                                             int B, int N, int Np, int Np_model)
 {
+    const int m = blockIdx.z;
+    const double *__restrict__ Xs_m = Xs + (size_t)m * Np_model * (D + 1);
+    const double *__restrict__ A_m = A + (size_t)m * D;
+    double *__restrict__ Kx_m = Kx + (size_t)m * Np * B;
     const int b_raw = blockIdx.x * 256 + threadIdx.x;
     const bool live = b_raw < B;
     const int b = live ? b_raw : B - 1;
@@ -64,64 +77,129 @@ __global__ __launch_bounds__(256) void posterior_rows_kernel(const double *__res
             for (int d = 0; d < D; ++d) t = fma(x[d], r[d], t);
             k = exp2_f64(t);
         }
-        if (live) Kx[(size_t)n * B + b] = k;
+        if (live) Kx_m[(size_t)n * B + b] = k;
     }
 }
 
-// Workgroup = 64 trajectories x 16 slices of the training points, one component (comp 0 -> f,
-// comp 1 + d -> J[d]) per blockIdx.y; the slices' sums are added through LDS in slice order, then
-// slice 0 finishes the moments.  out[comp * B + b] of output m.
+// Tile (blockIdx.y, blockIdx.x) of Q_m = K_hat_m^-1 Kx_m for m = blockIdx.z, folded at once into the
+// sums over the tile's 64 training points: sums[m][blockIdx.y][v][b], v = 0: sum a k, 1: sum q k,
+// 2 + d: sum a k Xs_d, 2 + D + d: sum q k Xs_d.  Every sum is formed in a fixed order (a lane's eight
+// rows, then the four lane groups, then the two waves that share the columns).
 template <int D>
-__global__ __launch_bounds__(1024) void posterior_reduce_kernel(const double *__restrict__ Xs_m, const double *__restrict__ A_m,
-                                                                const double *__restrict__ alpha_m,
-                                                                const double *__restrict__ Kx, const double *__restrict__ Q,
-                                                                const double *__restrict__ xbuf,
-                                                                const float *__restrict__ xi_t, double sf2,
-                                                                double *__restrict__ out, int B, int N, int M, int m)
+__global__ __launch_bounds__(256, (D <= 8 ? 4 : 2)) void posterior_gemm_kernel(const double *__restrict__ Kinv, const double *__restrict__ Kx,
+                                                             const double *__restrict__ alpha,
+                                                             const double *__restrict__ Xs, double *__restrict__ sums,
+                                                             int B, int N, int Np, int Np_model)
 {
-    __shared__ double red[15][4][64];
-    const int lane = threadIdx.x & 63;
-    const int slice = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int b_raw = blockIdx.x * 64 + lane;
-    const bool live = b_raw < B;
-    const int b = live ? b_raw : B - 1;
-    const int comp = blockIdx.y;
-    const int d = comp - 1;
-    const int per = (N + 15) / 16;
-    const int n_begin = slice * per, n_end = min(N, n_begin + per);
-    double mu = 0.0, quad = 0.0, gmu = 0.0, gq = 0.0;
-    for (int n = n_begin; n < n_end; ++n) {
-        const double k = Kx[(size_t)n * B + b];
-        const double ak = alpha_m[n] * k, qk = Q[(size_t)n * B + b] * k;
-        mu += ak;
-        quad += qk;
-        if (comp > 0) {
-            const double xs = Xs_m[(size_t)n * (D + 1) + d];
-            gmu = fma(ak, xs, gmu);
-            gq = fma(qk, xs, gq);
-        }
-    }
-    if (slice > 0) {
-        red[slice - 1][0][lane] = mu; red[slice - 1][1][lane] = quad;
-        red[slice - 1][2][lane] = gmu; red[slice - 1][3][lane] = gq;
+    constexpr int NV = 2 * (1 + D);
+    __shared__ bagel_gemm::tile_lds sh;
+    __shared__ double red[2][2][NV][16];
+    const int m = blockIdx.z;
+    const int i0 = blockIdx.y * bagel_gemm::TM, j0 = blockIdx.x * bagel_gemm::TN;
+    const double *__restrict__ Kx_m = Kx + (size_t)m * Np * B;
+    const double *__restrict__ alpha_m = alpha + (size_t)m * Np;
+    const double *__restrict__ Xs_m = Xs + (size_t)m * Np_model * (D + 1);
+    bagel_gemm::d4v acc[2][2];
+    bagel_gemm::tile_product(acc, sh, i0, j0, Np, B, Np, Kinv + (size_t)m * Np * Np, Np, 1, Kx_m, B, 1);
+    // scaled inputs and alpha of the tile's 64 training points, into the LDS the product is done with
+    // (zero on the padding rows); tile_product ended with a barrier
+    constexpr int LW = D + 1;
+    double *xl = reinterpret_cast<double *>(&sh);
+    static_assert(64 * LW * sizeof(double) <= sizeof(bagel_gemm::tile_lds), "tile LDS too small for the staged rows");
+    for (int idx = threadIdx.x; idx < 64 * LW; idx += 256) {
+        const int row = idx / LW, col = idx - row * LW, gi = i0 + row;
+        double val = 0.0;
+        if (gi < N) val = col < D ? Xs_m[(size_t)gi * (D + 1) + col] : alpha_m[gi];
+        xl[idx] = val;
     }
     __syncthreads();
-    if (slice > 0 || !live) return;
-    for (int s = 0; s < 15; ++s) {
-        mu += red[s][0][lane]; quad += red[s][1][lane]; gmu += red[s][2][lane]; gq += red[s][3][lane];
+    const bagel_gemm::lane_pos pos = bagel_gemm::lane_position();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int half = wave & 1;                        // which 32 columns of the tile
+    double *__restrict__ out = sums + ((size_t)m * gridDim.y + blockIdx.y) * NV * B;
+    // one of the lane's two columns at a time, to keep the sums within the register budget
+#pragma unroll
+    for (int y = 0; y < 2; ++y) {
+        const int gj = j0 + pos.col0 + 16 * y;
+        double kv[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {                 // e = 4 x + r; padding rows of Kx are zero
+            const int gi = i0 + pos.row0 + 16 * (e >> 2) + 4 * (e & 3);
+            kv[e] = gj < B ? Kx_m[(size_t)gi * B + gj] : 0.0;
+        }
+        double s[NV];
+#pragma unroll
+        for (int v = 0; v < NV; ++v) s[v] = 0.0;
+#pragma unroll
+        for (int x = 0; x < 2; ++x)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const double *__restrict__ row = xl + (pos.row0 + 16 * x + 4 * r) * LW;
+                const double k = kv[4 * x + r];
+                const double ak = row[D] * k, qk = acc[x][y][r] * k;
+                s[0] += ak;
+                s[1] += qk;
+#pragma unroll
+                for (int d = 0; d < D; ++d) {
+                    s[2 + d] = fma(ak, row[d], s[2 + d]);
+                    s[2 + D + d] = fma(qk, row[d], s[2 + D + d]);
+                }
+            }
+        // the four lane groups of a wave hold different rows of the same columns
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            s[v] += __shfl_xor(s[v], 16);
+            s[v] += __shfl_xor(s[v], 32);
+        }
+        // the waves of the lower half of the tile hand their sums to the waves of the upper half
+        if ((wave >> 1) == 1 && lane < 16) {
+#pragma unroll
+            for (int v = 0; v < NV; ++v) red[half][y][v][lane] = s[v];
+        }
+        __syncthreads();
+        if ((wave >> 1) == 0 && lane < 16 && gj < B) {
+#pragma unroll
+            for (int v = 0; v < NV; ++v) out[(size_t)v * B + gj] = s[v] + red[half][y][v][lane];
+        }
     }
-    double var = sf2 - quad;
+}
+
+// Adds the tile rows in order and finishes the draw: thread = trajectory, blockIdx.y = component
+// (0 -> f, 1 + d -> J[d]), blockIdx.z = output.  out[m][comp][b].
+template <int D>
+__global__ __launch_bounds__(256) void posterior_final_kernel(const double *__restrict__ sums, const double *__restrict__ A,
+                                                              const double *__restrict__ xbuf,
+                                                              const float *__restrict__ xi_t, bagel_post_sf2 sf2,
+                                                              double *__restrict__ out, int B, int M, int ntile)
+{
+    constexpr int NV = 2 * (1 + D);
+    const int b = blockIdx.x * 256 + threadIdx.x;
+    if (b >= B) return;
+    const int comp = blockIdx.y, d = comp - 1, m = blockIdx.z;
+    const double *__restrict__ p = sums + (size_t)m * ntile * NV * B + b;
+    double mu = 0.0, quad = 0.0, gmu = 0.0, gq = 0.0;
+    for (int t = 0; t < ntile; ++t) {
+        const double *__restrict__ pt = p + (size_t)t * NV * B;
+        mu += pt[0];
+        quad += pt[(size_t)B];
+        if (comp > 0) {
+            gmu += pt[(size_t)(2 + d) * B];
+            gq += pt[(size_t)(2 + D + d) * B];
+        }
+    }
+    double var = sf2.v[m] - quad;
     const bool floored = var < VAR_FLOOR;
     if (floored) var = VAR_FLOOR;
     const double sd = sqrt(var);
     const double z = (double)xi_t[(size_t)b * M + m];
+    double *__restrict__ o = out + (size_t)m * (1 + D) * B;
     if (comp == 0) {
-        out[b] = mu + sd * z;
+        o[b] = mu + sd * z;
     } else {
-        const double ax = A_m[d] * xbuf[(size_t)d * B + b];
+        const double ax = A[(size_t)m * D + d] * xbuf[(size_t)d * B + b];
         const double dmu = LN2 * (gmu - ax * mu);
         const double dvar = floored ? 0.0 : -2.0 * LN2 * (gq - ax * quad);
-        out[(size_t)comp * B + b] = dmu + z * dvar / (2.0 * sd);
+        o[(size_t)comp * B + b] = dmu + z * dvar / (2.0 * sd);
     }
 }
 
@@ -129,16 +207,15 @@ template <int D>
 hipError_t step_d(bagel_ctx *c, bool jac, const float *xi_t)
 {
     const int B = c->dm.B, N = c->dm.N, Np = c->post_Np, M = c->M;
-    for (int m = 0; m < M; ++m) {
-        const double *Xs_m = c->Xs + (size_t)m * c->Np * (D + 1);
-        const double *A_m = c->A + (size_t)m * D;
-        hipLaunchKernelGGL((posterior_rows_kernel<D>), dim3((B + 255) / 256, (Np + 31) / 32), dim3(256), 0, c->stream, Xs_m,
-                           A_m, c->xbuf, c->post_Kx, B, N, Np);
-        bagel_dgemm(c->stream, Np, B, Np, 1.0, c->post_Kinv + (size_t)m * Np * Np, Np, 1, c->post_Kx, B, 1, c->post_Q, B, true);
-        hipLaunchKernelGGL((posterior_reduce_kernel<D>), dim3((B + 63) / 64, jac ? 1 + D : 1), dim3(1024), 0, c->stream,
-                           Xs_m, A_m, c->post_alpha + (size_t)m * Np, c->post_Kx, c->post_Q, c->xbuf, xi_t, c->post_sf2[m],
-                           c->part + (size_t)m * (1 + D) * B, B, N, M, m);
-    }
+    const int ntile = Np / bagel_gemm::TM;
+    bagel_post_sf2 sf2;
+    for (int m = 0; m < 8; ++m) sf2.v[m] = c->post_sf2[m];
+    hipLaunchKernelGGL((posterior_rows_kernel<D>), dim3((B + 255) / 256, (Np + 31) / 32, M), dim3(256), 0, c->stream,
+                       c->Xs, c->A, c->xbuf, c->post_Kx, B, N, Np, c->Np);
+    hipLaunchKernelGGL((posterior_gemm_kernel<D>), dim3((B + 63) / 64, ntile, M), dim3(256), 0, c->stream, c->post_Kinv,
+                       c->post_Kx, c->post_alpha, c->Xs, c->post_sums, B, N, Np, c->Np);
+    hipLaunchKernelGGL((posterior_final_kernel<D>), dim3((B + 255) / 256, jac ? 1 + D : 1, M), dim3(256), 0, c->stream,
+                       c->post_sums, c->A, c->xbuf, xi_t, sf2, c->part, B, M, ntile);
     return hipGetLastError();
 }
 

@@ -16,11 +16,13 @@
 #include <stdio.h>
 
 #include "bagel_internal.h"
+#include "dgemm_tile.h"
 
 namespace {
 
 constexpr int NB = 64;    // Cholesky / substitution block
-constexpr int TM = 64, TN = 64, TK = 16;   // GEMM tile
+using bagel_gemm::TM;
+using bagel_gemm::TN;
 
 // K_hat[i][j] for i, j < Np (row-major, leading dimension Np); identity on the padding
 __global__ void build_khat_kernel(const float *__restrict__ X, const float *__restrict__ ell, float sf2, float sn2,
@@ -83,18 +85,7 @@ __global__ void convert_w_kernel(const float *__restrict__ w, double *__restrict
 
 // C[i][j] (ldc) += alpha * sum_k A(i,k) * B(k,j), A(i,k) = A[i*sai + k*sak], B(k,j) = B[k*sbk + j*sbj]
 // (C = alpha * ... with overwrite).  lower_only: skip tiles entirely above the diagonal (used for the
-// symmetric trailing update).
-// A workgroup owns a 64 x 64 tile of C; its four waves own 32 x 32 quarters as 2 x 2 tiles of
-// v_mfma_f64_16x16x4 (D[16x16] += A[16x4] B[4x16]; lane l feeds A[i = l % 16][k = l / 16] and
-// B[k = l / 16][j = l % 16]; register r of lane l holds D[row = l / 16 + 4 r][col = l % 16]).
-// Operand tiles of 16 contraction indices go through LDS as [k][i] with rows padded by one element,
-// so the 16 lanes of a k-row read consecutive addresses.  The float64 matrix pipe has the rate of the
-// vector pipe on this chip, but it needs one LDS read per 512 FMAs where a vector-FMA micro-tile
-// needs one per 2.  (A 128 x 128 tile with register prefetch was measured too: no faster on the
-// [2048 x 2048] x [2048 x 1024] products of the posterior sampler, where it leaves half the compute
-// units without a tile, and slower on the 64-deep updates of the blocked factorisation.)
-typedef double d4v __attribute__((ext_vector_type(4)));
-
+// symmetric trailing update).  The tile product itself is in dgemm_tile.h.
 __global__ __launch_bounds__(256) void dgemm_kernel(int Mr, int Nc, int Kd, double alpha,
                                                     const double *__restrict__ A, long sai, long sak,
                                                     const double *__restrict__ Bm, long sbk, long sbj,
@@ -102,79 +93,18 @@ __global__ __launch_bounds__(256) void dgemm_kernel(int Mr, int Nc, int Kd, doub
 {
     const int i0 = blockIdx.y * TM, j0 = blockIdx.x * TN;
     if (lower_only && j0 > i0 + TM - 1) return;
-    __shared__ double As[TK][TM + 1];
-    __shared__ double Bs[TK][TN + 1];
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wi = (wave >> 1) * 32, wj = (wave & 1) * 32;     // the wave's quarter of the tile
-    const int lr = lane & 15, lk = lane >> 4;
-    d4v acc[2][2];
-#pragma unroll
-    for (int x = 0; x < 2; ++x)
-#pragma unroll
-        for (int y = 0; y < 2; ++y) acc[x][y] = d4v{0.0, 0.0, 0.0, 0.0};
-    // loaders: pick the thread->element map that walks the unit-stride direction fastest
-    const bool a_k_fast = (sak == 1);
-    const bool b_j_fast = (sbj == 1);
-    constexpr int PER = TM * TK / 256;                // elements of each operand tile per thread
-    double ra[PER], rb[PER];
-    auto fetch = [&](int k0) {                        // global -> registers (zero outside the matrices)
-#pragma unroll
-        for (int e = 0; e < PER; ++e) {
-            const int idx = tid + e * 256;
-            int ii, kk;
-            if (a_k_fast) { kk = idx % TK; ii = idx / TK; } else { ii = idx % TM; kk = idx / TM; }
-            const int gi = i0 + ii, gk = k0 + kk;
-            ra[e] = (gi < Mr && gk < Kd) ? A[(long)gi * sai + (long)gk * sak] : 0.0;
-            int jj, kb;
-            if (b_j_fast) { jj = idx % TN; kb = idx / TN; } else { kb = idx % TK; jj = idx / TK; }
-            const int gj = j0 + jj, gkb = k0 + kb;
-            rb[e] = (gj < Nc && gkb < Kd) ? Bm[(long)gkb * sbk + (long)gj * sbj] : 0.0;
-        }
-    };
-    auto stash = [&]() {                              // registers -> LDS
-#pragma unroll
-        for (int e = 0; e < PER; ++e) {
-            const int idx = tid + e * 256;
-            int ii, kk;
-            if (a_k_fast) { kk = idx % TK; ii = idx / TK; } else { ii = idx % TM; kk = idx / TM; }
-            As[kk][ii] = ra[e];
-            int jj, kb;
-            if (b_j_fast) { jj = idx % TN; kb = idx / TN; } else { kb = idx % TK; jj = idx / TK; }
-            Bs[kb][jj] = rb[e];
-        }
-    };
-    fetch(0);
-    stash();
-    __syncthreads();
-    for (int k0 = 0; k0 < Kd; k0 += TK) {
-        const bool more = k0 + TK < Kd;
-        if (more) fetch(k0 + TK);                     // in flight under the MFMAs below
-#pragma unroll
-        for (int ks = 0; ks < TK; ks += 4) {
-            double av[2], bv[2];
-#pragma unroll
-            for (int x = 0; x < 2; ++x) av[x] = As[ks + lk][wi + 16 * x + lr];
-#pragma unroll
-            for (int y = 0; y < 2; ++y) bv[y] = Bs[ks + lk][wj + 16 * y + lr];
-#pragma unroll
-            for (int x = 0; x < 2; ++x)
-#pragma unroll
-                for (int y = 0; y < 2; ++y)
-                    acc[x][y] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[x], bv[y], acc[x][y], 0, 0, 0);
-        }
-        __syncthreads();
-        if (more) stash();
-        __syncthreads();
-    }
+    __shared__ bagel_gemm::tile_lds sh;
+    bagel_gemm::d4v acc[2][2];
+    bagel_gemm::tile_product(acc, sh, i0, j0, Mr, Nc, Kd, A, sai, sak, Bm, sbk, sbj);
+    const bagel_gemm::lane_pos pos = bagel_gemm::lane_position();
 #pragma unroll
     for (int x = 0; x < 2; ++x)
 #pragma unroll
         for (int y = 0; y < 2; ++y)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const int gi = i0 + wi + 16 * x + lk + 4 * r;
-                const int gj = j0 + wj + 16 * y + lr;
+                const int gi = i0 + pos.row0 + 16 * x + 4 * r;
+                const int gj = j0 + pos.col0 + 16 * y;
                 if (gi < Mr && gj < Nc) {
                     double *dst = Cm + (long)gi * ldc + gj;
                     *dst = (overwrite ? 0.0 : *dst) + alpha * acc[x][y][r];
