@@ -34,6 +34,10 @@
  *   - No random numbers are drawn inside the library: omega, phase, w, eps are inputs.
  *   - Return value: 0 on success, a negative BAGEL_E* code otherwise; bagel_last_error
  *     gives a message.  NaN/Inf inputs are not screened; they propagate.
+ *   - Range of the kernel row (eq. (4)): training inputs and GP inputs are expected within about
+ *     400 length scales of the origin (sum_d x_d^2 / l_d^2 < 1.8e5; the paper's data are
+ *     normalised).  A training point further out is dropped from the kernel row, and a trajectory
+ *     further out sees a kernel row of zero; both are exact as long as the other side stays inside.
  *   - One context must not be used from two threads at once.
  */
 #ifndef BAGEL_H

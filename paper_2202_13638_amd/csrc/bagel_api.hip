@@ -76,7 +76,7 @@ static hipError_t dev_alloc(bagel_ctx *c, T **p, size_t count)
 
 static void free_all(bagel_ctx *c)
 {
-    void *ptrs[] = {c->Xs, c->Os, c->A, c->amp, c->v4, c->w4, c->xbuf, c->part, c->lpt, c->lam,
+    void *ptrs[] = {c->Xs, c->Os, c->A, c->amp, c->exp_tab, c->v4, c->w4, c->xbuf, c->part, c->lpt, c->lam,
                     c->tape_s, c->tape_J, c->tape_h[0], c->tape_h[1], c->tape_h[2], c->tape_a, c->tape_d[0],
                     c->tape_d[1], c->tape_d[2], c->ckpt_s, c->wpad_f, c->wpad_b, c->gsplit, c->gacc, c->fbuf, c->gtheta, c->post_alpha, c->post_Kinv, c->post_Kx, c->post_sums};
     for (void *p : ptrs)
@@ -158,6 +158,7 @@ extern "C" int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_s
     ALLOC(c->Os, (size_t)M * c->Lp * (D + 1));
     ALLOC(c->A, (size_t)M * D);
     ALLOC(c->amp, (size_t)M);
+    ALLOC(c->exp_tab, 256);
     ALLOC(c->v4, (size_t)M * (c->Np / 4) * dims->S);
     ALLOC(c->w4, (size_t)M * (c->Lp / 4) * dims->S);
     ALLOC(c->xbuf, (size_t)D * Bz);
@@ -179,6 +180,11 @@ extern "C" int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_s
     ALLOC(c->gacc, (size_t)c->P);
     ALLOC(c->gtheta, (size_t)c->P);
 #undef ALLOC
+    if (e == hipSuccess) {
+        double tab[256];
+        for (int i = 0; i < 256; ++i) tab[i] = exp2((double)i / 256.0);
+        e = hipMemcpy(c->exp_tab, tab, sizeof(tab), hipMemcpyHostToDevice);
+    }
     if (e != hipSuccess) {
         const int64_t want = c->bytes;
         free_all(c);

@@ -31,6 +31,7 @@ struct bagel_ctx {
     double *Os;                  // [M][Lp][D+1]: omega_mld / (2 pi) (revolutions per unit x_d), then phase / (2 pi)
     double *A;                   // [M][D]: log2(e) / l_md^2
     double *amp;                 // [M]: sqrt(2 alpha_m^2 / L)
+    double *exp_tab;             // [256]: 2^(i/256), the table of the step kernel's exp2
     float4 *v4;                  // [M][Np/4][S]: four consecutive training points of one sample
     float4 *w4;                  // [M][Lp/4][S]
 

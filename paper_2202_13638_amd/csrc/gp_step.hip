@@ -23,7 +23,8 @@
 //   log2 k_mn(x) = q_m(x) + c_mn + sum_d x_d * Xs_mnd,
 //   Xs_mnd = log2(e)/l_md^2 * X_nd,  c_mn = log2(alpha_m^2) - 1/2 sum_d Xs_mnd X_nd,
 //   q_m(x) = -1/2 sum_d log2(e)/l_md^2 x_d^2.
-// exp2 splits off the integer part and squares a degree-7 polynomial for 2^(f/2) on [-1/2, 1/2].
+// exp2 takes the integer part and the next eight bits of the exponent from a rounding addition,
+// looks 2^(i/256) up in an LDS table and multiplies with a degree-3 polynomial (exp2_tab below).
 // Jacobian: d k_mn / d x_d = ln2 * k_mn * (Xs_mnd - log2(e)/l_md^2 x_d); the kernel
 // accumulates G_d = sum_n v_n k_n Xs_mnd and u = sum_n v_n k_n, the reduction finishes it.
 //
@@ -35,34 +36,36 @@ namespace {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
-// 2^t for t <= log2(alpha^2): split off the integer part, evaluate 2^(f/2) for |f| <= 1/2 with a
-// degree-7 polynomial and square it (relative error 4e-13), scale with ldexp.  Very negative t
-// underflows to zero in ldexp.
-// The two highest coefficients come in from the caller, c7 in a scalar and c6 in a vector register:
-// the first Horner step is then a single three-operand FMA (an FMA takes at most one scalar operand;
-// with both as literals the compiler spends an extra register move per evaluation).
-__device__ __forceinline__ double exp2_poly(double t, double c7, double c6)
+// 2^t from u = 256 t.  Adding 1.5 * 2^52 rounds u to the integer J = 256 n + i in the low word of the
+// sum (two's complement; |u| < 2^31), so 2^t = 2^n * 2^(i/256) * 2^(g/256) with g = u - J, |g| <= 1/2:
+// the middle factor comes from a 256-entry table in LDS (the LDS port is otherwise idle in this
+// kernel), the last one from a degree-3 polynomial (relative error 4e-14 over all t), the first one
+// from ldexp, which also takes very negative t to zero.  Ten vector instructions; the form without a
+// table (degree-7 polynomial for 2^(f/2), squared) takes twelve and is ten times less accurate.
+// a3 and a2 come in from the caller, a3 in a scalar and a2 in a vector register: the first Horner
+// step is then a single three-operand FMA (an FMA takes at most one scalar operand).
+__device__ __forceinline__ double exp2_tab(double u, const double *tab, double a3, double a2)
 {
-    const double n = rint(t);
-    const double f = t - n;                       // exact, |f| <= 1/2
-    double p = fma(c7, f, c6);
-    p = fma(p, f, 4.1667353769980764e-05);
-    p = fma(p, f, 0.0006011326659205452);
-    p = fma(p, f, 0.006938013583872582);
-    p = fma(p, f, 0.060056626759929704);
-    p = fma(p, f, 0.3465735902799663);
-    p = fma(p, f, 0.9999999999998426);
-    return ldexp(p * p, (int)n);
+    constexpr double MAGIC = 6755399441055744.0;  // 1.5 * 2^52
+    const double s = u + MAGIC;
+    const int J = __double2loint(s);
+    const double g = u - (s - MAGIC);             // exact
+    const double T = tab[J & 255];
+    double p = fma(a3, g, a2);
+    p = fma(p, g, 0x1.62e42fefa39ddp-9);
+    p = fma(p, g, 1.0);
+    return ldexp(T * p, J >> 8);
 }
 
 template <int D, bool JAC>
 __global__ __launch_bounds__(BAGEL_BLOCK) void gp_step_kernel(
     const double *__restrict__ Xs, const double *__restrict__ Os, const double *__restrict__ A,
     const float4 *__restrict__ v4, const float4 *__restrict__ w4, const double *__restrict__ xbuf,
-    double *__restrict__ part, int B, int S, int per_sample, int Np, int Lp, int CK, int CL, int nck,
-    int ncl, int M)
+    double *__restrict__ part, const double *__restrict__ exp_tab, int B, int S, int per_sample, int Np, int Lp,
+    int CK, int CL, int nck, int ncl, int M)
 {
     __shared__ double red[3][1 + D][64];
+    __shared__ double tab[256];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int b_raw = blockIdx.x * 64 + lane;
@@ -86,23 +89,36 @@ __global__ __launch_bounds__(BAGEL_BLOCK) void gp_step_kernel(
         // ---------------- kernel-row unit: CK training points of output m ----------------
         const int m = group / ngk, c = 4 * (group - m * ngk) + wave;
         const int n_iter = c < nck ? CK / 4 : 0;   // a wave past the last chunk adds nothing
+        tab[threadIdx.x] = exp_tab[threadIdx.x];   // BAGEL_BLOCK = 256 threads, 256 entries
+        __syncthreads();
         double q = 0.0;
 #pragma unroll
         for (int d = 0; d < D; ++d) q = fma(-0.5 * A[m * D + d] * x[d], x[d], q);
+        // The exponent is formed times 256 (exact scaling).  exp2_tab needs |256 t| < 2^31: with
+        // |q| <= 2^17 and the table rows limited to c_n >= -2^17 (model set-up turns rows beyond that
+        // into padding), |t| <= |q| + |c_n| + 2 sqrt(|q| |c_n|) + |log2 alpha^2| < 2^20.  A trajectory
+        // further out (about 400 length scales from the origin) is that far from every training point
+        // that is kept, and its kernel row is zero: it gets a constant exponent of -3000.
+        const bool far = q < -131072.0;
+        double xs[D];
+#pragma unroll
+        for (int d = 0; d < D; ++d) xs[d] = far ? 0.0 : 256.0 * x[d];
+        const double qs = far ? -768000.0 : 256.0 * q;
+        double k256 = 256.0;
         const double *__restrict__ Xr = Xs + ((size_t)m * Np + (size_t)c * CK) * (D + 1);
         const float4 *__restrict__ vp = v4 + ((size_t)m * (Np / 4) + (size_t)c * (CK / 4)) * S + sidx;
-        double c7 = 1.192611307487823e-07, c6 = 2.409383341728244e-06;
-        asm volatile("" : "+s"(c7), "+v"(c6));    // pin the register classes (see exp2_poly)
+        double a3 = 0x1.c6b0902a6389dp-29, a2 = 0x1.ebfbe3a9ac89ap-19;
+        asm volatile("" : "+s"(a3), "+v"(a2), "+v"(k256));    // pin the register classes (see exp2_tab)
         for (int n4 = 0; n4 < n_iter; ++n4) {
             const v4f vv = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(vp + (size_t)n4 * S));   // read-once stream
             const float vj[4] = {vv.x, vv.y, vv.z, vv.w};
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const double *__restrict__ r = Xr + (size_t)(n4 * 4 + j) * (D + 1);
-                double t = q + r[D];
+                double t = fma(r[D], k256, qs);
 #pragma unroll
-                for (int d = 0; d < D; ++d) t = fma(x[d], r[d], t);
-                const double k = exp2_poly(t, c7, c6);
+                for (int d = 0; d < D; ++d) t = fma(xs[d], r[d], t);
+                const double k = exp2_tab(t, tab, a3, a2);
                 const double vk = (double)vj[j] * k;
                 u += vk;
                 if (JAC) {
@@ -181,12 +197,12 @@ hipError_t launch_d(bagel_ctx *c, bool jac)
     const int per_sample = c->dm.B / c->dm.S;
     if (jac)
         hipLaunchKernelGGL((gp_step_kernel<D, true>), grid, dim3(BAGEL_BLOCK), 0, c->stream, c->Xs, c->Os, c->A,
-                           c->v4, c->w4, c->xbuf, c->part, c->dm.B, c->dm.S, per_sample, c->Np, c->Lp, c->CK,
-                           c->CL, c->nck, c->ncl, c->M);
+                           c->v4, c->w4, c->xbuf, c->part, c->exp_tab, c->dm.B, c->dm.S, per_sample, c->Np,
+                           c->Lp, c->CK, c->CL, c->nck, c->ncl, c->M);
     else
         hipLaunchKernelGGL((gp_step_kernel<D, false>), grid, dim3(BAGEL_BLOCK), 0, c->stream, c->Xs, c->Os, c->A,
-                           c->v4, c->w4, c->xbuf, c->part, c->dm.B, c->dm.S, per_sample, c->Np, c->Lp, c->CK,
-                           c->CL, c->nck, c->ncl, c->M);
+                           c->v4, c->w4, c->xbuf, c->part, c->exp_tab, c->dm.B, c->dm.S, per_sample, c->Np,
+                           c->Lp, c->CK, c->CL, c->nck, c->ncl, c->M);
     return hipGetLastError();
 }
 

@@ -32,6 +32,10 @@ __global__ void build_model_kernel(const float *__restrict__ X, const float *__r
                 c -= 0.5 * a * xv * xv;
             }
             row[D] = c;
+            if (c < -131072.0) {                     // outside the step kernel's range (see gp_step.hip): k = 0
+                for (int d = 0; d < D; ++d) row[d] = 0.0;
+                row[D] = -2000.0;
+            }
         } else {
             for (int d = 0; d < D; ++d) row[d] = 0.0;
             row[D] = -2000.0;

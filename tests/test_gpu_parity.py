@@ -124,6 +124,23 @@ def test_stress_full_size():
     dict(d_s=8, d_a=8, N=33, L=45, B=5, S=5),            # largest input dimension
 ])
 def test_sample_eval_value_and_jacobian(shape):
+    x = np.random.default_rng(3).uniform(-1.2, 1.2, (shape["B"], shape["d_s"] + shape["d_a"])).astype(np.float32)
+    _check_sample_eval(shape, x)
+
+
+def test_sample_eval_inputs_far_from_the_data():
+    """GP inputs hundreds of length scales away from every training point: the kernel row is zero
+    there (the step kernel flushes it beyond about 400 length scales), the feature part is not."""
+    shape = dict(d_s=3, d_a=2, N=50, L=70, B=37, S=37)
+    x = np.random.default_rng(4).uniform(-1.2, 1.2, (shape["B"], 5)).astype(np.float32)
+    x[3] = 150.0                       # about 190 length scales out (length scales of the recipe are >= 0.5 ... 2)
+    x[4] *= 400.0
+    x[5] = -2500.0                     # beyond the kernel's range
+    x[6, 2] = 1.0e4
+    _check_sample_eval(shape, x)
+
+
+def _check_sample_eval(shape, x):
     import torch
     from paper_2202_13638_amd import binding
     cfg = synth.Config("e", 11, shape["d_s"], shape["d_a"], 1, shape["N"], shape["L"], shape["B"], 2, (4,), 0.0,
@@ -131,7 +148,6 @@ def test_sample_eval_value_and_jacobian(shape):
     inp = synth.make_inputs(cfg, S=shape["S"])
     dm = oracle.dims_from_config(cfg, S=shape["S"])
     v32 = oracle.prepare_samples(dm, inp).astype(np.float32)
-    x = np.random.default_rng(3).uniform(-1.2, 1.2, (cfg.B, cfg.D)).astype(np.float32)
     ctx = binding.Bagel(binding.dims_from_config(cfg, S=shape["S"]))
     g = harness.to_gpu(inp)
     ctx.bagel_set_samples(g["X"], g["lengthscale"], g["signal_var"], g["omega"], g["phase"], g["w"],
