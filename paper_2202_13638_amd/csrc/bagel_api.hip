@@ -131,6 +131,14 @@ extern "C" int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_s
     c->Lp = c->ncl * c->CL;
     c->units = M * (c->nck + c->ncl);
     c->groups = M * ((c->nck + 3) / 4 + (c->ncl + 3) / 4);
+    // The table form of exp2 pays when the launch has many workgroups per compute unit (see
+    // gp_step.hip).  Measured, table vs polynomial: stress (4608 workgroups) 0.628 vs 0.647 ms per
+    // launch; large policy (3072) 0.0892 vs 0.0872; medium (1280) 0.0346 vs 0.0258; small 0.0176 vs 0.0124.
+    {
+        const int64_t wgs = (int64_t)((B + 63) / 64) * c->groups;
+        const int tab = env_int("BAGEL_EXP_TABLE", 0);         // 1: off, 2: on, otherwise by launch size
+        c->exp_table = tab == 2 ? true : (tab == 1 ? false : wgs >= 256 * 16);
+    }
     if (c->units > 65535) {
         delete c;
         CREATE_FAIL(BAGEL_EINVAL, "bagel_create: too many work units (%d)", M * (int)((N + 31) / 32 + (L + 31) / 32));

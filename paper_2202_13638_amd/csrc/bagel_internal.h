@@ -27,6 +27,7 @@ struct bagel_ctx {
     int nck, ncl;                // chunks per output
     int units;                   // M * (nck + ncl)
     int groups;                  // M * (ceil(nck/4) + ceil(ncl/4)): four units per workgroup and partial sum
+    bool exp_table;              // sample-evaluation kernel with the table form of exp2 (large launches)
     double *Xs;                  // [M][Np][D+1]: log2(e)/l_md^2 * X_nd, then log2(alpha_m^2) - 1/2 sum_d log2(e)/l_md^2 X_nd^2
     double *Os;                  // [M][Lp][D+1]: omega_mld / (2 pi) (revolutions per unit x_d), then phase / (2 pi)
     double *A;                   // [M][D]: log2(e) / l_md^2

@@ -57,7 +57,29 @@ __device__ __forceinline__ double exp2_tab(double u, const double *tab, double a
     return ldexp(T * p, J >> 8);
 }
 
-template <int D, bool JAC>
+// 2^t without a table: split off the integer part, evaluate 2^(f/2) for |f| <= 1/2 with a degree-7
+// polynomial and square it (relative error 4e-13), scale with ldexp.  Twelve vector instructions and
+// no LDS access.  c7 in a scalar and c6 in a vector register, as in exp2_tab.
+__device__ __forceinline__ double exp2_poly(double t, double c7, double c6)
+{
+    const double n = rint(t);
+    const double f = t - n;                       // exact, |f| <= 1/2
+    double p = fma(c7, f, c6);
+    p = fma(p, f, 4.1667353769980764e-05);
+    p = fma(p, f, 0.0006011326659205452);
+    p = fma(p, f, 0.006938013583872582);
+    p = fma(p, f, 0.060056626759929704);
+    p = fma(p, f, 0.3465735902799663);
+    p = fma(p, f, 0.9999999999998426);
+    return ldexp(p * p, (int)n);
+}
+
+// TAB selects the exp2: the table form saves two instructions per training point, but its LDS read
+// shares a wait counter with the scalar loads of the shared operands, so every table look-up also
+// waits for the operand rows requested ahead.  A launch that fills the chip many times over hides
+// that behind other waves (stress workload: 0.647 -> 0.629 ms); a small launch does not (N = 2048,
+// B = 1024: 26 -> 35 us), and takes the polynomial form.
+template <int D, bool JAC, bool TAB>
 __global__ __launch_bounds__(BAGEL_BLOCK) void gp_step_kernel(
     const double *__restrict__ Xs, const double *__restrict__ Os, const double *__restrict__ A,
     const float4 *__restrict__ v4, const float4 *__restrict__ w4, const double *__restrict__ xbuf,
@@ -89,36 +111,42 @@ __global__ __launch_bounds__(BAGEL_BLOCK) void gp_step_kernel(
         // ---------------- kernel-row unit: CK training points of output m ----------------
         const int m = group / ngk, c = 4 * (group - m * ngk) + wave;
         const int n_iter = c < nck ? CK / 4 : 0;   // a wave past the last chunk adds nothing
-        tab[threadIdx.x] = exp_tab[threadIdx.x];   // BAGEL_BLOCK = 256 threads, 256 entries
-        __syncthreads();
+        if (TAB) {
+            tab[threadIdx.x] = exp_tab[threadIdx.x];   // BAGEL_BLOCK = 256 threads, 256 entries
+            __syncthreads();
+        }
         double q = 0.0;
 #pragma unroll
         for (int d = 0; d < D; ++d) q = fma(-0.5 * A[m * D + d] * x[d], x[d], q);
-        // The exponent is formed times 256 (exact scaling).  exp2_tab needs |256 t| < 2^31: with
-        // |q| <= 2^17 and the table rows limited to c_n >= -2^17 (model set-up turns rows beyond that
-        // into padding), |t| <= |q| + |c_n| + 2 sqrt(|q| |c_n|) + |log2 alpha^2| < 2^20.  A trajectory
-        // further out (about 400 length scales from the origin) is that far from every training point
-        // that is kept, and its kernel row is zero: it gets a constant exponent of -3000.
+        // Table form: the exponent is formed times 256 (exact scaling).  exp2_tab needs |256 t| < 2^31:
+        // with |q| <= 2^17 and the table rows limited to c_n >= -2^17 (model set-up turns rows beyond
+        // that into padding), |t| <= |q| + |c_n| + 2 sqrt(|q| |c_n|) + |log2 alpha^2| < 2^20.  A
+        // trajectory further out (about 400 length scales from the origin) is that far from every
+        // training point that is kept, and its kernel row is zero: it gets a constant exponent of
+        // -3000.  The polynomial form applies the same rule, so both forms agree everywhere.
+        const double scale = TAB ? 256.0 : 1.0;
         const bool far = q < -131072.0;
         double xs[D];
 #pragma unroll
-        for (int d = 0; d < D; ++d) xs[d] = far ? 0.0 : 256.0 * x[d];
-        const double qs = far ? -768000.0 : 256.0 * q;
-        double k256 = 256.0;
+        for (int d = 0; d < D; ++d) xs[d] = far ? 0.0 : scale * x[d];
+        const double qs = far ? -3000.0 * scale : scale * q;
+        double kscale = scale;
         const double *__restrict__ Xr = Xs + ((size_t)m * Np + (size_t)c * CK) * (D + 1);
         const float4 *__restrict__ vp = v4 + ((size_t)m * (Np / 4) + (size_t)c * (CK / 4)) * S + sidx;
-        double a3 = 0x1.c6b0902a6389dp-29, a2 = 0x1.ebfbe3a9ac89ap-19;
-        asm volatile("" : "+s"(a3), "+v"(a2), "+v"(k256));    // pin the register classes (see exp2_tab)
+        // leading polynomial coefficients of the exp2 in use, pinned to register classes (see exp2_tab)
+        double ca = TAB ? 0x1.c6b0902a6389dp-29 : 1.192611307487823e-07;
+        double cb = TAB ? 0x1.ebfbe3a9ac89ap-19 : 2.409383341728244e-06;
+        asm volatile("" : "+s"(ca), "+v"(cb), "+v"(kscale));
         for (int n4 = 0; n4 < n_iter; ++n4) {
             const v4f vv = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(vp + (size_t)n4 * S));   // read-once stream
             const float vj[4] = {vv.x, vv.y, vv.z, vv.w};
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const double *__restrict__ r = Xr + (size_t)(n4 * 4 + j) * (D + 1);
-                double t = fma(r[D], k256, qs);
+                double t = TAB ? fma(r[D], kscale, qs) : qs + r[D];
 #pragma unroll
                 for (int d = 0; d < D; ++d) t = fma(xs[d], r[d], t);
-                const double k = exp2_tab(t, tab, a3, a2);
+                const double k = TAB ? exp2_tab(t, tab, ca, cb) : exp2_poly(t, ca, cb);
                 const double vk = (double)vj[j] * k;
                 u += vk;
                 if (JAC) {
@@ -190,19 +218,26 @@ __global__ __launch_bounds__(BAGEL_BLOCK) void gp_step_kernel(
     }
 }
 
-template <int D>
-hipError_t launch_d(bagel_ctx *c, bool jac)
+template <int D, bool JAC, bool TAB>
+void launch_variant(bagel_ctx *c)
 {
     dim3 grid((c->dm.B + 63) / 64, c->groups);
     const int per_sample = c->dm.B / c->dm.S;
-    if (jac)
-        hipLaunchKernelGGL((gp_step_kernel<D, true>), grid, dim3(BAGEL_BLOCK), 0, c->stream, c->Xs, c->Os, c->A,
-                           c->v4, c->w4, c->xbuf, c->part, c->exp_tab, c->dm.B, c->dm.S, per_sample, c->Np,
-                           c->Lp, c->CK, c->CL, c->nck, c->ncl, c->M);
-    else
-        hipLaunchKernelGGL((gp_step_kernel<D, false>), grid, dim3(BAGEL_BLOCK), 0, c->stream, c->Xs, c->Os, c->A,
-                           c->v4, c->w4, c->xbuf, c->part, c->exp_tab, c->dm.B, c->dm.S, per_sample, c->Np,
-                           c->Lp, c->CK, c->CL, c->nck, c->ncl, c->M);
+    hipLaunchKernelGGL((gp_step_kernel<D, JAC, TAB>), grid, dim3(BAGEL_BLOCK), 0, c->stream, c->Xs, c->Os, c->A, c->v4,
+                       c->w4, c->xbuf, c->part, c->exp_tab, c->dm.B, c->dm.S, per_sample, c->Np, c->Lp, c->CK, c->CL,
+                       c->nck, c->ncl, c->M);
+}
+
+template <int D>
+hipError_t launch_d(bagel_ctx *c, bool jac)
+{
+    if (c->exp_table) {
+        if (jac) launch_variant<D, true, true>(c);
+        else launch_variant<D, false, true>(c);
+    } else {
+        if (jac) launch_variant<D, true, false>(c);
+        else launch_variant<D, false, false>(c);
+    }
     return hipGetLastError();
 }
 
