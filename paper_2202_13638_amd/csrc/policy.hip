@@ -9,7 +9,8 @@
 //   A operand = weights, zero-padded to [rows % 32 == 0][K % 32 == 0] and re-ordered once per call
 //               so that a wave reads the operands of four MFMAs as 1 KB of contiguous memory; the
 //               forward kernels keep the wave's share of all layers in registers, the backward
-//               sweep streams its share from L2 one batch of 16 MFMAs ahead;
+//               sweep keeps the two narrow layers there and streams the wide one from L2 one batch
+//               of 16 MFMAs ahead;
 //   B operand = the layer's input activations, kept in LDS as [K/4][trajectory][4] so a lane
 //               reads the matching four K values of its trajectory with one 16-byte load.
 // Lanes 0-31 feed K = k0..k0+3 and lanes 32-63 feed K = k0+4..k0+7 over four MFMAs; the order in
@@ -75,12 +76,6 @@ __device__ __forceinline__ wave_plan plan_layer(int rows, int kp, int wave)
     return p;
 }
 
-// acc = W[32 rt .. +32][8 k_begin .. 8 k_end) * act[same K][32 trajectories].
-// Packed weights: element W[32 rt + c][8 k8 + 4 hf + e] sits at ((rt * kp/8 + k8) * 64 + c + 32 hf) * 4 + e,
-// so a wave reads 1 KB contiguous per 8 values of K.  The contraction is consumed in batches of 32
-// (16 MFMAs); the weight fragments of the next batch are requested before the MFMAs of the current
-// one issue.  All loads are unconditional (kp is padded to a multiple of 32 with zero weights; the
-// look-ahead past the end re-reads the last batch).
 // 16-byte read that the optimiser will not move across loop iterations (two relaxed wave-scope
 // atomic loads: an ordinary load instruction, but one the compiler keeps where it is written).
 // Used to keep the look-ahead operand loads of the MFMA loops ahead of the MFMAs; plain loads of
@@ -110,6 +105,12 @@ __device__ __forceinline__ f16v mfma_batch(f16v acc, const float4 *av, const flo
     return acc;
 }
 
+// acc = W[32 rt .. +32][8 k_begin .. 8 k_end) * act[same K][32 trajectories].
+// Packed weights: element W[32 rt + c][8 k8 + 4 hf + e] sits at ((rt * kp/8 + k8) * 64 + c + 32 hf) * 4 + e,
+// so a wave reads 1 KB contiguous per 8 values of K.  The contraction is consumed in batches of 32
+// (16 MFMAs); the weight fragments of the next batch are requested before the MFMAs of the current
+// one issue.  All loads are unconditional (kp is padded to a multiple of 32 with zero weights; the
+// look-ahead past the end re-reads the last batch).
 __device__ __forceinline__ f16v tile_contract(const float *__restrict__ W, int kp, const wave_plan &p, int lane,
                                               const float4 *__restrict__ act4)
 {
