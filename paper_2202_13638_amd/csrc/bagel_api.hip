@@ -119,10 +119,11 @@ extern "C" int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_s
     // units first, so short feature units at the end fill the tail of the launch.  Measured on MI355X:
     // stress 0.650 ms per launch at (CK, CL) = (1024, 512), 0.628 ms at (1024, 256); the large-policy
     // step 140.6 ms at (128, 64), 136.8 ms at (256, 64).
-    // A launch that stays under the target even with the smallest chunk is bound by the latency of one
-    // wave's chain of iterations (about 0.5 us each: the scalar loads of the operand rows miss the
-    // scalar cache and nothing else is there to hide them), so its units are kept short: medium
-    // 10.7 ms per call at (128, 32), 9.7 ms at (64, 64); small 3.78 ms at (64, 32), 3.46 ms at (32, 32).
+    // A launch that stays under the target even with the smallest chunk has only a handful of waves per
+    // SIMD, and the longest of them sets its duration (measured: launch time grows in proportion to
+    // CK), so its units are kept short and alike: medium 10.7 ms per call at (128, 32), 9.7 ms at
+    // (64, 64); small 3.78 ms at (64, 32), 3.46 ms at (32, 32).  (Staging the operand rows through LDS
+    // and look-ahead loads of the stream changed nothing there: those launches are not latency-bound.)
     const bool small_launch = chunk == 32 && items / chunk < target;
     const int ck_default = small_launch ? (N / chunk >= 64 ? 64 : 32)
                                         : (N / chunk >= 32 ? 4 * chunk : (N / chunk >= 16 ? 2 * chunk : chunk));
