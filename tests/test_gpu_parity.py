@@ -128,12 +128,27 @@ def test_sample_eval_value_and_jacobian(shape):
     _check_sample_eval(shape, x)
 
 
-def test_sample_eval_inputs_far_from_the_data():
+# the library picks the form of its float64 exp2 by launch size (polynomial on small launches, table
+# look-up on large ones); BAGEL_EXP_TABLE = 1 / 2 forces one, so that both are checked at test sizes
+EXP2_FORMS = {"polynomial": "1", "table": "2"}
+
+
+@pytest.mark.parametrize("form", list(EXP2_FORMS))
+def test_sample_eval_with_either_exp2(form, monkeypatch):
+    monkeypatch.setenv("BAGEL_EXP_TABLE", EXP2_FORMS[form])
+    shape = dict(d_s=6, d_a=2, N=300, L=200, B=130, S=13)
+    x = np.random.default_rng(5).uniform(-1.2, 1.2, (shape["B"], 8)).astype(np.float32)
+    _check_sample_eval(shape, x)
+
+
+@pytest.mark.parametrize("form", list(EXP2_FORMS))
+def test_sample_eval_inputs_far_from_the_data(form, monkeypatch):
     """GP inputs hundreds of length scales away from every training point: the kernel row is zero
     there (the step kernel flushes it beyond about 400 length scales), the feature part is not."""
+    monkeypatch.setenv("BAGEL_EXP_TABLE", EXP2_FORMS[form])
     shape = dict(d_s=3, d_a=2, N=50, L=70, B=37, S=37)
     x = np.random.default_rng(4).uniform(-1.2, 1.2, (shape["B"], 5)).astype(np.float32)
-    x[3] = 150.0                       # about 190 length scales out (length scales of the recipe are >= 0.5 ... 2)
+    x[3] = 150.0                       # 80 to 170 length scales out (the recipe draws them from 0.5 ... 2)
     x[4] *= 400.0
     x[5] = -2500.0                     # beyond the kernel's range
     x[6, 2] = 1.0e4
@@ -196,6 +211,16 @@ def test_rollout_variants(name):
     fwd = harness.gpu_rollout(cfg, inp, ref["v32"], S=S, grad=False, **spec["dims"])
     np.testing.assert_array_equal(fwd["states"], got["states"])
     assert fwd["loss"] == got["loss"]
+
+
+def test_rollout_with_table_exp2(monkeypatch):
+    """The exp2 form of large launches, forced at a size the oracle finishes in seconds."""
+    monkeypatch.setenv("BAGEL_EXP_TABLE", EXP2_FORMS["table"])
+    cfg = _cfg("small", B=96, H=30)
+    inp = synth.make_inputs(cfg)
+    ref = harness.oracle_reference(cfg, inp)
+    got = harness.gpu_rollout(cfg, inp, ref["v32"])
+    harness.assert_parity(ref, got, label="small/B96/H30/table")
 
 
 def test_checkpointing_does_not_change_the_result():
