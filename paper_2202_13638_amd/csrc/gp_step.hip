@@ -112,7 +112,8 @@ __global__ __launch_bounds__(BAGEL_BLOCK) void gp_step_kernel(
         const int m = group / ngk, c = 4 * (group - m * ngk) + wave;
         const int n_iter = c < nck ? CK / 4 : 0;   // a wave past the last chunk adds nothing
         if (TAB) {
-            tab[threadIdx.x] = exp_tab[threadIdx.x];   // BAGEL_BLOCK = 256 threads, 256 entries
+            static_assert(BAGEL_BLOCK == 256, "one table entry per thread");
+            tab[threadIdx.x] = exp_tab[threadIdx.x];
             __syncthreads();
         }
         double q = 0.0;
