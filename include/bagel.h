@@ -151,7 +151,8 @@ int bagel_rollout_loss_grad(bagel_ctx *ctx, const float *theta, const float *s0,
  * sampler is meant for N of a few thousand; the pathwise calls above cost 2 N (D+1).
  *
  * bagel_prepare_posterior: alpha_m = K_hat_m^-1 y_m and K_hat_m^-1 for every output, float64, kept in
- * the context (the first call allocates 8 (M Np^2 + 2 Np B) bytes, Np = N rounded up to 64).
+ * the context (the first call allocates 8 M (Np^2 + Np B (1 + (1+D)/32)) bytes, Np = N rounded up to 64:
+ * K_hat^-1, the kernel rows of a step and the per-tile sums of its moments).
  * Arrays as in bagel_prepare_samples.  Synchronises the stream.  Errors: EINVAL, ENOMEM, ENOTPD, EHIP.
  *
  * bagel_posterior_rollout_loss / _grad: as bagel_rollout_loss / bagel_rollout_loss_grad, with
