@@ -229,7 +229,8 @@ def main():
         torch.cuda.synchronize()
         t_h = time.perf_counter() - t0
         Np = (cfg.N + 63) // 64 * 64
-        flop = 2.0 * cfg.M * args.hyper_iters * (Np ** 3 / 3 + 2.0 * Np ** 3)     # Cholesky + K_hat^-1 by substitution
+        # Cholesky Np^3/6 FMA; forward and backward substitution on Np+1 right-hand sides Np^2/2 FMA each
+        flop = 2.0 * cfg.M * args.hyper_iters * (Np ** 3 / 6 + float(Np) ** 2 * (Np + 1))
         out["hyper_fit"] = {"iterations": args.hyper_iters, "ms_per_iteration": 1e3 * t_h / args.hyper_iters,
                             "TFLOP/s": flop / t_h / 1e12, "frac_of_f64_peak": flop / t_h / 1e12 / PEAK_FP64_VECTOR_TFLOPS,
                             "lml_first": [float(x) for x in hist[0].cpu()], "lml_last": [float(x) for x in hist[-1].cpu()]}
