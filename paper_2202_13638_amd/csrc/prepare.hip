@@ -590,6 +590,78 @@ __global__ __launch_bounds__(256) void hyper_grad_final_kernel(const double *__r
     }
 }
 
+// The GP outputs are independent, and the work on one of them is a chain of small dependent kernels
+// (diagonal blocks, panel solves) between its deep products: on its own it leaves the chip idle a third
+// of the time.  So up to three outputs are worked on side by side, each on a stream of its own with
+// buffers of its own; what one leaves idle the deep products of another fill.  The side streams start
+// after everything already enqueued on the context's stream and the context's stream continues after
+// them; all have the default priority.
+struct side_lanes {
+    static constexpr int MAXL = 3;
+    int n = 0;
+    hipStream_t st[MAXL] = {};
+    hipEvent_t done[MAXL] = {};
+    hipEvent_t start = nullptr;
+
+    hipError_t open(int want)
+    {
+        if (want > MAXL) want = MAXL;
+        if (want < 1) want = 1;
+        hipError_t e = hipEventCreateWithFlags(&start, hipEventDisableTiming);
+        for (int l = 0; l < want && e == hipSuccess; ++l) {
+            e = hipStreamCreateWithFlags(&st[l], hipStreamNonBlocking);
+            if (e == hipSuccess) e = hipEventCreateWithFlags(&done[l], hipEventDisableTiming);
+            if (e == hipSuccess) n = l + 1;
+        }
+        return e;
+    }
+    hipError_t fork(hipStream_t main)
+    {
+        hipError_t e = hipEventRecord(start, main);
+        for (int l = 0; l < n && e == hipSuccess; ++l) e = hipStreamWaitEvent(st[l], start, 0);
+        return e;
+    }
+    hipError_t join(hipStream_t main)
+    {
+        hipError_t e = hipSuccess;
+        for (int l = 0; l < n && e == hipSuccess; ++l) {
+            e = hipEventRecord(done[l], st[l]);
+            if (e == hipSuccess) e = hipStreamWaitEvent(main, done[l], 0);
+        }
+        return e;
+    }
+    void close()
+    {
+        for (int l = 0; l < MAXL; ++l) {
+            if (st[l]) { (void)hipStreamSynchronize(st[l]); (void)hipStreamDestroy(st[l]); }
+            if (done[l]) (void)hipEventDestroy(done[l]);
+        }
+        if (start) (void)hipEventDestroy(start);
+    }
+};
+
+// One buffer per lane; a lane whose buffer cannot be had is given up (n shrinks), the first one must succeed.
+hipError_t lane_alloc(double *(&buf)[side_lanes::MAXL], int &n, size_t count)
+{
+    for (int l = 0; l < n; ++l) {
+        const hipError_t e = hipMalloc((void **)&buf[l], count * sizeof(double));
+        if (e != hipSuccess) {
+            buf[l] = nullptr;
+            (void)hipGetLastError();
+            if (l == 0) return e;
+            n = l;
+            break;
+        }
+    }
+    return hipSuccess;
+}
+
+void lane_free(double *(&buf)[side_lanes::MAXL])
+{
+    for (double *&p : buf)
+        if (p) { (void)hipFree(p); p = nullptr; }
+}
+
 }  // namespace
 
 void bagel_dgemm(hipStream_t st, int Mr, int Nc, int Kd, double alpha, const double *A, long sai, long sak,
@@ -605,7 +677,8 @@ int bagel_prepare_impl(bagel_ctx *c, const float *X, const float *y, const float
     const int N = c->dm.N, L = c->dm.L, S = c->dm.S, M = c->M, D = c->D;
     const int Np = (N + NB - 1) / NB * NB;
     hipStream_t st = c->stream;
-    double *K = nullptr, *Phi = nullptr, *R = nullptr, *Wd = nullptr;
+    side_lanes lanes;
+    double *K[side_lanes::MAXL] = {}, *Phi[side_lanes::MAXL] = {}, *R[side_lanes::MAXL] = {}, *Wd[side_lanes::MAXL] = {};
     int *flag = nullptr;
     float h_sf2[8], h_sn2[8];
     int rc = BAGEL_OK;
@@ -622,33 +695,38 @@ int bagel_prepare_impl(bagel_ctx *c, const float *X, const float *y, const float
         }                                                                                        \
     } while (0)
 
-    P_HIP(hipMalloc((void **)&K, (size_t)Np * Np * sizeof(double)));
-    P_HIP(hipMalloc((void **)&Phi, (size_t)Np * L * sizeof(double)));
-    P_HIP(hipMalloc((void **)&R, (size_t)Np * S * sizeof(double)));
-    P_HIP(hipMalloc((void **)&Wd, (size_t)S * L * sizeof(double)));
+    P_HIP(lanes.open(M));
+    P_HIP(lane_alloc(K, lanes.n, (size_t)Np * Np));
+    P_HIP(lane_alloc(Phi, lanes.n, (size_t)Np * L));
+    P_HIP(lane_alloc(R, lanes.n, (size_t)Np * S));
+    P_HIP(lane_alloc(Wd, lanes.n, (size_t)S * L));
     P_HIP(hipMalloc((void **)&flag, sizeof(int)));
     P_HIP(hipMemsetAsync(flag, 0, sizeof(int), st));
     P_HIP(hipMemcpyAsync(h_sf2, sf2, M * sizeof(float), hipMemcpyDeviceToHost, st));
     P_HIP(hipMemcpyAsync(h_sn2, sn2, M * sizeof(float), hipMemcpyDeviceToHost, st));
     P_HIP(hipStreamSynchronize(st));
 
+    P_HIP(lanes.fork(st));
     for (int m = 0; m < M; ++m) {
-        hipLaunchKernelGGL(build_khat_kernel, dim3((Np + 255) / 256, Np), dim3(256), 0, st, X, ell + (size_t)m * D,
-                           h_sf2[m], h_sn2[m], K, N, Np, D);
-        hipLaunchKernelGGL(build_phi_kernel, dim3((L + 255) / 256, Np), dim3(256), 0, st, X,
-                           omega + (size_t)m * L * D, phase + (size_t)m * L, h_sf2[m], Phi, N, Np, L, D);
-        hipLaunchKernelGGL(init_rhs_kernel, dim3((S + 255) / 256, Np), dim3(256), 0, st, y + (size_t)m * N, eps, R, N,
-                           Np, S, M, m);
+        const int l = m % lanes.n;
+        hipStream_t ls = lanes.st[l];
+        hipLaunchKernelGGL(build_khat_kernel, dim3((Np + 255) / 256, Np), dim3(256), 0, ls, X, ell + (size_t)m * D,
+                           h_sf2[m], h_sn2[m], K[l], N, Np, D);
+        hipLaunchKernelGGL(build_phi_kernel, dim3((L + 255) / 256, Np), dim3(256), 0, ls, X,
+                           omega + (size_t)m * L * D, phase + (size_t)m * L, h_sf2[m], Phi[l], N, Np, L, D);
+        hipLaunchKernelGGL(init_rhs_kernel, dim3((S + 255) / 256, Np), dim3(256), 0, ls, y + (size_t)m * N, eps, R[l],
+                           N, Np, S, M, m);
         // W of output m as float64 [S][L], so the GEMM reads one layout
-        hipLaunchKernelGGL(convert_w_kernel, dim3((L + 255) / 256, S), dim3(256), 0, st, w, Wd, S, M, L, m);
+        hipLaunchKernelGGL(convert_w_kernel, dim3((L + 255) / 256, S), dim3(256), 0, ls, w, Wd[l], S, M, L, m);
         // R -= Phi W^T : A = Phi [Np][L] (k fast), B(k=l, j=s) = Wd[s][l]
-        gemm(st, Np, S, L, -1.0, Phi, L, 1, Wd, 1, L, R, S, false);
+        gemm(ls, Np, S, L, -1.0, Phi[l], L, 1, Wd[l], 1, L, R[l], S, false);
 
-        factor_and_solve(st, K, Np, R, S, m * Np, flag);
-        hipLaunchKernelGGL(emit_v_kernel, dim3((S + 255) / 256, c->Np / 4), dim3(256), 0, st, R, v_out, c->v4, N, c->Np,
-                           S, M, m);
+        factor_and_solve(ls, K[l], Np, R[l], S, m * Np, flag);
+        hipLaunchKernelGGL(emit_v_kernel, dim3((S + 255) / 256, c->Np / 4), dim3(256), 0, ls, R[l], v_out, c->v4, N,
+                           c->Np, S, M, m);
         P_HIP(hipGetLastError());
     }
+    P_HIP(lanes.join(st));
     P_HIP(hipMemcpyAsync(&h_flag, flag, sizeof(int), hipMemcpyDeviceToHost, st));
     P_HIP(hipStreamSynchronize(st));
     if (h_flag != 0) {
@@ -658,11 +736,9 @@ int bagel_prepare_impl(bagel_ctx *c, const float *X, const float *y, const float
         rc = BAGEL_ENOTPD;
     }
 done:
+    lanes.close();
     (void)hipStreamSynchronize(st);
-    if (K) (void)hipFree(K);
-    if (Phi) (void)hipFree(Phi);
-    if (R) (void)hipFree(R);
-    if (Wd) (void)hipFree(Wd);
+    lane_free(K); lane_free(Phi); lane_free(R); lane_free(Wd);
     if (flag) (void)hipFree(flag);
     return rc;
 #undef P_HIP
@@ -677,7 +753,8 @@ int bagel_prepare_posterior_impl(bagel_ctx *c, const float *X, const float *y, c
     const int N = c->dm.N, M = c->M, D = c->D;
     const int Np = c->post_Np;
     hipStream_t st = c->stream;
-    double *K = nullptr, *R = nullptr;
+    side_lanes lanes;
+    double *K[side_lanes::MAXL] = {}, *R[side_lanes::MAXL] = {};
     int *flag = nullptr;
     float h_sf2[8], h_sn2[8];
     int rc = BAGEL_OK;
@@ -692,24 +769,29 @@ int bagel_prepare_posterior_impl(bagel_ctx *c, const float *X, const float *y, c
             goto done;                                                                           \
         }                                                                                        \
     } while (0)
-    P_HIP(hipMalloc((void **)&K, (size_t)Np * Np * sizeof(double)));
-    P_HIP(hipMalloc((void **)&R, (size_t)Np * (Np + 1) * sizeof(double)));
+    P_HIP(lanes.open(M));
+    P_HIP(lane_alloc(K, lanes.n, (size_t)Np * Np));
+    P_HIP(lane_alloc(R, lanes.n, (size_t)Np * (Np + 1)));
     P_HIP(hipMalloc((void **)&flag, sizeof(int)));
     P_HIP(hipMemsetAsync(flag, 0, sizeof(int), st));
     P_HIP(hipMemcpyAsync(h_sf2, sf2, M * sizeof(float), hipMemcpyDeviceToHost, st));
     P_HIP(hipMemcpyAsync(h_sn2, sn2, M * sizeof(float), hipMemcpyDeviceToHost, st));
     P_HIP(hipStreamSynchronize(st));
+    P_HIP(lanes.fork(st));
     for (int m = 0; m < M; ++m) {
+        const int l = m % lanes.n;
+        hipStream_t ls = lanes.st[l];
         c->post_sf2[m] = (double)h_sf2[m];
-        hipLaunchKernelGGL(build_khat_kernel, dim3((Np + 255) / 256, Np), dim3(256), 0, st, X, ell + (size_t)m * D,
-                           h_sf2[m], h_sn2[m], K, N, Np, D);
-        hipLaunchKernelGGL(posterior_rhs_kernel, dim3((Np + 1 + 255) / 256, Np), dim3(256), 0, st, y + (size_t)m * N, R,
-                           N, Np);
-        factor_and_solve(st, K, Np, R, Np + 1, m * Np, flag);
-        hipLaunchKernelGGL(posterior_emit_kernel, dim3((Np + 1 + 255) / 256, Np), dim3(256), 0, st, R,
+        hipLaunchKernelGGL(build_khat_kernel, dim3((Np + 255) / 256, Np), dim3(256), 0, ls, X, ell + (size_t)m * D,
+                           h_sf2[m], h_sn2[m], K[l], N, Np, D);
+        hipLaunchKernelGGL(posterior_rhs_kernel, dim3((Np + 1 + 255) / 256, Np), dim3(256), 0, ls, y + (size_t)m * N,
+                           R[l], N, Np);
+        factor_and_solve(ls, K[l], Np, R[l], Np + 1, m * Np, flag);
+        hipLaunchKernelGGL(posterior_emit_kernel, dim3((Np + 1 + 255) / 256, Np), dim3(256), 0, ls, R[l],
                            c->post_Kinv + (size_t)m * Np * Np, c->post_alpha + (size_t)m * Np, Np);
         P_HIP(hipGetLastError());
     }
+    P_HIP(lanes.join(st));
     P_HIP(hipMemcpyAsync(&h_flag, flag, sizeof(int), hipMemcpyDeviceToHost, st));
     P_HIP(hipStreamSynchronize(st));
     if (h_flag != 0) {
@@ -719,9 +801,9 @@ int bagel_prepare_posterior_impl(bagel_ctx *c, const float *X, const float *y, c
         rc = BAGEL_ENOTPD;
     }
 done:
+    lanes.close();
     (void)hipStreamSynchronize(st);
-    if (K) (void)hipFree(K);
-    if (R) (void)hipFree(R);
+    lane_free(K); lane_free(R);
     if (flag) (void)hipFree(flag);
     return rc;
 #undef P_HIP
@@ -737,7 +819,8 @@ int bagel_hyper_impl(bagel_ctx *c, const float *X, const float *y, float *log_hy
     const int N = c->dm.N, M = c->M, D = c->D, H2 = c->D + 2;
     const int Np = (N + NB - 1) / NB * NB;
     hipStream_t st = c->stream;
-    double *K = nullptr, *R = nullptr, *partial = nullptr;
+    side_lanes lanes;
+    double *K[side_lanes::MAXL] = {}, *R[side_lanes::MAXL] = {}, *partial[side_lanes::MAXL] = {};
     float *gneg = nullptr;
     int *flag = nullptr;
     int rc = BAGEL_OK, h_flag = 0;
@@ -750,26 +833,31 @@ int bagel_hyper_impl(bagel_ctx *c, const float *X, const float *y, float *log_hy
             goto done;                                                                           \
         }                                                                                        \
     } while (0)
-    P_HIP(hipMalloc((void **)&K, (size_t)Np * Np * sizeof(double)));
-    P_HIP(hipMalloc((void **)&R, (size_t)Np * (Np + 1) * sizeof(double)));
-    P_HIP(hipMalloc((void **)&partial, (size_t)N * H2 * sizeof(double)));
+    P_HIP(lanes.open(M));
+    P_HIP(lane_alloc(K, lanes.n, (size_t)Np * Np));
+    P_HIP(lane_alloc(R, lanes.n, (size_t)Np * (Np + 1)));
+    P_HIP(lane_alloc(partial, lanes.n, (size_t)N * H2));
     P_HIP(hipMalloc((void **)&gneg, (size_t)M * H2 * sizeof(float)));
     P_HIP(hipMalloc((void **)&flag, sizeof(int)));
     P_HIP(hipMemsetAsync(flag, 0, sizeof(int), st));
     for (int it = 0; it < (n_iters > 0 ? n_iters : 1); ++it) {
+        P_HIP(lanes.fork(st));                          // after the parameter update of the previous iteration
         for (int m = 0; m < M; ++m) {
+            const int l = m % lanes.n;
+            hipStream_t ls = lanes.st[l];
             const float *lh = log_hyp + (size_t)m * H2;
-            hipLaunchKernelGGL(build_khat_log_kernel, dim3((Np + 255) / 256, Np), dim3(256), 0, st, X, lh, K, N, Np, D);
-            hipLaunchKernelGGL(posterior_rhs_kernel, dim3((Np + 1 + 255) / 256, Np), dim3(256), 0, st, y + (size_t)m * N,
-                               R, N, Np);
-            factor_and_solve(st, K, Np, R, Np + 1, m * Np, flag);
-            hipLaunchKernelGGL(hyper_lml_kernel, dim3(1), dim3(256), 0, st, K, R, y + (size_t)m * N, N, Np,
+            hipLaunchKernelGGL(build_khat_log_kernel, dim3((Np + 255) / 256, Np), dim3(256), 0, ls, X, lh, K[l], N, Np, D);
+            hipLaunchKernelGGL(posterior_rhs_kernel, dim3((Np + 1 + 255) / 256, Np), dim3(256), 0, ls, y + (size_t)m * N,
+                               R[l], N, Np);
+            factor_and_solve(ls, K[l], Np, R[l], Np + 1, m * Np, flag);
+            hipLaunchKernelGGL(hyper_lml_kernel, dim3(1), dim3(256), 0, ls, K[l], R[l], y + (size_t)m * N, N, Np,
                                lml + (size_t)it * M + m);
-            hipLaunchKernelGGL(hyper_grad_rows_kernel, dim3(N), dim3(256), 0, st, X, lh, R, partial, N, Np, D);
-            hipLaunchKernelGGL(hyper_grad_final_kernel, dim3(H2), dim3(256), 0, st, partial, N, D,
+            hipLaunchKernelGGL(hyper_grad_rows_kernel, dim3(N), dim3(256), 0, ls, X, lh, R[l], partial[l], N, Np, D);
+            hipLaunchKernelGGL(hyper_grad_final_kernel, dim3(H2), dim3(256), 0, ls, partial[l], N, D,
                                grad ? grad + (size_t)m * H2 : nullptr, gneg + (size_t)m * H2);
             P_HIP(hipGetLastError());
         }
+        P_HIP(lanes.join(st));
         if (n_iters > 0) {
             const int step = first_step + it;
             P_HIP(bagel_launch_adam(c, log_hyp, gneg, adam_m, adam_v, M * H2, lr, beta1, beta2, eps,
@@ -784,10 +872,9 @@ int bagel_hyper_impl(bagel_ctx *c, const float *X, const float *y, float *log_hy
         rc = BAGEL_ENOTPD;
     }
 done:
+    lanes.close();
     (void)hipStreamSynchronize(st);
-    if (K) (void)hipFree(K);
-    if (R) (void)hipFree(R);
-    if (partial) (void)hipFree(partial);
+    lane_free(K); lane_free(R); lane_free(partial);
     if (gneg) (void)hipFree(gneg);
     if (flag) (void)hipFree(flag);
     return rc;
