@@ -103,8 +103,11 @@ int64_t bagel_workspace_bytes(const bagel_ctx *ctx);
  *   omega[M][L][D] (already divided by the length scales)  phase[M][L]
  *   w[S][M][L]  eps[S][M][N]      (M = d_s)
  *   v_out[S][M][N] or NULL: receives the float32 representer weights.
- * Synchronises the stream (it must learn whether the factorisation succeeded).
- * Errors: EINVAL, ENOTPD (context is left unprepared), EHIP.
+ * Synchronises the stream (it must learn whether the factorisation succeeded).  Set-up work: it
+ * allocates float64 scratch of its own and frees it before returning, 8 (Np^2 + Np L + Np S + S L) bytes
+ * for each of up to three outputs that it works on side by side on internal streams (ordered after
+ * what is already enqueued on the context's stream; all finished on return).
+ * Errors: EINVAL, ENOMEM, ENOTPD (context is left unprepared), EHIP.
  */
 int bagel_prepare_samples(bagel_ctx *ctx, const float *X, const float *y, const float *lengthscale,
                           const float *signal_var, const float *noise_var, const float *omega,
