@@ -70,9 +70,13 @@ typedef struct {
     float act_bound;         /* <= 0: linear output */
     int32_t tracked[8];      /* state index of goal component j, j < d_g */
     float q[8];              /* cost weight of goal component j */
-    int32_t ckpt_interval;   /* 0: keep the whole tape in the gradient call; K > 0: keep the state every K
-                                steps and re-run each K-step segment in the backward sweep (Sec. IV-C:
-                                trading compute for memory).  Results are identical. */
+    int32_t ckpt_interval;   /* 0: keep the whole tape in the gradient call; K > 0: gradient checkpointing
+                                (Sec. IV-C: trading compute for memory): the activations and adjoints of
+                                the policy, which are nearly all of the tape, are held for K steps at a
+                                time and recomputed segment by segment in the backward sweep from the kept
+                                states; the states and the Jacobians of the sample evaluation
+                                (d_s + d_s (d_s + d_a) floats per trajectory and step) are kept for the
+                                whole horizon.  Results are identical. */
     int32_t cost_kind;       /* 0 quadratic tracking cost, 1 negative saturating reward of eq. (8) */
     float sigma_r;           /* width of eq. (8); used only if cost_kind == 1 */
 } bagel_dims;

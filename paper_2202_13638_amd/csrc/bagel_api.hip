@@ -78,7 +78,7 @@ static void free_all(bagel_ctx *c)
 {
     void *ptrs[] = {c->Xs, c->Os, c->A, c->amp, c->exp_tab, c->v4, c->w4, c->xbuf, c->part, c->lpt, c->lam,
                     c->tape_s, c->tape_J, c->tape_h[0], c->tape_h[1], c->tape_h[2], c->tape_a, c->tape_d[0],
-                    c->tape_d[1], c->tape_d[2], c->ckpt_s, c->wpad_f, c->wpad_b, c->gsplit, c->gacc, c->fbuf, c->gtheta, c->post_alpha, c->post_Kinv, c->post_Kx, c->post_sums};
+                    c->tape_d[1], c->tape_d[2], c->wpad_f, c->wpad_b, c->gsplit, c->gacc, c->fbuf, c->gtheta, c->post_alpha, c->post_Kinv, c->post_Kx, c->post_sums};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
 }
@@ -155,7 +155,6 @@ extern "C" int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_s
     const int K = dims->ckpt_interval;
     const int H = dims->H;
     c->T_tape = (K > 0 && K < H) ? K : H;
-    const int n_seg = (K > 0 && K < H) ? (H + K - 1) / K : 1;
     c->ksplit = env_int("BAGEL_KSPLIT", 256);
     int wf_total = 0, wb_total = 0;
     for (int l = 0; l < c->n_layers; ++l) {
@@ -183,13 +182,12 @@ extern "C" int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_s
     ALLOC(c->lam, (size_t)dims->d_s * Bz);
     ALLOC(c->fbuf, (size_t)M * Bz);
     ALLOC(c->tape_s, (size_t)(H + 1) * dims->d_s * Bz);
-    ALLOC(c->tape_J, T * M * D * Bz);
+    ALLOC(c->tape_J, (size_t)H * M * D * Bz);
     for (int l = 0; l < c->n_layers; ++l) {
         ALLOC(c->tape_h[l], T * c->width[l] * Bz);
         ALLOC(c->tape_d[l], T * c->width[l + 1] * Bz);
     }
     ALLOC(c->tape_a, T * dims->d_a * Bz);
-    ALLOC(c->ckpt_s, (size_t)n_seg * dims->d_s * Bz);
     ALLOC(c->wpad_f, (size_t)wf_total);
     ALLOC(c->wpad_b, (size_t)wb_total);
     ALLOC(c->gsplit, (size_t)c->ksplit * c->P);
@@ -332,20 +330,20 @@ extern "C" int bagel_profile_read(bagel_ctx *c, double *kernel_ms, int *launches
     return BAGEL_OK;
 }
 
-// forward steps t0 .. t1-1 starting from the state in xbuf and the policy input in slot (t0 - slot_base)
-static int run_forward(bagel_ctx *c, int t0, int t1, int slot_base, bool jac, bool add_cost, bool write_tape_s,
-                       bool write_ckpt, const float *theta, const float *goals, float *states_out)
+// Forward steps 0 .. H-1 from the state in xbuf and the policy input in tape slot 0.  jac: the sample
+// evaluation also returns its Jacobian, kept in slot t of the Jacobian tape; acts: the policy's
+// activations are kept in slot t of their tape (otherwise every step reuses slot 0).
+static int run_forward(bagel_ctx *c, bool jac, bool acts, bool write_tape_s, const float *theta, const float *goals,
+                       float *states_out)
 {
-    const int K = c->T_tape;
-    for (int t = t0; t < t1; ++t) {
-        const int slot = jac ? t - slot_base : 0;
-        const int next_slot = t + 1 < t1 ? (jac ? slot + 1 : 0) : -1;
+    const int H = c->dm.H;
+    for (int t = 0; t < H; ++t) {
+        const int next_slot = t + 1 < H ? (acts ? t + 1 : 0) : -1;
         // the policy of the first step runs on its own; every later one is part of the previous step's tail
-        if (t == t0) BAGEL_HIP(c, bagel_launch_policy_forward(c, slot, theta));
+        if (t == 0) BAGEL_HIP(c, bagel_launch_policy_forward(c, 0, theta));
         BAGEL_HIP(c, gp_step_timed(c, jac, c->cur_xi ? c->cur_xi + (size_t)t * c->dm.B * c->M : nullptr));
-        const int ck = (write_ckpt && (t + 1) % K == 0 && t + 1 < c->dm.H) ? (t + 1) / K : -1;
-        BAGEL_HIP(c, bagel_launch_step_tail(c, t, slot, next_slot, jac, add_cost, write_tape_s, ck, theta, goals,
-                                            states_out, c->cur_xi != nullptr));
+        BAGEL_HIP(c, bagel_launch_step_tail(c, t, t, next_slot, jac, true, write_tape_s, theta, goals, states_out,
+                                            c->cur_xi != nullptr));
     }
     return BAGEL_OK;
 }
@@ -361,8 +359,8 @@ static int rollout_loss_impl(bagel_ctx *c, const char *who, const float *theta, 
         BAGEL_FAIL(c, BAGEL_ENOTPREPARED, "%s: %s", who, posterior ? "no posterior cache installed" : "no samples installed");
     c->cur_xi = posterior ? xi : nullptr;
     BAGEL_HIP(c, bagel_launch_pack_theta(c, theta));
-    BAGEL_HIP(c, bagel_launch_init_state(c, s0, goals, states, false, false));
-    const int rc = run_forward(c, 0, c->dm.H, 0, false, true, false, false, theta, goals, states);
+    BAGEL_HIP(c, bagel_launch_init_state(c, s0, goals, states, false));
+    const int rc = run_forward(c, false, false, false, theta, goals, states);
     if (rc != BAGEL_OK) return rc;
     BAGEL_HIP(c, bagel_launch_finish_loss(c, loss, loss_per_traj));
     return BAGEL_OK;
@@ -395,26 +393,25 @@ static int rollout_loss_grad_impl(bagel_ctx *c, const char *who, const float *th
     const bool ckpt = K < H;
     int rc;
     BAGEL_HIP(c, bagel_launch_pack_theta(c, theta));
-    BAGEL_HIP(c, bagel_launch_init_state(c, s0, goals, states, true, ckpt));
+    BAGEL_HIP(c, bagel_launch_init_state(c, s0, goals, states, true));
+    // One forward pass with Jacobians.  Without checkpointing it also keeps the policy's activations.
+    rc = run_forward(c, true, !ckpt, true, theta, goals, states);
+    if (rc != BAGEL_OK) return rc;
+    BAGEL_HIP(c, bagel_launch_finish_loss(c, loss, loss_per_traj));
     if (!ckpt) {
-        rc = run_forward(c, 0, H, 0, true, true, true, false, theta, goals, states);
-        if (rc != BAGEL_OK) return rc;
-        BAGEL_HIP(c, bagel_launch_finish_loss(c, loss, loss_per_traj));
         BAGEL_HIP(c, bagel_launch_backward_sweep(c, 0, H, goals, grad_s0));
         BAGEL_HIP(c, bagel_launch_weight_grad(c, H, false, grad_theta));
         return BAGEL_OK;
     }
-    // checkpointed: a plain forward pass that keeps the state every K steps, then one segment at a
-    // time from the end: re-run it with Jacobians and tapes, sweep it backwards, add its weight gradient.
-    rc = run_forward(c, 0, H, 0, false, true, true, true, theta, goals, states);
-    if (rc != BAGEL_OK) return rc;
-    BAGEL_HIP(c, bagel_launch_finish_loss(c, loss, loss_per_traj));
+    // Checkpointed (Sec. IV-C): what is large, the activations and adjoints of the policy (about 4 KB
+    // per trajectory and step with 256-wide layers), is held for one segment of K steps at a time and
+    // rebuilt from the kept float32 states, all steps of the segment in one launch; what is small and
+    // expensive to recompute, the state (d_s floats) and the Jacobian of the sample evaluation (M D
+    // floats), is kept for the whole horizon.  Segments are swept from the last to the first.
     const int n_seg = (H + K - 1) / K;
     for (int seg = n_seg - 1; seg >= 0; --seg) {
         const int t0 = seg * K, t1 = (t0 + K < H) ? t0 + K : H;
-        BAGEL_HIP(c, bagel_launch_restore(c, seg, t0, goals));
-        rc = run_forward(c, t0, t1, t0, true, false, false, false, theta, goals, nullptr);
-        if (rc != BAGEL_OK) return rc;
+        BAGEL_HIP(c, bagel_launch_policy_replay(c, t0, t1, theta, goals));
         BAGEL_HIP(c, bagel_launch_backward_sweep(c, t0, t1, goals, grad_s0));
         BAGEL_HIP(c, bagel_launch_weight_grad(c, t1 - t0, seg != n_seg - 1, seg == 0 ? grad_theta : nullptr));
     }

@@ -43,14 +43,14 @@ struct bagel_ctx {
     double *lam;                 // [d_s][B] adjoint of the state between the segments of a checkpointed sweep
     double *fbuf;                // [M][B] sample values of the current step, summed over work units
 
-    // ---- tape (T_tape slots: H, or ckpt_interval when checkpointing) ----------------------
+    // ---- tape: activations and adjoints have T_tape slots (H, or ckpt_interval when checkpointing:
+    // they are rebuilt segment by segment); states and Jacobians are kept for the whole horizon
     int T_tape;
     float *tape_s;               // [H+1][d_s][B]
-    float *tape_J;               // [T][M][D][B]
+    float *tape_J;               // [H][M][D][B]
     float *tape_h[3];            // activations feeding layer l: [T][width[l]][B]
     float *tape_a;               // [T][d_a][B] policy output (after tanh, before scaling, if bounded)
     float *tape_d[3];            // adjoint of the pre-activation of layer l: [T][width[l+1]][B]
-    double *ckpt_s;              // [n_seg][d_s][B] state at the start of each segment
 
     // ---- parameters and gradient -----------------------------------------------------------
     float *wpad_f, *wpad_b;      // zero-padded weights: forward [out pad 32][in pad 32], backward [in pad 32][out pad 32]
@@ -101,8 +101,7 @@ hipError_t bagel_launch_pack_samples(bagel_ctx *ctx, const float *w, const float
 
 // ---- lane.hip ----------------------------------------------------------------------------
 hipError_t bagel_launch_init_state(bagel_ctx *ctx, const float *s0, const float *goals, float *states_out,
-                                   bool tape, bool ckpt);
-hipError_t bagel_launch_restore(bagel_ctx *ctx, int seg, int t, const float *goals);
+                                   bool tape);
 hipError_t bagel_launch_finish_loss(bagel_ctx *ctx, float *loss, float *loss_per_traj);
 hipError_t bagel_launch_eval_io(bagel_ctx *ctx, int phase, const float *x, float *f);
 // add up the per-unit partial sums: value into fbuf, Jacobian into tape slot `slot` (or jac_out if slot < 0)
@@ -115,8 +114,10 @@ hipError_t bagel_launch_policy_forward(bagel_ctx *ctx, int slot, const float *th
 // advance the state, cost against goals[t], tapes, and the policy of step t+1 into tape slot next_slot
 // (no policy if t is the last step or next_slot < 0); direct: ctx->part holds final values [m][1+D][B]
 hipError_t bagel_launch_step_tail(bagel_ctx *ctx, int t, int slot, int next_slot, bool jac, bool add_cost,
-                                  bool write_tape_s, int ckpt_index, const float *theta, const float *goals,
+                                  bool write_tape_s, const float *theta, const float *goals,
                                   float *states_out, bool direct);
+// activation tape of steps t0 .. t1-1 (slots 0 .. t1-t0-1) rebuilt from the kept states
+hipError_t bagel_launch_policy_replay(bagel_ctx *ctx, int t0, int t1, const float *theta, const float *goals);
 // backward sweep over steps t_hi-1 .. t_lo (tape slot of step k is k - t_lo); grad_s0 is written when t_lo == 0
 hipError_t bagel_launch_backward_sweep(bagel_ctx *ctx, int t_lo, int t_hi, const float *goals, float *grad_s0);
 hipError_t bagel_launch_weight_grad(bagel_ctx *ctx, int n_slots, bool accumulate, float *grad_theta);

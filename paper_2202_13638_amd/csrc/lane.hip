@@ -1,4 +1,4 @@
-// Lane-per-trajectory kernels at the edges of a rollout: initial state and checkpoint restore,
+// Lane-per-trajectory kernels at the edges of a rollout: initial state,
 // the final loss reduction (Algorithm 1: loss = mean over trajectories of the summed cost), and the
 // plumbing of bagel_sample_eval (reduction of the partial sums of one sample evaluation on its own;
 // inside a rollout that reduction is part of the end-of-step kernel).
@@ -21,7 +21,6 @@ struct lane_args {
     const double *A, *amp, *part;
     double *xbuf, *lpt;
     float *tape_s;
-    double *ckpt_s;
 };
 
 // Add up the partial sums of one sample evaluation in unit order and finish value and Jacobian.
@@ -69,27 +68,11 @@ __global__ __launch_bounds__(BAGEL_BLOCK) void init_state_kernel(lane_args a, co
         const float v = s0[(size_t)b * a.ds + i];
         a.xbuf[(size_t)i * a.B + b] = (double)v;
         if (a.tape_s) a.tape_s[(size_t)i * a.B + b] = v;
-        if (a.ckpt_s) a.ckpt_s[(size_t)i * a.B + b] = (double)v;
         if (states_out) states_out[(size_t)b * a.ds + i] = v;
         h0_slot[(size_t)i * a.B + b] = v;
     }
     for (int j = 0; j < a.dg; ++j) h0_slot[(size_t)(a.ds + j) * a.B + b] = goals0[(size_t)b * a.dg + j];
     a.lpt[b] = 0.0;
-}
-
-// restore the state of a checkpoint and write the policy input of step t
-__global__ __launch_bounds__(BAGEL_BLOCK) void restore_kernel(lane_args a, const double *__restrict__ ck,
-                                                              const float *__restrict__ goals_t,
-                                                              float *__restrict__ h0_slot)
-{
-    const int b = blockIdx.x * BAGEL_BLOCK + threadIdx.x;
-    if (b >= a.B) return;
-    for (int i = 0; i < a.ds; ++i) {
-        const double v = ck[(size_t)i * a.B + b];
-        a.xbuf[(size_t)i * a.B + b] = v;
-        h0_slot[(size_t)i * a.B + b] = (float)v;
-    }
-    for (int j = 0; j < a.dg; ++j) h0_slot[(size_t)(a.ds + j) * a.B + b] = goals_t[(size_t)b * a.dg + j];
 }
 
 // loss = (1/B) sum_b lpt[b], summed in a fixed tree order by one workgroup
@@ -136,7 +119,7 @@ lane_args make_args(const bagel_ctx *c)
     for (int j = 0; j < 8; ++j) { a.tracked[j] = c->dm.tracked[j]; a.q[j] = c->dm.q[j]; }
     a.A = c->A; a.amp = c->amp; a.part = c->part;
     a.xbuf = c->xbuf; a.lpt = c->lpt;
-    a.tape_s = nullptr; a.ckpt_s = nullptr;
+    a.tape_s = nullptr;
     return a;
 }
 
@@ -147,22 +130,11 @@ inline dim3 lane_grid(const bagel_ctx *c) { return dim3((c->dm.B + BAGEL_BLOCK -
 static inline float *slot_ptr(float *base, int slot, int width, int B) { return base + (size_t)slot * width * B; }
 
 hipError_t bagel_launch_init_state(bagel_ctx *c, const float *s0, const float *goals, float *states_out,
-                                   bool tape, bool ckpt)
+                                   bool tape)
 {
     lane_args a = make_args(c);
     a.tape_s = tape ? c->tape_s : nullptr;
-    a.ckpt_s = ckpt ? c->ckpt_s : nullptr;
     hipLaunchKernelGGL(init_state_kernel, lane_grid(c), dim3(BAGEL_BLOCK), 0, c->stream, a, s0, goals, states_out,
-                       slot_ptr(c->tape_h[0], 0, c->d_in, c->dm.B));
-    return hipGetLastError();
-}
-
-hipError_t bagel_launch_restore(bagel_ctx *c, int seg, int t, const float *goals)
-{
-    lane_args a = make_args(c);
-    const size_t B = c->dm.B;
-    hipLaunchKernelGGL(restore_kernel, lane_grid(c), dim3(BAGEL_BLOCK), 0, c->stream, a,
-                       c->ckpt_s + (size_t)seg * c->dm.d_s * B, goals + (size_t)t * B * c->dm.d_g,
                        slot_ptr(c->tape_h[0], 0, c->d_in, c->dm.B));
     return hipGetLastError();
 }

@@ -335,7 +335,7 @@ __device__ __forceinline__ void policy_layers(const policy_args &a, const float4
                             act_out = a.act_bound * act_v;
                         }
                         a.a_slot[(size_t)j * a.B + b] = act_v;
-                        a.xbuf[(size_t)(a.ds + j) * a.B + b] = (double)act_out;
+                        if (a.xbuf) a.xbuf[(size_t)(a.ds + j) * a.B + b] = (double)act_out;
                     }
                 }
                 if (l < a.nl - 1) act4[(jb >> 2) * PL + c] = make_float4(out[0], out[1], out[2], out[3]);
@@ -362,6 +362,53 @@ __global__ __launch_bounds__(PW * 64) void policy_forward_kernel(policy_args a)
     policy_layers(a, w_first, w_last, w_wide, p_first, p_last, p_wide, wave, lane, b0, act4, red4, biasS);
 }
 
+// Policy of the steps t0 .. t0 + gridDim.y - 1 at once, from the kept states: rebuilds the activation
+// tape of a segment (gradient checkpointing, Sec. IV-C).  blockIdx.y = tape slot = t - t0; the input
+// [s_t ; g_t] is the float32 state of the tape, the same numbers the forward pass fed to the policy,
+// so the activations come out bit for bit as they were.  Nothing is written to xbuf.
+struct replay_args {
+    const float *tape_s;      // [H+1][d_s][B]
+    const float *goals;       // [H][B][d_g]
+    int t0, dg;
+};
+
+__global__ __launch_bounds__(PW * 64) void policy_replay_kernel(policy_args a, replay_args r)
+{
+    __shared__ float4 act4[(BAGEL_MAX_HIDDEN / 4) * PL];
+    __shared__ float4 red4[PW * 4 * 64];
+    __shared__ float biasS[3][BAGEL_MAX_HIDDEN];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int b0 = blockIdx.x * PL;
+    const size_t slot = blockIdx.y, B = a.B;
+    const int t = r.t0 + (int)slot;
+    for (int l = 0; l < a.nl; ++l) a.h[l] += slot * a.width[l] * B;
+    a.a_slot += slot * a.width[a.nl] * B;
+    a.xbuf = nullptr;
+    FORWARD_WEIGHTS_DECL;
+    load_forward_weights(a, wave, lane, w_first, w_last, w_wide, p_first, p_last, p_wide, bias_r);
+    {   // layer-0 input from the state tape and the goals, to LDS and to its tape slot
+        const int bl = threadIdx.x & (PL - 1);
+        const bool live = b0 + bl < a.B;
+        const int b = live ? b0 + bl : a.B - 1;
+        for (int kg = threadIdx.x / PL; kg < (a.kp[0] >> 2); kg += PW * 64 / PL) {
+            float v[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int k = kg * 4 + e;
+                v[e] = 0.0f;
+                if (k < a.ds) v[e] = r.tape_s[((size_t)t * a.ds + k) * B + b];
+                else if (k < a.ds + r.dg) v[e] = r.goals[((size_t)t * B + b) * r.dg + (k - a.ds)];
+                if (live && k < a.ds + r.dg) a.h[0][(size_t)k * B + b] = v[e];
+            }
+            act4[kg * PL + bl] = make_float4(v[0], v[1], v[2], v[3]);
+        }
+    }
+    stash_biases(a, bias_r, biasS);
+    __syncthreads();
+    policy_layers(a, w_first, w_last, w_wide, p_first, p_last, p_wide, wave, lane, b0, act4, red4, biasS);
+}
+
 // ---- end of step t and policy of step t+1 in one launch -------------------------------------
 // After the sample evaluation of step t: add up its partial sums (value f and Jacobian J_f, as in
 // finalize_kernel), advance the state s_{t+1} = s_t + f (state increments as GP targets, Sec. III-A),
@@ -379,7 +426,6 @@ struct tail_args {
     double *lpt;                        // [B]
     float *tape_s_next;                 // [d_s][B] slot of s_{t+1}, or null
     float *states_out_next;             // [B][d_s] or null
-    double *ckpt_next;                  // [d_s][B] or null
     const float *goals_t, *goals_next;  // [B][d_g]; goals_next null at the last step
     float *jdst;                        // tape slot [M][D][B] of step t, or null
 };
@@ -459,7 +505,6 @@ __global__ __launch_bounds__(PW * 64) void step_tail_kernel(tail_args r, policy_
                 a.xbuf[(size_t)k * B + bq] = s;
                 if (r.tape_s_next) r.tape_s_next[(size_t)k * B + bq] = hin;
                 if (r.states_out_next) r.states_out_next[(size_t)bq * ds + k] = hin;
-                if (r.ckpt_next) r.ckpt_next[(size_t)k * B + bq] = s;
             }
         } else if (k < d_in && r.goals_next) {
             hin = r.goals_next[(size_t)bq * r.dg + (k - ds)];
@@ -1079,8 +1124,8 @@ hipError_t bagel_launch_policy_forward(bagel_ctx *c, int slot, const float *thet
 }
 
 hipError_t bagel_launch_step_tail(bagel_ctx *c, int t, int slot, int next_slot, bool jac, bool add_cost,
-                                  bool write_tape_s, int ckpt_index, const float *theta, const float *goals,
-                                  float *states_out, bool direct)
+                                  bool write_tape_s, const float *theta, const float *goals, float *states_out,
+                                  bool direct)
 {
     const size_t B = c->dm.B;
     const bool has_next = t + 1 < c->dm.H && next_slot >= 0;
@@ -1095,13 +1140,22 @@ hipError_t bagel_launch_step_tail(bagel_ctx *c, int t, int slot, int next_slot, 
     r.A = c->A; r.amp = c->amp; r.part = c->part; r.lpt = c->lpt;
     r.tape_s_next = write_tape_s ? c->tape_s + (size_t)(t + 1) * c->dm.d_s * B : nullptr;
     r.states_out_next = states_out ? states_out + (size_t)(t + 1) * B * c->dm.d_s : nullptr;
-    r.ckpt_next = ckpt_index >= 0 ? c->ckpt_s + (size_t)ckpt_index * c->dm.d_s * B : nullptr;
     r.goals_t = goals + (size_t)t * B * c->dm.d_g;
     r.goals_next = has_next ? goals + (size_t)(t + 1) * B * c->dm.d_g : nullptr;
     r.jdst = jac ? c->tape_J + (size_t)slot * c->M * c->D * B : nullptr;
     policy_args a = make_pargs(c, has_next ? next_slot : 0);
     a.theta = theta;
     hipLaunchKernelGGL(step_tail_kernel, dim3((c->dm.B + PL - 1) / PL), dim3(PW * 64), 0, c->stream, r, a);
+    return hipGetLastError();
+}
+
+hipError_t bagel_launch_policy_replay(bagel_ctx *c, int t0, int t1, const float *theta, const float *goals)
+{
+    policy_args a = make_pargs(c, 0);
+    a.theta = theta;
+    replay_args r;
+    r.tape_s = c->tape_s; r.goals = goals; r.t0 = t0; r.dg = c->dm.d_g;
+    hipLaunchKernelGGL(policy_replay_kernel, dim3((c->dm.B + PL - 1) / PL, t1 - t0), dim3(PW * 64), 0, c->stream, a, r);
     return hipGetLastError();
 }
 
@@ -1120,7 +1174,10 @@ hipError_t bagel_launch_backward_sweep(bagel_ctx *c, int t_lo, int t_hi, const f
     a.act_bound = c->dm.act_bound; a.cost_kind = c->dm.cost_kind; a.sigma_r = c->dm.sigma_r;
     for (int j = 0; j < 8; ++j) { a.tracked[j] = c->dm.tracked[j]; a.q[j] = c->dm.q[j]; }
     a.Wp = c->wpad_b;
-    a.tape_a = c->tape_a; a.tape_J = c->tape_J; a.tape_s = c->tape_s;
+    // the Jacobian tape spans the whole horizon when the activation tape is kept per segment
+    const bool per_segment = c->T_tape < c->dm.H;
+    a.tape_a = c->tape_a; a.tape_s = c->tape_s;
+    a.tape_J = c->tape_J + (per_segment ? (size_t)t_lo * c->M * c->D * c->dm.B : 0);
     a.goals = goals; a.lam = c->lam; a.grad_s0 = grad_s0;
     hipLaunchKernelGGL(backward_sweep_kernel, dim3((c->dm.B + PL - 1) / PL), dim3(PW * 64), 0, c->stream, a);
     return hipGetLastError();
