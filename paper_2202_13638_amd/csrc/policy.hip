@@ -362,15 +362,16 @@ __global__ __launch_bounds__(PW * 64) void policy_forward_kernel(policy_args a)
     policy_layers(a, w_first, w_last, w_wide, p_first, p_last, p_wide, wave, lane, b0, act4, red4, biasS);
 }
 
-// Policy of the steps t0 .. t0 + gridDim.y - 1 at once, from the kept states: rebuilds the activation
-// tape of a segment (gradient checkpointing, Sec. IV-C).  blockIdx.y = tape slot = t - t0; the input
+// Policy of the steps t0 .. t0 + n_slots - 1 at once, from the kept states: rebuilds the activation
+// tape of a segment (gradient checkpointing, Sec. IV-C).  Tape slot = t - t0; the input
 // [s_t ; g_t] is the float32 state of the tape, the same numbers the forward pass fed to the policy,
 // so the activations come out bit for bit as they were.  Nothing is written to xbuf.
 struct replay_args {
     const float *tape_s;      // [H+1][d_s][B]
     const float *goals;       // [H][B][d_g]
-    int t0, dg;
+    int t0, dg, n_slots;
 };
+constexpr int REPLAY_SLOTS = 5;   // steps per workgroup
 
 __global__ __launch_bounds__(PW * 64) void policy_replay_kernel(policy_args a, replay_args r)
 {
@@ -380,33 +381,42 @@ __global__ __launch_bounds__(PW * 64) void policy_replay_kernel(policy_args a, r
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int b0 = blockIdx.x * PL;
-    const size_t slot = blockIdx.y, B = a.B;
-    const int t = r.t0 + (int)slot;
-    for (int l = 0; l < a.nl; ++l) a.h[l] += slot * a.width[l] * B;
-    a.a_slot += slot * a.width[a.nl] * B;
-    a.xbuf = nullptr;
+    const size_t B = a.B;
     FORWARD_WEIGHTS_DECL;
     load_forward_weights(a, wave, lane, w_first, w_last, w_wide, p_first, p_last, p_wide, bias_r);
-    {   // layer-0 input from the state tape and the goals, to LDS and to its tape slot
-        const int bl = threadIdx.x & (PL - 1);
-        const bool live = b0 + bl < a.B;
-        const int b = live ? b0 + bl : a.B - 1;
-        for (int kg = threadIdx.x / PL; kg < (a.kp[0] >> 2); kg += PW * 64 / PL) {
-            float v[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int k = kg * 4 + e;
-                v[e] = 0.0f;
-                if (k < a.ds) v[e] = r.tape_s[((size_t)t * a.ds + k) * B + b];
-                else if (k < a.ds + r.dg) v[e] = r.goals[((size_t)t * B + b) * r.dg + (k - a.ds)];
-                if (live && k < a.ds + r.dg) a.h[0][(size_t)k * B + b] = v[e];
-            }
-            act4[kg * PL + bl] = make_float4(v[0], v[1], v[2], v[3]);
-        }
-    }
     stash_biases(a, bias_r, biasS);
-    __syncthreads();
-    policy_layers(a, w_first, w_last, w_wide, p_first, p_last, p_wide, wave, lane, b0, act4, red4, biasS);
+    a.xbuf = nullptr;
+    const policy_args base = a;
+    // A workgroup keeps the weights in its registers for REPLAY_SLOTS consecutive steps: fetching them
+    // is what a replay launch spends most of its time on when every step has workgroups of its own.
+    const int s_begin = blockIdx.y * REPLAY_SLOTS;
+    const int s_end = min(r.n_slots, s_begin + REPLAY_SLOTS);
+    for (int sl = s_begin; sl < s_end; ++sl) {
+        const size_t slot = (size_t)sl;
+        const int t = r.t0 + sl;
+        for (int l = 0; l < a.nl; ++l) a.h[l] = base.h[l] + slot * a.width[l] * B;
+        a.a_slot = base.a_slot + slot * a.width[a.nl] * B;
+        {   // layer-0 input from the state tape and the goals, to LDS and to its tape slot
+            const int bl = threadIdx.x & (PL - 1);
+            const bool live = b0 + bl < a.B;
+            const int b = live ? b0 + bl : a.B - 1;
+            for (int kg = threadIdx.x / PL; kg < (a.kp[0] >> 2); kg += PW * 64 / PL) {
+                float v[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int k = kg * 4 + e;
+                    v[e] = 0.0f;
+                    if (k < a.ds) v[e] = r.tape_s[((size_t)t * a.ds + k) * B + b];
+                    else if (k < a.ds + r.dg) v[e] = r.goals[((size_t)t * B + b) * r.dg + (k - a.ds)];
+                    if (live && k < a.ds + r.dg) a.h[0][(size_t)k * B + b] = v[e];
+                }
+                act4[kg * PL + bl] = make_float4(v[0], v[1], v[2], v[3]);
+            }
+        }
+        __syncthreads();
+        // ends with a barrier: act4 may be rewritten for the next slot
+        policy_layers(a, w_first, w_last, w_wide, p_first, p_last, p_wide, wave, lane, b0, act4, red4, biasS);
+    }
 }
 
 // ---- end of step t and policy of step t+1 in one launch -------------------------------------
@@ -1154,8 +1164,9 @@ hipError_t bagel_launch_policy_replay(bagel_ctx *c, int t0, int t1, const float 
     policy_args a = make_pargs(c, 0);
     a.theta = theta;
     replay_args r;
-    r.tape_s = c->tape_s; r.goals = goals; r.t0 = t0; r.dg = c->dm.d_g;
-    hipLaunchKernelGGL(policy_replay_kernel, dim3((c->dm.B + PL - 1) / PL, t1 - t0), dim3(PW * 64), 0, c->stream, a, r);
+    r.tape_s = c->tape_s; r.goals = goals; r.t0 = t0; r.dg = c->dm.d_g; r.n_slots = t1 - t0;
+    hipLaunchKernelGGL(policy_replay_kernel, dim3((c->dm.B + PL - 1) / PL, (t1 - t0 + REPLAY_SLOTS - 1) / REPLAY_SLOTS),
+                       dim3(PW * 64), 0, c->stream, a, r);
     return hipGetLastError();
 }
 
