@@ -499,3 +499,28 @@ def test_marginal_likelihood_and_fit_against_oracle():
     assert d_hist.max() <= 1e-5 and d_lh.max() <= 1e-4
     assert np.all(hist_o[-1] > hist_o[0]) and bool((hist[-1] > hist[0]).all())
     ctx.close()
+
+
+def test_marginal_likelihood_deep_blocking():
+    """Marginal likelihood and gradient at a size where the factorisation and the substitutions recurse
+    (N = 700: ranges of 704 -> 384 + 320 -> 192 + 192 + 192 + 128 columns) and with more outputs than the
+    library works on side by side."""
+    import torch
+    from paper_2202_13638_amd import binding
+    cfg = synth.Config("hy2", 32, 4, 1, 1, 700, 16, 8, 2, (4,), 0.0, "sinusoid", "const", 0, 0.5, 1e-3)
+    inp = synth.make_inputs(cfg)
+    M, D = cfg.M, cfg.D
+    lh0 = np.concatenate([np.log(inp["lengthscale"]), np.log(inp["signal_var"])[:, None],
+                          np.log(inp["noise_var"])[:, None]], axis=1).astype(np.float32)
+    ctx = binding.Bagel(binding.dims_from_config(cfg))
+    g = harness.to_gpu(inp)
+    lml = torch.zeros(M, device="cuda")
+    grad = torch.zeros((M, D + 2), device="cuda")
+    ctx.bagel_hyper_lml_grad(g["X"], g["y"], torch.from_numpy(lh0).cuda(), lml, grad)
+    torch.cuda.synchronize()
+    for m in range(M):
+        ref, ref_g = oracle.hyper_lml_grad(inp["X"], inp["y"][m], lh0[m])
+        assert abs(float(lml[m]) - ref) <= 2e-7 * abs(ref)
+        np.testing.assert_allclose(grad[m].cpu().numpy(), ref_g, rtol=5e-6, atol=5e-6 * np.abs(ref_g).max())
+    ctx.close()
+
