@@ -85,6 +85,10 @@ CONFIGS: Dict[str, Config] = {
         Config("medium", 2, 4, 1, 1, 2048, 2048, 1024, 200, (64, 64), 0.0, "sinusoid", "steps", 0, 1.0),
         Config("large_policy", 3, 4, 1, 1, 4096, 2048, 4096, 500, (256, 256), 0.0, "sinusoid", "steps", 50, 1.0),
         Config("stress", 4, 6, 2, 2, 8192, 4096, 8192, 1000, (256, 256), 1.0, "sinusoid", "steps", 0, 0.01),
+        # not one of the five benchmark configurations: the shape of the paper's own Exp. 1 (Sec. IV-A:
+        # two states, one bounded action, 2200 training points, 100 trajectories of 300 steps, policy
+        # with two hidden layers of 8), on the synthetic recipe, for a timing to set beside the paper's
+        Config("paper_exp1", 5, 2, 1, 2, 2200, 1024, 100, 300, (8, 8), 1.0, "sinusoid", "const", 0, 1.0),
     ]
 }
 

@@ -30,7 +30,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_num_params_matches_configs(lib):
-    expected = {"tiny": 81, "small": 4609, "medium": 4609, "large_policy": 67585, "stress": 68610}
+    expected = {"tiny": 81, "small": 4609, "medium": 4609, "large_policy": 67585, "stress": 68610, "paper_exp1": 121}
     for name, cfg in synth.CONFIGS.items():
         assert binding.bagel_num_params(binding.dims_from_config(cfg)) == expected[name] == cfg.P
 

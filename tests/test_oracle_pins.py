@@ -336,7 +336,7 @@ def test_tiny_config_gradient_all_81_entries():
 
 
 def test_config_table():
-    P = {"tiny": 81, "small": 4609, "medium": 4609, "large_policy": 67585, "stress": 68610}
+    P = {"tiny": 81, "small": 4609, "medium": 4609, "large_policy": 67585, "stress": 68610, "paper_exp1": 121}
     for name, cfg in synth.CONFIGS.items():
         assert cfg.P == P[name]
         assert cfg.M == cfg.d_s and cfg.d_in == cfg.d_s + cfg.d_g
