@@ -233,6 +233,29 @@ int bagel_hyper_fit(bagel_ctx *ctx, const float *X, const float *y, float *log_h
 int bagel_sample_eval(bagel_ctx *ctx, const float *x, float *f, float *jac);
 
 /*
+ * bagel_sample_eval for callers that cannot allocate device memory or hold a context: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  One call does what
+ * bagel_set_samples + bagel_sample_eval do (model re-layout, then f and optionally jac for every
+ * trajectory, arrays as documented there: X[N][D] lengthscale[M][D] signal_var[M] omega[M][L][D]
+ * phase[M][L] w[S][M][L] v[S][M][N] x[B][D] -> f[B][M], jac[B][M][D] or NULL; of dims only d_s, d_a,
+ * N, L, S, B matter, the rest must merely be valid) with the same kernels, on `hip_stream`, but keeps
+ * every intermediate buffer in one static device array of BAGEL_STATIC_SCRATCH_BYTES that the library
+ * holds on each GPU it runs on until the process ends.  It calls no hipMalloc, hipFree or other
+ * allocating routine, creates no context and does not synchronise.  The first call on a device looks
+ * up the array's address (hipGetSymbolAddress); make that call outside a capture.
+ * Size limit: 8 M (Np + Lp) (D+1) + 4 M (Np + Lp) S + 8 B (D + M + groups (1+D)) bytes plus alignment
+ * must fit the array (Np, Lp: N, L rounded up to the work-unit size, groups <= M (N + L) / 128 + 2 M);
+ * e.g. N = 512, L = 1024, S = B = 256, D = 5 needs 7 MB.  Larger sizes are rejected with EINVAL.
+ * All calls on one GPU share that GPU's array: two calls that overlap in time on one GPU (different
+ * streams or threads) race; calls on one stream are safe, and a call never reads what an earlier call
+ * left in the array.  Errors: EINVAL, EHIP; message through bagel_last_error(NULL).
+ */
+#define BAGEL_STATIC_SCRATCH_BYTES (32u << 20)
+int bagel_sample_eval_static(const bagel_dims *dims, void *hip_stream, const float *X, const float *lengthscale,
+                             const float *signal_var, const float *omega, const float *phase, const float *w,
+                             const float *v, const float *x, float *f, float *jac);
+
+/*
  * Measurement hooks (used by bench.py; not part of the method).  With every > 0, every
  * `every`-th launch of the sample-evaluation kernel inside the rollout calls (for the posterior
  * sampler: the launches of one step, all outputs) is bracketed by

@@ -22,7 +22,7 @@ EXPORTS = ["bagel_num_params", "bagel_create", "bagel_destroy", "bagel_workspace
            "bagel_prepare_samples", "bagel_set_samples", "bagel_rollout_loss",
            "bagel_rollout_loss_grad", "bagel_sample_eval", "bagel_last_error", "bagel_adam_step", "bagel_optimize",
            "bagel_hyper_lml_grad", "bagel_hyper_fit", "bagel_prepare_posterior", "bagel_posterior_rollout_loss", "bagel_posterior_rollout_loss_grad",
-           "bagel_profile_enable", "bagel_profile_read"]
+           "bagel_profile_enable", "bagel_profile_read", "bagel_sample_eval_static"]
 
 
 class BagelError(RuntimeError):
@@ -117,6 +117,8 @@ def load():
         L.bagel_adam_step.argtypes = [vp] + [fp] * 4 + [C.c_int] + [C.c_float] * 4
         L.bagel_optimize.restype = C.c_int
         L.bagel_optimize.argtypes = [vp] + [fp] * 5 + [C.c_int] * 3 + [C.c_float] * 4 + [fp]
+        L.bagel_sample_eval_static.restype = C.c_int
+        L.bagel_sample_eval_static.argtypes = [C.POINTER(Dims), vp] + [fp] * 10
         L.bagel_last_error.restype = C.c_char_p
         L.bagel_last_error.argtypes = [vp]
         _lib = L
@@ -138,6 +140,23 @@ def _ptr(t, shape, name, optional=False):
     if tuple(t.shape) != tuple(shape):
         raise ValueError(f"{name} has shape {tuple(t.shape)}, expected {tuple(shape)}")
     return C.c_void_p(t.data_ptr())
+
+
+def bagel_sample_eval_static(dims: Dims, X, lengthscale, signal_var, omega, phase, w, v, x, f, jac=None, stream=None):
+    """The context-free, allocation-free sample evaluation (see include/bagel.h)."""
+    import torch
+    lib = load()
+    M, D = dims.d_s, dims.d_s + dims.d_a
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    rc = lib.bagel_sample_eval_static(
+        C.byref(dims), C.c_void_p(stream.cuda_stream), _ptr(X, (dims.N, D), "X"),
+        _ptr(lengthscale, (M, D), "lengthscale"), _ptr(signal_var, (M,), "signal_var"),
+        _ptr(omega, (M, dims.L, D), "omega"), _ptr(phase, (M, dims.L), "phase"), _ptr(w, (dims.S, M, dims.L), "w"),
+        _ptr(v, (dims.S, M, dims.N), "v"), _ptr(x, (dims.B, D), "x"), _ptr(f, (dims.B, M), "f"),
+        _ptr(jac, (dims.B, M, D), "jac", optional=True))
+    if rc != OK:
+        raise BagelError(rc, lib.bagel_last_error(None).decode())
 
 
 class Bagel:

@@ -10,6 +10,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 
 #include "bagel_internal.h"
@@ -91,24 +92,13 @@ static int env_int(const char *name, int dflt)
     return v > 0 ? v : dflt;
 }
 
-extern "C" int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_stream)
+// Work decomposition of one sample evaluation (sets CK, CL, nck, ncl, Np, Lp, units, groups and the
+// exp2 form from dm, D, M); returns a message if the problem cannot be decomposed.
+static const char *plan_sample_eval(bagel_ctx *c)
 {
-    if (!out || !dims) CREATE_FAIL(BAGEL_EINVAL, "bagel_create: null argument");
-    *out = nullptr;
-    if (const char *msg = check_dims(dims)) CREATE_FAIL(BAGEL_EINVAL, "bagel_create: %s", msg);
-    bagel_ctx *c = new (std::nothrow) bagel_ctx();
-    if (!c) CREATE_FAIL(BAGEL_ENOMEM, "bagel_create: host allocation failed");
-    memset(c, 0, sizeof(*c));
-    c->dm = *dims;
-    c->D = dims->d_s + dims->d_a;
-    c->M = dims->d_s;
-    c->d_in = dims->d_s + dims->d_g;
-    c->n_layers = dims->n_hidden + 1;
-    layer_layout(dims, c->width, c->w_off, c->b_off, &c->P);
-    c->stream = (hipStream_t)hip_stream;
-
     // work decomposition of one sample evaluation: power-of-two chunk of training points / features
-    const int B = dims->B, N = dims->N, L = dims->L, M = c->M, D = c->D;
+    const bagel_dims *dims = &c->dm;
+    const int B = dims->B, N = dims->N, L = dims->L, M = c->M;
     const int64_t tb = (B + BAGEL_BLOCK - 1) / BAGEL_BLOCK;
     const int64_t items = (int64_t)(N + L) * M * tb;
     const int target = env_int("BAGEL_TARGET_WGS", 4096);
@@ -147,10 +137,31 @@ extern "C" int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_s
         const int tab = env_int("BAGEL_EXP_TABLE", 0);         // 1: off, 2: on, otherwise by launch size
         c->exp_table = tab == 2 ? true : (tab == 1 ? false : wgs >= 256 * 16);
     }
-    if (c->units > 65535) {
+    if (c->units > 65535) return "too many work units (M * (N + L) / 32 must stay below 65536)";
+    return nullptr;
+}
+
+extern "C" int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_stream)
+{
+    if (!out || !dims) CREATE_FAIL(BAGEL_EINVAL, "bagel_create: null argument");
+    *out = nullptr;
+    if (const char *msg = check_dims(dims)) CREATE_FAIL(BAGEL_EINVAL, "bagel_create: %s", msg);
+    bagel_ctx *c = new (std::nothrow) bagel_ctx();
+    if (!c) CREATE_FAIL(BAGEL_ENOMEM, "bagel_create: host allocation failed");
+    memset(c, 0, sizeof(*c));
+    c->dm = *dims;
+    c->D = dims->d_s + dims->d_a;
+    c->M = dims->d_s;
+    c->d_in = dims->d_s + dims->d_g;
+    c->n_layers = dims->n_hidden + 1;
+    layer_layout(dims, c->width, c->w_off, c->b_off, &c->P);
+    c->stream = (hipStream_t)hip_stream;
+
+    if (const char *msg = plan_sample_eval(c)) {     // msg is a string literal: it outlives c
         delete c;
-        CREATE_FAIL(BAGEL_EINVAL, "bagel_create: too many work units (%d)", M * (int)((N + 31) / 32 + (L + 31) / 32));
+        CREATE_FAIL(BAGEL_EINVAL, "bagel_create: %s", msg);
     }
+    const int B = dims->B, M = c->M, D = c->D;
 
     const int K = dims->ckpt_interval;
     const int H = dims->H;
@@ -274,6 +285,121 @@ extern "C" int bagel_sample_eval(bagel_ctx *c, const float *x, float *f, float *
     BAGEL_HIP(c, gp_step_timed(c, jac != nullptr));
     BAGEL_HIP(c, bagel_launch_finalize(c, jac != nullptr, -1, jac));
     BAGEL_HIP(c, bagel_launch_eval_io(c, 1, nullptr, f));
+    return BAGEL_OK;
+}
+
+// ---- sample evaluation without a context and without any allocation -------------------------------
+// Everything bagel_sample_eval keeps in context-owned device buffers (the model in its internal layout,
+// the re-laid-out sample streams, the inputs in float64, the partial sums of the work units, the
+// summed values) lives here in one file-scope device array.  Every GPU the library runs on holds its
+// own copy of the array at its own address until the process ends; host code may use the array only
+// through the address hipGetSymbolAddress returns for the current device.
+static __device__ __align__(256) unsigned char scratch[BAGEL_STATIC_SCRATCH_BYTES];
+
+#define BAGEL_MAX_DEVICES 64
+static std::mutex g_scratch_mutex;
+static unsigned char *g_scratch_ptr[BAGEL_MAX_DEVICES];   // per device, resolved on the first call there
+
+// device address of `scratch` on the current device (null and *err set on failure)
+static unsigned char *scratch_base(hipError_t *err)
+{
+    int dev = -1;
+    *err = hipGetDevice(&dev);
+    if (*err != hipSuccess) return nullptr;
+    if (dev < 0 || dev >= BAGEL_MAX_DEVICES) {
+        *err = hipErrorInvalidDevice;
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        *err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (*err != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = static_cast<unsigned char *>(p);
+    }
+    return g_scratch_ptr[dev];
+}
+
+// bytes of the static array a call with these dims uses, or BAGEL_EINVAL
+static int64_t static_scratch_bytes(const bagel_dims *dims)
+{
+    if (!dims || check_dims(dims)) return BAGEL_EINVAL;
+    bagel_ctx c;
+    memset(&c, 0, sizeof(c));
+    c.dm = *dims;
+    c.D = dims->d_s + dims->d_a;
+    c.M = dims->d_s;
+    if (plan_sample_eval(&c)) return BAGEL_EINVAL;
+    const int64_t M = c.M, D = c.D, B = dims->B, S = dims->S;
+    const int64_t counts[] = {8 * M * c.Np * (D + 1), 8 * M * c.Lp * (D + 1), 8 * M * D, 8 * M,
+                              16 * M * (c.Np / 4) * S, 16 * M * (c.Lp / 4) * S, 8 * D * B,
+                              8 * (int64_t)c.groups * (1 + D) * B, 8 * M * B};
+    int64_t total = 0;
+    for (int64_t n : counts) total += (n + 255) / 256 * 256;
+    return total;
+}
+
+extern "C" int bagel_sample_eval_static(const bagel_dims *dims, void *hip_stream, const float *X,
+                                        const float *lengthscale, const float *signal_var, const float *omega,
+                                        const float *phase, const float *w, const float *v, const float *x, float *f,
+                                        float *jac)
+{
+    if (!dims) CREATE_FAIL(BAGEL_EINVAL, "bagel_sample_eval_static: null argument");
+    if (const char *msg = check_dims(dims)) CREATE_FAIL(BAGEL_EINVAL, "bagel_sample_eval_static: %s", msg);
+    if (!X || !lengthscale || !signal_var || !omega || !phase || !w || !v || !x || !f)
+        CREATE_FAIL(BAGEL_EINVAL, "bagel_sample_eval_static: null argument");
+    const int64_t need = static_scratch_bytes(dims);
+    if (need < 0) CREATE_FAIL(BAGEL_EINVAL, "bagel_sample_eval_static: too many work units for these sizes");
+    if (need > (int64_t)BAGEL_STATIC_SCRATCH_BYTES)
+        CREATE_FAIL(BAGEL_EINVAL, "bagel_sample_eval_static: these sizes need %lld bytes of scratch, the static buffer holds %lld",
+                    (long long)need, (long long)BAGEL_STATIC_SCRATCH_BYTES);
+    hipError_t e = hipSuccess;
+    unsigned char *base = scratch_base(&e);
+    if (!base) CREATE_FAIL(BAGEL_EHIP, "bagel_sample_eval_static: address of the static buffer: %s", hipGetErrorString(e));
+
+    // a context on the host stack whose device pointers are carved out of the static array
+    bagel_ctx c;
+    memset(&c, 0, sizeof(c));
+    c.dm = *dims;
+    c.D = dims->d_s + dims->d_a;
+    c.M = dims->d_s;
+    c.stream = (hipStream_t)hip_stream;
+    (void)plan_sample_eval(&c);             // cannot fail: static_scratch_bytes has planned the same dims
+    c.exp_table = false;                    // the table form of exp2 reads a table this call does not have
+    const size_t M = c.M, D = c.D, B = dims->B, S = dims->S;
+    size_t off = 0;
+    auto carve = [&](size_t bytes) {
+        unsigned char *p = base + off;
+        off += (bytes + 255) / 256 * 256;
+        return p;
+    };
+    c.Xs = reinterpret_cast<double *>(carve(8 * M * c.Np * (D + 1)));
+    c.Os = reinterpret_cast<double *>(carve(8 * M * c.Lp * (D + 1)));
+    c.A = reinterpret_cast<double *>(carve(8 * M * D));
+    c.amp = reinterpret_cast<double *>(carve(8 * M));
+    c.v4 = reinterpret_cast<float4 *>(carve(16 * M * (c.Np / 4) * S));
+    c.w4 = reinterpret_cast<float4 *>(carve(16 * M * (c.Lp / 4) * S));
+    c.xbuf = reinterpret_cast<double *>(carve(8 * D * B));
+    c.part = reinterpret_cast<double *>(carve(8 * (size_t)c.groups * (1 + D) * B));
+    c.fbuf = reinterpret_cast<double *>(carve(8 * M * B));
+    if ((int64_t)off != need) CREATE_FAIL(BAGEL_EINVAL, "bagel_sample_eval_static: internal size mismatch");
+
+    // every byte a kernel below reads was written by a kernel before it in this call (padding rows
+    // included), so nothing of an earlier call's contents is ever used and nothing needs clearing
+#define STATIC_HIP(call)                                                                                  \
+    do {                                                                                                  \
+        hipError_t e__ = (call);                                                                          \
+        if (e__ != hipSuccess)                                                                            \
+            CREATE_FAIL(BAGEL_EHIP, "bagel_sample_eval_static: %s failed: %s", #call, hipGetErrorString(e__)); \
+    } while (0)
+    STATIC_HIP(bagel_launch_build_model(&c, X, lengthscale, signal_var, omega, phase));
+    STATIC_HIP(bagel_launch_pack_samples(&c, w, v));
+    STATIC_HIP(bagel_launch_eval_io(&c, 0, x, nullptr));
+    STATIC_HIP(bagel_launch_gp_step(&c, jac != nullptr));
+    STATIC_HIP(bagel_launch_finalize(&c, jac != nullptr, -1, jac));
+    STATIC_HIP(bagel_launch_eval_io(&c, 1, nullptr, f));
+#undef STATIC_HIP
+    g_create_err[0] = 0;
     return BAGEL_OK;
 }
 
