@@ -77,7 +77,7 @@ static hipError_t dev_alloc(bagel_ctx *c, T **p, size_t count)
 
 static void free_all(bagel_ctx *c)
 {
-    void *ptrs[] = {c->Xs, c->Os, c->A, c->amp, c->exp_tab, c->v4, c->w4, c->xbuf, c->part, c->lpt, c->lam,
+    void *ptrs[] = {c->Xs, c->Xn, c->near_ok, c->Os, c->Of, c->A, c->amp, c->exp_tab, c->v4, c->w4, c->xbuf, c->part, c->lpt, c->lam,
                     c->tape_s, c->tape_J, c->tape_h[0], c->tape_h[1], c->tape_h[2], c->tape_a, c->tape_d[0],
                     c->tape_d[1], c->tape_d[2], c->wpad_f, c->wpad_b, c->gsplit, c->gacc, c->fbuf, c->gtheta, c->post_alpha, c->post_Kinv, c->post_Kx, c->post_sums};
     for (void *p : ptrs)
@@ -181,7 +181,10 @@ extern "C" int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_s
 #define ALLOC(ptr, count)                         \
     if (e == hipSuccess) e = dev_alloc(c, &(ptr), (size_t)(count))
     ALLOC(c->Xs, (size_t)M * c->Np * (D + 1));
+    ALLOC(c->Xn, (size_t)M * c->Np * (D + 1));
+    ALLOC(c->near_ok, 1);
     ALLOC(c->Os, (size_t)M * c->Lp * (D + 1));
+    ALLOC(c->Of, (size_t)M * c->Lp * 4 * ((D + 3) / 4));
     ALLOC(c->A, (size_t)M * D);
     ALLOC(c->amp, (size_t)M);
     ALLOC(c->exp_tab, 256);
@@ -206,8 +209,14 @@ extern "C" int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_s
     ALLOC(c->gtheta, (size_t)c->P);
 #undef ALLOC
     if (e == hipSuccess) {
-        double tab[256];
-        for (int i = 0; i < 256; ++i) tab[i] = exp2((double)i / 256.0);
+        // table of the sample-evaluation kernel's table form: -2^(i/256), high word lowered by i << 12
+        uint64_t tab[256];
+        for (int i = 0; i < 256; ++i) {
+            const double t = exp2((double)i / 256.0);
+            uint64_t bits;
+            memcpy(&bits, &t, sizeof(bits));
+            tab[i] = (bits | 0x8000000000000000ull) - ((uint64_t)i << 44);
+        }
         e = hipMemcpy(c->exp_tab, tab, sizeof(tab), hipMemcpyHostToDevice);
     }
     if (e != hipSuccess) {
@@ -331,7 +340,7 @@ static int64_t static_scratch_bytes(const bagel_dims *dims)
     c.M = dims->d_s;
     if (plan_sample_eval(&c)) return BAGEL_EINVAL;
     const int64_t M = c.M, D = c.D, B = dims->B, S = dims->S;
-    const int64_t counts[] = {8 * M * c.Np * (D + 1), 8 * M * c.Lp * (D + 1), 8 * M * D, 8 * M,
+    const int64_t counts[] = {8 * M * c.Np * (D + 1), 8 * M * c.Lp * (D + 1), 16 * M * c.Lp * ((D + 3) / 4), 8 * M * D, 8 * M,
                               16 * M * (c.Np / 4) * S, 16 * M * (c.Lp / 4) * S, 8 * D * B,
                               8 * (int64_t)c.groups * (1 + D) * B, 8 * M * B};
     int64_t total = 0;
@@ -375,6 +384,7 @@ extern "C" int bagel_sample_eval_static(const bagel_dims *dims, void *hip_stream
     };
     c.Xs = reinterpret_cast<double *>(carve(8 * M * c.Np * (D + 1)));
     c.Os = reinterpret_cast<double *>(carve(8 * M * c.Lp * (D + 1)));
+    c.Of = reinterpret_cast<float *>(carve(16 * M * c.Lp * ((D + 3) / 4)));
     c.A = reinterpret_cast<double *>(carve(8 * M * D));
     c.amp = reinterpret_cast<double *>(carve(8 * M));
     c.v4 = reinterpret_cast<float4 *>(carve(16 * M * (c.Np / 4) * S));

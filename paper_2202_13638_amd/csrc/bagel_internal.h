@@ -27,12 +27,16 @@ struct bagel_ctx {
     int nck, ncl;                // chunks per output
     int units;                   // M * (nck + ncl)
     int groups;                  // M * (ceil(nck/4) + ceil(ncl/4)): four units per workgroup and partial sum
-    bool exp_table;              // sample-evaluation kernel with the table form of exp2 (large launches)
+    bool exp_table;              // sample-evaluation kernel with the table form of the kernel-row loop (large launches)
     double *Xs;                  // [M][Np][D+1]: log2(e)/l_md^2 * X_nd, then log2(alpha_m^2) - 1/2 sum_d log2(e)/l_md^2 X_nd^2
     double *Os;                  // [M][Lp][D+1]: omega_mld / (2 pi) (revolutions per unit x_d), then phase / (2 pi)
+    float *Of;                   // [M][Lp/4][4][NQ][4], NQ = ceil(D/4): omega / (2 pi) in float32 in the order of the matrix-core
+                                 // B operand of the feature Jacobian: entry (m, l4, j, q, f) is column 4q+j of feature 4 l4 + f
     double *A;                   // [M][D]: log2(e) / l_md^2
     double *amp;                 // [M]: sqrt(2 alpha_m^2 / L)
-    double *exp_tab;             // [256]: 2^(i/256), the table of the step kernel's exp2
+    double *Xn;                  // [M][Np][D+1]: as Xs, last entry + 6144 (the table form's rows; see gp_step.hip)
+    int *near_ok;                // [1]: 1 if every training point and alpha^2 are inside the table form's range
+    double *exp_tab;             // [256]: -2^(i/256) with i << 12 subtracted from its high word (see gp_step.hip)
     float4 *v4;                  // [M][Np/4][S]: four consecutive training points of one sample
     float4 *w4;                  // [M][Lp/4][S]
 

@@ -23,8 +23,9 @@
 //   log2 k_mn(x) = q_m(x) + c_mn + sum_d x_d * Xs_mnd,
 //   Xs_mnd = log2(e)/l_md^2 * X_nd,  c_mn = log2(alpha_m^2) - 1/2 sum_d Xs_mnd X_nd,
 //   q_m(x) = -1/2 sum_d log2(e)/l_md^2 x_d^2.
-// exp2 takes the integer part and the next eight bits of the exponent from a rounding addition,
-// looks 2^(i/256) up in an LDS table and multiplies with a degree-3 polynomial (exp2_tab below).
+// exp2 is evaluated in software (there is no float64 exp instruction): a polynomial form for any
+// argument (exp2_poly), and a table form for the normal range that reads the split of the exponent
+// straight off the bits of a sum (see gp_step_kernel).
 // Jacobian: d k_mn / d x_d = ln2 * k_mn * (Xs_mnd - log2(e)/l_md^2 x_d); the kernel
 // accumulates G_d = sum_n v_n k_n Xs_mnd and u = sum_n v_n k_n, the reduction finishes it.
 //
@@ -34,32 +35,30 @@
 
 namespace {
 
-typedef float v4f __attribute__((ext_vector_type(4)));
+#ifndef BAGEL_SAME_ROWS
+#define BAGEL_SAME_ROWS 0      // timing experiment only: every work unit reads the first unit's rows
+#endif
 
-// 2^t from u = 256 t.  Adding 1.5 * 2^52 rounds u to the integer J = 256 n + i in the low word of the
-// sum (two's complement; |u| < 2^31), so 2^t = 2^n * 2^(i/256) * 2^(g/256) with g = u - J, |g| <= 1/2:
-// the middle factor comes from a 256-entry table in LDS (the LDS port is otherwise idle in this
-// kernel), the last one from a degree-3 polynomial (relative error 4e-14 over all t), the first one
-// from ldexp, which also takes very negative t to zero.  Ten vector instructions; the form without a
-// table (degree-7 polynomial for 2^(f/2), squared) takes twelve and is ten times less accurate.
-// a3 and a2 come in from the caller, a3 in a scalar and a2 in a vector register: the first Horner
-// step is then a single three-operand FMA (an FMA takes at most one scalar operand).
-__device__ __forceinline__ double exp2_tab(double u, const double *tab, double a3, double a2)
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float f4v __attribute__((ext_vector_type(4)));
+
+// The per-sample streams (v and w) are read through buffer loads: a wave-uniform descriptor of the
+// work unit's rows, a wave-uniform row offset that the scalar unit advances, and a constant 32-bit
+// byte offset per lane (the lane's sample).  The load instruction adds the three itself, so the loop
+// spends no vector instruction on addresses.  Non-temporal: each float4 is read once per launch.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t stream_descriptor(const float4 *rows, size_t bytes)
 {
-    constexpr double MAGIC = 6755399441055744.0;  // 1.5 * 2^52
-    const double s = u + MAGIC;
-    const int J = __double2loint(s);
-    const double g = u - (s - MAGIC);             // exact
-    const double T = tab[J & 255];
-    double p = fma(a3, g, a2);
-    p = fma(p, g, 0x1.62e42fefa39ddp-9);
-    p = fma(p, g, 1.0);
-    return ldexp(T * p, J >> 8);
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<float4 *>(rows), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ v4f stream_load(__amdgpu_buffer_rsrc_t desc, unsigned lane_off, unsigned row_off)
+{
+    return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(desc, lane_off, row_off, 2));
 }
 
 // 2^t without a table: split off the integer part, evaluate 2^(f/2) for |f| <= 1/2 with a degree-7
 // polynomial and square it (relative error 4e-13), scale with ldexp.  Twelve vector instructions and
-// no LDS access.  c7 in a scalar and c6 in a vector register, as in exp2_tab.
+// no LDS access.  c7 comes in a scalar and c6 in a vector register: the first Horner step is then a
+// single three-operand FMA (an FMA takes at most one scalar operand).
 __device__ __forceinline__ double exp2_poly(double t, double c7, double c6)
 {
     const double n = rint(t);
@@ -74,125 +73,14 @@ __device__ __forceinline__ double exp2_poly(double t, double c7, double c6)
     return ldexp(p * p, (int)n);
 }
 
-// TAB selects the exp2: the table form saves two instructions per training point, but its LDS read
-// shares a wait counter with the scalar loads of the shared operands, so every table look-up also
-// waits for the operand rows requested ahead.  A launch that fills the chip many times over hides
-// that behind other waves (stress workload: 0.647 -> 0.629 ms); a small launch does not (N = 2048,
-// B = 1024: 26 -> 35 us), and takes the polynomial form.
-template <int D, bool JAC, bool TAB>
-__global__ __launch_bounds__(BAGEL_BLOCK) void gp_step_kernel(
-    const double *__restrict__ Xs, const double *__restrict__ Os, const double *__restrict__ A,
-    const float4 *__restrict__ v4, const float4 *__restrict__ w4, const double *__restrict__ xbuf,
-    double *__restrict__ part, const double *__restrict__ exp_tab, int B, int S, int per_sample, int Np, int Lp,
-    int CK, int CL, int nck, int ncl, int M)
+// End of a workgroup: waves 1-3 hand their sums (value u, Jacobian sums G) to wave 0 through LDS slots
+// 0-2, wave 0 adds them in wave order and writes the group's partial sum.  in_lds: every wave, wave 0
+// included (slot 3), has already stored its sums (the feature units of a Jacobian launch).
+template <int D, bool JAC, int RC>
+__device__ __forceinline__ void combine_waves(double (*red)[RC][64], int wave, int lane, bool live, double *out, int B,
+                                              bool in_lds, double u, double (&G)[D])
 {
-    __shared__ double red[3][1 + D][64];
-    __shared__ double tab[256];
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int b_raw = blockIdx.x * 64 + lane;
-    const bool live = b_raw < B;
-    const int b = live ? b_raw : B - 1;
-    const int sidx = b / per_sample;
-    const int group = blockIdx.y;                  // four consecutive units of one output and kind
-    const int ngk = (nck + 3) >> 2, ngl = (ncl + 3) >> 2;
-
-    double x[D];
-#pragma unroll
-    for (int d = 0; d < D; ++d) x[d] = xbuf[(size_t)d * B + b];
-
-    double *out = part + (size_t)group * (1 + D) * B + b;
-    double u = 0.0;                                // this wave's sums: value, then the D Jacobian sums
-    double G[D];
-#pragma unroll
-    for (int d = 0; d < D; ++d) G[d] = 0.0;
-
-    if (group < M * ngk) {
-        // ---------------- kernel-row unit: CK training points of output m ----------------
-        const int m = group / ngk, c = 4 * (group - m * ngk) + wave;
-        const int n_iter = c < nck ? CK / 4 : 0;   // a wave past the last chunk adds nothing
-        if (TAB) {
-            static_assert(BAGEL_BLOCK == 256, "one table entry per thread");
-            tab[threadIdx.x] = exp_tab[threadIdx.x];
-            __syncthreads();
-        }
-        double q = 0.0;
-#pragma unroll
-        for (int d = 0; d < D; ++d) q = fma(-0.5 * A[m * D + d] * x[d], x[d], q);
-        // Table form: the exponent is formed times 256 (exact scaling).  exp2_tab needs |256 t| < 2^31:
-        // with |q| <= 2^17 and the table rows limited to c_n >= -2^17 (model set-up turns rows beyond
-        // that into padding), |t| <= |q| + |c_n| + 2 sqrt(|q| |c_n|) + |log2 alpha^2| < 2^20.  A
-        // trajectory further out (about 400 length scales from the origin) is that far from every
-        // training point that is kept, and its kernel row is zero: it gets a constant exponent of
-        // -3000.  The polynomial form applies the same rule, so both forms agree everywhere.
-        const double scale = TAB ? 256.0 : 1.0;
-        const bool far = q < -131072.0;
-        double xs[D];
-#pragma unroll
-        for (int d = 0; d < D; ++d) xs[d] = far ? 0.0 : scale * x[d];
-        const double qs = far ? -3000.0 * scale : scale * q;
-        double kscale = scale;
-        const double *__restrict__ Xr = Xs + ((size_t)m * Np + (size_t)c * CK) * (D + 1);
-        const float4 *__restrict__ vp = v4 + ((size_t)m * (Np / 4) + (size_t)c * (CK / 4)) * S + sidx;
-        // leading polynomial coefficients of the exp2 in use, pinned to register classes (see exp2_tab)
-        double ca = TAB ? 0x1.c6b0902a6389dp-29 : 1.192611307487823e-07;
-        double cb = TAB ? 0x1.ebfbe3a9ac89ap-19 : 2.409383341728244e-06;
-        asm volatile("" : "+s"(ca), "+v"(cb), "+v"(kscale));
-        for (int n4 = 0; n4 < n_iter; ++n4) {
-            const v4f vv = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(vp + (size_t)n4 * S));   // read-once stream
-            const float vj[4] = {vv.x, vv.y, vv.z, vv.w};
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const double *__restrict__ r = Xr + (size_t)(n4 * 4 + j) * (D + 1);
-                double t = TAB ? fma(r[D], kscale, qs) : qs + r[D];
-#pragma unroll
-                for (int d = 0; d < D; ++d) t = fma(xs[d], r[d], t);
-                const double k = TAB ? exp2_tab(t, tab, ca, cb) : exp2_poly(t, ca, cb);
-                const double vk = (double)vj[j] * k;
-                u += vk;
-                if (JAC) {
-#pragma unroll
-                    for (int d = 0; d < D; ++d) G[d] = fma(vk, r[d], G[d]);
-                }
-            }
-        }
-    } else {
-        // ---------------- random-feature unit: CL features of output m -------------------
-        const int gg = group - M * ngk;
-        const int m = gg / ngl, c = 4 * (gg - m * ngl) + wave;
-        const int n_iter = c < ncl ? CL / 4 : 0;
-        const double *__restrict__ Or = Os + ((size_t)m * Lp + (size_t)c * CL) * (D + 1);
-        const float4 *__restrict__ wp = w4 + ((size_t)m * (Lp / 4) + (size_t)c * (CL / 4)) * S + sidx;
-        float p = 0.0f;
-        for (int l4 = 0; l4 < n_iter; ++l4) {
-            const v4f ww = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(wp + (size_t)l4 * S));
-            const float wj[4] = {ww.x, ww.y, ww.z, ww.w};
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const double *__restrict__ r = Or + (size_t)(l4 * 4 + j) * (D + 1);
-                // product first, phase offset last: both are scalar operands, and an FMA takes only one
-                double z = x[0] * r[0];
-#pragma unroll
-                for (int d = 1; d < D; ++d) z = fma(x[d], r[d], z);
-                z += r[D];
-                // z is the phase in revolutions; its fractional part is exact in float64 and the
-                // hardware sin / cos take revolutions (absolute error about one float32 ulp)
-                const float y = (float)__builtin_amdgcn_fract(z);
-                const float sn = __builtin_amdgcn_sinf(y);
-                const float cs = __builtin_amdgcn_cosf(y);
-                p = fmaf(wj[j], cs, p);
-                if (JAC) {
-                    const double ws = (double)(wj[j] * sn);
-#pragma unroll
-                    for (int d = 0; d < D; ++d) G[d] = fma(ws, r[d], G[d]);
-                }
-            }
-        }
-        u = (double)p;
-    }
-
-    // waves 1-3 hand their sums to wave 0, which adds them in wave order and writes the group's partial
-    if (wave > 0) {
+    if (wave > 0 && !in_lds) {
         red[wave - 1][0][lane] = u;
         if (JAC) {
 #pragma unroll
@@ -201,6 +89,11 @@ __global__ __launch_bounds__(BAGEL_BLOCK) void gp_step_kernel(
     }
     __syncthreads();
     if (wave == 0) {
+        if (in_lds) {
+            u = red[3][0][lane];
+#pragma unroll
+            for (int d = 0; d < D; ++d) G[d] = red[3][1 + d][lane];
+        }
 #pragma unroll
         for (int w = 0; w < 3; ++w) {
             u += red[w][0][lane];
@@ -219,14 +112,252 @@ __global__ __launch_bounds__(BAGEL_BLOCK) void gp_step_kernel(
     }
 }
 
-template <int D, bool JAC, bool TAB>
+// NEAR adds the fast form of the kernel-row loop for the normal case that data and trajectory are
+// within about 19 length scales of the origin; the loop above is then the fallback of a wave that
+// holds a trajectory further out, or of a model with training points further out (near_ok == 0).
+// With  q = -1/2 sum_d a_d x_d^2  taken out of the exponent (the sums are multiplied by 2^q at the end),
+//   t'_n = c_n + sum_d x_d Xs_nd   lies in [-770, 270]   for |q|, |c_n| <= 250 and |log2 alpha^2| <= 20,
+// and the near table holds c_n + 6144 in place of c_n: 6144 = 1.5 * 2^12 puts the sum s = t'_n + 6144 into
+// [2^12, 2^13), where one unit in the last place is 2^-40, so the bits of s ARE the split of t'_n:
+//   high word bits 19..8 = 2048 + floor(t'), bits 7..0 = the next eight bits i (t' in units of 1/256),
+//   low word = the remaining fraction g in units of 2^-40 (t' rounded to 2^-41: relative error 3e-13 of k).
+// Then 2^t' = 2^floor(t') * 2^(i/256) * 2^g: the middle factor comes from a 256-entry table in LDS,
+// indexed by the low byte of the high word; 2^g is a degree-3 polynomial in the low word converted to
+// float64 (coefficients pre-scaled by 2^-40k; relative error 7e-14 on [0, 2^-8)); and the power of two is
+// applied by adding the high word of s, shifted left by 12, to the high word of the table entry: the
+// shift drops the exponent of s and leaves (2048 + floor t') << 20 | i << 12, so the table stores
+// 2^(i/256) with i << 12 subtracted from its high word and its sign bit set (adding 2048 << 20 clears
+// it again).  No exponent can wrap for t' in the range above.  Per training point: 9 instructions for s,
+// 7 for k (address, conversion, 3 polynomial steps, exponent add, product), 2 for v k, 9 to accumulate
+// = 27, against 32 of the general loop.
+// The table form needs many workgroups per compute unit to pay: its LDS read shares a wait counter
+// with the scalar loads of the shared operands, so every look-up also waits for the operand rows
+// requested ahead; small launches take the general loop only.
+template <int D, bool JAC, bool NEAR>
+__global__ __launch_bounds__(BAGEL_BLOCK) __attribute__((amdgpu_waves_per_eu(D <= 8 ? 8 : (D <= 11 ? 5 : 4), 8))) void gp_step_kernel(
+    const double *__restrict__ Xs, const double *__restrict__ Xn, const double *__restrict__ Os,
+    const float4 *__restrict__ Of, const double *__restrict__ A, const float4 *__restrict__ v4,
+    const float4 *__restrict__ w4,
+    const double *__restrict__ xbuf, double *__restrict__ part, const double *__restrict__ exp_tab,
+    const int *__restrict__ near_ok, int B, int S, int per_sample, int Np, int Lp, int CK, int CL, int nck, int ncl,
+    int M)
+{
+    // Sums handed from wave to wave at the end.  Slot 3 is used only by the feature units of a
+    // Jacobian launch; the kernel-row units keep the table of the table form there.
+    constexpr int RC = 1 + D > 4 ? 1 + D : 4;      // rows per slot: at least the 256 entries of the exp2 table
+    __shared__ double red[4][RC][64];
+    double *tab = &red[3][0][0];
+    constexpr int NQ = (D + 3) / 4;                // matrix instructions per feature: four Jacobian columns each
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int b_raw = blockIdx.x * 64 + lane;
+    const bool live = b_raw < B;
+    const int b = live ? b_raw : B - 1;
+    const int sidx = b / per_sample;
+    const int group = blockIdx.y;                  // four consecutive units of one output and kind
+    const int ngk = (nck + 3) >> 2, ngl = (ncl + 3) >> 2;
+
+    double x[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) x[d] = xbuf[(size_t)d * B + b];
+
+    double *out = part + (size_t)group * (1 + D) * B + b;
+
+    if (group < M * ngk) {
+        double u = 0.0;                            // this wave's sums: value, then the D Jacobian sums
+        double G[D];
+#pragma unroll
+        for (int d = 0; d < D; ++d) G[d] = 0.0;
+        // ---------------- kernel-row unit: CK training points of output m ----------------
+        const int m = group / ngk, c = 4 * (group - m * ngk) + wave;
+        const int n_iter = c < nck ? CK / 4 : 0;   // a wave past the last chunk adds nothing
+        if (NEAR) {
+            static_assert(BAGEL_BLOCK == 256, "one table entry per thread");
+            tab[threadIdx.x] = exp_tab[threadIdx.x];
+            __syncthreads();
+        }
+        double q = 0.0;
+#pragma unroll
+        for (int d = 0; d < D; ++d) q = fma(-0.5 * A[m * D + d] * x[d], x[d], q);
+        const size_t row0 = BAGEL_SAME_ROWS ? 0 : ((size_t)m * Np + (size_t)c * CK) * (D + 1);
+        // the stream of this unit for this lane's sample: uniform base address plus a 32-bit lane offset
+        const unsigned vstep = (unsigned)S * (unsigned)sizeof(float4);       // one row: four points of every sample
+        const __amdgpu_buffer_rsrc_t vdesc =
+            stream_descriptor(v4 + ((size_t)m * (Np / 4) + (size_t)c * (CK / 4)) * S, (size_t)(CK / 4) * vstep);
+        const unsigned voff = (unsigned)sidx * (unsigned)sizeof(float4);
+        bool wave_near = false;
+        if (NEAR) wave_near = near_ok[0] != 0 && !__any(!(q >= -250.0));
+        if (NEAR && wave_near) {
+            const double *__restrict__ Xr = Xn + row0;
+            // leading polynomial coefficients pinned to register classes: the first Horner step is then a
+            // single three-operand FMA (an FMA takes at most one scalar operand)
+            double ca = 0x1.c726cfe5bfc26p-125, cb = 0x1.ebfbd4e173a43p-83;
+            asm volatile("" : "+s"(ca), "+v"(cb));
+            {
+                for (int n4 = 0; n4 < n_iter; ++n4) {
+                    const v4f vv = stream_load(vdesc, voff, (unsigned)n4 * vstep);
+                    const float vj[4] = {vv.x, vv.y, vv.z, vv.w};
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const double *__restrict__ r = Xr + (size_t)(n4 * 4 + j) * (D + 1);
+                        double t = x[0] * r[0];
+#pragma unroll
+                        for (int d = 1; d < D; ++d) t = fma(x[d], r[d], t);
+                        const double s = t + r[D];
+                        const int hs = __double2hiint(s);
+                        const double T = tab[hs & 255];
+                        const double g = (double)(unsigned)__double2loint(s);
+                        double p = fma(ca, g, cb);
+                        p = fma(p, g, 0x1.62e42fefcb0c8p-41);
+                        p = fma(p, g, 1.0);
+                        const double sc = __hiloint2double(__double2hiint(T) + (hs << 12), __double2loint(T));
+                        const double vk = (double)vj[j] * (sc * p);
+                        u += vk;
+                        if (JAC) {
+#pragma unroll
+                            for (int d = 0; d < D; ++d) G[d] = fma(vk, r[d], G[d]);
+                        }
+                    }
+                }
+            }
+            const double eq = exp2_poly(q, 1.192611307487823e-07, 2.409383341728244e-06);
+            u *= eq;
+            if (JAC) {
+#pragma unroll
+                for (int d = 0; d < D; ++d) G[d] *= eq;
+            }
+        } else {
+            // A trajectory further out than about 400 length scales (q < -2^17) is that far from every
+            // training point that is kept (model set-up turns rows with c_n < -2^17 into padding), and its
+            // kernel row is zero: it gets a constant exponent of -3000.
+            const bool far = q < -131072.0;
+            double xs[D];
+#pragma unroll
+            for (int d = 0; d < D; ++d) xs[d] = far ? 0.0 : x[d];
+            const double qs = far ? -3000.0 : q;
+            const double *__restrict__ Xr = Xs + row0;
+            double ca = 1.192611307487823e-07, cb = 2.409383341728244e-06;
+            asm volatile("" : "+s"(ca), "+v"(cb));
+            for (int n4 = 0; n4 < n_iter; ++n4) {
+                const v4f vv = stream_load(vdesc, voff, (unsigned)n4 * vstep);
+                const float vj[4] = {vv.x, vv.y, vv.z, vv.w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const double *__restrict__ r = Xr + (size_t)(n4 * 4 + j) * (D + 1);
+                    double t = qs + r[D];
+#pragma unroll
+                    for (int d = 0; d < D; ++d) t = fma(xs[d], r[d], t);
+                    const double k = exp2_poly(t, ca, cb);
+                    const double vk = (double)vj[j] * k;
+                    u += vk;
+                    if (JAC) {
+#pragma unroll
+                        for (int d = 0; d < D; ++d) G[d] = fma(vk, r[d], G[d]);
+                    }
+                }
+            }
+        }
+        combine_waves<D, JAC, RC>(red, wave, lane, live, out, B, false, u, G);
+    } else {
+        // ---------------- random-feature unit: CL features of output m -------------------
+        const int gg = group - M * ngk;
+        const int m = gg / ngl, c = 4 * (gg - m * ngl) + wave;
+        const int n_iter = c < ncl ? CL / 4 : 0;
+        const double *__restrict__ Or = Os + (BAGEL_SAME_ROWS ? 0 : ((size_t)m * Lp + (size_t)c * CL) * (D + 1));
+        const unsigned wstep = (unsigned)S * (unsigned)sizeof(float4);
+        const __amdgpu_buffer_rsrc_t wdesc =
+            stream_descriptor(w4 + ((size_t)m * (Lp / 4) + (size_t)c * (CL / 4)) * S, (size_t)(CL / 4) * wstep);
+        const unsigned woff = (unsigned)sidx * (unsigned)sizeof(float4);
+        float p = 0.0f;
+        if (JAC) {
+            // The Jacobian sums of the feature part, G[b][d] = sum_l (w_l sin z_l) omega_ld, tolerate
+            // float32 (no cancellation: w has random signs), so they run on the matrix cores as rank-1
+            // updates: v_mfma_f32_4x4x1 (16 blocks) multiplies, within every group of four lanes, the A
+            // values of the four lanes (here: w sin z of four trajectories) with the B values of the four
+            // lanes (here: omega_ld for d = 4 q + lane % 4) and adds the 4 x 4 products to four registers
+            // (register i of lane 4 g + j: trajectory 4 g + i, column 4 q + j).  One instruction takes the
+            // issue time of two vector FMAs and replaces four of them (and the float64 conversion).
+            // Of holds omega / (2 pi) in float32 in the order the B operand needs: per four features and
+            // lane class j, NQ float4 (feature 0..3 of column 4 q + j), read through a buffer load whose
+            // lane offset is constant; columns >= D are zero.
+            const unsigned ostep = 64u * NQ;            // bytes per four features
+            const __amdgpu_buffer_rsrc_t odesc = __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<float4 *>(Of + ((size_t)m * (Lp / 4) + (size_t)c * (CL / 4)) * 4 * NQ), 0,
+                (int)((size_t)(CL / 4) * ostep), 0x00020000);
+            const unsigned ooff = (unsigned)(lane & 3) * (16u * NQ);
+            f4v acc[NQ];
+#pragma unroll
+            for (int qd = 0; qd < NQ; ++qd) acc[qd] = f4v{0.0f, 0.0f, 0.0f, 0.0f};
+            for (int l4 = 0; l4 < n_iter; ++l4) {
+                const v4f ww = stream_load(wdesc, woff, (unsigned)l4 * wstep);
+                v4f bq[NQ];
+#pragma unroll
+                for (int qd = 0; qd < NQ; ++qd)
+                    bq[qd] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(odesc, ooff + 16u * qd, (unsigned)l4 * ostep, 0));
+                const float wj[4] = {ww.x, ww.y, ww.z, ww.w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const double *__restrict__ r = Or + (size_t)(l4 * 4 + j) * (D + 1);
+                    double z = x[0] * r[0];
+#pragma unroll
+                    for (int d = 1; d < D; ++d) z = fma(x[d], r[d], z);
+                    z += r[D];
+                    const float y = (float)__builtin_amdgcn_fract(z);
+                    const float sn = __builtin_amdgcn_sinf(y);
+                    const float cs = __builtin_amdgcn_cosf(y);
+                    p = fmaf(wj[j], cs, p);
+                    const float ws = wj[j] * sn;
+#pragma unroll
+                    for (int qd = 0; qd < NQ; ++qd)
+                        acc[qd] = __builtin_amdgcn_mfma_f32_4x4x1f32(ws, bq[qd][j], acc[qd], 0, 0, 0);
+                }
+            }
+            // every wave, wave 0 included, hands its sums over through LDS: that is also the transposition
+            // from the accumulator layout (lane = column, register = trajectory) to lane = trajectory
+            const int slot = (wave + 3) & 3;
+            red[slot][0][lane] = (double)p;
+#pragma unroll
+            for (int qd = 0; qd < NQ; ++qd) {
+                const int d = 4 * qd + (lane & 3);
+                if (d < D) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) red[slot][1 + d][(lane & ~3) + i] = (double)acc[qd][i];
+                }
+            }
+            double u = 0.0, G[D];
+            combine_waves<D, JAC, RC>(red, wave, lane, live, out, B, true, u, G);
+        } else {
+            for (int l4 = 0; l4 < n_iter; ++l4) {
+                const v4f ww = stream_load(wdesc, woff, (unsigned)l4 * wstep);
+                const float wj[4] = {ww.x, ww.y, ww.z, ww.w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const double *__restrict__ r = Or + (size_t)(l4 * 4 + j) * (D + 1);
+                    // product first, phase offset last: both are scalar operands, and an FMA takes only one
+                    double z = x[0] * r[0];
+#pragma unroll
+                    for (int d = 1; d < D; ++d) z = fma(x[d], r[d], z);
+                    z += r[D];
+                    // z is the phase in revolutions; its fractional part is exact in float64 and the
+                    // hardware sin / cos take revolutions (absolute error about one float32 ulp)
+                    const float y = (float)__builtin_amdgcn_fract(z);
+                    p = fmaf(wj[j], __builtin_amdgcn_cosf(y), p);
+                }
+            }
+            double u = (double)p, G[D];
+            combine_waves<D, JAC, RC>(red, wave, lane, live, out, B, false, u, G);
+        }
+    }
+}
+
+template <int D, bool JAC, bool NEAR>
 void launch_variant(bagel_ctx *c)
 {
     dim3 grid((c->dm.B + 63) / 64, c->groups);
     const int per_sample = c->dm.B / c->dm.S;
-    hipLaunchKernelGGL((gp_step_kernel<D, JAC, TAB>), grid, dim3(BAGEL_BLOCK), 0, c->stream, c->Xs, c->Os, c->A, c->v4,
-                       c->w4, c->xbuf, c->part, c->exp_tab, c->dm.B, c->dm.S, per_sample, c->Np, c->Lp, c->CK, c->CL,
-                       c->nck, c->ncl, c->M);
+    hipLaunchKernelGGL((gp_step_kernel<D, JAC, NEAR>), grid, dim3(BAGEL_BLOCK), 0, c->stream, c->Xs, c->Xn, c->Os,
+                       reinterpret_cast<const float4 *>(c->Of), c->A, c->v4, c->w4, c->xbuf, c->part, c->exp_tab, c->near_ok, c->dm.B, c->dm.S, per_sample, c->Np,
+                       c->Lp, c->CK, c->CL, c->nck, c->ncl, c->M);
 }
 
 template <int D>

@@ -1,6 +1,10 @@
 // Re-layout of the model and of the per-sample streams into the form the step kernel reads.
 //   Xs[m][n][0..D-1] = log2(e)/l_md^2 * X_nd,   Xs[m][n][D] = log2(alpha_m^2) - 1/2 sum_d Xs_mnd X_nd
+//   Xn[m][n] = the same row with 6144 added to its last entry (rows of the step kernel's table form);
+//   near_ok = 0 if a training point or a signal variance lies outside the range of that form
 //   Os[m][l][0..D-1] = omega_mld / (2 pi),      Os[m][l][D] = phase_ml / (2 pi)   (revolutions)
+//   Of[m][l/4][j][q][l%4] = (float) omega_ml,4q+j / (2 pi), zero for columns >= D: the same frequencies in the
+//                           order of the matrix-core operand of the feature Jacobian (see gp_step.hip)
 //   v4[m][n/4][s] = v[s][m][4(n/4) .. +3],      w4[m][l/4][s] likewise
 // Rows past N (or L) are padding: they evaluate to a kernel value of zero (or a feature of one)
 // and carry a zero weight, so they add nothing.  Everything is computed in float64 from the
@@ -12,11 +16,14 @@ namespace {
 constexpr double LOG2E = 1.4426950408889634074;
 constexpr double INV_TWO_PI = 0.15915494309189533577;
 
+__global__ void set_flag_kernel(int *flag, int value) { flag[0] = value; }
+
 __global__ void build_model_kernel(const float *__restrict__ X, const float *__restrict__ ell,
                                    const float *__restrict__ sf2, const float *__restrict__ omega,
                                    const float *__restrict__ phase, double *__restrict__ Xs,
-                                   double *__restrict__ Os, double *__restrict__ A, double *__restrict__ amp,
-                                   int M, int N, int L, int D, int Np, int Lp)
+                                   double *__restrict__ Xn, int *__restrict__ near_ok,
+                                   double *__restrict__ Os, float *__restrict__ Of, double *__restrict__ A,
+                                   double *__restrict__ amp, int M, int N, int L, int D, int Np, int Lp)
 {
     const int m = blockIdx.y;
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -32,6 +39,14 @@ __global__ void build_model_kernel(const float *__restrict__ X, const float *__r
                 c -= 0.5 * a * xv * xv;
             }
             row[D] = c;
+            if (Xn) {
+                double *rown = Xn + ((size_t)m * Np + i) * (D + 1);
+                for (int d = 0; d < D; ++d) rown[d] = row[d];
+                rown[D] = c + 6144.0;
+                const double la = log2((double)sf2[m]);
+                // the table form needs |c_n| <= 250 and |log2 alpha^2| <= 20 (negated tests: NaN fails them)
+                if (!(c >= -250.0) || !(la >= -20.0 && la <= 20.0)) near_ok[0] = 0;
+            }
             if (c < -131072.0) {                     // outside the step kernel's range (see gp_step.hip): k = 0
                 for (int d = 0; d < D; ++d) row[d] = 0.0;
                 row[D] = -2000.0;
@@ -39,6 +54,11 @@ __global__ void build_model_kernel(const float *__restrict__ X, const float *__r
         } else {
             for (int d = 0; d < D; ++d) row[d] = 0.0;
             row[D] = -2000.0;
+            if (Xn) {                                // padding row of the table form: k = 1, weight 0
+                double *rown = Xn + ((size_t)m * Np + i) * (D + 1);
+                for (int d = 0; d < D; ++d) rown[d] = 0.0;
+                rown[D] = 6144.0;
+            }
         }
     }
     if (omega && i < Lp) {
@@ -48,6 +68,11 @@ __global__ void build_model_kernel(const float *__restrict__ X, const float *__r
             row[D] = INV_TWO_PI * (double)phase[(size_t)m * L + i];
         } else {
             for (int d = 0; d <= D; ++d) row[d] = 0.0;
+        }
+        const int NQ = (D + 3) / 4;
+        for (int col = 0; col < 4 * NQ; ++col) {
+            const int qd = col >> 2, j = col & 3;
+            Of[((((size_t)m * (Lp / 4) + (i >> 2)) * 4 + j) * NQ + qd) * 4 + (i & 3)] = col < D ? (float)row[col] : 0.0f;
         }
     }
     if (i < D) {
@@ -85,8 +110,11 @@ hipError_t bagel_launch_build_model(bagel_ctx *c, const float *X, const float *e
 {
     const int big = c->Np > c->Lp ? c->Np : c->Lp;
     dim3 grid((big + 255) / 256, c->M);
-    hipLaunchKernelGGL(build_model_kernel, grid, dim3(256), 0, c->stream, X, ell, sf2, omega, phase, c->Xs, c->Os,
-                       c->A, c->amp, c->M, c->dm.N, c->dm.L, c->D, c->Np, c->Lp);
+    // near_ok starts at 1 and is cleared by any row outside the table form's range (contexts without the
+    // table form have no Xn)
+    if (c->Xn) hipLaunchKernelGGL(set_flag_kernel, dim3(1), dim3(1), 0, c->stream, c->near_ok, 1);
+    hipLaunchKernelGGL(build_model_kernel, grid, dim3(256), 0, c->stream, X, ell, sf2, omega, phase, c->Xs, c->Xn,
+                       c->near_ok, c->Os, c->Of, c->A, c->amp, c->M, c->dm.N, c->dm.L, c->D, c->Np, c->Lp);
     return hipGetLastError();
 }
 
