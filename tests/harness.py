@@ -91,7 +91,7 @@ def assert_parity(ref, got, grad=True, label=""):
     assert np.isfinite(got["states"]).all() and np.isfinite(got["loss"])
     assert d["state"] <= TOL_STATE, d
     assert d["loss"] <= TOL_LOSS, d
-    assert d["loss_per_traj"] <= 10 * TOL_LOSS, d
+    assert d["loss_per_traj"] <= TOL_LOSS, d
     if grad:
         assert np.isfinite(got["grad_theta"]).all()
         assert d["grad_l2"] <= TOL_GRAD and d["grad_max"] <= TOL_GRAD, d

@@ -37,83 +37,143 @@ def test_medium_full_config():
     harness.assert_parity(ref, harness.gpu_rollout(cfg, inp, ref["v32"]), label="medium/grad")
 
 
-def _full_size_case(name, n_sampled):
-    """The configuration at its full sizes, in the launch configuration bench.py times.  The oracle
-    cannot afford the whole batch, so `n_sampled` strided trajectories are checked:
-      (a) as a batch of their own (S = B = n_sampled, full N, L, H, policy): everything incl. grad_theta;
-      (b) inside the full batch: their states, per-trajectory losses and d loss / d s0 (a per-trajectory
-          quantity that exercises the whole backward sweep) must match the oracle, and the other
-          trajectories run on v from the library's own prepare."""
+N_SAMPLED = 256     # trajectories the oracle follows inside the two largest workloads
+
+
+def _sampled_indices(cfg):
+    """Strided sample of N_SAMPLED trajectories: every (B / N_SAMPLED)-th one, starting at 3."""
+    return np.arange(N_SAMPLED) * (cfg.B // N_SAMPLED) + 3
+
+
+def _run_full_batch(cfg, inp, v_rows=None, idx=None):
+    """The configuration at its full sizes through bagel_prepare_samples (the library's own v for
+    every sample; rows `idx` replaced by `v_rows`, the float32 v the oracle used) and one
+    bagel_rollout_loss_grad call in the launch configuration bench.py times.  Returns numpy results and
+    the library's v of the rows idx."""
     import torch
     from paper_2202_13638_amd import binding
-    cfg = _cfg(name)
-    inp = synth.make_inputs(cfg)
-    idx = np.arange(n_sampled) * (cfg.B // n_sampled) + 3
-    sub_cfg, sub_inp = synth.subset_trajectories(cfg, inp, idx)
-    ref = harness.oracle_reference(sub_cfg, sub_inp)                      # oracle prepare + rollout on the sample
-    got = harness.gpu_rollout(sub_cfg, sub_inp, ref["v32"])
-    harness.assert_parity(ref, got, label=f"{name}/sampled-batch")
-
     ctx = binding.Bagel(binding.dims_from_config(cfg))
     g = harness.to_gpu(inp)
     v_all = torch.empty((cfg.B, cfg.M, cfg.N), dtype=torch.float32, device="cuda")
     ctx.bagel_prepare_samples(g["X"], g["y"], g["lengthscale"], g["signal_var"], g["noise_var"], g["omega"],
                               g["phase"], g["w"], g["eps"], v_all)
     torch.cuda.synchronize()
-    v_lib = v_all[torch.from_numpy(idx).cuda()].cpu().numpy().astype(np.float64)
-    err = np.abs(v_lib - ref["v64"]).max() / np.abs(ref["v64"]).max()
-    print(f"[prepare {name} full size] max|dv|/max|v| on the sampled rows = {err:.3e}", flush=True)
-    assert err <= 5e-7
-    v_all[torch.from_numpy(idx).cuda()] = torch.from_numpy(ref["v32"]).cuda()
+    v_lib = None
+    if idx is not None:
+        ti = torch.from_numpy(idx).cuda()
+        v_lib = v_all[ti].cpu().numpy().astype(np.float64)
+        v_all[ti] = torch.from_numpy(np.ascontiguousarray(v_rows, dtype=np.float32)).cuda()
     ctx.bagel_set_samples(g["X"], g["lengthscale"], g["signal_var"], g["omega"], g["phase"], g["w"], v_all)
-    del v_all
     B, H, ds = cfg.B, cfg.H, cfg.d_s
-    loss = torch.zeros(1, device="cuda")
-    lpt = torch.zeros(B, device="cuda")
-    states = torch.zeros((H + 1, B, ds), device="cuda")
-    gth = torch.zeros(ctx.P, device="cuda")
-    gs0 = torch.zeros((B, ds), device="cuda")
+    loss = torch.full((1,), float("nan"), device="cuda")
+    lpt = torch.full((B,), float("nan"), device="cuda")
+    states = torch.full((H + 1, B, ds), float("nan"), device="cuda")
+    gth = torch.full((ctx.P,), float("nan"), device="cuda")
+    gs0 = torch.full((B, ds), float("nan"), device="cuda")
     ctx.bagel_rollout_loss_grad(g["theta"], g["s0"], g["goals"], loss, gth, lpt, states, gs0)
     torch.cuda.synchronize()
-    st = states[:, torch.from_numpy(idx).cuda()].cpu().numpy().astype(np.float64)
-    d_state = np.abs(st - ref["states"]).max() / np.abs(ref["states"]).max()
-    lp = lpt.cpu().numpy().astype(np.float64)
-    d_lpt = np.abs(lp[idx] - ref["loss_per_traj"]).max() / np.abs(ref["loss_per_traj"]).max()
-    gs = gs0.cpu().numpy().astype(np.float64)[idx] * (B / n_sampled)      # 1/B normalisation of the loss
-    d_gs0 = np.abs(gs - ref["grad_s0"]).max() / np.abs(ref["grad_s0"]).max()
-    print(f"[parity {name}/full-size sampled] state={d_state:.3e} loss_per_traj={d_lpt:.3e} grad_s0={d_gs0:.3e}",
-          flush=True)
-    assert d_state <= harness.TOL_STATE and d_lpt <= 10 * harness.TOL_LOSS and d_gs0 <= harness.TOL_GRAD
-    # properties that hold at any size
-    assert abs(float(loss.item()) - lp.mean()) <= 1e-5 * abs(lp.mean())
-    assert bool(torch.isfinite(gth).all()) and bool(torch.isfinite(states).all())
-    # the same trajectories give (up to the summation order of a different work split) the same
-    # numbers whether they run alone or inside the full batch
-    np.testing.assert_allclose(st, got["states"], rtol=0, atol=2e-5 * np.abs(got["states"]).max())
+    out = dict(loss=float(loss.item()), loss_per_traj=lpt.cpu().numpy().astype(np.float64),
+               states=states.cpu().numpy().astype(np.float64), grad_theta=gth.cpu().numpy().astype(np.float64),
+               grad_s0=gs0.cpu().numpy().astype(np.float64))
     ctx.close()
-    return got
+    return out, v_lib, v_all
 
 
-@pytest.mark.timeout(900)
-def test_large_policy_full_size_with_checkpointing():
-    """N=4096, L=2048, B=4096, H=500, policy 5-256-256-1, ckpt_interval=50."""
+def _check_sampled_inside_full(name, cfg, full, ref, alone, idx):
+    """The sampled trajectories inside the full batch against the oracle: states, per-trajectory loss and
+    d loss / d s0 (a per-trajectory quantity that exercises the whole backward sweep)."""
+    st = full["states"][:, idx]
+    d_state = np.abs(st - ref["states"]).max() / np.abs(ref["states"]).max()
+    d_lpt = np.abs(full["loss_per_traj"][idx] - ref["loss_per_traj"]).max() / np.abs(ref["loss_per_traj"]).max()
+    gs = full["grad_s0"][idx] * (cfg.B / len(idx))                         # 1/B normalisation of the loss
+    d_gs0 = np.abs(gs - ref["grad_s0"]).max() / np.abs(ref["grad_s0"]).max()
+    print(f"[parity {name}/sampled inside the full batch] state={d_state:.3e} loss_per_traj={d_lpt:.3e} "
+          f"grad_s0={d_gs0:.3e}", flush=True)
+    assert d_state <= harness.TOL_STATE and d_lpt <= harness.TOL_LOSS and d_gs0 <= harness.TOL_GRAD
+    # the same trajectories give (up to the summation order of a different work split) the same numbers
+    # whether they run alone or inside the full batch
+    np.testing.assert_allclose(st, alone["states"], rtol=0, atol=2e-5 * np.abs(alone["states"]).max())
+
+
+@pytest.mark.timeout(1500)
+def test_large_policy_full_batch_against_the_oracle():
+    """N=4096, L=2048, B=S=4096, H=500, policy 5-256-256-1, ckpt_interval=50: the whole batch through
+    the oracle (prepare in float64, v rounded once, rollout and gradient of all 4096 trajectories) and
+    through bagel_set_samples + bagel_rollout_loss_grad at full size: loss, every state, every
+    per-trajectory loss, grad_theta and grad_s0.  Then the library's own prepare at full size against the
+    oracle's float64 v, and checkpointing against the full tape on a sampled batch."""
     cfg = _cfg("large_policy")
-    got = _full_size_case("large_policy", 64)
-    # the same sampled batch without checkpointing: identical states, same gradient
-    idx = np.arange(64) * (cfg.B // 64) + 3
-    sub_cfg, sub_inp = synth.subset_trajectories(cfg, synth.make_inputs(cfg), idx)
-    ref = harness.oracle_reference(sub_cfg, sub_inp, grad=False)
-    plain = harness.gpu_rollout(sub_cfg, sub_inp, ref["v32"], ckpt_interval=0)
-    np.testing.assert_array_equal(plain["states"], got["states"])
-    np.testing.assert_allclose(plain["grad_theta"], got["grad_theta"], rtol=1e-5,
-                               atol=1e-6 * np.abs(got["grad_theta"]).max())
+    inp = synth.make_inputs(cfg)
+    ref = harness.oracle_reference(cfg, inp)
+    got = harness.gpu_rollout(cfg, inp, ref["v32"])
+    harness.assert_parity(ref, got, label="large_policy/full batch")
+    _, v_lib, v_all = _run_full_batch(cfg, inp, ref["v32"][:8], np.arange(8))
+    del v_all
+    err = np.abs(v_lib - ref["v64"][:8]).max() / np.abs(ref["v64"]).max()
+    print(f"[prepare large_policy full size] max|dv|/max|v| = {err:.3e}", flush=True)
+    assert err <= 5e-7
+    # a sampled batch with and without checkpointing: identical states, same gradient
+    idx = _sampled_indices(cfg)[:64]
+    sub_cfg, sub_inp = synth.subset_trajectories(cfg, inp, idx)
+    ck = harness.gpu_rollout(sub_cfg, sub_inp, ref["v32"][idx])
+    plain = harness.gpu_rollout(sub_cfg, sub_inp, ref["v32"][idx], ckpt_interval=0)
+    np.testing.assert_array_equal(plain["states"], ck["states"])
+    np.testing.assert_allclose(plain["grad_theta"], ck["grad_theta"], rtol=1e-5,
+                               atol=1e-6 * np.abs(ck["grad_theta"]).max())
 
 
 @pytest.mark.timeout(1500)
 def test_stress_full_size():
-    """N=8192, D=8, M=6, L=4096, B=S=8192, H=1000, policy 8-256-256-2 with bounded actions: the
-    workload bench.py times."""
-    _full_size_case("stress", 32)
+    """N=8192, D=8, M=6, L=4096, B=S=8192, H=1000, policy 8-256-256-2 with bounded actions: the workload
+    bench.py times.  The oracle cannot afford the whole batch (8.2e6 trajectory-steps), so:
+      (a) 256 strided trajectories as a batch of their own (S = B = 256, full N, L, H, policy) against the
+          oracle: everything, grad_theta included;
+      (b) the same 256 inside the full batch: states, per-trajectory losses, d loss / d s0 against the oracle;
+      (c) loss and grad_theta of the full batch against the 32 disjoint 256-trajectory sub-batches it is
+          made of, each run on its own (same v): the mean of the sub-batch losses and gradients must give
+          the full-batch values to summation-order accuracy, and one of the 32 is the oracle-checked
+          batch of (a).  Trajectories are independent (eq. (10): the loss is a mean over them), so (a) and
+          (c) together tie the full-batch loss and gradient to the oracle."""
+    import torch
+    name = "stress"
+    cfg = _cfg(name)
+    inp = synth.make_inputs(cfg)
+    stride = cfg.B // N_SAMPLED
+    idx = _sampled_indices(cfg)
+    sub_cfg, sub_inp = synth.subset_trajectories(cfg, inp, idx)
+    ref = harness.oracle_reference(sub_cfg, sub_inp)                      # oracle prepare + rollout on the sample
+    alone = harness.gpu_rollout(sub_cfg, sub_inp, ref["v32"])
+    harness.assert_parity(ref, alone, label=f"{name}/sampled batch of {N_SAMPLED}")
+
+    full, v_lib, v_all = _run_full_batch(cfg, inp, ref["v32"], idx)
+    err = np.abs(v_lib - ref["v64"]).max() / np.abs(ref["v64"]).max()
+    print(f"[prepare {name} full size] max|dv|/max|v| on the sampled rows = {err:.3e}", flush=True)
+    assert err <= 5e-7
+    _check_sampled_inside_full(name, cfg, full, ref, alone, idx)
+    assert np.isfinite(full["grad_theta"]).all() and np.isfinite(full["states"]).all()
+    assert abs(full["loss"] - full["loss_per_traj"].mean()) <= 1e-5 * abs(full["loss"])
+
+    # (c) the 32 disjoint sub-batches {k, k + 32, k + 64, ...}; k = 3 is the oracle-checked one
+    loss_sum, grad_sum = 0.0, np.zeros_like(full["grad_theta"])
+    for k in range(stride):
+        idx_k = np.arange(N_SAMPLED) * stride + k
+        cfg_k, inp_k = synth.subset_trajectories(cfg, inp, idx_k)
+        v_k = v_all[torch.from_numpy(idx_k).cuda()].cpu().numpy()
+        part = harness.gpu_rollout(cfg_k, inp_k, v_k)
+        if k == 3:
+            np.testing.assert_array_equal(part["states"], alone["states"])
+            np.testing.assert_array_equal(part["grad_theta"], alone["grad_theta"])
+        loss_sum += part["loss"]
+        grad_sum += part["grad_theta"]
+        np.testing.assert_allclose(part["loss_per_traj"], full["loss_per_traj"][idx_k], rtol=0,
+                                   atol=1e-5 * np.abs(full["loss_per_traj"]).max())
+    del v_all
+    d_loss = abs(loss_sum / stride - full["loss"]) / abs(full["loss"])
+    d_grad = np.abs(grad_sum / stride - full["grad_theta"]).max() / np.abs(full["grad_theta"]).max()
+    d_grad_l2 = np.linalg.norm(grad_sum / stride - full["grad_theta"]) / np.linalg.norm(full["grad_theta"])
+    print(f"[stress full batch vs its 32 sub-batches] loss={d_loss:.3e} grad_max={d_grad:.3e} grad_l2={d_grad_l2:.3e}",
+          flush=True)
+    assert d_loss <= 1e-5 and d_grad <= 1e-5 and d_grad_l2 <= 1e-5
 
 
 # ------------------------------------------------------------------ one evaluation of the samples
