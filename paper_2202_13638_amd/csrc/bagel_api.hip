@@ -121,21 +121,23 @@ static const char *plan_sample_eval(bagel_ctx *c)
                                         : ((chunk >= 512 && L / chunk >= 8) ? chunk / 2 : chunk);
     c->CK = env_int("BAGEL_CK", ck_default);
     c->CL = env_int("BAGEL_CL", cl_default);
-    c->CK = (c->CK + 3) & ~3;
-    c->CL = (c->CL + 3) & ~3;
+    c->CK = (c->CK + 7) & ~7;         // the sample-evaluation loops take two float4 (eight points) per trip
+    c->CL = (c->CL + 7) & ~7;
     c->nck = (N + c->CK - 1) / c->CK;
     c->ncl = (L + c->CL - 1) / c->CL;
     c->Np = c->nck * c->CK;
     c->Lp = c->ncl * c->CL;
     c->units = M * (c->nck + c->ncl);
     c->groups = M * ((c->nck + 3) / 4 + (c->ncl + 3) / 4);
-    // The table form of exp2 pays when the launch has many workgroups per compute unit (see
-    // gp_step.hip).  Measured, table vs polynomial: stress (4608 workgroups) 0.628 vs 0.647 ms per
-    // launch; large policy (3072) 0.0892 vs 0.0872; medium (1280) 0.0346 vs 0.0258; small 0.0176 vs 0.0124.
+    // The table form of the kernel-row loop (gp_step.hip) pays once the launch has a few workgroups per
+    // compute unit; below that its extra set-up per workgroup (the table copy) and the wait counter its
+    // LDS read shares with the scalar loads cost more than its five fewer instructions per training point
+    // save.  Measured on MI355X, table vs general form, per launch: stress (4608 workgroups) 0.561 vs
+    // 0.60 ms; large policy (3072) 83.7 vs 86.4 us; medium (1280) 20.9 vs 22.4 us; small (192) 9.6 vs 9.2 us.
     {
         const int64_t wgs = (int64_t)((B + 63) / 64) * c->groups;
         const int tab = env_int("BAGEL_EXP_TABLE", 0);         // 1: off, 2: on, otherwise by launch size
-        c->exp_table = tab == 2 ? true : (tab == 1 ? false : wgs >= 256 * 16);
+        c->exp_table = tab == 2 ? true : (tab == 1 ? false : wgs >= 1024);
     }
     if (c->units > 65535) return "too many work units (M * (N + L) / 32 must stay below 65536)";
     return nullptr;

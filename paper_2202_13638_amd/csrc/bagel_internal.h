@@ -23,7 +23,7 @@ struct bagel_ctx {
 
     // ---- model, internal layout --------------------------------------------------------
     int Np, Lp;                  // N and L rounded up to a whole number of chunks
-    int CK, CL;                  // training points / features per work unit (multiples of 4)
+    int CK, CL;                  // training points / features per work unit (multiples of 8)
     int nck, ncl;                // chunks per output
     int units;                   // M * (nck + ncl)
     int groups;                  // M * (ceil(nck/4) + ceil(ncl/4)): four units per workgroup and partial sum

@@ -35,6 +35,9 @@
 
 namespace {
 
+#ifndef BAGEL_MIN_WAVES
+#define BAGEL_MIN_WAVES(D) ((D) <= 8 ? 8 : ((D) <= 11 ? 5 : 4))
+#endif
 #ifndef BAGEL_SAME_ROWS
 #define BAGEL_SAME_ROWS 0      // timing experiment only: every work unit reads the first unit's rows
 #endif
@@ -134,7 +137,7 @@ __device__ __forceinline__ void combine_waves(double (*red)[RC][64], int wave, i
 // with the scalar loads of the shared operands, so every look-up also waits for the operand rows
 // requested ahead; small launches take the general loop only.
 template <int D, bool JAC, bool NEAR>
-__global__ __launch_bounds__(BAGEL_BLOCK) __attribute__((amdgpu_waves_per_eu(D <= 8 ? 8 : (D <= 11 ? 5 : 4), 8))) void gp_step_kernel(
+__global__ __launch_bounds__(BAGEL_BLOCK) __attribute__((amdgpu_waves_per_eu(BAGEL_MIN_WAVES(D), 8))) void gp_step_kernel(
     const double *__restrict__ Xs, const double *__restrict__ Xn, const double *__restrict__ Os,
     const float4 *__restrict__ Of, const double *__restrict__ A, const float4 *__restrict__ v4,
     const float4 *__restrict__ w4,
@@ -189,35 +192,62 @@ __global__ __launch_bounds__(BAGEL_BLOCK) __attribute__((amdgpu_waves_per_eu(D <
         if (NEAR) wave_near = near_ok[0] != 0 && !__any(!(q >= -250.0));
         if (NEAR && wave_near) {
             const double *__restrict__ Xr = Xn + row0;
+            const int last = n_iter - 1;
             // leading polynomial coefficients pinned to register classes: the first Horner step is then a
             // single three-operand FMA (an FMA takes at most one scalar operand)
             double ca = 0x1.c726cfe5bfc26p-125, cb = 0x1.ebfbd4e173a43p-83;
             asm volatile("" : "+s"(ca), "+v"(cb));
             {
-                for (int n4 = 0; n4 < n_iter; ++n4) {
-                    const v4f vv = stream_load(vdesc, voff, (unsigned)n4 * vstep);
-                    const float vj[4] = {vv.x, vv.y, vv.z, vv.w};
+                // One training point with its row in rc; the next point's row is requested into rn right at
+                // the start, so that its trip through the scalar cache overlaps this point's arithmetic and
+                // table look-up instead of preceding the next point's.
+                auto one_point = [&](const double (&rc)[D + 1], double (&rn)[D + 1], const double *__restrict__ next,
+                                     float vf) {
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const double *__restrict__ r = Xr + (size_t)(n4 * 4 + j) * (D + 1);
-                        double t = x[0] * r[0];
+                    for (int d = 0; d <= D; ++d) rn[d] = next[d];
+                    __builtin_amdgcn_sched_barrier(0);
+                    double t = x[0] * rc[0];
 #pragma unroll
-                        for (int d = 1; d < D; ++d) t = fma(x[d], r[d], t);
-                        const double s = t + r[D];
-                        const int hs = __double2hiint(s);
-                        const double T = tab[hs & 255];
-                        const double g = (double)(unsigned)__double2loint(s);
-                        double p = fma(ca, g, cb);
-                        p = fma(p, g, 0x1.62e42fefcb0c8p-41);
-                        p = fma(p, g, 1.0);
-                        const double sc = __hiloint2double(__double2hiint(T) + (hs << 12), __double2loint(T));
-                        const double vk = (double)vj[j] * (sc * p);
-                        u += vk;
-                        if (JAC) {
+                    for (int d = 1; d < D; ++d) t = fma(x[d], rc[d], t);
+                    const double s = t + rc[D];
+                    const int hs = __double2hiint(s);
+                    const double T = tab[hs & 255];
+                    const double g = (double)(unsigned)__double2loint(s);
+                    double p = fma(ca, g, cb);
+                    p = fma(p, g, 0x1.62e42fefcb0c8p-41);
+                    p = fma(p, g, 1.0);
+                    const double sc = __hiloint2double(__double2hiint(T) + (hs << 12), __double2loint(T));
+                    const double vk = (double)vf * (sc * p);
+                    u += vk;
+                    if (JAC) {
 #pragma unroll
-                            for (int d = 0; d < D; ++d) G[d] = fma(vk, r[d], G[d]);
-                        }
+                        for (int d = 0; d < D; ++d) G[d] = fma(vk, rc[d], G[d]);
                     }
+                    __builtin_amdgcn_sched_barrier(0);
+                };
+                double ra[D + 1], rb[D + 1];
+#pragma unroll
+                for (int d = 0; d <= D; ++d) ra[d] = Xr[d];
+                // rows follow each other in memory; the request past the unit's last row reads the first
+                // row of the next unit or, after the very last one, stays inside the table (see below)
+                auto four_points = [&](const v4f vv, int n4) {
+                    const double *__restrict__ r = Xr + (size_t)(n4 * 4) * (D + 1);
+                    one_point(ra, rb, r + 1 * (D + 1), vv.x);
+                    one_point(rb, ra, r + 2 * (D + 1), vv.y);
+                    one_point(ra, rb, r + 3 * (D + 1), vv.z);
+                    one_point(rb, ra, n4 < last ? r + 4 * (D + 1) : Xr, vv.w);
+                };
+                // The stream is requested one float4 ahead, alternating between two register sets (a request
+                // past the end repeats the last row): HBM latency under load is several times a wave's own
+                // work on four points, and the loop was idle waiting for it.
+                // (CK is a multiple of 8: the loop body handles two float4 without a branch, which keeps
+                // the compiler from moving a request down to its use.)
+                v4f va = stream_load(vdesc, voff, 0u);
+                for (int n4 = 0; n4 < n_iter; n4 += 2) {
+                    const v4f vb = stream_load(vdesc, voff, (unsigned)(n4 + 1) * vstep);
+                    four_points(va, n4);
+                    va = stream_load(vdesc, voff, (unsigned)(n4 + 2 < last ? n4 + 2 : last) * vstep);
+                    four_points(vb, n4 + 1);
                 }
             }
             const double eq = exp2_poly(q, 1.192611307487823e-07, 2.409383341728244e-06);
@@ -238,23 +268,42 @@ __global__ __launch_bounds__(BAGEL_BLOCK) __attribute__((amdgpu_waves_per_eu(D <
             const double *__restrict__ Xr = Xs + row0;
             double ca = 1.192611307487823e-07, cb = 2.409383341728244e-06;
             asm volatile("" : "+s"(ca), "+v"(cb));
-            for (int n4 = 0; n4 < n_iter; ++n4) {
-                const v4f vv = stream_load(vdesc, voff, (unsigned)n4 * vstep);
-                const float vj[4] = {vv.x, vv.y, vv.z, vv.w};
+            // same pipeline as the table form: the next point's row is requested while this one is worked
+            // on, the stream one float4 ahead
+            const int last = n_iter - 1;
+            auto one_point = [&](const double (&rc)[D + 1], double (&rn)[D + 1], const double *__restrict__ next,
+                                 float vf) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const double *__restrict__ r = Xr + (size_t)(n4 * 4 + j) * (D + 1);
-                    double t = qs + r[D];
+                for (int d = 0; d <= D; ++d) rn[d] = next[d];
+                __builtin_amdgcn_sched_barrier(0);
+                double t = qs + rc[D];
 #pragma unroll
-                    for (int d = 0; d < D; ++d) t = fma(xs[d], r[d], t);
-                    const double k = exp2_poly(t, ca, cb);
-                    const double vk = (double)vj[j] * k;
-                    u += vk;
-                    if (JAC) {
+                for (int d = 0; d < D; ++d) t = fma(xs[d], rc[d], t);
+                const double k = exp2_poly(t, ca, cb);
+                const double vk = (double)vf * k;
+                u += vk;
+                if (JAC) {
 #pragma unroll
-                        for (int d = 0; d < D; ++d) G[d] = fma(vk, r[d], G[d]);
-                    }
+                    for (int d = 0; d < D; ++d) G[d] = fma(vk, rc[d], G[d]);
                 }
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            double ra[D + 1], rb[D + 1];
+#pragma unroll
+            for (int d = 0; d <= D; ++d) ra[d] = Xr[d];
+            auto four_points = [&](const v4f vv, int n4) {
+                const double *__restrict__ r = Xr + (size_t)(n4 * 4) * (D + 1);
+                one_point(ra, rb, r + 1 * (D + 1), vv.x);
+                one_point(rb, ra, r + 2 * (D + 1), vv.y);
+                one_point(ra, rb, r + 3 * (D + 1), vv.z);
+                one_point(rb, ra, n4 < last ? r + 4 * (D + 1) : Xr, vv.w);
+            };
+            v4f va = stream_load(vdesc, voff, 0u);
+            for (int n4 = 0; n4 < n_iter; n4 += 2) {
+                const v4f vb = stream_load(vdesc, voff, (unsigned)(n4 + 1) * vstep);
+                four_points(va, n4);
+                va = stream_load(vdesc, voff, (unsigned)(n4 + 2 < last ? n4 + 2 : last) * vstep);
+                four_points(vb, n4 + 1);
             }
         }
         combine_waves<D, JAC, RC>(red, wave, lane, live, out, B, false, u, G);
@@ -288,29 +337,56 @@ __global__ __launch_bounds__(BAGEL_BLOCK) __attribute__((amdgpu_waves_per_eu(D <
             f4v acc[NQ];
 #pragma unroll
             for (int qd = 0; qd < NQ; ++qd) acc[qd] = f4v{0.0f, 0.0f, 0.0f, 0.0f};
-            for (int l4 = 0; l4 < n_iter; ++l4) {
-                const v4f ww = stream_load(wdesc, woff, (unsigned)l4 * wstep);
+            const int last = n_iter - 1;         // CL is a multiple of 8: two float4 per trip, no branch
+            auto one_feature = [&](const double (&rc)[D + 1], double (&rn)[D + 1], const double *__restrict__ next,
+                                   float wf, const v4f (&bq)[NQ], int j) {
+#pragma unroll
+                for (int d = 0; d <= D; ++d) rn[d] = next[d];
+                __builtin_amdgcn_sched_barrier(0);
+                // product first, phase offset last: both are scalar operands, and an FMA takes only one
+                double z = x[0] * rc[0];
+#pragma unroll
+                for (int d = 1; d < D; ++d) z = fma(x[d], rc[d], z);
+                z += rc[D];
+                // z is the phase in revolutions; its fractional part is exact in float64 and the
+                // hardware sin / cos take revolutions (absolute error about one float32 ulp)
+                const float y = (float)__builtin_amdgcn_fract(z);
+                const float sn = __builtin_amdgcn_sinf(y);
+                const float cs = __builtin_amdgcn_cosf(y);
+                p = fmaf(wf, cs, p);
+                const float ws = wf * sn;
+#pragma unroll
+                for (int qd = 0; qd < NQ; ++qd)
+                    acc[qd] = __builtin_amdgcn_mfma_f32_4x4x1f32(ws, bq[qd][j], acc[qd], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            double fa[D + 1], fb[D + 1];
+#pragma unroll
+            for (int d = 0; d <= D; ++d) fa[d] = Or[d];
+            // four features whose weights are in ww; `next` receives the stream's float4 of step l4_next,
+            // requested after this step's B operands (loads return in order: the wait for the operands,
+            // which hit in cache, must not include the stream's trip to HBM)
+            auto four_features = [&](const v4f ww, int l4, v4f &next, int l4_next) {
                 v4f bq[NQ];
 #pragma unroll
                 for (int qd = 0; qd < NQ; ++qd)
                     bq[qd] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(odesc, ooff + 16u * qd, (unsigned)l4 * ostep, 0));
-                const float wj[4] = {ww.x, ww.y, ww.z, ww.w};
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const double *__restrict__ r = Or + (size_t)(l4 * 4 + j) * (D + 1);
-                    double z = x[0] * r[0];
-#pragma unroll
-                    for (int d = 1; d < D; ++d) z = fma(x[d], r[d], z);
-                    z += r[D];
-                    const float y = (float)__builtin_amdgcn_fract(z);
-                    const float sn = __builtin_amdgcn_sinf(y);
-                    const float cs = __builtin_amdgcn_cosf(y);
-                    p = fmaf(wj[j], cs, p);
-                    const float ws = wj[j] * sn;
-#pragma unroll
-                    for (int qd = 0; qd < NQ; ++qd)
-                        acc[qd] = __builtin_amdgcn_mfma_f32_4x4x1f32(ws, bq[qd][j], acc[qd], 0, 0, 0);
-                }
+                __builtin_amdgcn_sched_barrier(0);
+                next = stream_load(wdesc, woff, (unsigned)l4_next * wstep);
+                __builtin_amdgcn_sched_barrier(0);
+                // each feature's row was requested while the previous feature was being worked on (see the
+                // kernel-row loop); the request after the unit's last row stays inside the table
+                const double *__restrict__ r = Or + (size_t)(l4 * 4) * (D + 1);
+                one_feature(fa, fb, r + 1 * (D + 1), ww.x, bq, 0);
+                one_feature(fb, fa, r + 2 * (D + 1), ww.y, bq, 1);
+                one_feature(fa, fb, r + 3 * (D + 1), ww.z, bq, 2);
+                one_feature(fb, fa, l4 < last ? r + 4 * (D + 1) : Or, ww.w, bq, 3);
+            };
+            // the stream of w one float4 ahead in alternating register sets, as in the kernel-row loop
+            v4f wa = stream_load(wdesc, woff, 0u), wb = wa;
+            for (int l4 = 0; l4 < n_iter; l4 += 2) {
+                four_features(wa, l4, wb, l4 + 1);
+                four_features(wb, l4 + 1, wa, l4 + 2 < last ? l4 + 2 : last);
             }
             // every wave, wave 0 included, hands its sums over through LDS: that is also the transposition
             // from the accumulator layout (lane = column, register = trajectory) to lane = trajectory
@@ -327,22 +403,37 @@ __global__ __launch_bounds__(BAGEL_BLOCK) __attribute__((amdgpu_waves_per_eu(D <
             double u = 0.0, G[D];
             combine_waves<D, JAC, RC>(red, wave, lane, live, out, B, true, u, G);
         } else {
-            for (int l4 = 0; l4 < n_iter; ++l4) {
-                const v4f ww = stream_load(wdesc, woff, (unsigned)l4 * wstep);
-                const float wj[4] = {ww.x, ww.y, ww.z, ww.w};
+            // value only: the same pipeline without the Jacobian sums
+            const int last = n_iter - 1;
+            auto one_feature = [&](const double (&rc)[D + 1], double (&rn)[D + 1], const double *__restrict__ next,
+                                   float wf) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const double *__restrict__ r = Or + (size_t)(l4 * 4 + j) * (D + 1);
-                    // product first, phase offset last: both are scalar operands, and an FMA takes only one
-                    double z = x[0] * r[0];
+                for (int d = 0; d <= D; ++d) rn[d] = next[d];
+                __builtin_amdgcn_sched_barrier(0);
+                double z = x[0] * rc[0];
 #pragma unroll
-                    for (int d = 1; d < D; ++d) z = fma(x[d], r[d], z);
-                    z += r[D];
-                    // z is the phase in revolutions; its fractional part is exact in float64 and the
-                    // hardware sin / cos take revolutions (absolute error about one float32 ulp)
-                    const float y = (float)__builtin_amdgcn_fract(z);
-                    p = fmaf(wj[j], __builtin_amdgcn_cosf(y), p);
-                }
+                for (int d = 1; d < D; ++d) z = fma(x[d], rc[d], z);
+                z += rc[D];
+                const float y = (float)__builtin_amdgcn_fract(z);
+                p = fmaf(wf, __builtin_amdgcn_cosf(y), p);
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            double fa[D + 1], fb[D + 1];
+#pragma unroll
+            for (int d = 0; d <= D; ++d) fa[d] = Or[d];
+            auto four_features = [&](const v4f ww, int l4) {
+                const double *__restrict__ r = Or + (size_t)(l4 * 4) * (D + 1);
+                one_feature(fa, fb, r + 1 * (D + 1), ww.x);
+                one_feature(fb, fa, r + 2 * (D + 1), ww.y);
+                one_feature(fa, fb, r + 3 * (D + 1), ww.z);
+                one_feature(fb, fa, l4 < last ? r + 4 * (D + 1) : Or, ww.w);
+            };
+            v4f wa = stream_load(wdesc, woff, 0u);
+            for (int l4 = 0; l4 < n_iter; l4 += 2) {
+                const v4f wb = stream_load(wdesc, woff, (unsigned)(l4 + 1) * wstep);
+                four_features(wa, l4);
+                wa = stream_load(wdesc, woff, (unsigned)(l4 + 2 < last ? l4 + 2 : last) * wstep);
+                four_features(wb, l4 + 1);
             }
             double u = (double)p, G[D];
             combine_waves<D, JAC, RC>(red, wave, lane, live, out, B, false, u, G);
