@@ -77,7 +77,7 @@ static hipError_t dev_alloc(bagel_ctx *c, T **p, size_t count)
 
 static void free_all(bagel_ctx *c)
 {
-    void *ptrs[] = {c->Xs, c->Xn, c->near_ok, c->Os, c->Of, c->A, c->amp, c->exp_tab, c->v4, c->w4, c->xbuf, c->part, c->lpt, c->lam,
+    void *ptrs[] = {c->Xs, c->Xn, c->near_ok, c->Os, c->Of, c->A, c->amp, c->exp_tab, c->v4, c->w4, c->xbuf, c->part, c->xbuf_alt, c->part_alt, c->lpt, c->lam,
                     c->tape_s, c->tape_J, c->tape_h[0], c->tape_h[1], c->tape_h[2], c->tape_a, c->tape_d[0],
                     c->tape_d[1], c->tape_d[2], c->wpad_f, c->wpad_b, c->gsplit, c->gacc, c->fbuf, c->gtheta, c->post_alpha, c->post_Kinv, c->post_Kx, c->post_sums};
     for (void *p : ptrs)
@@ -139,7 +139,7 @@ static const char *plan_sample_eval(bagel_ctx *c)
         const int tab = env_int("BAGEL_EXP_TABLE", 0);         // 1: off, 2: on, otherwise by launch size
         c->exp_table = tab == 2 ? true : (tab == 1 ? false : wgs >= 1024);
     }
-    if (c->units > 65535) return "too many work units (M * (N + L) / 32 must stay below 65536)";
+    if (c->units > 65535 - BAGEL_MAX_STATE) return "too many work units (M * (N + L) / 32 must stay below 65527)";
     return nullptr;
 }
 
@@ -194,6 +194,8 @@ extern "C" int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_s
     ALLOC(c->w4, (size_t)M * (c->Lp / 4) * dims->S);
     ALLOC(c->xbuf, (size_t)D * Bz);
     ALLOC(c->part, (size_t)c->groups * (1 + D) * Bz);
+    ALLOC(c->xbuf_alt, (size_t)D * Bz);
+    ALLOC(c->part_alt, (size_t)c->groups * (1 + D) * Bz);
     ALLOC(c->lpt, Bz);
     ALLOC(c->lam, (size_t)dims->d_s * Bz);
     ALLOC(c->fbuf, (size_t)M * Bz);
@@ -284,7 +286,7 @@ extern "C" int bagel_prepare_samples(bagel_ctx *c, const float *X, const float *
     return BAGEL_OK;
 }
 
-static hipError_t gp_step_timed(bagel_ctx *c, bool jac, const float *xi_t = nullptr);
+static hipError_t gp_step_timed(bagel_ctx *c, bool jac, const float *xi_t = nullptr, float *prev_jac = nullptr);
 
 extern "C" int bagel_sample_eval(bagel_ctx *c, const float *x, float *f, float *jac)
 {
@@ -407,7 +409,7 @@ extern "C" int bagel_sample_eval_static(const bagel_dims *dims, void *hip_stream
     STATIC_HIP(bagel_launch_build_model(&c, X, lengthscale, signal_var, omega, phase));
     STATIC_HIP(bagel_launch_pack_samples(&c, w, v));
     STATIC_HIP(bagel_launch_eval_io(&c, 0, x, nullptr));
-    STATIC_HIP(bagel_launch_gp_step(&c, jac != nullptr));
+    STATIC_HIP(bagel_launch_gp_step(&c, jac != nullptr, nullptr));
     STATIC_HIP(bagel_launch_finalize(&c, jac != nullptr, -1, jac));
     STATIC_HIP(bagel_launch_eval_io(&c, 1, nullptr, f));
 #undef STATIC_HIP
@@ -417,7 +419,7 @@ extern "C" int bagel_sample_eval_static(const bagel_dims *dims, void *hip_stream
 
 // the sample-evaluation launch (pathwise samples, or with xi_t the launches of one posterior step),
 // optionally bracketed by events
-static hipError_t gp_step_timed(bagel_ctx *c, bool jac, const float *xi_t)
+static hipError_t gp_step_timed(bagel_ctx *c, bool jac, const float *xi_t, float *prev_jac)
 {
     bool timed = false;
     if (c->prof_every > 0) {
@@ -427,7 +429,7 @@ static hipError_t gp_step_timed(bagel_ctx *c, bool jac, const float *xi_t)
             if (e != hipSuccess) return e;
         }
     }
-    hipError_t e = xi_t ? bagel_launch_posterior_step(c, jac, xi_t) : bagel_launch_gp_step(c, jac);
+    hipError_t e = xi_t ? bagel_launch_posterior_step(c, jac, xi_t) : bagel_launch_gp_step(c, jac, prev_jac);
     if (timed && e == hipSuccess) {
         e = hipEventRecord(c->prof_ev[2 * c->prof_used + 1], c->stream);
         c->prof_used++;
@@ -471,17 +473,32 @@ extern "C" int bagel_profile_read(bagel_ctx *c, double *kernel_ms, int *launches
 // Forward steps 0 .. H-1 from the state in xbuf and the policy input in tape slot 0.  jac: the sample
 // evaluation also returns its Jacobian, kept in slot t of the Jacobian tape; acts: the policy's
 // activations are kept in slot t of their tape (otherwise every step reuses slot 0).
+// Only the value sums of a step are on the critical path (state, cost, next action); the Jacobian sums
+// of the pathwise sampler, eight ninths of the partial sums with D = 8, feed nothing but the tape, so
+// they are added up one step late, by extra workgroups inside the next step's sample evaluation (after
+// the last step: by a launch of their own).  The two steps' inputs and sums live in buffers that swap.
 static int run_forward(bagel_ctx *c, bool jac, bool acts, bool write_tape_s, const float *theta, const float *goals,
                        float *states_out)
 {
     const int H = c->dm.H;
+    const bool posterior = c->cur_xi != nullptr;
+    const size_t jslot = (size_t)c->M * c->D * c->dm.B;
     for (int t = 0; t < H; ++t) {
         const int next_slot = t + 1 < H ? (acts ? t + 1 : 0) : -1;
         // the policy of the first step runs on its own; every later one is part of the previous step's tail
         if (t == 0) BAGEL_HIP(c, bagel_launch_policy_forward(c, 0, theta));
-        BAGEL_HIP(c, gp_step_timed(c, jac, c->cur_xi ? c->cur_xi + (size_t)t * c->dm.B * c->M : nullptr));
+        float *prev_jac = (jac && !posterior && t > 0) ? c->tape_J + (size_t)(t - 1) * jslot : nullptr;
+        BAGEL_HIP(c, gp_step_timed(c, jac, posterior ? c->cur_xi + (size_t)t * c->dm.B * c->M : nullptr, prev_jac));
         BAGEL_HIP(c, bagel_launch_step_tail(c, t, t, next_slot, jac, true, write_tape_s, theta, goals, states_out,
-                                            c->cur_xi != nullptr));
+                                            posterior));
+        double *tx = c->xbuf; c->xbuf = c->xbuf_alt; c->xbuf_alt = tx;
+        double *tp = c->part; c->part = c->part_alt; c->part_alt = tp;
+    }
+    if (jac && !posterior) {
+        // the last step's sums are in what is now the alternate pair
+        double *tx = c->xbuf; c->xbuf = c->xbuf_alt; c->xbuf_alt = tx;
+        double *tp = c->part; c->part = c->part_alt; c->part_alt = tp;
+        BAGEL_HIP(c, bagel_launch_jac_reduce(c, c->tape_J + (size_t)(H - 1) * jslot));
     }
     return BAGEL_OK;
 }

@@ -42,7 +42,10 @@ struct bagel_ctx {
 
     // ---- per-step workspace (lane = trajectory, arrays are [component][B]) ---------------
     double *xbuf;                // [D][B]   GP input of the current step; rows 0..d_s-1 are the state (float64)
-    double *part;                // [groups][1+D][B] partial sums of one step
+    double *part;                // [groups][1+D][B] partial sums of the current step
+    double *xbuf_alt, *part_alt; // the same two buffers for the neighbouring step: a rollout swaps them with
+                                 // xbuf / part after every step, so that the Jacobian sums of step t-1 can be
+                                 // added up while step t is evaluated (both need their own inputs and sums)
     double *lpt;                 // [B] running cost per trajectory
     double *lam;                 // [d_s][B] adjoint of the state between the segments of a checkpointed sweep
     double *fbuf;                // [M][B] sample values of the current step, summed over work units
@@ -96,7 +99,11 @@ struct bagel_ctx {
 
 // ---- gp_step.hip -------------------------------------------------------------------------
 // One evaluation of all function samples at xbuf: partial sums per work unit into ctx->part.
-hipError_t bagel_launch_gp_step(bagel_ctx *ctx, bool jac);
+// prev_jac: if not null, the same launch also adds up the Jacobian sums of the previous step (in
+// ctx->part_alt, evaluated at ctx->xbuf_alt) into prev_jac[M][D][B] (a slot of the Jacobian tape).
+hipError_t bagel_launch_gp_step(bagel_ctx *ctx, bool jac, float *prev_jac);
+// The Jacobian sums in ctx->part (evaluated at ctx->xbuf) added up into jdst[M][D][B], on their own.
+hipError_t bagel_launch_jac_reduce(bagel_ctx *ctx, float *jdst);
 
 // ---- model.hip ---------------------------------------------------------------------------
 hipError_t bagel_launch_build_model(bagel_ctx *ctx, const float *X, const float *ell, const float *sf2,
@@ -114,9 +121,12 @@ hipError_t bagel_launch_finalize(bagel_ctx *ctx, bool jac, int slot, float *jac_
 // ---- policy.hip --------------------------------------------------------------------------
 hipError_t bagel_launch_pack_theta(bagel_ctx *ctx, const float *theta);
 hipError_t bagel_launch_policy_forward(bagel_ctx *ctx, int slot, const float *theta);
-// after the sample evaluation of step t: reduce its partial sums (Jacobian into tape slot `slot` if jac),
-// advance the state, cost against goals[t], tapes, and the policy of step t+1 into tape slot next_slot
-// (no policy if t is the last step or next_slot < 0); direct: ctx->part holds final values [m][1+D][B]
+// after the sample evaluation of step t: add up the value sums in ctx->part, advance the state (read from
+// ctx->xbuf, written to ctx->xbuf_alt), cost against goals[t], state tape, and the policy of step t+1
+// into tape slot next_slot, its action into ctx->xbuf_alt (no policy if t is the last step or
+// next_slot < 0).  The caller swaps xbuf / xbuf_alt and part / part_alt afterwards.  The Jacobian sums
+// are not touched (bagel_launch_gp_step / bagel_launch_jac_reduce), except with direct: ctx->part
+// then holds final values [m][1+D][B], whose Jacobian goes to tape slot `slot` here if jac.
 hipError_t bagel_launch_step_tail(bagel_ctx *ctx, int t, int slot, int next_slot, bool jac, bool add_cost,
                                   bool write_tape_s, const float *theta, const float *goals,
                                   float *states_out, bool direct);

@@ -115,6 +115,56 @@ __device__ __forceinline__ void combine_waves(double (*red)[RC][64], int wave, i
     }
 }
 
+// ---- Jacobian sums of one step, added up --------------------------------------------------------
+// J[m][d] = -amp_m (2 pi) sum_g Gr_g[d] + ln2 (sum_g Gk_g[d] - log2(e)/l_md^2 x_d sum_g u_g)   (groups in order)
+// for the 64 trajectories of one tile, from the partial sums `part` of a sample evaluation at x; the
+// result goes to a slot of the Jacobian tape, jdst[M][D][B] (float32).  Nothing on the critical path of
+// a rollout needs J, so this runs as M extra rows of workgroups (one per output) inside the NEXT step's
+// sample evaluation (or, after the last step, as a launch of its own).  256 threads: the four waves
+// share the D entries of the output.
+struct jac_sums {
+    const double *part;      // [groups][1+D][B]
+    const double *x;         // [D][B] inputs the sums were evaluated at
+    const double *A, *amp;   // [M][D], [M]
+    float *jdst;             // [M][D][B]
+};
+
+__device__ __forceinline__ double sum_in_order(const double *__restrict__ p, int n, size_t stride)
+{
+    double s = 0.0;
+    for (int c0 = 0; c0 < n; c0 += 4) {      // four loads in flight at a time, added in order
+        double v[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = (c0 + i < n) ? p[(size_t)(c0 + i) * stride] : 0.0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) s += v[i];
+    }
+    return s;
+}
+
+__device__ __forceinline__ void jacobian_tile(const jac_sums &j, int tile, int m, int B, int D, int M, int ngk, int ngl)
+{
+    constexpr double LN2 = 0.69314718055994530942, TWO_PI = 6.28318530717958647693;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int b = tile * 64 + lane;
+    if (b >= B) return;
+    const size_t stride = (size_t)(1 + D) * B;
+    const double *pk = j.part + (size_t)(m * ngk) * stride + b;
+    const double *pr = j.part + (size_t)(M * ngk + m * ngl) * stride + b;
+    const double u = sum_in_order(pk, ngk, stride);
+    for (int d = wave; d < D; d += BAGEL_BLOCK / 64) {
+        const double gk = sum_in_order(pk + (size_t)(1 + d) * B, ngk, stride);
+        const double gr = sum_in_order(pr + (size_t)(1 + d) * B, ngl, stride);
+        const double xd = j.x[(size_t)d * B + b];
+        j.jdst[(size_t)(m * D + d) * B + b] = (float)(-j.amp[m] * TWO_PI * gr + LN2 * (gk - j.A[m * D + d] * xd * u));
+    }
+}
+
+__global__ __launch_bounds__(BAGEL_BLOCK) void jac_reduce_kernel(jac_sums j, int B, int D, int M, int ngk, int ngl)
+{
+    jacobian_tile(j, blockIdx.x, blockIdx.y, B, D, M, ngk, ngl);
+}
+
 // NEAR adds the fast form of the kernel-row loop for the normal case that data and trajectory are
 // within about 19 length scales of the origin; the loop above is then the fallback of a wave that
 // holds a trajectory further out, or of a model with training points further out (near_ok == 0).
@@ -143,8 +193,14 @@ __global__ __launch_bounds__(BAGEL_BLOCK) __attribute__((amdgpu_waves_per_eu(BAG
     const float4 *__restrict__ w4,
     const double *__restrict__ xbuf, double *__restrict__ part, const double *__restrict__ exp_tab,
     const int *__restrict__ near_ok, int B, int S, int per_sample, int Np, int Lp, int CK, int CL, int nck, int ncl,
-    int M)
+    int M, jac_sums prev)
 {
+    // M rows of workgroups past the work units: the previous step's Jacobian sums (see jacobian_tile)
+    if ((int)blockIdx.y >= M * (((nck + 3) >> 2) + ((ncl + 3) >> 2))) {
+        jacobian_tile(prev, blockIdx.x, (int)blockIdx.y - M * (((nck + 3) >> 2) + ((ncl + 3) >> 2)), B, D, M,
+                      (nck + 3) >> 2, (ncl + 3) >> 2);
+        return;
+    }
     // Sums handed from wave to wave at the end.  Slot 3 is used only by the feature units of a
     // Jacobian launch; the kernel-row units keep the table of the table form there.
     constexpr int RC = 1 + D > 4 ? 1 + D : 4;      // rows per slot: at least the 256 entries of the exp2 table
@@ -442,37 +498,46 @@ __global__ __launch_bounds__(BAGEL_BLOCK) __attribute__((amdgpu_waves_per_eu(BAG
 }
 
 template <int D, bool JAC, bool NEAR>
-void launch_variant(bagel_ctx *c)
+void launch_variant(bagel_ctx *c, float *prev_jac)
 {
-    dim3 grid((c->dm.B + 63) / 64, c->groups);
+    dim3 grid((c->dm.B + 63) / 64, c->groups + (prev_jac ? c->M : 0));
     const int per_sample = c->dm.B / c->dm.S;
+    const jac_sums prev = {c->part_alt, c->xbuf_alt, c->A, c->amp, prev_jac};
     hipLaunchKernelGGL((gp_step_kernel<D, JAC, NEAR>), grid, dim3(BAGEL_BLOCK), 0, c->stream, c->Xs, c->Xn, c->Os,
-                       reinterpret_cast<const float4 *>(c->Of), c->A, c->v4, c->w4, c->xbuf, c->part, c->exp_tab, c->near_ok, c->dm.B, c->dm.S, per_sample, c->Np,
-                       c->Lp, c->CK, c->CL, c->nck, c->ncl, c->M);
+                       reinterpret_cast<const float4 *>(c->Of), c->A, c->v4, c->w4, c->xbuf, c->part, c->exp_tab,
+                       c->near_ok, c->dm.B, c->dm.S, per_sample, c->Np, c->Lp, c->CK, c->CL, c->nck, c->ncl, c->M, prev);
 }
 
 template <int D>
-hipError_t launch_d(bagel_ctx *c, bool jac)
+hipError_t launch_d(bagel_ctx *c, bool jac, float *prev_jac)
 {
     if (c->exp_table) {
-        if (jac) launch_variant<D, true, true>(c);
-        else launch_variant<D, false, true>(c);
+        if (jac) launch_variant<D, true, true>(c, prev_jac);
+        else launch_variant<D, false, true>(c, prev_jac);
     } else {
-        if (jac) launch_variant<D, true, false>(c);
-        else launch_variant<D, false, false>(c);
+        if (jac) launch_variant<D, true, false>(c, prev_jac);
+        else launch_variant<D, false, false>(c, prev_jac);
     }
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t bagel_launch_gp_step(bagel_ctx *c, bool jac)
+hipError_t bagel_launch_gp_step(bagel_ctx *c, bool jac, float *prev_jac)
 {
     switch (c->D) {
-#define CASE(n) case n: return launch_d<n>(c, jac);
+#define CASE(n) case n: return launch_d<n>(c, jac, prev_jac);
         CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(7) CASE(8) CASE(9) CASE(10) CASE(11) CASE(12)
         CASE(13) CASE(14) CASE(15) CASE(16)
 #undef CASE
     }
     return hipErrorInvalidValue;
+}
+
+hipError_t bagel_launch_jac_reduce(bagel_ctx *c, float *jdst)
+{
+    const jac_sums j = {c->part, c->xbuf, c->A, c->amp, jdst};
+    hipLaunchKernelGGL(jac_reduce_kernel, dim3((c->dm.B + 63) / 64, c->M), dim3(BAGEL_BLOCK), 0, c->stream, j, c->dm.B, c->D,
+                       c->M, (c->nck + 3) / 4, (c->ncl + 3) / 4);
+    return hipGetLastError();
 }

@@ -420,11 +420,14 @@ __global__ __launch_bounds__(PW * 64) void policy_replay_kernel(policy_args a, r
 }
 
 // ---- end of step t and policy of step t+1 in one launch -------------------------------------
-// After the sample evaluation of step t: add up its partial sums (value f and Jacobian J_f, as in
-// finalize_kernel), advance the state s_{t+1} = s_t + f (state increments as GP targets, Sec. III-A),
-// add the cost of s_{t+1} against the goal of step t (Algorithm 1, return accumulation), write the
-// tapes, and - unless this was the last step - run pi_theta([s_{t+1} ; g_{t+1}]) for the same 32
-// trajectories straight from LDS.  The weights are requested before the reduction starts.
+// After the sample evaluation of step t: add up the value sums of its work units (f; the Jacobian sums
+// are added up off the critical path, see gp_step.hip), advance the state s_{t+1} = s_t + f (state
+// increments as GP targets, Sec. III-A), add the cost of s_{t+1} against the goal of step t (Algorithm 1,
+// return accumulation), write the state tape, and - unless this was the last step - run
+// pi_theta([s_{t+1} ; g_{t+1}]) for the same 32 trajectories straight from LDS.  The weights are
+// requested before the reduction starts.  The state is read from one input buffer and written, with the
+// new action, to the other (the caller swaps them), so that the inputs of step t stay intact for the
+// deferred Jacobian sums.
 struct tail_args {
     int D, M, dg, ngk, ngl, ncomp;      // ncomp = 1 (value only) or 1 + D (with Jacobian)
     int cost_kind, add_cost, do_policy;
@@ -433,6 +436,8 @@ struct tail_args {
     int tracked[8];
     float q[8];
     const double *A, *amp, *part;       // part: [groups][1+D][B]
+    const double *x_cur;                // [D][B] inputs of step t (rows < d_s: s_t)
+    double *x_next;                     // [D][B] receives s_{t+1} (the policy adds a_{t+1})
     double *lpt;                        // [B]
     float *tape_s_next;                 // [d_s][B] slot of s_{t+1}, or null
     float *states_out_next;             // [B][d_s] or null
@@ -461,7 +466,6 @@ __global__ __launch_bounds__(PW * 64) void step_tail_kernel(tail_args r, policy_
     __shared__ float4 red4[PW * 4 * 64];
     __shared__ float biasS[3][BAGEL_MAX_HIDDEN];
     __shared__ double fS[8][PL], sS[8][PL];
-    constexpr double LN2 = 0.69314718055994530942, TWO_PI = 6.28318530717958647693;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -474,31 +478,21 @@ __global__ __launch_bounds__(PW * 64) void step_tail_kernel(tail_args r, policy_
     FORWARD_WEIGHTS_DECL;
     if (r.do_policy) load_forward_weights(a, wave, lane, w_first, w_last, w_wide, p_first, p_last, p_wide, bias_r);
 
-    // ---- partial sums -> f (LDS) and J_f (tape): one (output m, component) pair per thread and pass
+    // ---- value sums -> f (LDS): one output m per thread row.  (direct: part holds f and J_f themselves,
+    // one (output, component) pair per thread row and pass; J_f goes to the tape from here.)
     const size_t stride = (size_t)(1 + r.D) * B;
-    for (int qi = row; qi < r.M * r.ncomp; qi += 16) {
-        const int m = qi / r.ncomp, comp = qi - m * r.ncomp;
-        if (r.direct) {
+    if (r.direct) {
+        for (int qi = row; qi < r.M * r.ncomp; qi += 16) {
+            const int m = qi / r.ncomp, comp = qi - m * r.ncomp;
             const double val = r.part[(size_t)m * stride + (size_t)comp * B + bq];
             if (comp == 0) fS[m][bl] = val;
             else if (liveq) r.jdst[(size_t)(m * r.D + comp - 1) * B + bq] = (float)val;
-            continue;
         }
-        const double *pk = r.part + (size_t)(m * r.ngk) * stride + bq;
-        const double *pr = r.part + (size_t)(r.M * r.ngk + m * r.ngl) * stride + bq;
-        const double u = sum_groups(pk, r.ngk, stride);
-        const double amp = r.amp[m];
-        if (comp == 0) {
-            const double p = sum_groups(pr, r.ngl, stride);
-            fS[m][bl] = amp * p + u;
-        } else {
-            const int d = comp - 1;
-            const double gk = sum_groups(pk + (size_t)comp * B, r.ngk, stride);
-            const double gr = sum_groups(pr + (size_t)comp * B, r.ngl, stride);
-            const double x = a.xbuf[(size_t)d * B + bq];
-            const double J = -amp * TWO_PI * gr + LN2 * (gk - r.A[m * r.D + d] * x * u);
-            if (liveq) r.jdst[(size_t)(m * r.D + d) * B + bq] = (float)J;
-        }
+    } else if (row < r.M) {
+        const int m = row;
+        const double u = sum_groups(r.part + (size_t)(m * r.ngk) * stride + bq, r.ngk, stride);
+        const double p = sum_groups(r.part + (size_t)(r.M * r.ngk + m * r.ngl) * stride + bq, r.ngl, stride);
+        fS[m][bl] = r.amp[m] * p + u;
     }
     __syncthreads();
 
@@ -508,11 +502,11 @@ __global__ __launch_bounds__(PW * 64) void step_tail_kernel(tail_args r, policy_
     for (int k = row; k < 32; k += 16) {
         float hin = 0.0f;
         if (k < ds) {
-            const double s = a.xbuf[(size_t)k * B + bq] + fS[k][bl];
+            const double s = r.x_cur[(size_t)k * B + bq] + fS[k][bl];
             sS[k][bl] = s;
             hin = (float)s;
             if (liveq) {
-                a.xbuf[(size_t)k * B + bq] = s;
+                r.x_next[(size_t)k * B + bq] = s;
                 if (r.tape_s_next) r.tape_s_next[(size_t)k * B + bq] = hin;
                 if (r.states_out_next) r.states_out_next[(size_t)bq * ds + k] = hin;
             }
@@ -1148,13 +1142,15 @@ hipError_t bagel_launch_step_tail(bagel_ctx *c, int t, int slot, int next_slot, 
     r.sigma_r = c->dm.sigma_r;
     for (int j = 0; j < 8; ++j) { r.tracked[j] = c->dm.tracked[j]; r.q[j] = c->dm.q[j]; }
     r.A = c->A; r.amp = c->amp; r.part = c->part; r.lpt = c->lpt;
+    r.x_cur = c->xbuf; r.x_next = c->xbuf_alt;
     r.tape_s_next = write_tape_s ? c->tape_s + (size_t)(t + 1) * c->dm.d_s * B : nullptr;
     r.states_out_next = states_out ? states_out + (size_t)(t + 1) * B * c->dm.d_s : nullptr;
     r.goals_t = goals + (size_t)t * B * c->dm.d_g;
     r.goals_next = has_next ? goals + (size_t)(t + 1) * B * c->dm.d_g : nullptr;
-    r.jdst = jac ? c->tape_J + (size_t)slot * c->M * c->D * B : nullptr;
+    r.jdst = (jac && direct) ? c->tape_J + (size_t)slot * c->M * c->D * B : nullptr;
     policy_args a = make_pargs(c, has_next ? next_slot : 0);
     a.theta = theta;
+    a.xbuf = c->xbuf_alt;              // the action of step t+1 joins s_{t+1}
     hipLaunchKernelGGL(step_tail_kernel, dim3((c->dm.B + PL - 1) / PL), dim3(PW * 64), 0, c->stream, r, a);
     return hipGetLastError();
 }
