@@ -9,18 +9,27 @@ Inputs are seeded synthetic data (paper_2202_13638_amd/synth.py), resident in HB
 timed region; the sample-set precompute (bagel_prepare_samples) runs before it, untimed.
 
 Prints ONE JSON line, with
+  value        B*H*steps / wall time of the timed steps (synchronised before and after);
+               median_ms_per_call is the median over the same calls, each timed with HIP events on the
+               library's stream.
   roofline     the dominant kernel (sample evaluation with Jacobian, one launch per rollout step):
                algorithmic flops per launch / average launch duration measured with HIP events on
-               the library's stream during the timed steps, against the float64 vector peak.
-  cpu_baseline the float64 oracle timed on this host's cores on a bounded sample of the workload.
+               the library's stream during the timed steps, against the float64 vector peak; hbm_frac is
+               the algorithmic bytes of the same launch against 8 TB/s; traffic is the counter reading
+               stored in profiles/ if that profile was taken from the kernel sources as they are now,
+               else null.
+  cpu_baseline the float64 oracle timed on this host's cores on a bounded sample of the workload, on all
+               threads and on one.
   forward_only, inner_loop   one bagel_rollout_loss call, and two iterations of bagel_optimize (rollout,
                gradient, Adam update), both outside the timed region.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
+import re
 import sys
 import time
 
@@ -32,9 +41,33 @@ sys.path.insert(0, ROOT)
 from paper_2202_13638_amd import synth  # noqa: E402
 
 PEAK_FP64_VECTOR_TFLOPS = 78.6   # MI355X vector float64 (= unpacked float32) peak
-# HBM bytes per launch of gp_step_kernel<8,true> on the stress workload from rocprofv3 --pmc
-# (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, factors from a plain 1 GiB copy): profiles/gp_step_stress_pmc.md
-STRESS_GP_STEP_TRAFFIC_BYTES = 2.5015e9 + 2.123e7
+PEAK_HBM_TBS = 8.0
+PMC_PROFILE = os.path.join("profiles", "gp_step_stress_pmc.md")
+KERNEL_SOURCES = ["gp_step.hip", "model.hip", "bagel_api.hip"]    # what fixes the launch the counters were read on
+
+
+def kernel_source_digest():
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2202_13638_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(cfg, S, horizon_override):
+    """HBM bytes per launch of the sample-evaluation kernel from the rocprofv3 --pmc passes recorded in
+    profiles/ (FETCH_SIZE and WRITE_SIZE, scaled by a plain copy of known size) - only if that profile
+    names this workload and was taken from the kernel sources as they are now; otherwise None."""
+    try:
+        text = open(os.path.join(ROOT, PMC_PROFILE)).read()
+    except OSError:
+        return None
+    m = re.search(r"traffic_bytes_per_launch=([0-9.eE+]+)\s+workload=(\w+)\s+S=(\d+)\s+sources=([0-9a-f]+)", text)
+    if not m:
+        return None
+    if m.group(2) != cfg.name or int(m.group(3)) != S or m.group(4) != kernel_source_digest():
+        return None
+    return float(m.group(1))
 
 
 def algorithmic_flops_per_traj_step(cfg, jac=True):
@@ -44,19 +77,35 @@ def algorithmic_flops_per_traj_step(cfg, jac=True):
     return 2 * fma + M * N + (2 if jac else 1) * M * L
 
 
-def cpu_baseline(cfg, inp, seconds_target=15.0):
+def algorithmic_bytes_per_launch(cfg, S):
+    """Sample evaluation: the per-sample streams v and w, read once per launch (4 M (N + L) bytes per
+    sample; trajectories that share a sample share its stream)."""
+    return 4.0 * cfg.M * (cfg.N + cfg.L) * S
+
+
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline(cfg, inp, seconds_target=12.0):
     """Time the oracle's loss+gradient on a bounded sample: min(B, 16*cores) trajectories, full N, L,
-    policy; horizon chosen so the run takes about `seconds_target`.  v is a random stand-in of the
-    right scale (the oracle's own prepare at N=8192 would take minutes and its values do not change
-    the work)."""
+    policy; horizon chosen so the run takes about `seconds_target`; then once more on ONE thread, on a
+    sample sized for about a third of that.  v is a random stand-in of the right scale (the oracle's own
+    prepare at N=8192 would take minutes and its values do not change the work)."""
+    import ctypes
     import oracle
     cores = oracle.num_threads()
-    Bc = min(cfg.B, 16 * cores)
-    idx = np.arange(Bc) * (cfg.B // Bc)
     rng = np.random.default_rng(7)
-    v = (100.0 * rng.standard_normal((Bc, cfg.M, cfg.N))).astype(np.float32)
 
-    def run(H):
+    def run(Bc, H):
+        idx = np.arange(Bc) * (cfg.B // Bc)
+        v = (100.0 * rng.standard_normal((Bc, cfg.M, cfg.N))).astype(np.float32)
         sub = synth.scaled(cfg, B=Bc, H=H)
         m = dict(inp)
         m["w"] = np.ascontiguousarray(inp["w"][idx])
@@ -67,19 +116,35 @@ def cpu_baseline(cfg, inp, seconds_target=15.0):
         oracle.rollout(dm, m, v, grad=True, want_states=False)
         return time.perf_counter() - t0
 
-    t_probe = run(2)
+    Bc = min(cfg.B, 16 * cores)
+    t_probe = run(Bc, 2)
     H = int(max(2, min(cfg.H, round(2 * seconds_target / max(t_probe, 1e-3)))))
-    t = run(H)
-    return {"value": Bc * H / t, "unit": "trajectory-steps/s", "cores": cores, "kind": "oracle",
-            "sample": f"{Bc} trajectories x {H} steps at full N={cfg.N}, L={cfg.L}, policy {cfg.hidden}; "
-                      f"random v of the workload's scale; {t:.1f} s"}
+    t = run(Bc, H)
+    out = {"value": Bc * H / t, "unit": "trajectory-steps/s", "cores": cores, "kind": "oracle",
+           "cpu": cpu_model(),
+           "sample": f"{Bc} trajectories x {H} steps at full N={cfg.N}, L={cfg.L}, policy {cfg.hidden}; "
+                     f"random v of the workload's scale; {t:.1f} s"}
+    # one thread: the OpenMP runtime the oracle is linked against takes the thread count
+    try:
+        gomp = ctypes.CDLL("libgomp.so.1")
+        gomp.omp_set_num_threads(1)
+        B1 = min(cfg.B, 4)
+        t_probe = run(B1, 2)
+        H1 = int(max(2, min(cfg.H, round(2 * (seconds_target / 3) / max(t_probe, 1e-3)))))
+        t1 = run(B1, H1)
+        gomp.omp_set_num_threads(cores)
+        out["single_thread"] = {"value": B1 * H1 / t1, "unit": "trajectory-steps/s",
+                                "sample": f"{B1} trajectories x {H1} steps; {t1:.1f} s"}
+    except OSError:
+        out["single_thread"] = None
+    return out
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
-    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="stress", choices=list(synth.CONFIGS))
     ap.add_argument("--sampler", default="pathwise", choices=["pathwise", "posterior"],
                     help="pathwise: one function sample per trajectory (the headline path); posterior: per-step "
@@ -153,11 +218,17 @@ def main():
         step()
     torch.cuda.synchronize()
     ctx.bagel_profile_enable(args.profile_every)
+    # every call between two events on the stream the library launches on (torch's current stream)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    ev[0].record()
+    for i in range(args.steps):
         step()
+        ev[i + 1].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    call_ms = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps))
+    median_ms = call_ms[len(call_ms) // 2] if len(call_ms) % 2 else 0.5 * (call_ms[len(call_ms) // 2 - 1] + call_ms[len(call_ms) // 2])
     k_ms, k_n = ctx.bagel_profile_read()
     ctx.bagel_profile_enable(0)
     if not os.environ.get("BAGEL_BENCH_TIMING_ONLY"):      # timing experiments with deliberately wrong operands
@@ -182,6 +253,9 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": 1e3 * elapsed / args.steps,
+        "median_ms_per_call": median_ms,
+        "min_ms_per_call": call_ms[0],
+        "max_ms_per_call": call_ms[-1],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -195,11 +269,14 @@ def main():
         "roofline": {"bound": "alu", "kernel": "posterior step: rows + dgemm_kernel + reduce, all outputs" if posterior
                      else "gp_step_kernel<D,jac>", "achieved": achieved,
                      "peak": PEAK_FP64_VECTOR_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP64_VECTOR_TFLOPS,
-                     "traffic": STRESS_GP_STEP_TRAFFIC_BYTES if (cfg.name == "stress" and args.horizon is None
-                                                                  and not posterior and S == cfg.B) else None,
+                     "traffic": None if posterior else measured_traffic(cfg, S, args.horizon),
+                     "traffic_source": PMC_PROFILE,
+                     "hbm_frac": None if posterior else
+                     algorithmic_bytes_per_launch(cfg, S) / (avg_ms * 1e-3) / (PEAK_HBM_TBS * 1e12) if k_n else None,
+                     "algorithmic_bytes_per_launch": None if posterior else algorithmic_bytes_per_launch(cfg, S),
                      "avg_launch_ms": avg_ms, "timed_launches": k_n,
                      "flops_per_launch": flops_launch,
-                     "share_of_step": (avg_ms * cfg.H * (2 if ckpt else 1)) / (1e3 * elapsed / args.steps)},
+                     "share_of_step": (avg_ms * cfg.H) / (1e3 * elapsed / args.steps)},
     }
     if not args.no_extras and not posterior:
         # reported alongside, outside the timed region: the forward pass alone, and the inner loop of

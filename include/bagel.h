@@ -38,7 +38,22 @@
  *     400 length scales of the origin (sum_d x_d^2 / l_d^2 < 1.8e5; the paper's data are
  *     normalised).  A training point further out is dropped from the kernel row, and a trajectory
  *     further out sees a kernel row of zero; both are exact as long as the other side stays inside.
+ *     (Within about 19 length scales - sum_d x_d^2 / l_d^2 < 346 for data and trajectory, signal
+ *     variance within 2^-20 .. 2^20 - large launches take a faster form of the same arithmetic; outside
+ *     they fall back by themselves, per group of 64 trajectories.  Results agree to rounding.)
+ *   - The two samplers share the model tables of a context: bagel_prepare_samples / bagel_set_samples
+ *     install the pathwise sampler and invalidate the posterior cache, bagel_prepare_posterior does
+ *     the reverse.  Use two contexts to hold both.
  *   - One context must not be used from two threads at once.
+ *
+ * Tuning knobs (environment variables read once by bagel_create; the defaults are the measured best and
+ * none of them changes results beyond the order of floating-point sums):
+ *   BAGEL_CK, BAGEL_CL     training points / features per work unit of the sample evaluation (rounded
+ *                          up to multiples of 8)
+ *   BAGEL_TARGET_WGS       number of workgroups the default unit sizes aim for (default 4096)
+ *   BAGEL_EXP_TABLE        1: always the general form of the kernel-row loop, 2: always the table form,
+ *                          unset: by launch size
+ *   BAGEL_KSPLIT           split of the weight-gradient contraction (default 256)
  */
 #ifndef BAGEL_H
 #define BAGEL_H
@@ -85,9 +100,13 @@ typedef struct {
 int bagel_num_params(const bagel_dims *dims);
 
 /*
- * Create a context for fixed dims on the current HIP device.  Allocates every buffer the
- * other calls need (model copy, tape, partial sums).  `hip_stream` is a hipStream_t
- * (NULL = default stream); all later work of this context is enqueued there.
+ * Create a context for fixed dims on the current HIP device.  Allocates every buffer the rollout
+ * calls, bagel_set_samples, bagel_sample_eval, bagel_adam_step and bagel_optimize need (model copy,
+ * tape, partial sums); those calls allocate nothing.  The set-up calls allocate on their own:
+ * bagel_prepare_samples and bagel_hyper_* take float64 scratch for the duration of the call, the first
+ * bagel_prepare_posterior allocates the posterior cache, which the context then keeps (sizes at their
+ * declarations).  `hip_stream` is a hipStream_t (NULL = default stream); all later work of this
+ * context is enqueued there.
  * Errors: EINVAL (bad dims, null pointers), ENOMEM, EHIP.
  */
 int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_stream);

@@ -263,6 +263,7 @@ extern "C" int bagel_set_samples(bagel_ctx *c, const float *X, const float *leng
     if (!X || !lengthscale || !signal_var || !omega || !phase || !w || !v)
         BAGEL_FAIL(c, BAGEL_EINVAL, "bagel_set_samples: null argument");
     c->prepared = false;
+    c->post_prepared = false;       // the model tables are shared: the posterior cache belongs to the old ones
     BAGEL_HIP(c, bagel_launch_build_model(c, X, lengthscale, signal_var, omega, phase));
     BAGEL_HIP(c, bagel_launch_pack_samples(c, w, v));
     c->prepared = true;
@@ -278,6 +279,7 @@ extern "C" int bagel_prepare_samples(bagel_ctx *c, const float *X, const float *
     if (!X || !y || !lengthscale || !signal_var || !noise_var || !omega || !phase || !w || !eps)
         BAGEL_FAIL(c, BAGEL_EINVAL, "bagel_prepare_samples: null argument");
     c->prepared = false;
+    c->post_prepared = false;       // the model tables are shared: the posterior cache belongs to the old ones
     BAGEL_HIP(c, bagel_launch_build_model(c, X, lengthscale, signal_var, omega, phase));
     BAGEL_HIP(c, bagel_launch_pack_samples(c, w, nullptr));
     const int rc = bagel_prepare_impl(c, X, y, lengthscale, signal_var, noise_var, omega, phase, w, eps, v_out);
@@ -598,6 +600,7 @@ extern "C" int bagel_prepare_posterior(bagel_ctx *c, const float *X, const float
     if (!X || !y || !lengthscale || !signal_var || !noise_var)
         BAGEL_FAIL(c, BAGEL_EINVAL, "bagel_prepare_posterior: null argument");
     c->post_prepared = false;
+    c->prepared = false;            // the scaled training inputs are rewritten below: installed samples belong to the old model
     if (!c->post_Kinv) {
         c->post_Np = (c->dm.N + 63) / 64 * 64;
         const size_t Np = (size_t)c->post_Np, B = (size_t)c->dm.B, M = (size_t)c->M;

@@ -1209,16 +1209,15 @@ hipError_t bagel_launch_weight_grad(bagel_ctx *c, int n_slots, bool accumulate, 
     for (int l = 0; l < c->n_layers; ++l) {
         const int no = c->width[l + 1], ni = c->width[l];
         if (no > 128 && ni > 128 && no <= 256 && ni <= 256 && B % WG_KC == 0) {
-            // wide layer: operands staged through LDS (147 KB of dynamic LDS, raised once per process)
+            // wide layer: operands staged through LDS (147 KB of dynamic LDS)
             const int tiles = n_slots * (B / WG_KC);
             const int per_t = (tiles + nz - 1) / nz;
             const size_t lds_bytes = (size_t)2 * 2 * 256 * WG_LD * sizeof(float);
-            static bool raised = false;
-            if (!raised) {
+            if (!c->wg_lds_raised) {       // a per-device function attribute: set once per context
                 hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(weight_grad_tiled_kernel),
                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
                 if (e != hipSuccess) return e;
-                raised = true;
+                c->wg_lds_raised = true;
             }
             hipLaunchKernelGGL(weight_grad_tiled_kernel, dim3(nz), dim3(1024), lds_bytes, c->stream, c->tape_d[l],
                                c->tape_h[l], c->gsplit, no, ni, B, n_slots, per_t, c->w_off[l], c->b_off[l], c->P);

@@ -496,6 +496,10 @@ def _posterior_case(cfg, label, S=None, **dims_kw):
                states=states.cpu().numpy().astype(np.float64), grad_theta=gth.cpu().numpy().astype(np.float64),
                grad_s0=gs0.cpu().numpy().astype(np.float64))
     harness.assert_parity(ref, got, label=f"{label}/grad")
+    # the samplers share the model tables: installing one leaves the other unprepared
+    with pytest.raises(binding.BagelError) as e:
+        ctx.bagel_rollout_loss(g["theta"], g["s0"], g["goals"], loss)
+    assert e.value.code == binding.ENOTPREPARED
     ctx.close()
     return got
 
