@@ -195,7 +195,8 @@ __global__ __launch_bounds__(BAGEL_BLOCK) __attribute__((amdgpu_waves_per_eu(BAG
     const int *__restrict__ near_ok, int B, int S, int per_sample, int Np, int Lp, int CK, int CL, int nck, int ncl,
     int M, jac_sums prev)
 {
-    // M rows of workgroups past the work units: the previous step's Jacobian sums (see jacobian_tile)
+    // M rows of workgroups past the work units: the previous step's Jacobian sums (see jacobian_tile).
+    // (Placed first in the grid instead, they made the launch slower: 571 vs 556 us.)
     if ((int)blockIdx.y >= M * (((nck + 3) >> 2) + ((ncl + 3) >> 2))) {
         jacobian_tile(prev, blockIdx.x, (int)blockIdx.y - M * (((nck + 3) >> 2) + ((ncl + 3) >> 2)), B, D, M,
                       (nck + 3) >> 2, (ncl + 3) >> 2);
@@ -241,12 +242,18 @@ __global__ __launch_bounds__(BAGEL_BLOCK) __attribute__((amdgpu_waves_per_eu(BAG
         const size_t row0 = BAGEL_SAME_ROWS ? 0 : ((size_t)m * Np + (size_t)c * CK) * (D + 1);
         // the stream of this unit for this lane's sample: uniform base address plus a 32-bit lane offset
         const unsigned vstep = (unsigned)S * (unsigned)sizeof(float4);       // one row: four points of every sample
-        const __amdgpu_buffer_rsrc_t vdesc =
-            stream_descriptor(v4 + ((size_t)m * (Np / 4) + (size_t)c * (CK / 4)) * S, (size_t)(CK / 4) * vstep);
+        const float4 *vrows = v4 + ((size_t)m * (Np / 4) + (size_t)c * (CK / 4)) * S;
         const unsigned voff = (unsigned)sidx * (unsigned)sizeof(float4);
         bool wave_near = false;
         if (NEAR) wave_near = near_ok[0] != 0 && !__any(!(q >= -250.0));
+        // (Each of the two loops builds the stream's descriptor for itself, from a base pointer the
+        // compiler cannot identify with the other loop's: one shared descriptor would live across both
+        // loops, and the scalar-register pressure of the general loop would then spill it inside the
+        // table loop too - eleven extra vector instructions per eight points.)
         if (NEAR && wave_near) {
+            const float4 *vrows_t = vrows;
+            asm volatile("" : "+s"(vrows_t));
+            const __amdgpu_buffer_rsrc_t vdesc = stream_descriptor(vrows_t, (size_t)(CK / 4) * vstep);
             const double *__restrict__ Xr = Xn + row0;
             const int last = n_iter - 1;
             // leading polynomial coefficients pinned to register classes: the first Horner step is then a
@@ -306,7 +313,17 @@ __global__ __launch_bounds__(BAGEL_BLOCK) __attribute__((amdgpu_waves_per_eu(BAG
                     four_points(vb, n4 + 1);
                 }
             }
-            const double eq = exp2_poly(q, 1.192611307487823e-07, 2.409383341728244e-06);
+            // 2^q (q in [-250, 0]) by the loop's own table form: it needs no constants beyond the loop's,
+            // whereas the polynomial form's seven would be kept in scalar registers across the loop
+            // (shared with the general loop below) and push the loop's operands out into spill lanes
+            const double sq = q + 6144.0;
+            const int hq = __double2hiint(sq);
+            const double Tq = tab[hq & 255];
+            const double gq = (double)(unsigned)__double2loint(sq);
+            double pq = fma(ca, gq, cb);
+            pq = fma(pq, gq, 0x1.62e42fefcb0c8p-41);
+            pq = fma(pq, gq, 1.0);
+            const double eq = pq * __hiloint2double(__double2hiint(Tq) + (hq << 12), __double2loint(Tq));
             u *= eq;
             if (JAC) {
 #pragma unroll
@@ -316,6 +333,9 @@ __global__ __launch_bounds__(BAGEL_BLOCK) __attribute__((amdgpu_waves_per_eu(BAG
             // A trajectory further out than about 400 length scales (q < -2^17) is that far from every
             // training point that is kept (model set-up turns rows with c_n < -2^17 into padding), and its
             // kernel row is zero: it gets a constant exponent of -3000.
+            const float4 *vrows_g = vrows;
+            asm volatile("" : "+s"(vrows_g));
+            const __amdgpu_buffer_rsrc_t vdesc = stream_descriptor(vrows_g, (size_t)(CK / 4) * vstep);
             const bool far = q < -131072.0;
             double xs[D];
 #pragma unroll

@@ -309,13 +309,26 @@ def test_repeated_calls_are_bitwise_reproducible():
 
 
 # ------------------------------------------------------------------ prepare
-@pytest.mark.parametrize("name,kw", [("tiny", {}), ("small", dict(B=48)), ("ragged", {})])
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("name,kw", [("tiny", {}), ("small", dict(B=48)), ("ragged", {}), ("medium", dict(sub=64)),
+                                     ("large_policy", dict(sub=64))])
 def test_prepare_matches_oracle_solution(name, kw):
+    """bagel_prepare_samples against the oracle's float64 solve, and the product path end to end
+    (bagel_prepare_samples -> bagel_rollout_loss_grad) against the oracle driven from the UNROUNDED
+    float64 v.  v is ill-conditioned (noise variance far below the signal variance): rounding it once to
+    float32, which the float32 interface implies, already moves a rollout by `cond` below, measured here
+    with the oracle alone (float64 v against the same v rounded).  The end-to-end deviation is held to a
+    small multiple of that; tests/conditioning.py prints the same numbers for all five workloads."""
     if name == "ragged":
         cfg = synth.Config("p", 13, 3, 1, 1, 150, 77, 9, 3, (4,), 0.0, "sinusoid", "const", 0, 0.8, 1e-3)
+        inp = synth.make_inputs(cfg)
+    elif "sub" in kw:
+        full = _cfg(name)
+        idx = np.arange(kw["sub"]) * (full.B // kw["sub"]) + 3
+        cfg, inp = synth.subset_trajectories(full, synth.make_inputs(full), idx)
     else:
         cfg = _cfg(name, **kw)
-    inp = synth.make_inputs(cfg)
+        inp = synth.make_inputs(cfg)
     dm = oracle.dims_from_config(cfg)
     v64 = oracle.prepare_samples(dm, inp)
     got = harness.gpu_rollout(cfg, inp, None, with_prepare=True, want_v=True)
@@ -323,11 +336,14 @@ def test_prepare_matches_oracle_solution(name, kw):
     err = np.abs(got["v"] - v64).max() / np.abs(v64).max()
     print(f"[prepare {name}] max|dv|/max|v| = {err:.3e}", flush=True)
     assert err <= 5e-7
-    # end to end (GPU prepare -> GPU rollout) stays close to the oracle; the gap is the float32 rounding of v
-    ref = oracle.rollout(dm, inp, v64.astype(np.float32))
-    d = harness.deviations(ref, got)
-    print(f"[prepare {name} end-to-end] " + " ".join(f"{k}={x:.3e}" for k, x in d.items()), flush=True)
-    assert d["state"] <= 5e-3 and d["grad_l2"] <= 5e-2
+    exact = oracle.rollout(dm, inp, v64)                       # unrounded v
+    cond = harness.deviations(exact, oracle.rollout(dm, inp, v64.astype(np.float32)))
+    d = harness.deviations(exact, got)
+    print(f"[prepare {name} end-to-end vs unrounded v] " + " ".join(f"{k}={x:.3e}" for k, x in d.items()), flush=True)
+    print(f"[prepare {name} effect of rounding v once ] " + " ".join(f"{k}={x:.3e}" for k, x in cond.items()), flush=True)
+    for k in ("state", "loss", "grad_l2", "grad_s0"):
+        tol = {"state": harness.TOL_STATE, "loss": harness.TOL_LOSS}.get(k, harness.TOL_GRAD)
+        assert d[k] <= 3.0 * cond[k] + tol, (k, d[k], cond[k])
 
 
 def test_prepare_reports_non_positive_definite():
