@@ -67,7 +67,7 @@ struct bagel_ctx {
     double *gacc;                // [P] gradient accumulated over segments
     float *gtheta;               // [P] gradient of the current iteration of bagel_optimize
     int ksplit;
-    bool wg_lds_raised;          // the weight-gradient kernel's dynamic-LDS limit has been raised on this context's device
+    int wg_lds_raised;           // bit i: the dynamic-LDS limit of weight-gradient kernel instance i has been raised on this context's device
 
     // ---- per-step posterior sampler (buffers allocated by the first bagel_prepare_posterior) -----
     bool post_prepared;

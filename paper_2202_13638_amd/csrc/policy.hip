@@ -940,106 +940,163 @@ __global__ __launch_bounds__(1024) void weight_grad_kernel(const float *__restri
     }
 }
 
-// The same GEMM for a wide layer (128 < rows, columns <= 256; B a multiple of 32), with both
-// operands staged through LDS.  The direct kernel above has every wave fetch its own operand rows
-// from global memory, 16 bytes per row and chunk, which re-fetches every cache line four times and
-// caps it at the L2-to-CU bandwidth.  Here the 16 waves of a workgroup load one tile of 32
-// contraction indices (32 trajectories of one tape slot) for all rows of both operands with
-// 128-byte row segments, write it to LDS with rows padded to 36 floats (a lane's 16-byte reads of
-// consecutive rows then fall into different banks), and every wave reads its 64 x 64 block's
-// operands from there.  Tiles are double-buffered: the global loads of tile k+1 are in flight while
-// the 64 MFMAs per wave of tile k run; one barrier per tile.
+// The same GEMM with both operands staged through LDS (B a multiple of 32).  The direct kernel above
+// has every lane fetch 16 bytes of a row of its own per chunk: a wave instruction touches 32 cache
+// lines for 1 KB, every line is asked for four times, and the kernel is held by the rate at which
+// the vector cache can look lines up (3.4 TB/s on a skinny layer), or by the L2-to-CU bandwidth on a
+// wide one.  Here the waves of a workgroup bring one tile of 32 contraction indices (32 trajectories
+// of one tape slot) for all rows of both operands into LDS with loads that write LDS directly (no
+// staging registers: on the wide layer the accumulators, the operand fragments of two contraction
+// steps and the addresses are all that a wave's 128 registers hold).  Such a load puts lane i's 16
+// bytes at byte 16 i of the wave's 1 KB destination, so a wave instruction carries 8 whole rows of
+// 128 bytes and the rows sit unpadded; the lane that fills the 16-byte column q of row r fetches
+// column q ^ (r & 7) of that row instead, which spreads the fragment reads of 8 consecutive rows
+// over all banks.  NST stages: the loads of tiles k+1 .. k+NST-1 are in flight while the MFMAs of
+// tile k run; one barrier per tile.
+//   WA x WB waves, each TA x TB MFMA tiles of 32 x 32: the workgroup covers 32 WA TA rows (outputs)
+//   and 32 WB TB columns (inputs); rows and columns past the layer's are clamped duplicates whose
+//   accumulators are never stored.  Instances: 4 x 4 waves of 2 x 2 tiles for a wide layer (both
+//   sides in (128, 256]); 8 x 1 and 1 x 8 waves of one tile for a skinny one (one side <= 32).
 constexpr int WG_KC = 32;              // contraction indices per tile
-constexpr int WG_LD = WG_KC + 4;       // padded row length in LDS (floats)
 
-__global__ __launch_bounds__(1024) void weight_grad_tiled_kernel(const float *__restrict__ Dl, const float *__restrict__ Hl,
-                                                                 float *__restrict__ gsplit, int no, int ni, int B,
-                                                                 int n_slots, int tiles_per_split, int w_off, int b_off,
-                                                                 int P)
+// One wave instruction: lane i's 16 bytes at g go to LDS byte address lds_addr + 16 i (lds_addr is
+// wave-uniform).  Written as assembly so that the loads of the next tile stay in flight under the
+// fragment reads of the current one: the compiler orders every LDS read after all outstanding loads
+// of this kind, whichever part of LDS they fill.  No register is written, so nothing the compiler
+// allocates depends on the load's completion; the caller waits (vmcnt) before the barrier that
+// publishes the tile.  M0 carries the LDS address; the kernel that calls this uses M0 for nothing else.
+__device__ __forceinline__ void load_16_bytes_per_lane_to_lds(const float *g, unsigned lds_addr)
 {
-    extern __shared__ float lds[];     // [2 stages][A: 256 x WG_LD | B: 256 x WG_LD]
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(lds_addr) : "memory");
+}
+
+// s_waitcnt with only the vector-memory counter set (expcnt and lgkmcnt left at their maxima)
+template <int N>
+__device__ __forceinline__ void wait_vector_loads_at_most()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt has six bits");
+    __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));
+}
+
+template <int WA, int WB, int TA, int TB, int NST>
+struct wg_tiling {
+    static constexpr int NW = WA * WB;                       // waves
+    static constexpr int RA = 32 * WA * TA, RB = 32 * WB * TB;   // rows of the two operands the MFMAs read
+    // rows brought into LDS: rounded up so that every wave issues the same number of loads per tile
+    static constexpr int LA = (RA + 8 * NW - 1) / (8 * NW) * (8 * NW), LB = (RB + 8 * NW - 1) / (8 * NW) * (8 * NW);
+    static constexpr int NA = LA / (8 * NW), NB = LB / (8 * NW);   // loads per wave and tile
+    static constexpr int STAGE = (LA + LB) * WG_KC;          // floats per stage: A rows, then B rows
+    static constexpr size_t LDS_BYTES = (size_t)NST * STAGE * sizeof(float);
+};
+
+template <int WA, int WB, int TA, int TB, int NST>
+__global__ __launch_bounds__(64 * WA * WB) void weight_grad_tiled_kernel(const float *__restrict__ Dl,
+                                                                         const float *__restrict__ Hl,
+                                                                         float *__restrict__ gsplit, int no, int ni, int B,
+                                                                         int n_slots, int tiles_per_split, int w_off,
+                                                                         int b_off, int P)
+{
+    using T = wg_tiling<WA, WB, TA, TB, NST>;
+    extern __shared__ float lds[];     // [NST stages][A: LA x WG_KC | B: LB x WG_KC]
+    const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) float *)lds;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wr = wave >> 2, wc = wave & 3;
+    const int wr = wave / WB, wc = wave - wr * WB;
     const int cl = lane & 31, hf = lane >> 5;
     const int tiles_per_slot = B / WG_KC;
     const int total = n_slots * tiles_per_slot;
     const int t_begin = blockIdx.x * tiles_per_split;
     const int t_end = min(total, t_begin + tiles_per_split);
 
-    // global -> register staging: thread handles rows r0 and r0 + 128 of both operands, 16 bytes each
-    const int r0 = tid >> 3, kq = tid & 7;
-    const int ra[2] = {min(r0, no - 1), min(r0 + 128, no - 1)};       // rows past the end are clamped: they
-    const int rb[2] = {min(r0, ni - 1), min(r0 + 128, ni - 1)};       // feed accumulators that are never stored
-    float4 ga[2], gb[2];
-    auto load_tile = [&](int t) {
-        const int slot = t / tiles_per_slot;
-        const int bb = (t - slot * tiles_per_slot) * WG_KC + 4 * kq;
+    // global -> LDS: load j of a wave brings rows [8 (j NW + wave), +8) of an operand
+    const int lr = lane >> 3;                                   // row within the instruction's 8
+    const int lq = (lane & 7) ^ lr;                             // 16-byte column this lane fetches
+    size_t offa[T::NA], offb[T::NB];                            // element offsets within a slot, column included
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            ga[j] = *reinterpret_cast<const float4 *>(Dl + ((size_t)slot * no + ra[j]) * B + bb);
-            gb[j] = *reinterpret_cast<const float4 *>(Hl + ((size_t)slot * ni + rb[j]) * B + bb);
-        }
-    };
-    auto store_tile = [&](int stage) {
-        float *As = lds + stage * (2 * 256 * WG_LD), *Bs = As + 256 * WG_LD;
+    for (int j = 0; j < T::NA; ++j) offa[j] = (size_t)min(8 * (j * T::NW + wave) + lr, no - 1) * B + 4 * lq;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            *reinterpret_cast<float4 *>(As + (r0 + 128 * j) * WG_LD + 4 * kq) = ga[j];
-            *reinterpret_cast<float4 *>(Bs + (r0 + 128 * j) * WG_LD + 4 * kq) = gb[j];
+    for (int j = 0; j < T::NB; ++j) offb[j] = (size_t)min(8 * (j * T::NW + wave) + lr, ni - 1) * B + 4 * lq;
+    // position of the next tile to load: first element of its 32 trajectories in row 0 of its slot
+    int ld_tb = t_begin % tiles_per_slot;
+    const float *ga = Dl + (size_t)(t_begin / tiles_per_slot) * no * B + ld_tb * WG_KC;
+    const float *gb = Hl + (size_t)(t_begin / tiles_per_slot) * ni * B + ld_tb * WG_KC;
+    auto load_next_tile = [&](int stage) {
+        const unsigned la = lds_base + (unsigned)(stage * T::STAGE + 8 * wave * WG_KC) * 4u, lb = la + T::LA * WG_KC * 4;
+#pragma unroll
+        for (int j = 0; j < T::NA; ++j) load_16_bytes_per_lane_to_lds(ga + offa[j], la + 8 * j * T::NW * WG_KC * 4);
+#pragma unroll
+        for (int j = 0; j < T::NB; ++j) load_16_bytes_per_lane_to_lds(gb + offb[j], lb + 8 * j * T::NW * WG_KC * 4);
+        if (++ld_tb == tiles_per_slot) {
+            ld_tb = 0;
+            ga += (size_t)no * B - (size_t)(tiles_per_slot - 1) * WG_KC;
+            gb += (size_t)ni * B - (size_t)(tiles_per_slot - 1) * WG_KC;
+        } else {
+            ga += WG_KC;
+            gb += WG_KC;
         }
     };
 
-    f16v acc[2][2];
+    f16v acc[TA][TB];
 #pragma unroll
-    for (int x = 0; x < 2; ++x)
+    for (int x = 0; x < TA; ++x)
 #pragma unroll
-        for (int y = 0; y < 2; ++y)
+        for (int y = 0; y < TB; ++y)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.0f;
-    float bsum[2] = {0.0f, 0.0f};
+    float bsum[TA];
+#pragma unroll
+    for (int x = 0; x < TA; ++x) bsum[x] = 0.0f;
 
-    if (t_begin < t_end) {
-        load_tile(t_begin);
-        store_tile(0);
-    }
+#pragma unroll
+    for (int k = 0; k < NST - 1; ++k)
+        if (t_begin + k < t_end) load_next_tile(k);
+    // the first tile is in LDS once every wave's share of it is; later tiles may still be in flight
+    if (t_begin + NST - 1 <= t_end) wait_vector_loads_at_most<(NST - 2) * (T::NA + T::NB)>();
+    else wait_vector_loads_at_most<0>();
     __syncthreads();
+    // fragment reads: row 32 (wr TA + f) + cl (its low three bits are cl's), 16-byte column (2 k8 + hf) ^ (cl & 7)
+    const int sw = cl & 7;
+    const float *Ar = lds + (32 * TA * wr + cl) * WG_KC, *Br = lds + T::LA * WG_KC + (32 * TB * wc + cl) * WG_KC;
+    int stage = 0, ld_stage = NST - 1;
     for (int t = t_begin; t < t_end; ++t) {
-        const int stage = (t - t_begin) & 1;
-        if (t + 1 < t_end) load_tile(t + 1);
-        const float *As = lds + stage * (2 * 256 * WG_LD) + (64 * wr + cl) * WG_LD + 4 * hf;
-        const float *Bs = lds + stage * (2 * 256 * WG_LD) + 256 * WG_LD + (64 * wc + cl) * WG_LD + 4 * hf;
+        const bool more = t + NST - 1 < t_end;
+        if (more) load_next_tile(ld_stage);     // into the stage that tile t-1 was read from
+        const float *As = Ar + stage * T::STAGE, *Bs = Br + stage * T::STAGE;
 #pragma unroll
         for (int k8 = 0; k8 < WG_KC / 8; ++k8) {
-            float4 a4[2], b4[2];
+            const int col = 4 * ((2 * k8 + hf) ^ sw);
+            float4 a4[TA], b4[TB];
 #pragma unroll
-            for (int f = 0; f < 2; ++f) {
-                a4[f] = *reinterpret_cast<const float4 *>(As + 32 * f * WG_LD + 8 * k8);
-                b4[f] = *reinterpret_cast<const float4 *>(Bs + 32 * f * WG_LD + 8 * k8);
-            }
+            for (int f = 0; f < TA; ++f) a4[f] = *reinterpret_cast<const float4 *>(As + 32 * f * WG_KC + col);
 #pragma unroll
-            for (int f = 0; f < 2; ++f) bsum[f] += (a4[f].x + a4[f].y) + (a4[f].z + a4[f].w);
+            for (int f = 0; f < TB; ++f) b4[f] = *reinterpret_cast<const float4 *>(Bs + 32 * f * WG_KC + col);
 #pragma unroll
-            for (int x = 0; x < 2; ++x)
+            for (int f = 0; f < TA; ++f) bsum[f] += (a4[f].x + a4[f].y) + (a4[f].z + a4[f].w);
 #pragma unroll
-                for (int y = 0; y < 2; ++y) {
+            for (int x = 0; x < TA; ++x)
+#pragma unroll
+                for (int y = 0; y < TB; ++y) {
                     acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[x].x, b4[y].x, acc[x][y], 0, 0, 0);
                     acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[x].y, b4[y].y, acc[x][y], 0, 0, 0);
                     acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[x].z, b4[y].z, acc[x][y], 0, 0, 0);
                     acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[x].w, b4[y].w, acc[x][y], 0, 0, 0);
                 }
         }
-        if (t + 1 < t_end) store_tile(stage ^ 1);
+        // tile t+1 has landed (loads complete in order; those of later tiles may stay in flight)
+        if (more) wait_vector_loads_at_most<(NST - 2) * (T::NA + T::NB)>();
+        else wait_vector_loads_at_most<0>();
         __syncthreads();
+        stage = stage + 1 == NST ? 0 : stage + 1;
+        ld_stage = ld_stage + 1 == NST ? 0 : ld_stage + 1;
     }
 
     float *g = gsplit + (size_t)blockIdx.x * P;
-    const int o_base = 64 * wr, i_base = 64 * wc;
+    const int o_base = 32 * TA * wr, i_base = 32 * TB * wc;
 #pragma unroll
-    for (int x = 0; x < 2; ++x)
+    for (int x = 0; x < TA; ++x)
 #pragma unroll
-        for (int y = 0; y < 2; ++y)
+        for (int y = 0; y < TB; ++y)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int o = o_base + x * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
@@ -1048,7 +1105,7 @@ __global__ __launch_bounds__(1024) void weight_grad_tiled_kernel(const float *__
             }
     if (wc == 0) {
 #pragma unroll
-        for (int f = 0; f < 2; ++f) {
+        for (int f = 0; f < TA; ++f) {
             const float tot = bsum[f] + __shfl_xor(bsum[f], 32);
             const int o = o_base + 32 * f + cl;
             if (hf == 0 && o < no) g[b_off + o] = tot;
@@ -1198,6 +1255,24 @@ hipError_t bagel_launch_adam(bagel_ctx *c, float *theta, const float *grad, floa
     return hipGetLastError();
 }
 
+namespace {
+template <int WA, int WB, int TA, int TB, int NST>
+hipError_t launch_wg_tiled(bagel_ctx *c, int which, int nz, int l, int no, int ni, int B, int n_slots, int per_t)
+{
+    using T = wg_tiling<WA, WB, TA, TB, NST>;
+    auto kernel = weight_grad_tiled_kernel<WA, WB, TA, TB, NST>;
+    if (!(c->wg_lds_raised & (1 << which))) {       // a per-device function attribute: set once per context
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)T::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        c->wg_lds_raised |= 1 << which;
+    }
+    hipLaunchKernelGGL(kernel, dim3(nz), dim3(64 * T::NW), T::LDS_BYTES, c->stream, c->tape_d[l], c->tape_h[l], c->gsplit,
+                       no, ni, B, n_slots, per_t, c->w_off[l], c->b_off[l], c->P);
+    return hipGetLastError();
+}
+}  // namespace
+
 hipError_t bagel_launch_weight_grad(bagel_ctx *c, int n_slots, bool accumulate, float *grad_theta)
 {
     const int B = c->dm.B;
@@ -1208,20 +1283,23 @@ hipError_t bagel_launch_weight_grad(bagel_ctx *c, int n_slots, bool accumulate, 
     const int nz = (total + per - 1) / per;
     for (int l = 0; l < c->n_layers; ++l) {
         const int no = c->width[l + 1], ni = c->width[l];
-        if (no > 128 && ni > 128 && no <= 256 && ni <= 256 && B % WG_KC == 0) {
-            // wide layer: operands staged through LDS (147 KB of dynamic LDS)
+        if (B % WG_KC == 0 && no <= 256 && ni <= 256) {
+            // operands staged through LDS: the wide layer (both sides above 128) and the skinny ones
+            // (one side of at most 32, the other above 128)
             const int tiles = n_slots * (B / WG_KC);
             const int per_t = (tiles + nz - 1) / nz;
-            const size_t lds_bytes = (size_t)2 * 2 * 256 * WG_LD * sizeof(float);
-            if (!c->wg_lds_raised) {       // a per-device function attribute: set once per context
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(weight_grad_tiled_kernel),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-                if (e != hipSuccess) return e;
-                c->wg_lds_raised = true;
-            }
-            hipLaunchKernelGGL(weight_grad_tiled_kernel, dim3(nz), dim3(1024), lds_bytes, c->stream, c->tape_d[l],
-                               c->tape_h[l], c->gsplit, no, ni, B, n_slots, per_t, c->w_off[l], c->b_off[l], c->P);
-            continue;
+            hipError_t e = hipSuccess;
+            bool done = true;
+            if (no > 128 && ni > 128)
+                e = launch_wg_tiled<4, 4, 2, 2, 2>(c, 0, nz, l, no, ni, B, n_slots, per_t);
+            else if (no > 128 && ni <= 32)
+                e = launch_wg_tiled<8, 1, 1, 1, 3>(c, 1, nz, l, no, ni, B, n_slots, per_t);
+            else if (no <= 32 && ni > 128)
+                e = launch_wg_tiled<1, 8, 1, 1, 3>(c, 2, nz, l, no, ni, B, n_slots, per_t);
+            else
+                done = false;
+            if (e != hipSuccess) return e;
+            if (done) continue;
         }
         dim3 grid(nz, (no + 255) / 256, (ni + 255) / 256);
         const int wrows = no >= 256 ? 4 : (no + 63) / 64, wcols = ni >= 256 ? 4 : (ni + 63) / 64;

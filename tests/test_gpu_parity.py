@@ -251,12 +251,19 @@ VARIANTS = {
     "one-step-one-trajectory": dict(cfg=dict(B=1, H=1), dims=dict()),
     "checkpoint-ragged": dict(cfg=dict(B=20, H=23), dims=dict(ckpt_interval=5)),
     "wide-policy": dict(cfg=dict(B=65, H=6, hidden=(256, 256)), dims=dict()),
+    # B a multiple of 32 and a layer with more than 128 rows and columns: the LDS-tiled weight gradient,
+    # with full (256 x 256) and ragged (136 x 200) operand rows, several tiles per workgroup
+    "wide-policy-tiled": dict(cfg=dict(B=96, H=7, hidden=(256, 256)), dims=dict()),
+    "wide-policy-tiled-ragged": dict(cfg=dict(B=64, H=5, hidden=(200, 136)), dims=dict()),
+    "wide-policy-tiled-one-split": dict(cfg=dict(B=160, H=6, hidden=(256, 256)), dims=dict(), env=dict(BAGEL_KSPLIT="4")),
 }
 
 
 @pytest.mark.parametrize("name", list(VARIANTS))
-def test_rollout_variants(name):
+def test_rollout_variants(name, monkeypatch):
     spec = VARIANTS[name]
+    for k, v in spec.get("env", {}).items():
+        monkeypatch.setenv(k, v)
     base = dict(d_s=2, d_a=1, d_g=1, N=90, L=130, B=16, H=8, hidden=(16,), act_bound=0.0)
     base.update(spec["cfg"])
     cfg = synth.Config("v", 12, base["d_s"], base["d_a"], base["d_g"], base["N"], base["L"], base["B"], base["H"],
