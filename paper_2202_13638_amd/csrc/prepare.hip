@@ -83,15 +83,15 @@ __global__ void convert_w_kernel(const float *__restrict__ w, double *__restrict
 }
 
 // C[i][j] (ldc) += alpha * sum_k A(i,k) * B(k,j), A(i,k) = A[i*sai + k*sak], B(k,j) = B[k*sbk + j*sbj]
-// (C = alpha * ... with overwrite).  lower_only: skip tiles entirely above the diagonal (used for the
-// symmetric trailing update).  The tile product itself is in dgemm_tile.h.
+// (C = alpha * ... with overwrite).  lower_only: skip tiles entirely above the diagonal j = i + diag
+// (used for the symmetric products).  The tile product itself is in dgemm_tile.h.
 __global__ __launch_bounds__(256, 4) void dgemm_kernel(int Mr, int Nc, int Kd, double alpha,
                                                     const double *__restrict__ A, long sai, long sak,
                                                     const double *__restrict__ Bm, long sbk, long sbj,
-                                                    double *__restrict__ Cm, long ldc, int lower_only, int overwrite)
+                                                    double *__restrict__ Cm, long ldc, int lower_only, int diag, int overwrite)
 {
     const int i0 = blockIdx.y * TM, j0 = blockIdx.x * TN;
-    if (lower_only && j0 > i0 + TM - 1) return;
+    if (lower_only && j0 > i0 + diag + TM - 1) return;
     __shared__ bagel_gemm::tile_lds sh;
     bagel_gemm::d4v acc[2][2];
     bagel_gemm::tile_product(acc, sh, i0, j0, Mr, Nc, Kd, A, sai, sak, Bm, sbk, sbj);
@@ -367,12 +367,13 @@ __global__ void emit_v_kernel(const double *__restrict__ V, float *__restrict__ 
 }
 
 void gemm(hipStream_t st, int Mr, int Nc, int Kd, double alpha, const double *A, long sai, long sak,
-          const double *Bm, long sbk, long sbj, double *Cm, long ldc, bool lower_only, bool overwrite = false)
+          const double *Bm, long sbk, long sbj, double *Cm, long ldc, bool lower_only, bool overwrite = false,
+          int diag = 0)
 {
     if (Mr <= 0 || Nc <= 0 || Kd <= 0) return;
     dim3 grid((Nc + TN - 1) / TN, (Mr + TM - 1) / TM);
     hipLaunchKernelGGL(dgemm_kernel, grid, dim3(256), 0, st, Mr, Nc, Kd, alpha, A, sai, sak, Bm, sbk, sbj, Cm, ldc,
-                       lower_only ? 1 : 0, overwrite ? 1 : 0);
+                       lower_only ? 1 : 0, diag, overwrite ? 1 : 0);
 }
 
 // In-place blocked Cholesky of K [Np][Np] (lower; Np a multiple of NB), then K_hat^-1 applied to the S
@@ -441,6 +442,28 @@ struct solver {
         }
     }
 
+    // The same with R = identity (S = Np columns): Z = L^-1 is lower triangular, so while the unknowns
+    // [k, k + n) are worked on only the columns below k + n hold anything; the products and block
+    // solves stop there, which leaves N^3/4 of the N^3/2 multiply-adds of the general case.
+    void forward_identity(int k, int n)
+    {
+        if (n > OB) {
+            const int h = half(n);
+            forward_identity(k, h);
+            gemm(st, n - h, k + h, h, -1.0, K + (size_t)(k + h) * Np + k, Np, 1, R + (size_t)k * S, S, 1,
+                 R + (size_t)(k + h) * S, S, false);
+            forward_identity(k + h, n - h);
+            return;
+        }
+        for (int kk = k; kk < k + n; kk += NB) {
+            hipLaunchKernelGGL(trsv_fwd_kernel, dim3((kk + NB) / NB), dim3(NB), 0, st, K, Np, kk, R, S);
+            const int rows = k + n - kk - NB;
+            if (rows > 0)
+                gemm(st, rows, kk + NB, NB, -1.0, K + (size_t)(kk + NB) * Np + kk, Np, 1, R + (size_t)kk * S, S, 1,
+                     R + (size_t)(kk + NB) * S, S, false);
+        }
+    }
+
     // backward substitution L^T V = Z on the unknowns [k, k + n)
     void backward(int k, int n)
     {
@@ -470,25 +493,91 @@ void factor_and_solve(hipStream_t st, double *K, int Np, double *R, int S, int f
     s.backward(0, Np);
 }
 
-// R[n][j] = [n == j] for j < Np, and R[n][Np] = y[n] (zero on the padding): right-hand sides for K_hat^-1 and alpha
-__global__ void posterior_rhs_kernel(const float *__restrict__ y_m, double *__restrict__ R, int N, int Np)
+// Z = identity [Np][Np]; yd[n] = y[n] in float64 (zero on the padding)
+__global__ void inverse_init_kernel(const float *__restrict__ y_m, double *__restrict__ Z, double *__restrict__ yd, int N,
+                                    int Np)
 {
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
     const int n = blockIdx.y;
-    if (j > Np) return;
-    R[(size_t)n * (Np + 1) + j] = (j < Np) ? (j == n ? 1.0 : 0.0) : (n < N ? (double)y_m[n] : 0.0);
+    if (j >= Np) return;
+    Z[(size_t)n * Np + j] = (j == n) ? 1.0 : 0.0;
+    if (n == 0) yd[j] = (j < N) ? (double)y_m[j] : 0.0;
 }
 
-// split the solved right-hand sides into Kinv[Np][Np] and alpha[Np]
-__global__ void posterior_emit_kernel(const double *__restrict__ R, double *__restrict__ Kinv, double *__restrict__ alpha,
-                                      int Np)
+// A[j][i] = A[i][j] for j > i, 32 x 32 blocks through LDS so that reads and writes are both row segments
+__global__ __launch_bounds__(256) void mirror_lower_kernel(double *__restrict__ A, int Np)
 {
-    const int j = blockIdx.x * blockDim.x + threadIdx.x;
-    const int n = blockIdx.y;
-    if (j > Np) return;
-    const double v = R[(size_t)n * (Np + 1) + j];
-    if (j < Np) Kinv[(size_t)n * Np + j] = v;
-    else alpha[n] = v;
+    __shared__ double t[32][33];
+    const int bi = blockIdx.y, bj = blockIdx.x;      // source block (rows bi, columns bj), bj <= bi
+    if (bj > bi) return;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    for (int r = ty; r < 32; r += 8) t[r][tx] = A[(size_t)(32 * bi + r) * Np + 32 * bj + tx];
+    __syncthreads();
+    for (int r = ty; r < 32; r += 8) {
+        const int row = 32 * bj + r, col = 32 * bi + tx;          // destination (row, col) = source (col, row)
+        if (col > row) A[(size_t)row * Np + col] = t[tx][r];
+    }
+}
+
+// t[i] = sum_{k <= i} Z[i][k] y[k] for lower-triangular Z: one wave per row, the lanes walk the row
+// together (contiguous reads), their sums are added by a fixed butterfly.
+__global__ __launch_bounds__(256) void lower_times_vector_kernel(const double *__restrict__ Z, const double *__restrict__ y,
+                                                                 double *__restrict__ t, int Np)
+{
+    const int lane = threadIdx.x & 63;
+    const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (i >= Np) return;
+    const double *row = Z + (size_t)i * Np;
+    double s = 0.0;
+    for (int k = lane; k <= i; k += 64) s += row[k] * y[k];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
+    if (lane == 0) t[i] = s;
+}
+
+// a[j] = sum_{k >= j} Z[k][j] t[k] for lower-triangular Z: lane = column (64 per workgroup, contiguous
+// reads of every row), wave w takes rows k = w mod 4; the four partial sums are added in wave order.
+__global__ __launch_bounds__(256) void lower_transposed_times_vector_kernel(const double *__restrict__ Z,
+                                                                            const double *__restrict__ t,
+                                                                            double *__restrict__ a, int Np)
+{
+    __shared__ double sh[4][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int j0 = blockIdx.x * 64, j = j0 + lane;
+    double s = 0.0;
+    if (j < Np)
+        for (int k = j0 + wave; k < Np; k += 4)
+            if (k >= j) s += Z[(size_t)k * Np + j] * t[k];
+    sh[wave][lane] = s;
+    __syncthreads();
+    if (wave == 0 && j < Np) a[j] = ((sh[0][lane] + sh[1][lane]) + sh[2][lane]) + sh[3][lane];
+}
+
+// K_hat^-1 and alpha = K_hat^-1 y from the factor L in K (eq. (2), (3), (5), (6) all need both):
+// Z = L^-1 by structured forward substitution on the identity, K_hat^-1 = Z^T Z on and below the
+// diagonal in row panels (entry (i, j) only sums over k >= max(i, j), so a panel that starts at row
+// i0 contracts over Np - i0 rows of Z), mirrored into the upper triangle; alpha = Z^T (Z y).
+// N^3/4 + N^3/6 multiply-adds after the N^3/6 of the factorisation, against N^3 for substitution both
+// ways on N right-hand sides.  Z [Np][Np], yd / tv [Np] are work space; Kinv and alpha the results.
+constexpr int INV_PANEL = 512;
+
+void inverse_from_factor(hipStream_t st, double *K, int Np, double *Z, const float *y_m, int N, double *yd, double *tv,
+                         double *Kinv, double *alpha, int flag_base, int *flag)
+{
+    hipLaunchKernelGGL(inverse_init_kernel, dim3((Np + 255) / 256, Np), dim3(256), 0, st, y_m, Z, yd, N, Np);
+    solver s{st, K, Np, Z, Np, flag_base, flag};
+    s.panel(0, Np);
+    s.forward_identity(0, Np);
+    for (int i0 = 0; i0 < Np; i0 += INV_PANEL) {
+        const int hb = Np - i0 < INV_PANEL ? Np - i0 : INV_PANEL;
+        // Kinv[i0 + i][j] = sum_k Z[i0 + k][i0 + i] Z[i0 + k][j], j <= i0 + i
+        gemm(st, hb, i0 + hb, Np - i0, 1.0, Z + (size_t)i0 * Np + i0, 1, Np, Z + (size_t)i0 * Np, Np, 1,
+             Kinv + (size_t)i0 * Np, Np, true, true, i0);
+    }
+    hipLaunchKernelGGL(mirror_lower_kernel, dim3(Np / 32, Np / 32), dim3(256), 0, st, Kinv, Np);
+    hipLaunchKernelGGL(lower_times_vector_kernel, dim3((Np + 3) / 4), dim3(256), 0, st, Z, yd, tv, Np);          // t = Z y
+    hipLaunchKernelGGL(lower_transposed_times_vector_kernel, dim3((Np + 63) / 64), dim3(256), 0, st, Z, tv, alpha,
+                       Np);                                                                                      // alpha = Z^T t
 }
 
 // ---- hyper-parameter learning: log marginal likelihood and its gradient (eq. (5), (6)) ----------
@@ -500,15 +589,18 @@ __global__ void build_khat_log_kernel(const float *__restrict__ X, const float *
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
     const int i = blockIdx.y;
     if (j >= Np) return;
+    double inv_l[BAGEL_MAX_D];                       // 1 / l_d, once per thread
+    for (int d = 0; d < D; ++d) inv_l[d] = exp(-(double)lh[d]);
+    const double sf2 = exp((double)lh[D]), sn2 = exp((double)lh[D + 1]);
     double val;
     if (i < N && j < N) {
         double r = 0.0;
         for (int d = 0; d < D; ++d) {
-            const double t = ((double)X[(size_t)i * D + d] - (double)X[(size_t)j * D + d]) / exp((double)lh[d]);
+            const double t = ((double)X[(size_t)i * D + d] - (double)X[(size_t)j * D + d]) * inv_l[d];
             r += t * t;
         }
-        val = exp((double)lh[D]) * exp(-0.5 * r);
-        if (i == j) val += exp((double)lh[D + 1]);
+        val = sf2 * exp(-0.5 * r);
+        if (i == j) val += sn2;
     } else {
         val = (i == j) ? 1.0 : 0.0;
     }
@@ -527,15 +619,15 @@ __device__ __forceinline__ double block_sum_256(double v, double *sh)
     return sh[0];
 }
 
-// lml = -1/2 y^T a - sum_i log L_ii - N/2 log(2 pi); L = factor in K (diagonal), a = last column of R
-__global__ __launch_bounds__(256) void hyper_lml_kernel(const double *__restrict__ Lf, const double *__restrict__ R,
+// lml = -1/2 y^T a - sum_i log L_ii - N/2 log(2 pi); L = factor in K (diagonal), a = alpha
+__global__ __launch_bounds__(256) void hyper_lml_kernel(const double *__restrict__ Lf, const double *__restrict__ alpha,
                                                         const float *__restrict__ y_m, int N, int Np,
                                                         float *__restrict__ lml_out)
 {
     __shared__ double sh[256];
     double ld = 0.0, quad = 0.0;
     for (int i = threadIdx.x; i < Np; i += 256) ld += log(Lf[(size_t)i * Np + i]);
-    for (int n = threadIdx.x; n < N; n += 256) quad += (double)y_m[n] * R[(size_t)n * (Np + 1) + Np];
+    for (int n = threadIdx.x; n < N; n += 256) quad += (double)y_m[n] * alpha[n];
     const double ld_tot = block_sum_256(ld, sh);
     __syncthreads();
     const double q_tot = block_sum_256(quad, sh);
@@ -543,33 +635,61 @@ __global__ __launch_bounds__(256) void hyper_lml_kernel(const double *__restrict
 }
 
 // row i of sum_ij (a_i a_j - Kinv_ij) dK_hat_ij / dphi_c for c = 0 .. D+1 -> partial[i][D+2]
+// (eq. (6) with dK/dlog l_d = K (x_d - x'_d)^2 / l_d^2, dK/dlog alpha^2 = K, dK_hat/dlog sigma_n^2 = sigma_n^2 I).
+// One workgroup per row; thread t takes columns t, t + 256, ...; the D + 2 sums are added over the
+// lanes of a wave by a fixed butterfly, then over the four waves in order.  All loops over d have the
+// compile-time bound BAGEL_MAX_D so that the per-thread arrays stay in registers.
 __global__ __launch_bounds__(256) void hyper_grad_rows_kernel(const float *__restrict__ X, const float *__restrict__ lh,
-                                                              const double *__restrict__ R, double *__restrict__ partial,
-                                                              int N, int Np, int D)
+                                                              const double *__restrict__ Kinv,
+                                                              const double *__restrict__ alpha,
+                                                              double *__restrict__ partial, int N, int Np, int D)
 {
-    __shared__ double sh[256];
+    __shared__ double sh[4][BAGEL_MAX_D + 2];
     const int i = blockIdx.x;
-    double acc[BAGEL_MAX_D + 2];
-    for (int c = 0; c < D + 2; ++c) acc[c] = 0.0;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    double acc[BAGEL_MAX_D + 2], inv_l[BAGEL_MAX_D], xi[BAGEL_MAX_D];
+#pragma unroll
+    for (int c = 0; c < BAGEL_MAX_D + 2; ++c) acc[c] = 0.0;
+#pragma unroll
+    for (int d = 0; d < BAGEL_MAX_D; ++d) {          // 1 / l_d and the row's own input, once per thread
+        inv_l[d] = d < D ? exp(-(double)lh[d]) : 0.0;
+        xi[d] = d < D ? (double)X[(size_t)i * D + d] : 0.0;
+    }
     const double sf2 = exp((double)lh[D]), sn2 = exp((double)lh[D + 1]);
-    const double ai = R[(size_t)i * (Np + 1) + Np];
+    const double ai = alpha[i];
     for (int j = threadIdx.x; j < N; j += 256) {
-        const double w = ai * R[(size_t)j * (Np + 1) + Np] - R[(size_t)i * (Np + 1) + j];
+        const double w = ai * alpha[j] - Kinv[(size_t)i * Np + j];
         double r = 0.0, t2[BAGEL_MAX_D];
-        for (int d = 0; d < D; ++d) {
-            const double t = ((double)X[(size_t)i * D + d] - (double)X[(size_t)j * D + d]) / exp((double)lh[d]);
-            t2[d] = t * t;
-            r += t2[d];
+#pragma unroll
+        for (int d = 0; d < BAGEL_MAX_D; ++d) {
+            if (d < D) {
+                const double t = (xi[d] - (double)X[(size_t)j * D + d]) * inv_l[d];
+                t2[d] = t * t;
+                r += t2[d];
+            }
         }
         const double wk = w * sf2 * exp(-0.5 * r);
-        for (int d = 0; d < D; ++d) acc[d] += wk * t2[d];
-        acc[D] += wk;
-        if (j == i) acc[D + 1] += w * sn2;
+#pragma unroll
+        for (int d = 0; d < BAGEL_MAX_D; ++d)
+            if (d < D) acc[d] += wk * t2[d];
+        acc[BAGEL_MAX_D] += wk;
+        if (j == i) acc[BAGEL_MAX_D + 1] += w * sn2;
     }
-    for (int c = 0; c < D + 2; ++c) {
-        const double tot = block_sum_256(acc[c], sh);
-        if (threadIdx.x == 0) partial[(size_t)i * (D + 2) + c] = tot;
-        __syncthreads();
+#pragma unroll
+    for (int c = 0; c < BAGEL_MAX_D + 2; ++c) {
+        if (c < D || c >= BAGEL_MAX_D) {
+            double v = acc[c];
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+            if (lane == 0) sh[wave][c] = v;
+        }
+    }
+    __syncthreads();
+    // thread c < D writes the length-scale sums, threads BAGEL_MAX_D and BAGEL_MAX_D + 1 the other two
+    const int c = threadIdx.x;
+    if (c < D || c == BAGEL_MAX_D || c == BAGEL_MAX_D + 1) {
+        const double tot = ((sh[0][c] + sh[1][c]) + sh[2][c]) + sh[3][c];
+        partial[(size_t)i * (D + 2) + (c < D ? c : D + (c - BAGEL_MAX_D))] = tot;
     }
 }
 
@@ -595,7 +715,8 @@ __global__ __launch_bounds__(256) void hyper_grad_final_kernel(const double *__r
 // of the time.  So up to three outputs are worked on side by side, each on a stream of its own with
 // buffers of its own; what one leaves idle the deep products of another fill.  The side streams start
 // after everything already enqueued on the context's stream and the context's stream continues after
-// them; all have the default priority.
+// them; all have the default priority.  (Four or six side by side were measured as well: 142 and 127 ms
+// per hyper-parameter iteration at N = 8192 against 127 ms with three.)
 struct side_lanes {
     static constexpr int MAXL = 3;
     int n = 0;
@@ -754,7 +875,7 @@ int bagel_prepare_posterior_impl(bagel_ctx *c, const float *X, const float *y, c
     const int Np = c->post_Np;
     hipStream_t st = c->stream;
     side_lanes lanes;
-    double *K[side_lanes::MAXL] = {}, *R[side_lanes::MAXL] = {};
+    double *K[side_lanes::MAXL] = {}, *Z[side_lanes::MAXL] = {}, *vec[side_lanes::MAXL] = {};
     int *flag = nullptr;
     float h_sf2[8], h_sn2[8];
     int rc = BAGEL_OK;
@@ -771,7 +892,8 @@ int bagel_prepare_posterior_impl(bagel_ctx *c, const float *X, const float *y, c
     } while (0)
     P_HIP(lanes.open(M));
     P_HIP(lane_alloc(K, lanes.n, (size_t)Np * Np));
-    P_HIP(lane_alloc(R, lanes.n, (size_t)Np * (Np + 1)));
+    P_HIP(lane_alloc(Z, lanes.n, (size_t)Np * Np));
+    P_HIP(lane_alloc(vec, lanes.n, (size_t)2 * Np));
     P_HIP(hipMalloc((void **)&flag, sizeof(int)));
     P_HIP(hipMemsetAsync(flag, 0, sizeof(int), st));
     P_HIP(hipMemcpyAsync(h_sf2, sf2, M * sizeof(float), hipMemcpyDeviceToHost, st));
@@ -784,11 +906,8 @@ int bagel_prepare_posterior_impl(bagel_ctx *c, const float *X, const float *y, c
         c->post_sf2[m] = (double)h_sf2[m];
         hipLaunchKernelGGL(build_khat_kernel, dim3((Np + 255) / 256, Np), dim3(256), 0, ls, X, ell + (size_t)m * D,
                            h_sf2[m], h_sn2[m], K[l], N, Np, D);
-        hipLaunchKernelGGL(posterior_rhs_kernel, dim3((Np + 1 + 255) / 256, Np), dim3(256), 0, ls, y + (size_t)m * N,
-                           R[l], N, Np);
-        factor_and_solve(ls, K[l], Np, R[l], Np + 1, m * Np, flag);
-        hipLaunchKernelGGL(posterior_emit_kernel, dim3((Np + 1 + 255) / 256, Np), dim3(256), 0, ls, R[l],
-                           c->post_Kinv + (size_t)m * Np * Np, c->post_alpha + (size_t)m * Np, Np);
+        inverse_from_factor(ls, K[l], Np, Z[l], y + (size_t)m * N, N, vec[l], vec[l] + Np,
+                            c->post_Kinv + (size_t)m * Np * Np, c->post_alpha + (size_t)m * Np, m * Np, flag);
         P_HIP(hipGetLastError());
     }
     P_HIP(lanes.join(st));
@@ -803,7 +922,7 @@ int bagel_prepare_posterior_impl(bagel_ctx *c, const float *X, const float *y, c
 done:
     lanes.close();
     (void)hipStreamSynchronize(st);
-    lane_free(K); lane_free(R);
+    lane_free(K); lane_free(Z); lane_free(vec);
     if (flag) (void)hipFree(flag);
     return rc;
 #undef P_HIP
@@ -820,7 +939,8 @@ int bagel_hyper_impl(bagel_ctx *c, const float *X, const float *y, float *log_hy
     const int Np = (N + NB - 1) / NB * NB;
     hipStream_t st = c->stream;
     side_lanes lanes;
-    double *K[side_lanes::MAXL] = {}, *R[side_lanes::MAXL] = {}, *partial[side_lanes::MAXL] = {};
+    double *K[side_lanes::MAXL] = {}, *Z[side_lanes::MAXL] = {}, *Kinv[side_lanes::MAXL] = {},
+           *vec[side_lanes::MAXL] = {}, *partial[side_lanes::MAXL] = {};
     float *gneg = nullptr;
     int *flag = nullptr;
     int rc = BAGEL_OK, h_flag = 0;
@@ -835,7 +955,9 @@ int bagel_hyper_impl(bagel_ctx *c, const float *X, const float *y, float *log_hy
     } while (0)
     P_HIP(lanes.open(M));
     P_HIP(lane_alloc(K, lanes.n, (size_t)Np * Np));
-    P_HIP(lane_alloc(R, lanes.n, (size_t)Np * (Np + 1)));
+    P_HIP(lane_alloc(Z, lanes.n, (size_t)Np * Np));
+    P_HIP(lane_alloc(Kinv, lanes.n, (size_t)Np * Np));
+    P_HIP(lane_alloc(vec, lanes.n, (size_t)3 * Np));            // y, Z y, alpha
     P_HIP(lane_alloc(partial, lanes.n, (size_t)N * H2));
     P_HIP(hipMalloc((void **)&gneg, (size_t)M * H2 * sizeof(float)));
     P_HIP(hipMalloc((void **)&flag, sizeof(int)));
@@ -847,12 +969,11 @@ int bagel_hyper_impl(bagel_ctx *c, const float *X, const float *y, float *log_hy
             hipStream_t ls = lanes.st[l];
             const float *lh = log_hyp + (size_t)m * H2;
             hipLaunchKernelGGL(build_khat_log_kernel, dim3((Np + 255) / 256, Np), dim3(256), 0, ls, X, lh, K[l], N, Np, D);
-            hipLaunchKernelGGL(posterior_rhs_kernel, dim3((Np + 1 + 255) / 256, Np), dim3(256), 0, ls, y + (size_t)m * N,
-                               R[l], N, Np);
-            factor_and_solve(ls, K[l], Np, R[l], Np + 1, m * Np, flag);
-            hipLaunchKernelGGL(hyper_lml_kernel, dim3(1), dim3(256), 0, ls, K[l], R[l], y + (size_t)m * N, N, Np,
+            double *al = vec[l] + 2 * Np;
+            inverse_from_factor(ls, K[l], Np, Z[l], y + (size_t)m * N, N, vec[l], vec[l] + Np, Kinv[l], al, m * Np, flag);
+            hipLaunchKernelGGL(hyper_lml_kernel, dim3(1), dim3(256), 0, ls, K[l], al, y + (size_t)m * N, N, Np,
                                lml + (size_t)it * M + m);
-            hipLaunchKernelGGL(hyper_grad_rows_kernel, dim3(N), dim3(256), 0, ls, X, lh, R[l], partial[l], N, Np, D);
+            hipLaunchKernelGGL(hyper_grad_rows_kernel, dim3(N), dim3(256), 0, ls, X, lh, Kinv[l], al, partial[l], N, Np, D);
             hipLaunchKernelGGL(hyper_grad_final_kernel, dim3(H2), dim3(256), 0, ls, partial[l], N, D,
                                grad ? grad + (size_t)m * H2 : nullptr, gneg + (size_t)m * H2);
             P_HIP(hipGetLastError());
@@ -874,7 +995,7 @@ int bagel_hyper_impl(bagel_ctx *c, const float *X, const float *y, float *log_hy
 done:
     lanes.close();
     (void)hipStreamSynchronize(st);
-    lane_free(K); lane_free(R); lane_free(partial);
+    lane_free(K); lane_free(Z); lane_free(Kinv); lane_free(vec); lane_free(partial);
     if (gneg) (void)hipFree(gneg);
     if (flag) (void)hipFree(flag);
     return rc;
