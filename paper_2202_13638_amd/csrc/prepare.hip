@@ -519,50 +519,33 @@ __global__ __launch_bounds__(256) void mirror_lower_kernel(double *__restrict__ 
     }
 }
 
-// t[i] = sum_{k <= i} Z[i][k] y[k] for lower-triangular Z: one wave per row, the lanes walk the row
+// out[i] = sum_k A[i][k] y[k] for a square row-major matrix: one wave per row, the lanes walk the row
 // together (contiguous reads), their sums are added by a fixed butterfly.
-__global__ __launch_bounds__(256) void lower_times_vector_kernel(const double *__restrict__ Z, const double *__restrict__ y,
-                                                                 double *__restrict__ t, int Np)
+__global__ __launch_bounds__(256) void matrix_times_vector_kernel(const double *__restrict__ A, const double *__restrict__ y,
+                                                                  double *__restrict__ out, int Np)
 {
     const int lane = threadIdx.x & 63;
     const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (i >= Np) return;
-    const double *row = Z + (size_t)i * Np;
+    const double *row = A + (size_t)i * Np;
     double s = 0.0;
-    for (int k = lane; k <= i; k += 64) s += row[k] * y[k];
+    for (int k = lane; k < Np; k += 64) s += row[k] * y[k];
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
-    if (lane == 0) t[i] = s;
-}
-
-// a[j] = sum_{k >= j} Z[k][j] t[k] for lower-triangular Z: lane = column (64 per workgroup, contiguous
-// reads of every row), wave w takes rows k = w mod 4; the four partial sums are added in wave order.
-__global__ __launch_bounds__(256) void lower_transposed_times_vector_kernel(const double *__restrict__ Z,
-                                                                            const double *__restrict__ t,
-                                                                            double *__restrict__ a, int Np)
-{
-    __shared__ double sh[4][64];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int j0 = blockIdx.x * 64, j = j0 + lane;
-    double s = 0.0;
-    if (j < Np)
-        for (int k = j0 + wave; k < Np; k += 4)
-            if (k >= j) s += Z[(size_t)k * Np + j] * t[k];
-    sh[wave][lane] = s;
-    __syncthreads();
-    if (wave == 0 && j < Np) a[j] = ((sh[0][lane] + sh[1][lane]) + sh[2][lane]) + sh[3][lane];
+    if (lane == 0) out[i] = s;
 }
 
 // K_hat^-1 and alpha = K_hat^-1 y from the factor L in K (eq. (2), (3), (5), (6) all need both):
 // Z = L^-1 by structured forward substitution on the identity, K_hat^-1 = Z^T Z on and below the
 // diagonal in row panels (entry (i, j) only sums over k >= max(i, j), so a panel that starts at row
-// i0 contracts over Np - i0 rows of Z), mirrored into the upper triangle; alpha = Z^T (Z y).
-// N^3/4 + N^3/6 multiply-adds after the N^3/6 of the factorisation, against N^3 for substitution both
-// ways on N right-hand sides.  Z [Np][Np], yd / tv [Np] are work space; Kinv and alpha the results.
+// i0 contracts over Np - i0 rows of Z), mirrored into the upper triangle; alpha = K_hat^-1 y as a
+// matrix-vector product.  N^3/4 + N^3/6 multiply-adds after the N^3/6 of the factorisation, against N^3
+// for substitution both ways on N right-hand sides.  Z [Np][Np] and yd [Np] are work space; Kinv and
+// alpha the results.
 constexpr int INV_PANEL = 512;
 
-void inverse_from_factor(hipStream_t st, double *K, int Np, double *Z, const float *y_m, int N, double *yd, double *tv,
-                         double *Kinv, double *alpha, int flag_base, int *flag)
+void inverse_from_factor(hipStream_t st, double *K, int Np, double *Z, const float *y_m, int N, double *yd, double *Kinv,
+                         double *alpha, int flag_base, int *flag)
 {
     hipLaunchKernelGGL(inverse_init_kernel, dim3((Np + 255) / 256, Np), dim3(256), 0, st, y_m, Z, yd, N, Np);
     solver s{st, K, Np, Z, Np, flag_base, flag};
@@ -575,9 +558,7 @@ void inverse_from_factor(hipStream_t st, double *K, int Np, double *Z, const flo
              Kinv + (size_t)i0 * Np, Np, true, true, i0);
     }
     hipLaunchKernelGGL(mirror_lower_kernel, dim3(Np / 32, Np / 32), dim3(256), 0, st, Kinv, Np);
-    hipLaunchKernelGGL(lower_times_vector_kernel, dim3((Np + 3) / 4), dim3(256), 0, st, Z, yd, tv, Np);          // t = Z y
-    hipLaunchKernelGGL(lower_transposed_times_vector_kernel, dim3((Np + 63) / 64), dim3(256), 0, st, Z, tv, alpha,
-                       Np);                                                                                      // alpha = Z^T t
+    hipLaunchKernelGGL(matrix_times_vector_kernel, dim3((Np + 3) / 4), dim3(256), 0, st, Kinv, yd, alpha, Np);
 }
 
 // ---- hyper-parameter learning: log marginal likelihood and its gradient (eq. (5), (6)) ----------
@@ -893,7 +874,7 @@ int bagel_prepare_posterior_impl(bagel_ctx *c, const float *X, const float *y, c
     P_HIP(lanes.open(M));
     P_HIP(lane_alloc(K, lanes.n, (size_t)Np * Np));
     P_HIP(lane_alloc(Z, lanes.n, (size_t)Np * Np));
-    P_HIP(lane_alloc(vec, lanes.n, (size_t)2 * Np));
+    P_HIP(lane_alloc(vec, lanes.n, (size_t)Np));
     P_HIP(hipMalloc((void **)&flag, sizeof(int)));
     P_HIP(hipMemsetAsync(flag, 0, sizeof(int), st));
     P_HIP(hipMemcpyAsync(h_sf2, sf2, M * sizeof(float), hipMemcpyDeviceToHost, st));
@@ -906,8 +887,8 @@ int bagel_prepare_posterior_impl(bagel_ctx *c, const float *X, const float *y, c
         c->post_sf2[m] = (double)h_sf2[m];
         hipLaunchKernelGGL(build_khat_kernel, dim3((Np + 255) / 256, Np), dim3(256), 0, ls, X, ell + (size_t)m * D,
                            h_sf2[m], h_sn2[m], K[l], N, Np, D);
-        inverse_from_factor(ls, K[l], Np, Z[l], y + (size_t)m * N, N, vec[l], vec[l] + Np,
-                            c->post_Kinv + (size_t)m * Np * Np, c->post_alpha + (size_t)m * Np, m * Np, flag);
+        inverse_from_factor(ls, K[l], Np, Z[l], y + (size_t)m * N, N, vec[l], c->post_Kinv + (size_t)m * Np * Np,
+                            c->post_alpha + (size_t)m * Np, m * Np, flag);
         P_HIP(hipGetLastError());
     }
     P_HIP(lanes.join(st));
@@ -957,7 +938,7 @@ int bagel_hyper_impl(bagel_ctx *c, const float *X, const float *y, float *log_hy
     P_HIP(lane_alloc(K, lanes.n, (size_t)Np * Np));
     P_HIP(lane_alloc(Z, lanes.n, (size_t)Np * Np));
     P_HIP(lane_alloc(Kinv, lanes.n, (size_t)Np * Np));
-    P_HIP(lane_alloc(vec, lanes.n, (size_t)3 * Np));            // y, Z y, alpha
+    P_HIP(lane_alloc(vec, lanes.n, (size_t)2 * Np));            // y, alpha
     P_HIP(lane_alloc(partial, lanes.n, (size_t)N * H2));
     P_HIP(hipMalloc((void **)&gneg, (size_t)M * H2 * sizeof(float)));
     P_HIP(hipMalloc((void **)&flag, sizeof(int)));
@@ -969,8 +950,8 @@ int bagel_hyper_impl(bagel_ctx *c, const float *X, const float *y, float *log_hy
             hipStream_t ls = lanes.st[l];
             const float *lh = log_hyp + (size_t)m * H2;
             hipLaunchKernelGGL(build_khat_log_kernel, dim3((Np + 255) / 256, Np), dim3(256), 0, ls, X, lh, K[l], N, Np, D);
-            double *al = vec[l] + 2 * Np;
-            inverse_from_factor(ls, K[l], Np, Z[l], y + (size_t)m * N, N, vec[l], vec[l] + Np, Kinv[l], al, m * Np, flag);
+            double *al = vec[l] + Np;
+            inverse_from_factor(ls, K[l], Np, Z[l], y + (size_t)m * N, N, vec[l], Kinv[l], al, m * Np, flag);
             hipLaunchKernelGGL(hyper_lml_kernel, dim3(1), dim3(256), 0, ls, K[l], al, y + (size_t)m * N, N, Np,
                                lml + (size_t)it * M + m);
             hipLaunchKernelGGL(hyper_grad_rows_kernel, dim3(N), dim3(256), 0, ls, X, lh, Kinv[l], al, partial[l], N, Np, D);
