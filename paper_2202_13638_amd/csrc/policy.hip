@@ -290,9 +290,47 @@ __device__ __forceinline__ void stash_biases(const policy_args &a, const float (
         if (l < a.nl && (int)threadIdx.x < a.width[l + 1]) biasS[l][threadIdx.x] = bias_r[l];
 }
 
+// Bias, activation, tape and next-layer input for four consecutive output units jb .. jb + 3 of layer l
+// and trajectory column c of the workgroup (z: the contraction results).
+__device__ __forceinline__ void layer_epilogue(const policy_args &a, int l, int jb, int c, int b0, const float (&z4)[4],
+                                               const float *bias, float4 *act4)
+{
+    const int nj = a.width[l + 1];
+    const int b = b0 + c;
+    const bool live = b < a.B;
+    float out[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int j = jb + e;
+        float z = 0.0f;
+        if (j < nj) z = z4[e] + bias[j];
+        out[e] = 0.0f;
+        if (l < a.nl - 1) {
+            const float hv = j < nj ? tanh_fast(z) : 0.0f;
+            out[e] = hv;
+            if (live && j < nj) a.h[l + 1][(size_t)j * a.B + b] = hv;
+        } else if (live && j < nj) {
+            float act_v = z, act_out = z;
+            if (a.act_bound > 0.0f) {
+                act_v = tanh_fast(z);
+                act_out = a.act_bound * act_v;
+            }
+            a.a_slot[(size_t)j * a.B + b] = act_v;
+            if (a.xbuf) a.xbuf[(size_t)(a.ds + j) * a.B + b] = (double)act_out;
+        }
+    }
+    if (l < a.nl - 1) act4[(jb >> 2) * PL + c] = make_float4(out[0], out[1], out[2], out[3]);
+}
+
 // The layers of pi_theta for the 32 trajectories of a workgroup, input in act4 (all waves past a
 // barrier after it was written).  Writes the tape (h of the hidden layers, the action before
 // scaling) and the action into xbuf.
+// A layer whose contraction is not split (8 row tiles: 256 units) finishes in the registers of the wave
+// that owns the tile.  A narrower layer splits the contraction over the waves; there every slice goes
+// to LDS and the sums, in slice order, and the epilogue are spread over all 512 threads (four units of
+// one trajectory each): with two row tiles the epilogue of a layer is 4 activations per thread
+// instead of 16 on two of the eight waves, and it is the epilogues, not the matrix instructions, that
+// a narrow policy's step spends its time on.
 __device__ __forceinline__ void policy_layers(const policy_args &a, const float4 (&w_first)[4],
                                               const float4 (&w_last)[4], const float4 (&w_wide)[32],
                                               const wave_plan &p_first, const wave_plan &p_last,
@@ -300,10 +338,7 @@ __device__ __forceinline__ void policy_layers(const policy_args &a, const float4
                                               float4 *red4, const float (*biasS)[BAGEL_MAX_HIDDEN])
 {
     const int c = lane & 31, hf = lane >> 5;
-    const int b = b0 + c;
-    const bool live = b < a.B;
     for (int l = 0; l < a.nl; ++l) {
-        const int nj = a.width[l + 1];
         const wave_plan p = l == 0 ? p_first : (l == a.nl - 1 ? p_last : p_wide);
         f16v acc;
         if (p.active) {
@@ -311,34 +346,32 @@ __device__ __forceinline__ void policy_layers(const policy_args &a, const float4
             else if (l == a.nl - 1) acc = contract_batches<1>(w_last, p, lane, act4);
             else acc = contract_batches<8>(w_wide, p, lane, act4);
         }
-        combine_slices(acc, p, wave, lane, red4);
-        if (p.active && p.ks == 0) {
-            const float *bias = biasS[l];
+        if (p.ksplit == 1) {
+            __syncthreads();                 // every wave has read the layer input: act4 may be rewritten
+            if (p.active) {
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int jb = p.rt * 32 + 8 * g + 4 * hf;
-                float out[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int j = jb + e;
-                    float z = 0.0f;
-                    if (j < nj) z = acc[4 * g + e] + bias[j];
-                    out[e] = 0.0f;
-                    if (l < a.nl - 1) {
-                        const float hv = j < nj ? tanh_fast(z) : 0.0f;
-                        out[e] = hv;
-                        if (live && j < nj) a.h[l + 1][(size_t)j * a.B + b] = hv;
-                    } else if (live && j < nj) {
-                        float act_v = z, act_out = z;
-                        if (a.act_bound > 0.0f) {
-                            act_v = tanh_fast(z);
-                            act_out = a.act_bound * act_v;
-                        }
-                        a.a_slot[(size_t)j * a.B + b] = act_v;
-                        if (a.xbuf) a.xbuf[(size_t)(a.ds + j) * a.B + b] = (double)act_out;
-                    }
+                for (int g = 0; g < 4; ++g) {
+                    const float z4[4] = {acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]};
+                    layer_epilogue(a, l, p.rt * 32 + 8 * g + 4 * hf, c, b0, z4, biasS[l], act4);
                 }
-                if (l < a.nl - 1) act4[(jb >> 2) * PL + c] = make_float4(out[0], out[1], out[2], out[3]);
+            }
+        } else {
+            if (p.active) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+                    red4[(wave * 4 + g) * 64 + lane] = make_float4(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]);
+            }
+            __syncthreads();
+            // item = (row tile, register group g, lane) of a tile: 256 per row tile, at most 7 row tiles here
+            for (int item = threadIdx.x; item < p.nrt * 256; item += PW * 64) {
+                const int rt = item >> 8, g = (item >> 6) & 3, ln = item & 63;
+                float4 t = red4[((0 * p.nrt + rt) * 4 + g) * 64 + ln];
+                for (int sl = 1; sl < p.ksplit; ++sl) {
+                    const float4 u = red4[((sl * p.nrt + rt) * 4 + g) * 64 + ln];
+                    t.x += u.x; t.y += u.y; t.z += u.z; t.w += u.w;
+                }
+                const float z4[4] = {t.x, t.y, t.z, t.w};
+                layer_epilogue(a, l, rt * 32 + 8 * g + 4 * (ln >> 5), ln & 31, b0, z4, biasS[l], act4);
             }
         }
         __syncthreads();
@@ -445,17 +478,17 @@ struct tail_args {
     float *jdst;                        // tape slot [M][D][B] of step t, or null
 };
 
-// p[0] + p[stride] + ... (n terms, added in that order); the loads go out four at a time so that
-// their latencies overlap
+// p[0] + p[stride] + ... (n terms, added in that order); the loads go out eight at a time so that
+// their latencies overlap (one round trip for up to eight work-unit groups)
 __device__ __forceinline__ double sum_groups(const double *__restrict__ p, int n, size_t stride)
 {
     double s = 0.0;
-    for (int c0 = 0; c0 < n; c0 += 4) {
-        double v[4];
+    for (int c0 = 0; c0 < n; c0 += 8) {
+        double v[8];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = (c0 + u < n) ? p[(size_t)(c0 + u) * stride] : 0.0;
+        for (int u = 0; u < 8; ++u) v[u] = (c0 + u < n) ? p[(size_t)(c0 + u) * stride] : 0.0;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) s += v[u];
+        for (int u = 0; u < 8; ++u) s += v[u];
     }
     return s;
 }
@@ -465,7 +498,7 @@ __global__ __launch_bounds__(PW * 64) void step_tail_kernel(tail_args r, policy_
     __shared__ float4 act4[(BAGEL_MAX_HIDDEN / 4) * PL];
     __shared__ float4 red4[PW * 4 * 64];
     __shared__ float biasS[3][BAGEL_MAX_HIDDEN];
-    __shared__ double fS[8][PL], sS[8][PL];
+    __shared__ double fS[16][PL], sS[8][PL];             // fS rows: u sums, then (from row M) feature sums
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -474,12 +507,25 @@ __global__ __launch_bounds__(PW * 64) void step_tail_kernel(tail_args r, policy_
     const bool liveq = b0 + bl < a.B;
     const int bq = liveq ? b0 + bl : a.B - 1;
     const int B = a.B, ds = a.ds;
+    const int d_in = a.width[0];                        // d_s + d_g <= 16: one policy input row per thread row
 
+    // Everything the end of the step reads from global memory is requested here, before anything waits
+    // for a value: the kernel is a chain of latencies, and they overlap only if they start together.
     FORWARD_WEIGHTS_DECL;
     if (r.do_policy) load_forward_weights(a, wave, lane, w_first, w_last, w_wide, p_first, p_last, p_wide, bias_r);
+    double x_in = 0.0, lp_in = 0.0;
+    float g_in = 0.0f, gt_in[8];
+    if (row < ds) x_in = r.x_cur[(size_t)row * B + bq];
+    else if (row < d_in && r.goals_next) g_in = r.goals_next[(size_t)bq * r.dg + (row - ds)];
+    if (r.add_cost && row == 0) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) gt_in[j] = j < r.dg ? r.goals_t[(size_t)bq * r.dg + j] : 0.0f;
+        lp_in = r.lpt[bq];
+    }
 
-    // ---- value sums -> f (LDS): one output m per thread row.  (direct: part holds f and J_f themselves,
-    // one (output, component) pair per thread row and pass; J_f goes to the tape from here.)
+    // ---- value sums -> LDS: thread row m adds the kernel-row sums of output m, row M + m its feature
+    // sums.  (direct: part holds f and J_f themselves, one (output, component) pair per thread row and
+    // pass; J_f goes to the tape from here.)
     const size_t stride = (size_t)(1 + r.D) * B;
     if (r.direct) {
         for (int qi = row; qi < r.M * r.ncomp; qi += 16) {
@@ -489,48 +535,51 @@ __global__ __launch_bounds__(PW * 64) void step_tail_kernel(tail_args r, policy_
             else if (liveq) r.jdst[(size_t)(m * r.D + comp - 1) * B + bq] = (float)val;
         }
     } else if (row < r.M) {
-        const int m = row;
-        const double u = sum_groups(r.part + (size_t)(m * r.ngk) * stride + bq, r.ngk, stride);
-        const double p = sum_groups(r.part + (size_t)(r.M * r.ngk + m * r.ngl) * stride + bq, r.ngl, stride);
-        fS[m][bl] = r.amp[m] * p + u;
+        fS[row][bl] = sum_groups(r.part + (size_t)(row * r.ngk) * stride + bq, r.ngk, stride);
+    } else if (row < 2 * r.M) {
+        const int m = row - r.M;
+        fS[row][bl] = sum_groups(r.part + (size_t)(r.M * r.ngk + m * r.ngl) * stride + bq, r.ngl, stride);
     }
     __syncthreads();
 
     // ---- s_{t+1}, tapes, and the policy input [s_{t+1} ; g_{t+1}] (rows up to 32 zero) in act4
     float *act1 = reinterpret_cast<float *>(act4);
-    const int d_in = a.width[0];
-    for (int k = row; k < 32; k += 16) {
+    {
         float hin = 0.0f;
-        if (k < ds) {
-            const double s = r.x_cur[(size_t)k * B + bq] + fS[k][bl];
-            sS[k][bl] = s;
-            hin = (float)s;
+        if (row < ds) {
+            const double f = r.direct ? fS[row][bl] : r.amp[row] * fS[r.M + row][bl] + fS[row][bl];
+            const double sn = x_in + f;
+            sS[row][bl] = sn;
+            hin = (float)sn;
             if (liveq) {
-                r.x_next[(size_t)k * B + bq] = s;
-                if (r.tape_s_next) r.tape_s_next[(size_t)k * B + bq] = hin;
-                if (r.states_out_next) r.states_out_next[(size_t)bq * ds + k] = hin;
+                r.x_next[(size_t)row * B + bq] = sn;
+                if (r.tape_s_next) r.tape_s_next[(size_t)row * B + bq] = hin;
+                if (r.states_out_next) r.states_out_next[(size_t)bq * ds + row] = hin;
             }
-        } else if (k < d_in && r.goals_next) {
-            hin = r.goals_next[(size_t)bq * r.dg + (k - ds)];
+        } else if (row < d_in) {
+            hin = g_in;
         }
         if (r.do_policy) {
-            act1[((k >> 2) * PL + bl) * 4 + (k & 3)] = hin;
-            if (liveq && k < d_in) a.h[0][(size_t)k * B + bq] = hin;
+            act1[((row >> 2) * PL + bl) * 4 + (row & 3)] = hin;
+            act1[(((row + 16) >> 2) * PL + bl) * 4 + (row & 3)] = 0.0f;
+            if (liveq && row < d_in) a.h[0][(size_t)row * B + bq] = hin;
         }
     }
     if (r.do_policy) stash_biases(a, bias_r, biasS);
     __syncthreads();
     if (r.add_cost && row == 0 && liveq) {
         double e = 0.0;
-        for (int j = 0; j < r.dg; ++j) {
-            const double dlt = sS[r.tracked[j]][bl] - (double)r.goals_t[(size_t)bq * r.dg + j];
-            e += (double)r.q[j] * dlt * dlt;
-        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if (j < r.dg) {
+                const double dlt = sS[r.tracked[j]][bl] - (double)gt_in[j];
+                e += (double)r.q[j] * dlt * dlt;
+            }
         if (r.cost_kind == 1) {
             const double sr2 = (double)r.sigma_r * (double)r.sigma_r;
             e = -exp(-e / (2.0 * sr2));
         }
-        r.lpt[bq] += e;
+        r.lpt[bq] = lp_in + e;
     }
     if (r.do_policy) policy_layers(a, w_first, w_last, w_wide, p_first, p_last, p_wide, wave, lane, b0, act4, red4, biasS);
 }
