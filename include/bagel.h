@@ -103,9 +103,11 @@ int bagel_num_params(const bagel_dims *dims);
  * Create a context for fixed dims on the current HIP device.  Allocates every buffer the rollout
  * calls, bagel_set_samples, bagel_sample_eval, bagel_adam_step and bagel_optimize need (model copy,
  * tape, partial sums); those calls allocate nothing.  The set-up calls allocate on their own:
- * bagel_prepare_samples and bagel_hyper_* take float64 scratch for the duration of the call, the first
- * bagel_prepare_posterior allocates the posterior cache, which the context then keeps (sizes at their
- * declarations).  `hip_stream` is a hipStream_t (NULL = default stream); all later work of this
+ * bagel_prepare_samples, bagel_prepare_posterior and bagel_hyper_* share one float64 work space and up to
+ * three internal streams, which the first of them makes, a later one enlarges if it needs more, and the
+ * context keeps until bagel_destroy (so a loop over set-up calls allocates in its first pass only); the
+ * first bagel_prepare_posterior also allocates the posterior cache, which the context keeps as well
+ * (sizes at their declarations; bagel_workspace_bytes counts all of it).  `hip_stream` is a hipStream_t (NULL = default stream); all later work of this
  * context is enqueued there.
  * Errors: EINVAL (bad dims, null pointers), ENOMEM, EHIP.
  */
@@ -127,9 +129,10 @@ int64_t bagel_workspace_bytes(const bagel_ctx *ctx);
  *   w[S][M][L]  eps[S][M][N]      (M = d_s)
  *   v_out[S][M][N] or NULL: receives the float32 representer weights.
  * Synchronises the stream (it must learn whether the factorisation succeeded).  Set-up work: it
- * allocates float64 scratch of its own and frees it before returning, 8 (Np^2 + Np L + Np S + S L) bytes
- * for each of up to three outputs that it works on side by side on internal streams (ordered after
- * what is already enqueued on the context's stream; all finished on return).
+ * needs 8 (Np^2 + Np L + Np S + S L) bytes of the set-up work space (see bagel_create) for each of up
+ * to three outputs that it works on side by side on internal streams (ordered after what is already
+ * enqueued on the context's stream; all finished on return; fewer side by side if the memory for three
+ * cannot be had).
  * Errors: EINVAL, ENOMEM, ENOTPD (context is left unprepared), EHIP.
  */
 int bagel_prepare_samples(bagel_ctx *ctx, const float *X, const float *y, const float *lengthscale,
@@ -230,7 +233,8 @@ int bagel_optimize(bagel_ctx *ctx, float *theta, float *adam_m, float *adam_v, c
  * with respect to the logarithms of the hyper-parameters of eq. (4):
  *   log_hyp[M][D+2] = (log l_1 .. log l_D, log alpha^2, log sigma_n^2) per output.
  * X[N][D], y[M][N] as in bagel_prepare_samples; lml[M]; grad[M][D+2] or NULL.  Float64 inside.
- * Set-up work: allocates its N x N buffers for the duration of the call and synchronises the stream.
+ * Set-up work: needs three Np x Np float64 matrices per output worked on (set-up work space, see
+ * bagel_create) and synchronises the stream.
  * Errors: EINVAL, ENOMEM, ENOTPD, EHIP.
  *
  * bagel_hyper_fit: n_iters Adam updates of log_hyp (in place) that raise lml / N of every output;

@@ -246,6 +246,7 @@ extern "C" int bagel_destroy(bagel_ctx *c)
             if (c->prof_ev[i]) (void)hipEventDestroy(c->prof_ev[i]);
         free(c->prof_ev);
     }
+    bagel_release_setup(c);
     free_all(c);
     delete c;
     return BAGEL_OK;

@@ -79,6 +79,9 @@ struct bagel_ctx {
     double *post_sums;           // [M][post_Np/64][2(1+D)][B]: per-tile sums of the moments
     const float *cur_xi;         // draws of the rollout in progress (null: pathwise sampler)
 
+    // ---- set-up calls (prepare.hip): side streams and float64 work space, made by the first of them --
+    void *setup;
+
     // ---- measurement hooks -------------------------------------------------------------------
     int prof_every, prof_seen, prof_used;
     hipEvent_t *prof_ev;         // 2 * BAGEL_PROF_MAX events, created on enable
@@ -154,6 +157,8 @@ int bagel_prepare_impl(bagel_ctx *ctx, const float *X, const float *y, const flo
 // K_hat^-1 and K_hat^-1 y of every output into ctx->post_Kinv / post_alpha (float64)
 int bagel_prepare_posterior_impl(bagel_ctx *ctx, const float *X, const float *y, const float *ell, const float *sf2,
                                  const float *sn2);
+// release the side streams and work space of the set-up calls (bagel_destroy)
+void bagel_release_setup(bagel_ctx *ctx);
 // C (+)= alpha * A * B in float64 with element strides (see dgemm_kernel); overwrite: C = alpha * A * B
 void bagel_dgemm(hipStream_t st, int Mr, int Nc, int Kd, double alpha, const double *A, long sai, long sak,
                  const double *Bm, long sbk, long sbj, double *Cm, long ldc, bool overwrite);

@@ -732,6 +732,10 @@ struct side_lanes {
         }
         return e;
     }
+    void sync()
+    {
+        for (int l = 0; l < n; ++l) (void)hipStreamSynchronize(st[l]);
+    }
     void close()
     {
         for (int l = 0; l < MAXL; ++l) {
@@ -742,27 +746,86 @@ struct side_lanes {
     }
 };
 
-// One buffer per lane; a lane whose buffer cannot be had is given up (n shrinks), the first one must succeed.
-hipError_t lane_alloc(double *(&buf)[side_lanes::MAXL], int &n, size_t count)
+// What the set-up calls need beyond the context's own buffers: the side streams and one device
+// allocation that their float64 work space is carved from.  Both are made by the first set-up call,
+// grown when a later call needs more, kept for the next call (a caller's own loop over
+// bagel_hyper_lml_grad, or a redraw of the samples with bagel_prepare_samples every few policy
+// updates, allocates nothing after its first pass) and released by bagel_destroy.
+struct setup_scratch {
+    side_lanes lanes;
+    bool lanes_open = false;
+    char *arena = nullptr;
+    size_t arena_bytes = 0;
+};
+
+constexpr size_t ARENA_ALIGN = 256;
+size_t arena_round(size_t bytes) { return (bytes + ARENA_ALIGN - 1) / ARENA_ALIGN * ARENA_ALIGN; }
+
+// The context's set-up scratch with its side streams open (at most `want` of them) and at least
+// shared_bytes + n * lane_bytes of device memory, n = number of outputs worked on side by side: as many
+// as there are streams, fewer if the memory for that many cannot be had (one must fit).  The stream is
+// idle when the arena is replaced: every set-up call ends with a synchronisation.
+hipError_t setup_reserve(bagel_ctx *c, int want, size_t lane_bytes, size_t shared_bytes, setup_scratch **out, int *n_side)
 {
-    for (int l = 0; l < n; ++l) {
-        const hipError_t e = hipMalloc((void **)&buf[l], count * sizeof(double));
+    setup_scratch *sc = static_cast<setup_scratch *>(c->setup);
+    if (!sc) {
+        sc = new (std::nothrow) setup_scratch();
+        if (!sc) return hipErrorOutOfMemory;
+        c->setup = sc;
+    }
+    if (!sc->lanes_open) {
+        const hipError_t e = sc->lanes.open(want);
         if (e != hipSuccess) {
-            buf[l] = nullptr;
-            (void)hipGetLastError();
-            if (l == 0) return e;
-            n = l;
-            break;
+            sc->lanes.close();
+            sc->lanes = side_lanes();
+            return e;
+        }
+        sc->lanes_open = true;
+    }
+    *out = sc;
+    lane_bytes = arena_round(lane_bytes);
+    shared_bytes = arena_round(shared_bytes);
+    for (int n = sc->lanes.n; n >= 1; --n) {
+        const size_t need = shared_bytes + (size_t)n * lane_bytes;
+        if (sc->arena_bytes >= need) {
+            *n_side = n;
+            return hipSuccess;
         }
     }
-    return hipSuccess;
+    (void)hipStreamSynchronize(c->stream);
+    if (sc->arena) {
+        (void)hipFree(sc->arena);
+        c->bytes -= (int64_t)sc->arena_bytes;
+        sc->arena = nullptr;
+        sc->arena_bytes = 0;
+    }
+    hipError_t e = hipErrorOutOfMemory;
+    for (int n = sc->lanes.n; n >= 1; --n) {
+        const size_t need = shared_bytes + (size_t)n * lane_bytes;
+        e = hipMalloc((void **)&sc->arena, need);
+        if (e == hipSuccess) {
+            sc->arena_bytes = need;
+            c->bytes += (int64_t)need;
+            *n_side = n;
+            return hipSuccess;
+        }
+        sc->arena = nullptr;
+        (void)hipGetLastError();
+    }
+    return e;
 }
 
-void lane_free(double *(&buf)[side_lanes::MAXL])
-{
-    for (double *&p : buf)
-        if (p) { (void)hipFree(p); p = nullptr; }
-}
+// consecutive pieces of the arena
+struct arena_cursor {
+    char *p;
+    template <class T>
+    T *take(size_t count)
+    {
+        T *r = reinterpret_cast<T *>(p);
+        p += arena_round(count * sizeof(T));
+        return r;
+    }
+};
 
 }  // namespace
 
@@ -772,6 +835,19 @@ void bagel_dgemm(hipStream_t st, int Mr, int Nc, int Kd, double alpha, const dou
     gemm(st, Mr, Nc, Kd, alpha, A, sai, sak, Bm, sbk, sbj, Cm, ldc, false, overwrite);
 }
 
+void bagel_release_setup(bagel_ctx *c)
+{
+    setup_scratch *sc = static_cast<setup_scratch *>(c->setup);
+    if (!sc) return;
+    sc->lanes.close();
+    if (sc->arena) {
+        (void)hipFree(sc->arena);
+        c->bytes -= (int64_t)sc->arena_bytes;
+    }
+    delete sc;
+    c->setup = nullptr;
+}
+
 int bagel_prepare_impl(bagel_ctx *c, const float *X, const float *y, const float *ell, const float *sf2,
                        const float *sn2, const float *omega, const float *phase, const float *w,
                        const float *eps, float *v_out)
@@ -779,7 +855,8 @@ int bagel_prepare_impl(bagel_ctx *c, const float *X, const float *y, const float
     const int N = c->dm.N, L = c->dm.L, S = c->dm.S, M = c->M, D = c->D;
     const int Np = (N + NB - 1) / NB * NB;
     hipStream_t st = c->stream;
-    side_lanes lanes;
+    setup_scratch *sc = nullptr;
+    int n_side = 1;
     double *K[side_lanes::MAXL] = {}, *Phi[side_lanes::MAXL] = {}, *R[side_lanes::MAXL] = {}, *Wd[side_lanes::MAXL] = {};
     int *flag = nullptr;
     float h_sf2[8], h_sn2[8];
@@ -797,21 +874,28 @@ int bagel_prepare_impl(bagel_ctx *c, const float *X, const float *y, const float
         }                                                                                        \
     } while (0)
 
-    P_HIP(lanes.open(M));
-    P_HIP(lane_alloc(K, lanes.n, (size_t)Np * Np));
-    P_HIP(lane_alloc(Phi, lanes.n, (size_t)Np * L));
-    P_HIP(lane_alloc(R, lanes.n, (size_t)Np * S));
-    P_HIP(lane_alloc(Wd, lanes.n, (size_t)S * L));
-    P_HIP(hipMalloc((void **)&flag, sizeof(int)));
+    {
+        const size_t nK = (size_t)Np * Np, nPhi = (size_t)Np * L, nR = (size_t)Np * S, nW = (size_t)S * L;
+        P_HIP(setup_reserve(c, M, arena_round(nK * 8) + arena_round(nPhi * 8) + arena_round(nR * 8) + arena_round(nW * 8),
+                            sizeof(int), &sc, &n_side));
+        arena_cursor cur{sc->arena};
+        flag = cur.take<int>(1);
+        for (int l = 0; l < n_side; ++l) {
+            K[l] = cur.take<double>(nK);
+            Phi[l] = cur.take<double>(nPhi);
+            R[l] = cur.take<double>(nR);
+            Wd[l] = cur.take<double>(nW);
+        }
+    }
     P_HIP(hipMemsetAsync(flag, 0, sizeof(int), st));
     P_HIP(hipMemcpyAsync(h_sf2, sf2, M * sizeof(float), hipMemcpyDeviceToHost, st));
     P_HIP(hipMemcpyAsync(h_sn2, sn2, M * sizeof(float), hipMemcpyDeviceToHost, st));
     P_HIP(hipStreamSynchronize(st));
 
-    P_HIP(lanes.fork(st));
+    P_HIP(sc->lanes.fork(st));
     for (int m = 0; m < M; ++m) {
-        const int l = m % lanes.n;
-        hipStream_t ls = lanes.st[l];
+        const int l = m % n_side;
+        hipStream_t ls = sc->lanes.st[l];
         hipLaunchKernelGGL(build_khat_kernel, dim3((Np + 255) / 256, Np), dim3(256), 0, ls, X, ell + (size_t)m * D,
                            h_sf2[m], h_sn2[m], K[l], N, Np, D);
         hipLaunchKernelGGL(build_phi_kernel, dim3((L + 255) / 256, Np), dim3(256), 0, ls, X,
@@ -828,7 +912,7 @@ int bagel_prepare_impl(bagel_ctx *c, const float *X, const float *y, const float
                            c->Np, S, M, m);
         P_HIP(hipGetLastError());
     }
-    P_HIP(lanes.join(st));
+    P_HIP(sc->lanes.join(st));
     P_HIP(hipMemcpyAsync(&h_flag, flag, sizeof(int), hipMemcpyDeviceToHost, st));
     P_HIP(hipStreamSynchronize(st));
     if (h_flag != 0) {
@@ -838,10 +922,8 @@ int bagel_prepare_impl(bagel_ctx *c, const float *X, const float *y, const float
         rc = BAGEL_ENOTPD;
     }
 done:
-    lanes.close();
+    if (sc) sc->lanes.sync();
     (void)hipStreamSynchronize(st);
-    lane_free(K); lane_free(Phi); lane_free(R); lane_free(Wd);
-    if (flag) (void)hipFree(flag);
     return rc;
 #undef P_HIP
 }
@@ -855,7 +937,8 @@ int bagel_prepare_posterior_impl(bagel_ctx *c, const float *X, const float *y, c
     const int N = c->dm.N, M = c->M, D = c->D;
     const int Np = c->post_Np;
     hipStream_t st = c->stream;
-    side_lanes lanes;
+    setup_scratch *sc = nullptr;
+    int n_side = 1;
     double *K[side_lanes::MAXL] = {}, *Z[side_lanes::MAXL] = {}, *vec[side_lanes::MAXL] = {};
     int *flag = nullptr;
     float h_sf2[8], h_sn2[8];
@@ -871,19 +954,25 @@ int bagel_prepare_posterior_impl(bagel_ctx *c, const float *X, const float *y, c
             goto done;                                                                           \
         }                                                                                        \
     } while (0)
-    P_HIP(lanes.open(M));
-    P_HIP(lane_alloc(K, lanes.n, (size_t)Np * Np));
-    P_HIP(lane_alloc(Z, lanes.n, (size_t)Np * Np));
-    P_HIP(lane_alloc(vec, lanes.n, (size_t)Np));
-    P_HIP(hipMalloc((void **)&flag, sizeof(int)));
+    {
+        const size_t nK = (size_t)Np * Np;
+        P_HIP(setup_reserve(c, M, 2 * arena_round(nK * 8) + arena_round((size_t)Np * 8), sizeof(int), &sc, &n_side));
+        arena_cursor cur{sc->arena};
+        flag = cur.take<int>(1);
+        for (int l = 0; l < n_side; ++l) {
+            K[l] = cur.take<double>(nK);
+            Z[l] = cur.take<double>(nK);
+            vec[l] = cur.take<double>(Np);
+        }
+    }
     P_HIP(hipMemsetAsync(flag, 0, sizeof(int), st));
     P_HIP(hipMemcpyAsync(h_sf2, sf2, M * sizeof(float), hipMemcpyDeviceToHost, st));
     P_HIP(hipMemcpyAsync(h_sn2, sn2, M * sizeof(float), hipMemcpyDeviceToHost, st));
     P_HIP(hipStreamSynchronize(st));
-    P_HIP(lanes.fork(st));
+    P_HIP(sc->lanes.fork(st));
     for (int m = 0; m < M; ++m) {
-        const int l = m % lanes.n;
-        hipStream_t ls = lanes.st[l];
+        const int l = m % n_side;
+        hipStream_t ls = sc->lanes.st[l];
         c->post_sf2[m] = (double)h_sf2[m];
         hipLaunchKernelGGL(build_khat_kernel, dim3((Np + 255) / 256, Np), dim3(256), 0, ls, X, ell + (size_t)m * D,
                            h_sf2[m], h_sn2[m], K[l], N, Np, D);
@@ -891,7 +980,7 @@ int bagel_prepare_posterior_impl(bagel_ctx *c, const float *X, const float *y, c
                             c->post_alpha + (size_t)m * Np, m * Np, flag);
         P_HIP(hipGetLastError());
     }
-    P_HIP(lanes.join(st));
+    P_HIP(sc->lanes.join(st));
     P_HIP(hipMemcpyAsync(&h_flag, flag, sizeof(int), hipMemcpyDeviceToHost, st));
     P_HIP(hipStreamSynchronize(st));
     if (h_flag != 0) {
@@ -901,10 +990,8 @@ int bagel_prepare_posterior_impl(bagel_ctx *c, const float *X, const float *y, c
         rc = BAGEL_ENOTPD;
     }
 done:
-    lanes.close();
+    if (sc) sc->lanes.sync();
     (void)hipStreamSynchronize(st);
-    lane_free(K); lane_free(Z); lane_free(vec);
-    if (flag) (void)hipFree(flag);
     return rc;
 #undef P_HIP
 }
@@ -919,7 +1006,8 @@ int bagel_hyper_impl(bagel_ctx *c, const float *X, const float *y, float *log_hy
     const int N = c->dm.N, M = c->M, D = c->D, H2 = c->D + 2;
     const int Np = (N + NB - 1) / NB * NB;
     hipStream_t st = c->stream;
-    side_lanes lanes;
+    setup_scratch *sc = nullptr;
+    int n_side = 1;
     double *K[side_lanes::MAXL] = {}, *Z[side_lanes::MAXL] = {}, *Kinv[side_lanes::MAXL] = {},
            *vec[side_lanes::MAXL] = {}, *partial[side_lanes::MAXL] = {};
     float *gneg = nullptr;
@@ -934,20 +1022,27 @@ int bagel_hyper_impl(bagel_ctx *c, const float *X, const float *y, float *log_hy
             goto done;                                                                           \
         }                                                                                        \
     } while (0)
-    P_HIP(lanes.open(M));
-    P_HIP(lane_alloc(K, lanes.n, (size_t)Np * Np));
-    P_HIP(lane_alloc(Z, lanes.n, (size_t)Np * Np));
-    P_HIP(lane_alloc(Kinv, lanes.n, (size_t)Np * Np));
-    P_HIP(lane_alloc(vec, lanes.n, (size_t)2 * Np));            // y, alpha
-    P_HIP(lane_alloc(partial, lanes.n, (size_t)N * H2));
-    P_HIP(hipMalloc((void **)&gneg, (size_t)M * H2 * sizeof(float)));
-    P_HIP(hipMalloc((void **)&flag, sizeof(int)));
+    {
+        const size_t nK = (size_t)Np * Np;
+        P_HIP(setup_reserve(c, M, 3 * arena_round(nK * 8) + arena_round((size_t)2 * Np * 8) + arena_round((size_t)N * H2 * 8),
+                            arena_round(sizeof(int)) + arena_round((size_t)M * H2 * sizeof(float)), &sc, &n_side));
+        arena_cursor cur{sc->arena};
+        flag = cur.take<int>(1);
+        gneg = cur.take<float>((size_t)M * H2);
+        for (int l = 0; l < n_side; ++l) {
+            K[l] = cur.take<double>(nK);
+            Z[l] = cur.take<double>(nK);
+            Kinv[l] = cur.take<double>(nK);
+            vec[l] = cur.take<double>((size_t)2 * Np);          // y, alpha
+            partial[l] = cur.take<double>((size_t)N * H2);
+        }
+    }
     P_HIP(hipMemsetAsync(flag, 0, sizeof(int), st));
     for (int it = 0; it < (n_iters > 0 ? n_iters : 1); ++it) {
-        P_HIP(lanes.fork(st));                          // after the parameter update of the previous iteration
+        P_HIP(sc->lanes.fork(st));                      // after the parameter update of the previous iteration
         for (int m = 0; m < M; ++m) {
-            const int l = m % lanes.n;
-            hipStream_t ls = lanes.st[l];
+            const int l = m % n_side;
+            hipStream_t ls = sc->lanes.st[l];
             const float *lh = log_hyp + (size_t)m * H2;
             hipLaunchKernelGGL(build_khat_log_kernel, dim3((Np + 255) / 256, Np), dim3(256), 0, ls, X, lh, K[l], N, Np, D);
             double *al = vec[l] + Np;
@@ -959,7 +1054,7 @@ int bagel_hyper_impl(bagel_ctx *c, const float *X, const float *y, float *log_hy
                                grad ? grad + (size_t)m * H2 : nullptr, gneg + (size_t)m * H2);
             P_HIP(hipGetLastError());
         }
-        P_HIP(lanes.join(st));
+        P_HIP(sc->lanes.join(st));
         if (n_iters > 0) {
             const int step = first_step + it;
             P_HIP(bagel_launch_adam(c, log_hyp, gneg, adam_m, adam_v, M * H2, lr, beta1, beta2, eps,
@@ -974,11 +1069,8 @@ int bagel_hyper_impl(bagel_ctx *c, const float *X, const float *y, float *log_hy
         rc = BAGEL_ENOTPD;
     }
 done:
-    lanes.close();
+    if (sc) sc->lanes.sync();
     (void)hipStreamSynchronize(st);
-    lane_free(K); lane_free(Z); lane_free(Kinv); lane_free(vec); lane_free(partial);
-    if (gneg) (void)hipFree(gneg);
-    if (flag) (void)hipFree(flag);
     return rc;
 #undef P_HIP
 }

@@ -353,6 +353,35 @@ def test_prepare_matches_oracle_solution(name, kw):
         assert d[k] <= 3.0 * cond[k] + tol, (k, d[k], cond[k])
 
 
+def test_setup_work_space_is_made_once_and_kept():
+    """The set-up calls share one work space: a second pass over them allocates nothing and gives the same bits."""
+    import torch
+    from paper_2202_13638_amd import binding
+    cfg = _cfg("small", B=64, H=4)
+    inp = synth.make_inputs(cfg)
+    ctx = binding.Bagel(binding.dims_from_config(cfg))
+    g = harness.to_gpu(inp)
+    base = ctx.workspace_bytes()
+    v = [torch.zeros((cfg.B, cfg.M, cfg.N), device="cuda") for _ in range(2)]
+    lh = torch.cat([g["lengthscale"].log(), g["signal_var"].log()[:, None], g["noise_var"].log()[:, None]], dim=1).contiguous()
+    yy = torch.from_numpy(inp["y"]).cuda()
+    lml = [torch.zeros(cfg.M, device="cuda") for _ in range(2)]
+    grad = [torch.zeros((cfg.M, cfg.D + 2), device="cuda") for _ in range(2)]
+    sizes = []
+    for rep in range(2):
+        ctx.bagel_prepare_samples(g["X"], g["y"], g["lengthscale"], g["signal_var"], g["noise_var"], g["omega"],
+                                  g["phase"], g["w"], g["eps"], v[rep])
+        sizes.append(ctx.workspace_bytes())
+        ctx.bagel_hyper_lml_grad(g["X"], yy, lh, lml[rep], grad[rep])
+        sizes.append(ctx.workspace_bytes())
+    torch.cuda.synchronize()
+    assert sizes[0] > base                       # the first call made the work space
+    assert sizes[1] >= sizes[0]                  # the next kind of call may enlarge it
+    assert sizes[2] == sizes[1] and sizes[3] == sizes[1]      # the second pass allocates nothing
+    assert torch.equal(v[0], v[1]) and torch.equal(lml[0], lml[1]) and torch.equal(grad[0], grad[1])
+    ctx.close()
+
+
 def test_prepare_reports_non_positive_definite():
     import torch
     from paper_2202_13638_amd import binding
