@@ -292,8 +292,8 @@ __device__ __forceinline__ void stash_biases(const policy_args &a, const float (
 
 // Bias, activation, tape and next-layer input for four consecutive output units jb .. jb + 3 of layer l
 // and trajectory column c of the workgroup (z: the contraction results).
-__device__ __forceinline__ void layer_epilogue(const policy_args &a, int l, int jb, int c, int b0, const float (&z4)[4],
-                                               const float *bias, float4 *act4)
+__device__ __forceinline__ void layer_epilogue(const policy_args &a, size_t slot, bool write_x, int l, int jb, int c,
+                                               int b0, const float (&z4)[4], const float *bias, float4 *act4)
 {
     const int nj = a.width[l + 1];
     const int b = b0 + c;
@@ -308,15 +308,15 @@ __device__ __forceinline__ void layer_epilogue(const policy_args &a, int l, int 
         if (l < a.nl - 1) {
             const float hv = j < nj ? tanh_fast(z) : 0.0f;
             out[e] = hv;
-            if (live && j < nj) a.h[l + 1][(size_t)j * a.B + b] = hv;
+            if (live && j < nj) a.h[l + 1][(slot * nj + j) * a.B + b] = hv;
         } else if (live && j < nj) {
             float act_v = z, act_out = z;
             if (a.act_bound > 0.0f) {
                 act_v = tanh_fast(z);
                 act_out = a.act_bound * act_v;
             }
-            a.a_slot[(size_t)j * a.B + b] = act_v;
-            if (a.xbuf) a.xbuf[(size_t)(a.ds + j) * a.B + b] = (double)act_out;
+            a.a_slot[(slot * nj + j) * a.B + b] = act_v;
+            if (write_x) a.xbuf[(size_t)(a.ds + j) * a.B + b] = (double)act_out;
         }
     }
     if (l < a.nl - 1) act4[(jb >> 2) * PL + c] = make_float4(out[0], out[1], out[2], out[3]);
@@ -324,7 +324,8 @@ __device__ __forceinline__ void layer_epilogue(const policy_args &a, int l, int 
 
 // The layers of pi_theta for the 32 trajectories of a workgroup, input in act4 (all waves past a
 // barrier after it was written).  Writes the tape (h of the hidden layers, the action before
-// scaling) and the action into xbuf.
+// scaling; `slot` counts tape slots from the ones a.h and a.a_slot point at) and, with write_x, the
+// action into xbuf.
 // A layer whose contraction is not split (8 row tiles: 256 units) finishes in the registers of the wave
 // that owns the tile.  A narrower layer splits the contraction over the waves; there every slice goes
 // to LDS and the sums, in slice order, and the epilogue are spread over all 512 threads (four units of
@@ -335,7 +336,8 @@ __device__ __forceinline__ void policy_layers(const policy_args &a, const float4
                                               const float4 (&w_last)[4], const float4 (&w_wide)[32],
                                               const wave_plan &p_first, const wave_plan &p_last,
                                               const wave_plan &p_wide, int wave, int lane, int b0, float4 *act4,
-                                              float4 *red4, const float (*biasS)[BAGEL_MAX_HIDDEN])
+                                              float4 *red4, const float (*biasS)[BAGEL_MAX_HIDDEN], size_t slot = 0,
+                                              bool write_x = true)
 {
     const int c = lane & 31, hf = lane >> 5;
     for (int l = 0; l < a.nl; ++l) {
@@ -352,7 +354,7 @@ __device__ __forceinline__ void policy_layers(const policy_args &a, const float4
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     const float z4[4] = {acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]};
-                    layer_epilogue(a, l, p.rt * 32 + 8 * g + 4 * hf, c, b0, z4, biasS[l], act4);
+                    layer_epilogue(a, slot, write_x, l, p.rt * 32 + 8 * g + 4 * hf, c, b0, z4, biasS[l], act4);
                 }
             }
         } else {
@@ -371,7 +373,7 @@ __device__ __forceinline__ void policy_layers(const policy_args &a, const float4
                     t.x += u.x; t.y += u.y; t.z += u.z; t.w += u.w;
                 }
                 const float z4[4] = {t.x, t.y, t.z, t.w};
-                layer_epilogue(a, l, rt * 32 + 8 * g + 4 * (ln >> 5), ln & 31, b0, z4, biasS[l], act4);
+                layer_epilogue(a, slot, write_x, l, rt * 32 + 8 * g + 4 * (ln >> 5), ln & 31, b0, z4, biasS[l], act4);
             }
         }
         __syncthreads();
@@ -418,8 +420,6 @@ __global__ __launch_bounds__(PW * 64) void policy_replay_kernel(policy_args a, r
     FORWARD_WEIGHTS_DECL;
     load_forward_weights(a, wave, lane, w_first, w_last, w_wide, p_first, p_last, p_wide, bias_r);
     stash_biases(a, bias_r, biasS);
-    a.xbuf = nullptr;
-    const policy_args base = a;
     // A workgroup keeps the weights in its registers for REPLAY_SLOTS consecutive steps: fetching them
     // is what a replay launch spends most of its time on when every step has workgroups of its own.
     const int s_begin = blockIdx.y * REPLAY_SLOTS;
@@ -427,8 +427,6 @@ __global__ __launch_bounds__(PW * 64) void policy_replay_kernel(policy_args a, r
     for (int sl = s_begin; sl < s_end; ++sl) {
         const size_t slot = (size_t)sl;
         const int t = r.t0 + sl;
-        for (int l = 0; l < a.nl; ++l) a.h[l] = base.h[l] + slot * a.width[l] * B;
-        a.a_slot = base.a_slot + slot * a.width[a.nl] * B;
         {   // layer-0 input from the state tape and the goals, to LDS and to its tape slot
             const int bl = threadIdx.x & (PL - 1);
             const bool live = b0 + bl < a.B;
@@ -441,14 +439,14 @@ __global__ __launch_bounds__(PW * 64) void policy_replay_kernel(policy_args a, r
                     v[e] = 0.0f;
                     if (k < a.ds) v[e] = r.tape_s[((size_t)t * a.ds + k) * B + b];
                     else if (k < a.ds + r.dg) v[e] = r.goals[((size_t)t * B + b) * r.dg + (k - a.ds)];
-                    if (live && k < a.ds + r.dg) a.h[0][(size_t)k * B + b] = v[e];
+                    if (live && k < a.ds + r.dg) a.h[0][(slot * a.width[0] + k) * B + b] = v[e];
                 }
                 act4[kg * PL + bl] = make_float4(v[0], v[1], v[2], v[3]);
             }
         }
         __syncthreads();
         // ends with a barrier: act4 may be rewritten for the next slot
-        policy_layers(a, w_first, w_last, w_wide, p_first, p_last, p_wide, wave, lane, b0, act4, red4, biasS);
+        policy_layers(a, w_first, w_last, w_wide, p_first, p_last, p_wide, wave, lane, b0, act4, red4, biasS, slot, false);
     }
 }
 
@@ -1162,16 +1160,28 @@ __global__ __launch_bounds__(64 * WA * WB) void weight_grad_tiled_kernel(const f
     }
 }
 
-// gacc[p] (+)= sum_z gsplit[z][p] in z order; optionally emit grad_theta = (float) gacc
-__global__ void grad_reduce_kernel(const float *__restrict__ gsplit, double *__restrict__ gacc, int P, int ksplit,
-                                   bool accumulate, float *__restrict__ grad_theta)
+// gacc[p] (+)= sum_z gsplit[z][p]; optionally emit grad_theta = (float) gacc.  64 parameters per workgroup;
+// wave q adds the q-th quarter of the splits in z order, the four quarters are added in order.
+__global__ __launch_bounds__(256) void grad_reduce_kernel(const float *__restrict__ gsplit, double *__restrict__ gacc, int P,
+                                                          int ksplit, bool accumulate, float *__restrict__ grad_theta)
 {
-    const int p = blockIdx.x * blockDim.x + threadIdx.x;
-    if (p >= P) return;
-    double s = accumulate ? gacc[p] : 0.0;
-    for (int z = 0; z < ksplit; ++z) s += (double)gsplit[(size_t)z * P + p];
-    gacc[p] = s;
-    if (grad_theta) grad_theta[p] = (float)s;
+    __shared__ double sh[4][64];
+    const int lane = threadIdx.x & 63, quarter = threadIdx.x >> 6;
+    const int p = blockIdx.x * 64 + lane;
+    const int per = (ksplit + 3) / 4;
+    const int z0 = quarter * per, z1 = min(ksplit, z0 + per);
+    double s = 0.0;
+    if (p < P) {
+#pragma unroll 8
+        for (int z = z0; z < z1; ++z) s += (double)gsplit[(size_t)z * P + p];
+    }
+    sh[quarter][lane] = s;
+    __syncthreads();
+    if (quarter == 0 && p < P) {
+        const double tot = (accumulate ? gacc[p] : 0.0) + (((sh[0][lane] + sh[1][lane]) + sh[2][lane]) + sh[3][lane]);
+        gacc[p] = tot;
+        if (grad_theta) grad_theta[p] = (float)tot;
+    }
 }
 
 // Adam update (Kingma & Ba, Algorithm 1) of theta, m, v in place; corr1 = 1 - beta1^step, corr2 = 1 - beta2^step
@@ -1361,7 +1371,7 @@ hipError_t bagel_launch_weight_grad(bagel_ctx *c, int n_slots, bool accumulate, 
                                c->tape_h[l], c->gsplit, no, ni, B, n_slots, chunks_per_slot, per, c->w_off[l],
                                c->b_off[l], c->P, wcols);
     }
-    hipLaunchKernelGGL(grad_reduce_kernel, dim3((c->P + 255) / 256), dim3(256), 0, c->stream, c->gsplit, c->gacc, c->P,
+    hipLaunchKernelGGL(grad_reduce_kernel, dim3((c->P + 63) / 64), dim3(256), 0, c->stream, c->gsplit, c->gacc, c->P,
                        nz, accumulate, grad_theta);
     return hipGetLastError();
 }
