@@ -18,12 +18,50 @@ TOL_LOSS = 1e-4
 TOL_GRAD = 1e-3
 
 
-def oracle_reference(cfg, inp, S=None, grad=True, **dims_kw):
-    """Oracle prepare (float64) -> v rounded once to float32 -> oracle rollout on that v."""
+def progress(msg):
+    """One line on the real stderr (pytest's capture suspended for it), flushed: the long tests say which
+    of their steps has finished, so that a run whose output is piped is never silent for minutes."""
+    import contextlib
+    import sys
+    import pytest
+    capman = getattr(pytest, "bagel_capture_manager", None)      # set by conftest.py
+    cm = capman.global_and_fixture_disabled() if capman is not None else contextlib.nullcontext()
+    with cm:
+        sys.stderr.write(f"[step] {msg}\n")
+        sys.stderr.flush()
+
+
+def oracle_reference(cfg, inp, S=None, grad=True, chunks=1, **dims_kw):
+    """Oracle prepare (float64) -> v rounded once to float32 -> oracle rollout on that v.
+
+    chunks > 1 (needs one sample per trajectory): the rollout is taken in that many consecutive groups of
+    trajectories, one oracle call each, and put together here: trajectories are independent and the loss
+    is their mean (eq. (10)), so the states and per-trajectory losses are concatenated and the loss and
+    its gradients are the means of the groups' weighted by their sizes.  Only the order of the last
+    float64 additions differs from a single call."""
     dm = oracle.dims_from_config(cfg, S=S, **dims_kw)
     v64 = oracle.prepare_samples(dm, inp)
     v32 = v64.astype(np.float32)
-    out = oracle.rollout(dm, inp, v32, grad=grad)
+    progress(f"oracle prepare done ({cfg.name}, N={cfg.N}, S={dm.S})")
+    if chunks <= 1:
+        out = oracle.rollout(dm, inp, v32, grad=grad)
+    else:
+        assert S is None or S == cfg.B
+        parts, sizes = [], []
+        for idx in np.array_split(np.arange(cfg.B), chunks):
+            sub_cfg, sub_inp = synth.subset_trajectories(cfg, inp, idx)
+            sub_dm = oracle.dims_from_config(sub_cfg, **dims_kw)
+            parts.append(oracle.rollout(sub_dm, sub_inp, v32[idx], grad=grad))
+            sizes.append(len(idx))
+            progress(f"oracle rollout: {sum(sizes)} of {cfg.B} trajectories done")
+        wts = np.asarray(sizes, dtype=np.float64) / cfg.B
+        out = {"states": np.concatenate([q["states"] for q in parts], axis=1),
+               "loss_per_traj": np.concatenate([q["loss_per_traj"] for q in parts]),
+               "loss": float(sum(w * q["loss"] for w, q in zip(wts, parts))),
+               "grad_theta": None, "grad_s0": None}
+        if grad:
+            out["grad_theta"] = sum(w * q["grad_theta"] for w, q in zip(wts, parts))
+            out["grad_s0"] = np.concatenate([w * q["grad_s0"] for w, q in zip(wts, parts)], axis=0)
     out["v32"] = v32
     out["v64"] = v64
     return out

@@ -104,9 +104,10 @@ def test_large_policy_full_batch_against_the_oracle():
     oracle's float64 v, and checkpointing against the full tape on a sampled batch."""
     cfg = _cfg("large_policy")
     inp = synth.make_inputs(cfg)
-    ref = harness.oracle_reference(cfg, inp)
+    ref = harness.oracle_reference(cfg, inp, chunks=8)
     got = harness.gpu_rollout(cfg, inp, ref["v32"])
     harness.assert_parity(ref, got, label="large_policy/full batch")
+    harness.progress("large_policy: full batch compared with the oracle")
     _, v_lib, v_all = _run_full_batch(cfg, inp, ref["v32"][:8], np.arange(8))
     del v_all
     err = np.abs(v_lib - ref["v64"][:8]).max() / np.abs(ref["v64"]).max()
@@ -144,8 +145,10 @@ def test_stress_full_size():
     ref = harness.oracle_reference(sub_cfg, sub_inp)                      # oracle prepare + rollout on the sample
     alone = harness.gpu_rollout(sub_cfg, sub_inp, ref["v32"])
     harness.assert_parity(ref, alone, label=f"{name}/sampled batch of {N_SAMPLED}")
+    harness.progress("stress: sampled batch compared with the oracle")
 
     full, v_lib, v_all = _run_full_batch(cfg, inp, ref["v32"], idx)
+    harness.progress("stress: full batch done on the GPU")
     err = np.abs(v_lib - ref["v64"]).max() / np.abs(ref["v64"]).max()
     print(f"[prepare {name} full size] max|dv|/max|v| on the sampled rows = {err:.3e}", flush=True)
     assert err <= 5e-7
@@ -167,6 +170,8 @@ def test_stress_full_size():
         grad_sum += part["grad_theta"]
         np.testing.assert_allclose(part["loss_per_traj"], full["loss_per_traj"][idx_k], rtol=0,
                                    atol=1e-5 * np.abs(full["loss_per_traj"]).max())
+        if k % 8 == 7:
+            harness.progress(f"stress: {k + 1} of {stride} sub-batches done")
     del v_all
     d_loss = abs(loss_sum / stride - full["loss"]) / abs(full["loss"])
     d_grad = np.abs(grad_sum / stride - full["grad_theta"]).max() / np.abs(full["grad_theta"]).max()
