@@ -217,22 +217,17 @@ __device__ __forceinline__ void combine_slices(f16v &acc, const wave_plan &p, in
     }
 }
 
-// tanh in float32 from the hardware exp2 and reciprocal: 1 - 2 / (e^{2|z|} + 1) with the sign of z,
-// and the odd Taylor polynomial up to z^9 below |z| = 1/4, where the first form loses relative
-// accuracy.  Absolute error about 1e-7, relative error below 1e-6; a fraction of the instructions of
-// the library routine, which matters because a layer's epilogue evaluates 8192 of them per workgroup.
+// tanh in float32 from the hardware exp2 and reciprocal: 1 - 2 / (e^{2z} + 1), five instructions
+// (e^{2z} overflows to +inf for large z, where the reciprocal gives 0, and underflows to 0 for very
+// negative z: both ends come out as +-1 without a case distinction).  Absolute error below 2.5e-7 over the
+// whole range; a fraction of the instructions of the library routine, which matters because a layer's
+// epilogue evaluates 8192 of them per workgroup and is bound by instruction issue.  (A form with a
+// polynomial branch below |z| = 1/4 kept the relative error small near zero as well, at three times the
+// instructions; what the next layer and the tanh derivative see is the absolute error.)
 __device__ __forceinline__ float tanh_fast(float z)
 {
-    const float az = fabsf(z);
-    const float t = __builtin_amdgcn_exp2f(az * 2.8853900817779268f);          // e^{2|z|}; +inf for large |z|
-    const float big = copysignf(1.0f - 2.0f * __builtin_amdgcn_rcpf(t + 1.0f), z);
-    const float z2 = z * z;
-    float p = 62.0f / 2835.0f;
-    p = fmaf(p, z2, -17.0f / 315.0f);
-    p = fmaf(p, z2, 2.0f / 15.0f);
-    p = fmaf(p, z2, -1.0f / 3.0f);
-    const float small = fmaf(z * z2, p, z);
-    return az < 0.25f ? small : big;
+    const float t = __builtin_amdgcn_exp2f(z * 2.8853900817779268f);           // e^{2z}
+    return fmaf(-2.0f, __builtin_amdgcn_rcpf(t + 1.0f), 1.0f);
 }
 
 // rows of a [n][B] array -> LDS [k/4][trajectory][4], zero-filled up to kp rows
@@ -290,36 +285,55 @@ __device__ __forceinline__ void stash_biases(const policy_args &a, const float (
         if (l < a.nl && (int)threadIdx.x < a.width[l + 1]) biasS[l][threadIdx.x] = bias_r[l];
 }
 
-// Bias, activation, tape and next-layer input for four consecutive output units jb .. jb + 3 of layer l
-// and trajectory column c of the workgroup (z: the contraction results).
-__device__ __forceinline__ void layer_epilogue(const policy_args &a, size_t slot, bool write_x, int l, int jb, int c,
-                                               int b0, const float (&z4)[4], const float *bias, float4 *act4)
+// Element at a wave-uniform base plus a 32-bit byte offset per lane: the form in which the address costs no
+// vector arithmetic (the base stays in scalar registers and is advanced there).
+__device__ __forceinline__ float *at_byte(float *base, unsigned byte_off)
+{
+    return reinterpret_cast<float *>(reinterpret_cast<char *>(base) + byte_off);
+}
+
+// Bias, activation, tape and next-layer input for the four consecutive output units row_u + 4 hf + (0..3)
+// of layer l (row_u: wave-uniform, a multiple of 8) and trajectory column c of the workgroup (z4: the
+// contraction results).  An epilogue is bound by instruction issue (8192 activations per workgroup and
+// 256-unit layer), so the tape addresses are a scalar row base plus one lane offset, and the four biases
+// come as one LDS read.
+__device__ __forceinline__ void layer_epilogue(const policy_args &a, size_t slot, bool write_x, int l, int row_u, int hf,
+                                               int c, int b0, const float (&z4)[4], const float *bias, float4 *act4)
 {
     const int nj = a.width[l + 1];
     const int b = b0 + c;
     const bool live = b < a.B;
+    const int jb = row_u + 4 * hf;
+    const unsigned lane_off = ((unsigned)(4 * hf) * (unsigned)a.B + (unsigned)b) * 4u;
+    const float4 bias4 = *reinterpret_cast<const float4 *>(bias + jb);      // entries past nj are not used
+    const float bz[4] = {bias4.x, bias4.y, bias4.z, bias4.w};
     float out[4];
+    if (l < a.nl - 1) {
+        float *hrow = a.h[l + 1] + (slot * nj + row_u) * a.B;              // wave-uniform
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        const int j = jb + e;
-        float z = 0.0f;
-        if (j < nj) z = z4[e] + bias[j];
-        out[e] = 0.0f;
-        if (l < a.nl - 1) {
-            const float hv = j < nj ? tanh_fast(z) : 0.0f;
+        for (int e = 0; e < 4; ++e) {
+            const bool on = jb + e < nj;
+            const float hv = on ? tanh_fast(z4[e] + bz[e]) : 0.0f;
             out[e] = hv;
-            if (live && j < nj) a.h[l + 1][(slot * nj + j) * a.B + b] = hv;
-        } else if (live && j < nj) {
-            float act_v = z, act_out = z;
-            if (a.act_bound > 0.0f) {
-                act_v = tanh_fast(z);
-                act_out = a.act_bound * act_v;
+            if (live && on) *at_byte(hrow + (size_t)e * a.B, lane_off) = hv;
+        }
+        act4[(jb >> 2) * PL + c] = make_float4(out[0], out[1], out[2], out[3]);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int j = jb + e;
+            if (live && j < nj) {
+                const float z = z4[e] + bz[e];
+                float act_v = z, act_out = z;
+                if (a.act_bound > 0.0f) {
+                    act_v = tanh_fast(z);
+                    act_out = a.act_bound * act_v;
+                }
+                a.a_slot[(slot * nj + j) * a.B + b] = act_v;
+                if (write_x) a.xbuf[(size_t)(a.ds + j) * a.B + b] = (double)act_out;
             }
-            a.a_slot[(slot * nj + j) * a.B + b] = act_v;
-            if (write_x) a.xbuf[(size_t)(a.ds + j) * a.B + b] = (double)act_out;
         }
     }
-    if (l < a.nl - 1) act4[(jb >> 2) * PL + c] = make_float4(out[0], out[1], out[2], out[3]);
 }
 
 // The layers of pi_theta for the 32 trajectories of a workgroup, input in act4 (all waves past a
@@ -354,7 +368,7 @@ __device__ __forceinline__ void policy_layers(const policy_args &a, const float4
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     const float z4[4] = {acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]};
-                    layer_epilogue(a, slot, write_x, l, p.rt * 32 + 8 * g + 4 * hf, c, b0, z4, biasS[l], act4);
+                    layer_epilogue(a, slot, write_x, l, p.rt * 32 + 8 * g, hf, c, b0, z4, biasS[l], act4);
                 }
             }
         } else {
@@ -366,14 +380,15 @@ __device__ __forceinline__ void policy_layers(const policy_args &a, const float4
             __syncthreads();
             // item = (row tile, register group g, lane) of a tile: 256 per row tile, at most 7 row tiles here
             for (int item = threadIdx.x; item < p.nrt * 256; item += PW * 64) {
-                const int rt = item >> 8, g = (item >> 6) & 3, ln = item & 63;
+                const int iw = __builtin_amdgcn_readfirstlane(item >> 6);     // the same for all lanes of a wave
+                const int rt = iw >> 2, g = iw & 3, ln = item & 63;
                 float4 t = red4[((0 * p.nrt + rt) * 4 + g) * 64 + ln];
                 for (int sl = 1; sl < p.ksplit; ++sl) {
                     const float4 u = red4[((sl * p.nrt + rt) * 4 + g) * 64 + ln];
                     t.x += u.x; t.y += u.y; t.z += u.z; t.w += u.w;
                 }
                 const float z4[4] = {t.x, t.y, t.z, t.w};
-                layer_epilogue(a, slot, write_x, l, rt * 32 + 8 * g + 4 * (ln >> 5), ln & 31, b0, z4, biasS[l], act4);
+                layer_epilogue(a, slot, write_x, l, rt * 32 + 8 * g, ln >> 5, ln & 31, b0, z4, biasS[l], act4);
             }
         }
         __syncthreads();
@@ -385,7 +400,7 @@ __global__ __launch_bounds__(PW * 64) void policy_forward_kernel(policy_args a)
 {
     __shared__ float4 act4[(BAGEL_MAX_HIDDEN / 4) * PL];   // layer input  [K/4][trajectory]
     __shared__ float4 red4[PW * 4 * 64];                   // partial tiles of split contractions
-    __shared__ float biasS[3][BAGEL_MAX_HIDDEN];
+    __shared__ __align__(16) float biasS[3][BAGEL_MAX_HIDDEN];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int b0 = blockIdx.x * PL;
@@ -412,7 +427,7 @@ __global__ __launch_bounds__(PW * 64) void policy_replay_kernel(policy_args a, r
 {
     __shared__ float4 act4[(BAGEL_MAX_HIDDEN / 4) * PL];
     __shared__ float4 red4[PW * 4 * 64];
-    __shared__ float biasS[3][BAGEL_MAX_HIDDEN];
+    __shared__ __align__(16) float biasS[3][BAGEL_MAX_HIDDEN];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int b0 = blockIdx.x * PL;
@@ -491,11 +506,22 @@ __device__ __forceinline__ double sum_groups(const double *__restrict__ p, int n
     return s;
 }
 
+// The first eight terms of such a sum, requested only (pinned where they are written, see load16_pinned, so
+// that the compiler does not sink them below the weight loads that follow); the caller adds them up later.
+__device__ __forceinline__ void request_groups(const double *__restrict__ p, int n, size_t stride, unsigned long long (&v)[8])
+{
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+        v[u] = (u < n) ? __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p + (size_t)u * stride),
+                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT)
+                       : 0ull;
+}
+
 __global__ __launch_bounds__(PW * 64) void step_tail_kernel(tail_args r, policy_args a)
 {
     __shared__ float4 act4[(BAGEL_MAX_HIDDEN / 4) * PL];
     __shared__ float4 red4[PW * 4 * 64];
-    __shared__ float biasS[3][BAGEL_MAX_HIDDEN];
+    __shared__ __align__(16) float biasS[3][BAGEL_MAX_HIDDEN];
     __shared__ double fS[16][PL], sS[8][PL];             // fS rows: u sums, then (from row M) feature sums
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -509,8 +535,9 @@ __global__ __launch_bounds__(PW * 64) void step_tail_kernel(tail_args r, policy_
 
     // Everything the end of the step reads from global memory is requested here, before anything waits
     // for a value: the kernel is a chain of latencies, and they overlap only if they start together.
-    FORWARD_WEIGHTS_DECL;
-    if (r.do_policy) load_forward_weights(a, wave, lane, w_first, w_last, w_wide, p_first, p_last, p_wide, bias_r);
+    // The order matters as well: a wave consumes its loads in the order it issued them, so the value sums
+    // (needed first) go out before the 264 KB of weights (needed by the second layer); issued after them
+    // they were not usable before the last weight had arrived (4.4 us into the kernel instead of 1.5).
     double x_in = 0.0, lp_in = 0.0;
     float g_in = 0.0f, gt_in[8];
     if (row < ds) x_in = r.x_cur[(size_t)row * B + bq];
@@ -525,6 +552,9 @@ __global__ __launch_bounds__(PW * 64) void step_tail_kernel(tail_args r, policy_
     // sums.  (direct: part holds f and J_f themselves, one (output, component) pair per thread row and
     // pass; J_f goes to the tape from here.)
     const size_t stride = (size_t)(1 + r.D) * B;
+    unsigned long long vreq[8] = {};
+    const double *vsrc = nullptr;
+    int vn = 0;
     if (r.direct) {
         for (int qi = row; qi < r.M * r.ncomp; qi += 16) {
             const int m = qi / r.ncomp, comp = qi - m * r.ncomp;
@@ -533,10 +563,21 @@ __global__ __launch_bounds__(PW * 64) void step_tail_kernel(tail_args r, policy_
             else if (liveq) r.jdst[(size_t)(m * r.D + comp - 1) * B + bq] = (float)val;
         }
     } else if (row < r.M) {
-        fS[row][bl] = sum_groups(r.part + (size_t)(row * r.ngk) * stride + bq, r.ngk, stride);
+        vsrc = r.part + (size_t)(row * r.ngk) * stride + bq;
+        vn = r.ngk;
     } else if (row < 2 * r.M) {
-        const int m = row - r.M;
-        fS[row][bl] = sum_groups(r.part + (size_t)(r.M * r.ngk + m * r.ngl) * stride + bq, r.ngl, stride);
+        vsrc = r.part + (size_t)(r.M * r.ngk + (row - r.M) * r.ngl) * stride + bq;
+        vn = r.ngl;
+    }
+    if (vn > 0) request_groups(vsrc, vn, stride, vreq);
+    FORWARD_WEIGHTS_DECL;
+    if (r.do_policy) load_forward_weights(a, wave, lane, w_first, w_last, w_wide, p_first, p_last, p_wide, bias_r);
+    if (vn > 0) {
+        double vsum = 0.0;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) vsum += __longlong_as_double((long long)vreq[u]);      // absent terms are +0.0
+        if (vn > 8) vsum += sum_groups(vsrc + 8 * stride, vn - 8, stride);
+        fS[row][bl] = vsum;
     }
     __syncthreads();
 
