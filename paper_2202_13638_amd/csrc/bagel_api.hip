@@ -202,7 +202,9 @@ extern "C" int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_s
     ALLOC(c->tape_s, (size_t)(H + 1) * dims->d_s * Bz);
     ALLOC(c->tape_J, (size_t)H * M * D * Bz);
     for (int l = 0; l < c->n_layers; ++l) {
-        ALLOC(c->tape_h[l], T * c->width[l] * Bz);
+        // four rows of slack: the sweep reads its tanh outputs at a scalar row base (clamped to the layer)
+        // plus a lane offset of up to four rows; what lies past the layer's rows is read but not used
+        ALLOC(c->tape_h[l], (T * c->width[l] + 4) * Bz);
         ALLOC(c->tape_d[l], T * c->width[l + 1] * Bz);
     }
     ALLOC(c->tape_a, T * dims->d_a * Bz);

@@ -121,24 +121,28 @@ __device__ __forceinline__ f16v tile_contract(const float *__restrict__ W, int k
     const int c = lane & 31, hf = lane >> 5;
     const float4 *wfrag = reinterpret_cast<const float4 *>(W) + (size_t)p.rt * (kp >> 3) * 64 + lane;
     const float4 *bcol = act4 + hf * PL + c;
-    const int k_last = p.k_end - 4;
     float4 a0[4], a1[4], bv[4];      // two weight batches in turn: one feeding MFMAs, one in flight
 #pragma unroll
     for (int u = 0; u < 4; ++u) a0[u] = load16_pinned(wfrag + (size_t)(p.k_begin + u) * 64);
-    for (int k8 = p.k_begin; k8 < p.k_end; k8 += 8) {
-        const int k1 = k8 + 4 <= k_last ? k8 + 4 : k_last;
+    for (int k8 = p.k_begin;; k8 += 8) {
+        const bool more1 = k8 + 4 < p.k_end;            // wave-uniform
+        if (more1) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) a1[u] = load16_pinned(wfrag + (size_t)(k1 + u) * 64);
+            for (int u = 0; u < 4; ++u) a1[u] = load16_pinned(wfrag + (size_t)(k8 + 4 + u) * 64);
+        }
 #pragma unroll
         for (int u = 0; u < 4; ++u) bv[u] = bcol[((k8 + u) * 2) * PL];
         acc = mfma_batch(acc, a0, bv);
-        if (k8 + 4 >= p.k_end) break;
-        const int k2 = k8 + 8 <= k_last ? k8 + 8 : k_last;
+        if (!more1) break;
+        const bool more2 = k8 + 8 < p.k_end;
+        if (more2) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) a0[u] = load16_pinned(wfrag + (size_t)(k2 + u) * 64);
+            for (int u = 0; u < 4; ++u) a0[u] = load16_pinned(wfrag + (size_t)(k8 + 8 + u) * 64);
+        }
 #pragma unroll
         for (int u = 0; u < 4; ++u) bv[u] = bcol[((k8 + 4 + u) * 2) * PL];
         acc = mfma_batch(acc, a1, bv);
+        if (!more2) break;
     }
     return acc;
 }
@@ -662,6 +666,11 @@ __device__ __forceinline__ float load_pinned(const float *p)
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
 }
 
+__device__ __forceinline__ const float *at_byte(const float *base, unsigned byte_off)
+{
+    return reinterpret_cast<const float *>(reinterpret_cast<const char *>(base) + byte_off);
+}
+
 // What thread (row, trajectory) reads from the tape for one step of the sweep: row d < D owns
 // component d of u = J^T lam.
 struct sweep_tape {
@@ -670,24 +679,36 @@ struct sweep_tape {
     float sv[8], gv[8];   // rows < d_s: tracked states of s_{t-1} and the goals they are compared with
 };
 
-// step k = t-1 (tape slot k - t_lo) and the cost data of state t-1
+// step k = t-1 (tape slot k - t_lo) and the cost data of state t-1.  Addresses: wave-uniform slot and row
+// bases plus one 32-bit lane offset (see at_byte); spelled out per access as 64-bit vector arithmetic they
+// cost more instructions than the loads themselves.
 __device__ __forceinline__ void sweep_tape_load(const sweep_args &a, int t, int row, int bq, sweep_tape &r)
 {
     const size_t slot = (size_t)(t - 1 - a.t_lo);
-    if (row < a.D) {
-        const float *Jt = a.tape_J + (slot * a.M * a.D + row) * a.B + bq;
+    const unsigned B = (unsigned)a.B, ubq = (unsigned)bq;
+    // All loads are issued without conditions (indices past M, d_g are clamped to the last one, rows past
+    // D to the last row: duplicates that nothing reads): with a branch per load the compiler must assume at
+    // every join that an earlier load may still be writing the registers it is about to reuse, and makes
+    // each load wait for the one before.
+    {
+        const int rowc = row < a.D ? row : a.D - 1;
+        const float *Jt = a.tape_J + slot * a.M * a.D * a.B;
+        const unsigned off = ((unsigned)rowc * B + ubq) * 4u;
 #pragma unroll
-        for (int m = 0; m < 8; ++m)
-            if (m < a.M) r.J[m] = load_pinned(Jt + (size_t)m * a.D * a.B);
-        if (row >= a.ds && a.act_bound > 0.0f) r.th = load_pinned(a.tape_a + (slot * a.da + (row - a.ds)) * a.B + bq);
+        for (int m = 0; m < 8; ++m) r.J[m] = load_pinned(at_byte(Jt + (size_t)(m < a.M ? m : a.M - 1) * a.D * a.B, off));
+        const int ra = rowc >= a.ds ? rowc - a.ds : 0;
+        r.th = load_pinned(at_byte(a.tape_a + slot * a.da * a.B, ((unsigned)ra * B + ubq) * 4u));
     }
-    if (row < a.ds && t - 1 >= 1) {
+    {
+        const int tc = t - 1 >= 1 ? t : 2;               // the cost data of state t-1 exist for t-1 >= 1
+        const float *st = a.tape_s + (size_t)(tc - 1) * a.ds * a.B;
+        const float *gt = a.goals + (size_t)(tc - 2) * a.B * a.dg;
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-            if (j < a.dg) {
-                r.sv[j] = load_pinned(a.tape_s + ((size_t)(t - 1) * a.ds + a.tracked[j]) * a.B + bq);
-                r.gv[j] = load_pinned(a.goals + ((size_t)(t - 2) * a.B + bq) * a.dg + j);
-            }
+        for (int j = 0; j < 8; ++j) {
+            const int jc = j < a.dg ? j : a.dg - 1;
+            r.sv[j] = load_pinned(at_byte(st + (size_t)a.tracked[jc] * a.B, ubq * 4u));
+            r.gv[j] = load_pinned(at_byte(gt + jc, ubq * (unsigned)a.dg * 4u));
+        }
     }
 }
 
@@ -716,16 +737,20 @@ __device__ __forceinline__ double add_cost_gradient(const sweep_args &a, double 
     return lam;
 }
 
-// tanh outputs h_l of the units a wave owns (the rows of its output tile), for the tanh derivative
-__device__ __forceinline__ void load_tanh_outputs(const float *hl, int ni, int B, const wave_plan &p, int hf,
+// tanh outputs h_l of the units a wave owns (the rows of its output tile), for the tanh derivative.
+// hl: the layer's tape slot (wave-uniform); lane_off: byte offset of (row 4 hf, the lane's trajectory).
+// The scalar row base is clamped to the layer's last row; with the lane's four rows on top a lane whose
+// unit does not exist reads up to four rows further (the next slot, or the slack behind the last one) and
+// does not use what it gets.
+__device__ __forceinline__ void load_tanh_outputs(const float *hl, int ni, int B, unsigned lane_off, const wave_plan &p,
                                                   float *hv)
 {
 #pragma unroll
     for (int g = 0; g < 4; ++g)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const int i = p.rt * 32 + 8 * g + 4 * hf + e;
-            hv[4 * g + e] = load_pinned(hl + (size_t)(i < ni ? i : ni - 1) * B);
+            const int iu = min(p.rt * 32 + 8 * g + e, ni - 1);
+            hv[4 * g + e] = load_pinned(at_byte(hl + (size_t)iu * B, lane_off));
         }
 }
 
@@ -743,6 +768,7 @@ __global__ __launch_bounds__(PW * 64) void backward_sweep_kernel(sweep_args a)
     const int b = b0 + c;
     const bool live = b < a.B;
     const int bc = live ? b : a.B - 1;            // clamped trajectory of the MFMA lanes
+    const unsigned lane_off = ((unsigned)(4 * hf) * (unsigned)a.B + (unsigned)bc) * 4u;   // (row 4 hf, trajectory)
     const int last = a.nl - 1;
     // the lane-per-(row, trajectory) phases see the workgroup as 16 rows x 32 trajectories
     const int bl = tid & (PL - 1), row = tid >> 5;
@@ -779,8 +805,8 @@ __global__ __launch_bounds__(PW * 64) void backward_sweep_kernel(sweep_args a)
     float hv_top[16] = {}, hv_top_next[16] = {};
     sweep_tape_load(a, a.t_hi, row, bq, cur);
     if (top_owner)
-        load_tanh_outputs(a.tape_h[last] + (size_t)(a.t_hi - 1 - a.t_lo) * a.width[last] * a.B + bc, a.width[last], a.B,
-                          p_top, hf, hv_top);
+        load_tanh_outputs(a.tape_h[last] + (size_t)(a.t_hi - 1 - a.t_lo) * a.width[last] * a.B, a.width[last], a.B,
+                          lane_off, p_top, hv_top);
     __syncthreads();
 
     for (int t = a.t_hi; t > a.t_lo; --t) {
@@ -816,7 +842,7 @@ __global__ __launch_bounds__(PW * 64) void backward_sweep_kernel(sweep_args a)
         if (t - 1 > a.t_lo) {
             sweep_tape_load(a, t - 1, row, bq, nxt);
             if (top_owner)
-                load_tanh_outputs(a.tape_h[last] + (slot - 1) * a.width[last] * a.B + bc, a.width[last], a.B, p_top, hf,
+                load_tanh_outputs(a.tape_h[last] + (slot - 1) * a.width[last] * a.B, a.width[last], a.B, lane_off, p_top,
                                   hv_top_next);
         }
 
@@ -826,7 +852,7 @@ __global__ __launch_bounds__(PW * 64) void backward_sweep_kernel(sweep_args a)
             const wave_plan p = l == last ? p_top : (l == 0 ? p_first : plan_layer(ni, a.kp[l], wave));
             const bool owner = p.active && p.ks == 0;
             float hv[16];
-            if (l > 0 && l < last && owner) load_tanh_outputs(a.tape_h[l] + slot * ni * a.B + bc, ni, a.B, p, hf, hv);
+            if (l > 0 && l < last && owner) load_tanh_outputs(a.tape_h[l] + slot * ni * a.B, ni, a.B, lane_off, p, hv);
             f16v acc;
             if (p.active) {
                 if (l == last) {
@@ -839,8 +865,36 @@ __global__ __launch_bounds__(PW * 64) void backward_sweep_kernel(sweep_args a)
                     acc = tile_contract(a.Wp + a.wp_off[l], a.kp[l], p, lane, act4);
                 }
             }
+            if (l == 0 && p.ksplit > 1) {
+                // the adjoint of the policy input: one row tile (at most 16 rows are used), the contraction
+                // split over up to eight waves.  Every slice goes to LDS and 128 threads add them up, four
+                // rows of one trajectory each, in slice order (one wave adding seven slices to its own took
+                // 1.5 us of a 20 us step).
+                if (p.active) {
+#pragma unroll
+                    for (int g = 0; g < 2; ++g)
+                        red4[(wave * 4 + g) * 64 + lane] = make_float4(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]);
+                }
+                __syncthreads();
+                if (tid < 128) {
+                    const int g = tid >> 6, ln = tid & 63;
+                    float4 t4 = red4[(0 * 4 + g) * 64 + ln];
+                    for (int sl = 1; sl < p.ksplit; ++sl) {
+                        const float4 u4 = red4[(sl * 4 + g) * 64 + ln];
+                        t4.x += u4.x; t4.y += u4.y; t4.z += u4.z; t4.w += u4.w;
+                    }
+                    const int ib = 8 * g + 4 * (ln >> 5);
+                    const float o4[4] = {t4.x, t4.y, t4.z, t4.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (ib + e < ni) dh0S[ib + e][ln & 31] = o4[e];
+                }
+                __syncthreads();
+                continue;
+            }
             combine_slices(acc, p, wave, lane, red4);
             if (owner) {
+                float *drow = l > 0 ? a.tape_d[l - 1] + (slot * ni + p.rt * 32) * a.B : nullptr;    // wave-uniform
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     const int ib = p.rt * 32 + 8 * g + 4 * hf;
@@ -854,7 +908,7 @@ __global__ __launch_bounds__(PW * 64) void backward_sweep_kernel(sweep_args a)
                             if (l > 0) {
                                 const float h = l == last ? hv_top[4 * g + e] : hv[4 * g + e];
                                 dv *= (1.0f - h * h);
-                                if (live) a.tape_d[l - 1][(slot * ni + i) * a.B + b] = dv;
+                                if (live) *at_byte(drow + (size_t)(8 * g + e) * a.B, lane_off) = dv;
                             } else if (i < 16) {
                                 dh0S[i][c] = dv;
                             }
