@@ -29,6 +29,7 @@
 // narrow ones (weight_grad_kernel).  The contraction range is split over workgroups in a fixed way
 // and the partial results are added in a fixed order, so the gradient is bitwise reproducible.
 #include "bagel_internal.h"
+#include <type_traits>
 
 namespace {
 
@@ -676,7 +677,9 @@ __device__ __forceinline__ const float *at_byte(const float *base, unsigned byte
 struct sweep_tape {
     float J[8];           // J[m][row]
     float th;             // rows d_s .. D-1: tanh output of the bounded action row - d_s
-    float sv[8], gv[8];   // rows < d_s: tracked states of s_{t-1} and the goals they are compared with
+};
+struct sweep_cost {
+    float sv[8], gv[8];   // tracked states of s_{t-1} and the goals they are compared with
 };
 
 // step k = t-1 (tape slot k - t_lo) and the cost data of state t-1.  Addresses: wave-uniform slot and row
@@ -699,16 +702,21 @@ __device__ __forceinline__ void sweep_tape_load(const sweep_args &a, int t, int 
         const int ra = rowc >= a.ds ? rowc - a.ds : 0;
         r.th = load_pinned(at_byte(a.tape_a + slot * a.da * a.B, ((unsigned)ra * B + ubq) * 4u));
     }
-    {
-        const int tc = t - 1 >= 1 ? t : 2;               // the cost data of state t-1 exist for t-1 >= 1
-        const float *st = a.tape_s + (size_t)(tc - 1) * a.ds * a.B;
-        const float *gt = a.goals + (size_t)(tc - 2) * a.B * a.dg;
+}
+
+// The cost data of state t-1, which the end of step t needs: requested at the start of that same step (a
+// whole step ahead of their use; a second register set for them would not pay).
+__device__ __forceinline__ void sweep_cost_load(const sweep_args &a, int t, int bq, sweep_cost &r)
+{
+    const unsigned ubq = (unsigned)bq;
+    const int tc = t - 1 >= 1 ? t : 2;                   // they exist for t-1 >= 1; otherwise any valid slot
+    const float *st = a.tape_s + (size_t)(tc - 1) * a.ds * a.B;
+    const float *gt = a.goals + (size_t)(tc - 2) * a.B * a.dg;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int jc = j < a.dg ? j : a.dg - 1;
-            r.sv[j] = load_pinned(at_byte(st + (size_t)a.tracked[jc] * a.B, ubq * 4u));
-            r.gv[j] = load_pinned(at_byte(gt + jc, ubq * (unsigned)a.dg * 4u));
-        }
+    for (int j = 0; j < 8; ++j) {
+        const int jc = j < a.dg ? j : a.dg - 1;
+        r.sv[j] = load_pinned(at_byte(st + (size_t)a.tracked[jc] * a.B, ubq * 4u));
+        r.gv[j] = load_pinned(at_byte(gt + jc, ubq * (unsigned)a.dg * 4u));
     }
 }
 
@@ -801,7 +809,9 @@ __global__ __launch_bounds__(PW * 64) void backward_sweep_kernel(sweep_args a)
     float4 w_first[4];
     load_wave_weights<1>(w_first, a.Wp + a.wp_off[0], a.kp[0], p_first, lane);
     const float4 w_top = reinterpret_cast<const float4 *>(a.Wp + a.wp_off[last])[(size_t)p_top.rt * (a.kp[last] >> 3) * 64 + lane];
+    const wave_plan p_mid = last == 2 ? plan_layer(a.width[1], a.kp[1], wave) : p_first;
     sweep_tape cur = {}, nxt = {};
+    sweep_cost cost = {};
     float hv_top[16] = {}, hv_top_next[16] = {};
     sweep_tape_load(a, a.t_hi, row, bq, cur);
     if (top_owner)
@@ -838,7 +848,9 @@ __global__ __launch_bounds__(PW * 64) void backward_sweep_kernel(sweep_args a)
             act1[((o >> 2) * PL + bl) * 4 + (o & 3)] = 0.0f;
         }
         __syncthreads();
-        // the tape of the next step of the sweep is requested now and arrives under the matrix work
+        // the cost data this step ends with, and the tape of the next step of the sweep, are requested now
+        // and arrive under the matrix work
+        sweep_cost_load(a, t, bq, cost);
         if (t - 1 > a.t_lo) {
             sweep_tape_load(a, t - 1, row, bq, nxt);
             if (top_owner)
@@ -846,26 +858,29 @@ __global__ __launch_bounds__(PW * 64) void backward_sweep_kernel(sweep_args a)
                                   hv_top_next);
         }
 
-        // ---- policy backward: delta_{l-1} = (W_l^T delta_l) * (1 - h_l^2)
-        for (int l = last; l >= 0; --l) {
+        // ---- policy backward: delta_{l-1} = (W_l^T delta_l) * (1 - h_l^2).  The layers are written out one
+        // after the other (top, middle if there are three, first) instead of a loop over l: a loop carries
+        // the accumulator from one trip to the next through register copies, and with loads in flight the
+        // compiler guards every such copy with a wait for all of them, the next step's tape values included.
+        auto backward_layer = [&](auto kind_tag, int l, const wave_plan &p) {
+            constexpr int KIND = decltype(kind_tag)::value;          // 2: top, 1: middle, 0: first
             const int ni = a.width[l];
-            const wave_plan p = l == last ? p_top : (l == 0 ? p_first : plan_layer(ni, a.kp[l], wave));
             const bool owner = p.active && p.ks == 0;
             float hv[16];
-            if (l > 0 && l < last && owner) load_tanh_outputs(a.tape_h[l] + slot * ni * a.B, ni, a.B, lane_off, p, hv);
+            if (KIND == 1 && owner) load_tanh_outputs(a.tape_h[l] + slot * ni * a.B, ni, a.B, lane_off, p, hv);
             f16v acc;
             if (p.active) {
-                if (l == last) {
+                if (KIND == 2) {
 #pragma unroll
                     for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
                     acc = mfma_group(acc, w_top, act4[hf * PL + c]);
-                } else if (l == 0) {
+                } else if (KIND == 0) {
                     acc = contract_batches<1>(w_first, p, lane, act4);
                 } else {
                     acc = tile_contract(a.Wp + a.wp_off[l], a.kp[l], p, lane, act4);
                 }
             }
-            if (l == 0 && p.ksplit > 1) {
+            if (KIND == 0 && p.ksplit > 1) {
                 // the adjoint of the policy input: one row tile (at most 16 rows are used), the contraction
                 // split over up to eight waves.  Every slice goes to LDS and 128 threads add them up, four
                 // rows of one trajectory each, in slice order (one wave adding seven slices to its own took
@@ -890,11 +905,11 @@ __global__ __launch_bounds__(PW * 64) void backward_sweep_kernel(sweep_args a)
                         if (ib + e < ni) dh0S[ib + e][ln & 31] = o4[e];
                 }
                 __syncthreads();
-                continue;
+                return;
             }
             combine_slices(acc, p, wave, lane, red4);
             if (owner) {
-                float *drow = l > 0 ? a.tape_d[l - 1] + (slot * ni + p.rt * 32) * a.B : nullptr;    // wave-uniform
+                float *drow = KIND > 0 ? a.tape_d[l - 1] + (slot * ni + p.rt * 32) * a.B : nullptr;    // wave-uniform
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     const int ib = p.rt * 32 + 8 * g + 4 * hf;
@@ -905,8 +920,8 @@ __global__ __launch_bounds__(PW * 64) void backward_sweep_kernel(sweep_args a)
                         float dv = 0.0f;
                         if (i < ni) {
                             dv = acc[4 * g + e];
-                            if (l > 0) {
-                                const float h = l == last ? hv_top[4 * g + e] : hv[4 * g + e];
+                            if (KIND > 0) {
+                                const float h = KIND == 2 ? hv_top[4 * g + e] : hv[4 * g + e];
                                 dv *= (1.0f - h * h);
                                 if (live) *at_byte(drow + (size_t)(8 * g + e) * a.B, lane_off) = dv;
                             } else if (i < 16) {
@@ -915,16 +930,19 @@ __global__ __launch_bounds__(PW * 64) void backward_sweep_kernel(sweep_args a)
                         }
                         out[e] = dv;
                     }
-                    if (l > 0) act4[(ib >> 2) * PL + c] = make_float4(out[0], out[1], out[2], out[3]);
+                    if (KIND > 0) act4[(ib >> 2) * PL + c] = make_float4(out[0], out[1], out[2], out[3]);
                 }
             }
             __syncthreads();
-        }
+        };
+        if (last > 0) backward_layer(std::integral_constant<int, 2>{}, last, p_top);
+        if (last == 2) backward_layer(std::integral_constant<int, 1>{}, 1, p_mid);
+        backward_layer(std::integral_constant<int, 0>{}, 0, p_first);
 
         // ---- lam_{t-1}
         if (row < a.ds) {
             double v = lamS[row][bl] + usS[row][bl] + (double)dh0S[row][bl];
-            if (t - 1 >= 1) v = add_cost_gradient(a, v, row, cur.sv, cur.gv);
+            if (t - 1 >= 1) v = add_cost_gradient(a, v, row, cost.sv, cost.gv);
             lamS[row][bl] = v;
         }
         cur = nxt;
