@@ -285,6 +285,48 @@ def test_rollout_variants(name, monkeypatch):
     assert fwd["loss"] == got["loss"]
 
 
+SWEEP_HIDDEN = [(8,), (33,), (64, 64), (96, 40), (128, 128), (130, 200), (200, 136), (256, 32), (32, 256), (256, 256),
+                (255, 129), (160,), (256,)]
+SWEEP_STATE = [dict(d_s=2, d_a=1, d_g=1), dict(d_s=6, d_a=2, d_g=2), dict(d_s=8, d_a=8, d_g=8), dict(d_s=3, d_a=1, d_g=2)]
+
+
+@pytest.mark.parametrize("hi", range(len(SWEEP_HIDDEN)))
+def test_policy_and_state_shape_sweep(hi, monkeypatch):
+    """Every hidden-layer shape (one or two layers; widths below, at and between the tile sizes of the
+    policy kernels) against every state/action/goal shape, with batch size, horizon, checkpointing,
+    action bound, cost kind and the contraction split of narrow layers rotating through the cases.
+    Some of these small random systems are chaotic over their few steps, so each case is held to the
+    tolerance plus twenty times its own conditioning figure: the deviation of the oracle from itself when
+    s0 moves by one unit in the last place of float32."""
+    hidden = SWEEP_HIDDEN[hi]
+    for si, sh in enumerate(SWEEP_STATE):
+        B = [32, 64, 96, 70, 160][(hi + si) % 5]
+        H = [5, 7, 6, 9][(hi + 2 * si) % 4]
+        ck = [0, 3][(hi + si) % 2]
+        bound = [0.0, 1.2][(hi // 2 + si) % 2]
+        split = ["256", "3"][(hi + si // 2) % 2]
+        monkeypatch.setenv("BAGEL_KSPLIT", split)
+        cfg = synth.Config("sweep", 20 + hi, sh["d_s"], sh["d_a"], sh["d_g"], 90, 130, B, H, tuple(hidden), bound,
+                           "sinusoid", "steps", 0, 0.5, 1e-3)
+        inp = synth.make_inputs(cfg, trial=si)
+        # an 8-dimensional action fed back through 8 states diverges within the horizon at the larger scale
+        inp["theta"] = (inp["theta"] * (0.3 if sh["d_s"] == 8 else 2)).astype(np.float32)
+        dims = dict(cost_kind=1, sigma_r=0.7) if (hi + si) % 3 == 0 else {}
+        label = f"hidden{hidden}/ds{sh['d_s']}da{sh['d_a']}dg{sh['d_g']}/B{B}/H{H}/ckpt{ck}/bound{bound}/split{split}"
+        harness.progress(f"sweep case {label}")
+        ref = harness.oracle_reference(cfg, inp, **dims)
+        got = harness.gpu_rollout(cfg, inp, ref["v32"], ckpt_interval=ck, **dims)
+        moved = dict(inp)
+        moved["s0"] = np.nextafter(inp["s0"], np.float32(np.inf), dtype=np.float32)
+        cond = harness.deviations(ref, oracle.rollout(oracle.dims_from_config(cfg, **dims), moved, ref["v32"]))
+        d = harness.deviations(ref, got)
+        print(f"[parity {label}] " + " ".join(f"{k}={d[k]:.1e} (cond {cond[k]:.1e})" for k in d), flush=True)
+        assert np.isfinite(got["states"]).all() and np.isfinite(got["grad_theta"]).all()
+        for k in d:
+            tol = harness.TOL_GRAD if k.startswith("grad") else (harness.TOL_STATE if k == "state" else harness.TOL_LOSS)
+            assert d[k] <= tol + 20 * cond[k], (label, k, d[k], cond[k])
+
+
 def test_rollout_with_table_exp2(monkeypatch):
     """The exp2 form of large launches, forced at a size the oracle finishes in seconds."""
     monkeypatch.setenv("BAGEL_EXP_TABLE", EXP2_FORMS["table"])
