@@ -206,6 +206,20 @@ def test_sample_eval_with_either_exp2(form, monkeypatch):
     _check_sample_eval(shape, x)
 
 
+@pytest.mark.parametrize("D", range(2, 17))
+def test_sample_eval_every_input_dimension(D, monkeypatch):
+    """The step kernel is compiled once per GP input dimension: every one of them, in both exp2 forms,
+    with ragged N, L and B and with samples shared by several trajectories on the even dimensions."""
+    d_s = (D + 1) // 2
+    for form, flag in EXP2_FORMS.items():
+        monkeypatch.setenv("BAGEL_EXP_TABLE", flag)
+        B = 64 + 3 * D
+        shape = dict(d_s=d_s, d_a=D - d_s, N=40 + 7 * D, L=30 + 9 * D, B=B, S=B // 2 if B % 2 == 0 else B)
+        x = np.random.default_rng(40 + D).uniform(-1.2, 1.2, (B, D)).astype(np.float32)
+        harness.progress(f"sample evaluation D={D} {form} {shape}")
+        _check_sample_eval(shape, x)
+
+
 @pytest.mark.parametrize("form", list(EXP2_FORMS))
 def test_sample_eval_inputs_far_from_the_data(form, monkeypatch):
     """GP inputs hundreds of length scales away from every training point: the kernel row is zero
