@@ -24,7 +24,9 @@
  *     caller memory after a call returns, except that prepare/set_samples copy the model
  *     into context-owned buffers in an internal layout.
  *   - The rollout calls enqueue work and return; they do not synchronise the stream and
- *     allocate nothing.  Outputs are valid once the stream has drained.
+ *     allocate nothing.  Outputs are valid once the stream has drained.  What they enqueue is
+ *     kernel launches only (no memset or copy nodes), so a call may be captured into a HIP graph on
+ *     the context's stream and replayed; the graph then holds the argument pointers of that call.
  *   - The kernel-row contraction over the N training points is evaluated in float64
  *     (operands are the float32 inputs promoted exactly); everything at the interface is
  *     float32.

@@ -366,6 +366,53 @@ def test_checkpointing_does_not_change_the_result():
     harness.assert_parity(ref, plain, label="small/B64/H40")
 
 
+@pytest.mark.parametrize("name", ["tiny", "small"])
+def test_gradient_call_captured_into_a_hip_graph(name):
+    """The rollout calls enqueue kernels only (no allocation, no memset, no host synchronisation), so a
+    caller may capture one into a HIP graph.  Every replay, with eager calls and synchronisations between
+    them, must reproduce the eager result bit for bit."""
+    import torch
+    from paper_2202_13638_amd import binding
+    cfg = _cfg(name)
+    inp = synth.make_inputs(cfg)
+    g = harness.to_gpu(inp)
+    stream = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(stream):
+        ctx = binding.Bagel(binding.dims_from_config(cfg))          # the context works on `stream`
+        ctx.bagel_prepare_samples(g["X"], g["y"], g["lengthscale"], g["signal_var"], g["noise_var"], g["omega"],
+                                  g["phase"], g["w"], g["eps"], None)
+        outs = [torch.full(sh, float("nan"), device="cuda")
+                for sh in [(1,), (cfg.B,), (cfg.H + 1, cfg.B, cfg.d_s), (ctx.P,), (cfg.B, cfg.d_s)]]
+        loss, lpt, states, gth, gs0 = outs
+
+        def call():
+            ctx.bagel_rollout_loss_grad(g["theta"], g["s0"], g["goals"], loss, gth, lpt, states, gs0)
+
+        call()
+        stream.synchronize()
+        eager = [t.clone() for t in outs]
+        assert all(torch.isfinite(t).all() for t in eager)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        call()
+    for replay in range(3):
+        for t in outs:
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(eager, outs):
+            assert torch.equal(a, b), f"replay {replay}"
+        with torch.cuda.stream(stream):
+            call()                                                  # eager work between the replays
+        stream.synchronize()
+        for a, b in zip(eager, outs):
+            assert torch.equal(a, b), f"eager call after replay {replay}"
+    del graph
+    ctx.close()
+
+
 def test_repeated_calls_are_bitwise_reproducible():
     cfg = _cfg("small", B=200, H=15)
     inp = synth.make_inputs(cfg)
