@@ -268,6 +268,10 @@ VARIANTS = {
     "shared-samples": dict(cfg=dict(B=96, H=12), S=8, dims=dict()),
     "saturating-reward": dict(cfg=dict(B=33, H=10, act_bound=1.0), dims=dict(cost_kind=1, sigma_r=0.6)),
     "one-step-one-trajectory": dict(cfg=dict(B=1, H=1), dims=dict()),
+    # the smallest model and the smallest policy: everything beyond them is padding inside the kernels
+    "one-training-point-one-feature": dict(cfg=dict(N=1, L=1, B=16, H=8), dims=dict()),
+    "hidden-layers-of-one-unit": dict(cfg=dict(hidden=(1, 1), B=40, H=6), dims=dict()),
+    "one-sample-for-all-trajectories": dict(cfg=dict(B=70, H=9), S=1, dims=dict()),
     "checkpoint-ragged": dict(cfg=dict(B=20, H=23), dims=dict(ckpt_interval=5)),
     "wide-policy": dict(cfg=dict(B=65, H=6, hidden=(256, 256)), dims=dict()),
     # B a multiple of 32 and a layer with more than 128 rows and columns: the LDS-tiled weight gradient,
@@ -425,8 +429,8 @@ def test_repeated_calls_are_bitwise_reproducible():
 
 # ------------------------------------------------------------------ prepare
 @pytest.mark.timeout(900)
-@pytest.mark.parametrize("name,kw", [("tiny", {}), ("small", dict(B=48)), ("ragged", {}), ("medium", dict(sub=64)),
-                                     ("large_policy", dict(sub=64))])
+@pytest.mark.parametrize("name,kw", [("tiny", {}), ("small", dict(B=48)), ("ragged", {}), ("one-point", {}),
+                                     ("medium", dict(sub=64)), ("large_policy", dict(sub=64))])
 def test_prepare_matches_oracle_solution(name, kw):
     """bagel_prepare_samples against the oracle's float64 solve, and the product path end to end
     (bagel_prepare_samples -> bagel_rollout_loss_grad) against the oracle driven from the UNROUNDED
@@ -436,6 +440,9 @@ def test_prepare_matches_oracle_solution(name, kw):
     small multiple of that; tests/conditioning.py prints the same numbers for all five workloads."""
     if name == "ragged":
         cfg = synth.Config("p", 13, 3, 1, 1, 150, 77, 9, 3, (4,), 0.0, "sinusoid", "const", 0, 0.8, 1e-3)
+        inp = synth.make_inputs(cfg)
+    elif name == "one-point":                  # N = 1 (K_hat is a scalar), L = 1, B = S = 5
+        cfg = synth.Config("p", 14, 2, 1, 1, 1, 1, 5, 4, (4,), 0.0, "sinusoid", "const", 0, 0.8, 1e-3)
         inp = synth.make_inputs(cfg)
     elif "sub" in kw:
         full = _cfg(name)
