@@ -68,6 +68,18 @@ def test_bad_hidden_tracked_and_null_arguments(lib):
     assert lib.bagel_optimize(None, None, None, None, None, None, 1, 1, 1, 1e-2, 0.9, 0.999, 1e-8, None) == binding.EINVAL
 
 
+def test_sizes_beyond_the_work_decomposition_are_rejected_without_a_device(lib):
+    """The largest problems: the sample evaluation addresses its work units with a 16-bit grid index, and
+    B * H is bounded; both limits are checked before anything is allocated."""
+    h = C.c_void_p()
+    dims = binding.make_dims(d_s=8, d_a=8, d_g=8, N=40_000_000, L=8, S=64, B=64, H=5, hidden=(8,))
+    assert lib.bagel_create(C.byref(h), C.byref(dims), None) == binding.EINVAL and not h.value
+    assert "work units" in lib.bagel_last_error(None).decode()
+    dims = binding.make_dims(d_s=2, d_a=1, d_g=1, N=8, L=8, S=1, B=2_000_000_000, H=1000, hidden=(8,))
+    assert lib.bagel_create(C.byref(h), C.byref(dims), None) == binding.EINVAL and not h.value
+    assert "too large" in lib.bagel_last_error(None).decode()
+
+
 def test_binding_rejects_host_tensors():
     import torch
     with pytest.raises(ValueError):
