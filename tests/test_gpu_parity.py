@@ -355,6 +355,22 @@ def test_rollout_with_table_exp2(monkeypatch):
     harness.assert_parity(ref, got, label="small/B96/H30/table")
 
 
+@pytest.mark.parametrize("trial", [1, 2, 3])
+def test_other_draws_sizes_exp2_forms_and_checkpointing(trial, monkeypatch):
+    """Further draws of the Small workload's inputs at three sizes (tile multiples and ragged N, L, B),
+    each in both exp2 forms, with the full tape and with a checkpoint interval that does not divide H."""
+    import dataclasses
+    for form, flag in EXP2_FORMS.items():
+        monkeypatch.setenv("BAGEL_EXP_TABLE", flag)
+        for B, H, N, L in [(96, 25, 512, 1024), (70, 18, 333, 517), (130, 12, 200, 90)]:
+            cfg = dataclasses.replace(synth.CONFIGS["small"], B=B, H=H, N=N, L=L)
+            inp = synth.make_inputs(cfg, trial=trial)
+            ref = harness.oracle_reference(cfg, inp)
+            for ck in (0, 7):
+                got = harness.gpu_rollout(cfg, inp, ref["v32"], ckpt_interval=ck)
+                harness.assert_parity(ref, got, label=f"trial{trial}/{form}/ckpt{ck}/B{B}/H{H}/N{N}/L{L}")
+
+
 def test_checkpointing_does_not_change_the_result():
     cfg = _cfg("small", B=64, H=40)
     inp = synth.make_inputs(cfg)
@@ -689,6 +705,18 @@ def test_posterior_sampler_one_training_point():
     # K_hat is a scalar: mu = k y / K_hat, sigma^2 = alpha^2 - k^2 / K_hat
     cfg = synth.Config("p1", 23, 2, 1, 1, 1, 16, 20, 6, (8,), 0.0, "sinusoid", "steps", 0, 0.5, 1e-3)
     _posterior_case(cfg, "posterior-one-point")
+
+
+@pytest.mark.parametrize("d_s,d_a,d_g,N,B,H,hidden,bound", [
+    (6, 2, 2, 300, 70, 6, (16, 8), 1.0),      # D = 8
+    (7, 3, 1, 129, 33, 5, (8,), 0.0),         # D = 10
+    (2, 1, 1, 700, 130, 4, (16,), 0.0),       # N over several tile rows, B over several tile columns
+    (8, 8, 3, 64, 5, 3, (4,), 0.5),           # D = 16
+])
+def test_posterior_sampler_shapes(d_s, d_a, d_g, N, B, H, hidden, bound):
+    cfg = synth.Config("ps", 40 + d_s, d_s, d_a, d_g, N, 16, B, H, hidden, bound, "sinusoid", "steps", 0, 0.6, 1e-3)
+    _posterior_case(cfg, f"posterior-D{d_s + d_a}")
+    _posterior_case(cfg, f"posterior-D{d_s + d_a}-ckpt", ckpt_interval=2)
 
 
 @pytest.mark.timeout(600)
