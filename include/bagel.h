@@ -93,7 +93,12 @@ typedef struct {
                                 time and recomputed segment by segment in the backward sweep from the kept
                                 states; the states and the Jacobians of the sample evaluation
                                 (d_s + d_s (d_s + d_a) floats per trajectory and step) are kept for the
-                                whole horizon.  Results are identical. */
+                                whole horizon.  Results are identical.  The per-segment tapes exist
+                                twice, and the backward pass of a gradient call uses a second stream
+                                owned by the context beside the caller's (forked after the forward pass,
+                                joined before the call's last kernel is ordered on the caller's stream):
+                                the replay of one segment and the weight gradient of another run beside
+                                the sweep of a third. */
     int32_t cost_kind;       /* 0 quadratic tracking cost, 1 negative saturating reward of eq. (8) */
     float sigma_r;           /* width of eq. (8); used only if cost_kind == 1 */
 } bagel_dims;

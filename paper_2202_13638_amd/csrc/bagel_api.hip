@@ -78,10 +78,28 @@ static hipError_t dev_alloc(bagel_ctx *c, T **p, size_t count)
 static void free_all(bagel_ctx *c)
 {
     void *ptrs[] = {c->Xs, c->Xn, c->near_ok, c->Os, c->Of, c->A, c->amp, c->exp_tab, c->v4, c->w4, c->xbuf, c->part, c->xbuf_alt, c->part_alt, c->lpt, c->lam,
-                    c->tape_s, c->tape_J, c->tape_h[0], c->tape_h[1], c->tape_h[2], c->tape_a, c->tape_d[0],
-                    c->tape_d[1], c->tape_d[2], c->wpad_f, c->wpad_b, c->gsplit, c->gacc, c->fbuf, c->gtheta, c->post_alpha, c->post_Kinv, c->post_Kx, c->post_sums};
+                    c->tape_s, c->tape_J, c->tape_h_set[0][0], c->tape_h_set[0][1], c->tape_h_set[0][2], c->tape_a_set[0],
+                    c->tape_d_set[0][0], c->tape_d_set[0][1], c->tape_d_set[0][2], c->tape_h_set[1][0], c->tape_h_set[1][1],
+                    c->tape_h_set[1][2], c->tape_a_set[1], c->tape_d_set[1][0], c->tape_d_set[1][1], c->tape_d_set[1][2], c->wpad_f, c->wpad_b, c->gsplit, c->gacc, c->fbuf, c->gtheta, c->post_alpha, c->post_Kinv, c->post_Kx, c->post_sums};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
+}
+
+static void use_tape_set(bagel_ctx *c, int set)
+{
+    for (int l = 0; l < 3; ++l) {
+        c->tape_h[l] = c->tape_h_set[set][l];
+        c->tape_d[l] = c->tape_d_set[set][l];
+    }
+    c->tape_a = c->tape_a_set[set];
+}
+
+static void destroy_side(bagel_ctx *c)
+{
+    hipEvent_t *evs[] = {&c->ev_fork, &c->ev_join, &c->ev_replay[0], &c->ev_replay[1], &c->ev_sweep[0], &c->ev_sweep[1]};
+    for (hipEvent_t *ev : evs)
+        if (*ev) { (void)hipEventDestroy(*ev); *ev = nullptr; }
+    if (c->side) { (void)hipStreamDestroy(c->side); c->side = nullptr; }
 }
 
 static int env_int(const char *name, int dflt)
@@ -201,13 +219,16 @@ extern "C" int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_s
     ALLOC(c->fbuf, (size_t)M * Bz);
     ALLOC(c->tape_s, (size_t)(H + 1) * dims->d_s * Bz);
     ALLOC(c->tape_J, (size_t)H * M * D * Bz);
-    for (int l = 0; l < c->n_layers; ++l) {
-        // four rows of slack: the sweep reads its tanh outputs at a scalar row base (clamped to the layer)
-        // plus a lane offset of up to four rows; what lies past the layer's rows is read but not used
-        ALLOC(c->tape_h[l], (T * c->width[l] + 4) * Bz);
-        ALLOC(c->tape_d[l], T * c->width[l + 1] * Bz);
+    for (int set = 0; set < (c->T_tape < H ? 2 : 1); ++set) {
+        for (int l = 0; l < c->n_layers; ++l) {
+            // four rows of slack: the sweep reads its tanh outputs at a scalar row base (clamped to the layer)
+            // plus a lane offset of up to four rows; what lies past the layer's rows is read but not used
+            ALLOC(c->tape_h_set[set][l], (T * c->width[l] + 4) * Bz);
+            ALLOC(c->tape_d_set[set][l], T * c->width[l + 1] * Bz);
+        }
+        ALLOC(c->tape_a_set[set], T * dims->d_a * Bz);
     }
-    ALLOC(c->tape_a, T * dims->d_a * Bz);
+    use_tape_set(c, 0);
     ALLOC(c->wpad_f, (size_t)wf_total);
     ALLOC(c->wpad_b, (size_t)wb_total);
     ALLOC(c->gsplit, (size_t)c->ksplit * c->P);
@@ -225,8 +246,16 @@ extern "C" int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_s
         }
         e = hipMemcpy(c->exp_tab, tab, sizeof(tab), hipMemcpyHostToDevice);
     }
+    if (e == hipSuccess && c->T_tape < H) {
+        // the side stream of the checkpointed backward pass (default priority) and the events that order it
+        e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
+        hipEvent_t *evs[] = {&c->ev_fork, &c->ev_join, &c->ev_replay[0], &c->ev_replay[1], &c->ev_sweep[0], &c->ev_sweep[1]};
+        for (hipEvent_t *ev : evs)
+            if (e == hipSuccess) e = hipEventCreateWithFlags(ev, hipEventDisableTiming);
+    }
     if (e != hipSuccess) {
         const int64_t want = c->bytes;
+        destroy_side(c);
         free_all(c);
         delete c;
         (void)hipGetLastError();
@@ -249,6 +278,8 @@ extern "C" int bagel_destroy(bagel_ctx *c)
         free(c->prof_ev);
     }
     bagel_release_setup(c);
+    if (c->side) (void)hipStreamSynchronize(c->side);
+    destroy_side(c);
     free_all(c);
     delete c;
     return BAGEL_OK;
@@ -568,13 +599,44 @@ static int rollout_loss_grad_impl(bagel_ctx *c, const char *who, const float *th
     // rebuilt from the kept float32 states, all steps of the segment in one launch; what is small and
     // expensive to recompute, the state (d_s floats) and the Jacobian of the sample evaluation (M D
     // floats), is kept for the whole horizon.  Segments are swept from the last to the first.
+    // Only the sweep is a chain from segment to segment (the adjoint of the state); the replay of a
+    // segment needs the kept states alone and the weight gradient of a segment only that segment's
+    // tapes.  The sweep occupies one workgroup per 32 trajectories for a whole segment, which leaves
+    // compute units idle below 8192 trajectories, so the other two run beside it on a second stream
+    // and a second set of tapes:  main: S(n-1) S(n-2) S(n-3) ...;  side: R(n-1) R(n-2) W(n-1) R(n-3) W(n-2) ...
+    // S(k) waits for R(k); W(k) waits for S(k); R(k-1), which reuses the tapes of segment k+1, follows
+    // W(k+1) in stream order.  The weight gradients are still added up in segment order, on one stream.
     const int n_seg = (H + K - 1) / K;
-    for (int seg = n_seg - 1; seg >= 0; --seg) {
+    const hipStream_t main_stream = c->stream;
+    hipError_t e = hipSuccess;
+    auto on_side = [&](int seg, bool replay) {
         const int t0 = seg * K, t1 = (t0 + K < H) ? t0 + K : H;
-        BAGEL_HIP(c, bagel_launch_policy_replay(c, t0, t1, theta, goals));
-        BAGEL_HIP(c, bagel_launch_backward_sweep(c, t0, t1, goals, grad_s0));
-        BAGEL_HIP(c, bagel_launch_weight_grad(c, t1 - t0, seg != n_seg - 1, seg == 0 ? grad_theta : nullptr));
+        use_tape_set(c, seg & 1);
+        c->stream = c->side;
+        hipError_t r = replay ? bagel_launch_policy_replay(c, t0, t1, theta, goals)
+                              : bagel_launch_weight_grad(c, t1 - t0, seg != n_seg - 1, seg == 0 ? grad_theta : nullptr);
+        c->stream = main_stream;
+        if (r == hipSuccess && replay) r = hipEventRecord(c->ev_replay[seg & 1], c->side);
+        return r;
+    };
+    e = hipEventRecord(c->ev_fork, main_stream);
+    if (e == hipSuccess) e = hipStreamWaitEvent(c->side, c->ev_fork, 0);
+    if (e == hipSuccess) e = on_side(n_seg - 1, true);
+    for (int seg = n_seg - 1; seg >= 0 && e == hipSuccess; --seg) {
+        const int t0 = seg * K, t1 = (t0 + K < H) ? t0 + K : H, set = seg & 1;
+        e = hipStreamWaitEvent(main_stream, c->ev_replay[set], 0);
+        use_tape_set(c, set);
+        if (e == hipSuccess) e = bagel_launch_backward_sweep(c, t0, t1, goals, grad_s0);
+        if (e == hipSuccess) e = hipEventRecord(c->ev_sweep[set], main_stream);
+        if (e == hipSuccess && seg > 0) e = on_side(seg - 1, true);
+        if (e == hipSuccess) e = hipStreamWaitEvent(c->side, c->ev_sweep[set], 0);
+        if (e == hipSuccess) e = on_side(seg, false);
     }
+    // the caller's stream continues after the last weight gradient
+    if (e == hipSuccess) e = hipEventRecord(c->ev_join, c->side);
+    if (e == hipSuccess) e = hipStreamWaitEvent(main_stream, c->ev_join, 0);
+    use_tape_set(c, 0);
+    if (e != hipSuccess) BAGEL_FAIL(c, BAGEL_EHIP, "%s: checkpointed backward pass failed: %s", who, hipGetErrorString(e));
     return BAGEL_OK;
 }
 

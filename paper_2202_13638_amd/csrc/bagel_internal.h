@@ -58,6 +58,13 @@ struct bagel_ctx {
     float *tape_h[3];            // activations feeding layer l: [T][width[l]][B]
     float *tape_a;               // [T][d_a][B] policy output (after tanh, before scaling, if bounded)
     float *tape_d[3];            // adjoint of the pre-activation of layer l: [T][width[l+1]][B]
+    // With checkpointing the three per-segment tapes above exist twice and tape_h / tape_a / tape_d point
+    // to the set in use (set 0 outside the backward pass): while the sweep walks one segment on the
+    // context's stream, the policy replay of the segment before it and the weight gradient of the
+    // segment after it run on `side`, each on the other set.  Without checkpointing set 1 is empty.
+    float *tape_h_set[2][3], *tape_a_set[2], *tape_d_set[2][3];
+    hipStream_t side;            // null without checkpointing
+    hipEvent_t ev_fork, ev_join, ev_replay[2], ev_sweep[2];
 
     // ---- parameters and gradient -----------------------------------------------------------
     float *wpad_f, *wpad_b;      // zero-padded weights: forward [out pad 32][in pad 32], backward [in pad 32][out pad 32]

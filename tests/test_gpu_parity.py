@@ -386,11 +386,12 @@ def test_checkpointing_does_not_change_the_result():
     harness.assert_parity(ref, plain, label="small/B64/H40")
 
 
-@pytest.mark.parametrize("name", ["tiny", "small"])
-def test_gradient_call_captured_into_a_hip_graph(name):
+@pytest.mark.parametrize("name,ckpt", [("tiny", 0), ("small", 0), ("small", 7)])
+def test_gradient_call_captured_into_a_hip_graph(name, ckpt):
     """The rollout calls enqueue kernels only (no allocation, no memset, no host synchronisation), so a
     caller may capture one into a HIP graph.  Every replay, with eager calls and synchronisations between
-    them, must reproduce the eager result bit for bit."""
+    them, must reproduce the eager result bit for bit.  With checkpointing the backward pass forks onto the
+    context's second stream and joins again, inside the capture."""
     import torch
     from paper_2202_13638_amd import binding
     cfg = _cfg(name)
@@ -399,7 +400,7 @@ def test_gradient_call_captured_into_a_hip_graph(name):
     stream = torch.cuda.Stream()
     torch.cuda.synchronize()
     with torch.cuda.stream(stream):
-        ctx = binding.Bagel(binding.dims_from_config(cfg))          # the context works on `stream`
+        ctx = binding.Bagel(binding.dims_from_config(cfg, ckpt_interval=ckpt))          # the context works on `stream`
         ctx.bagel_prepare_samples(g["X"], g["y"], g["lengthscale"], g["signal_var"], g["noise_var"], g["omega"],
                                   g["phase"], g["w"], g["eps"], None)
         outs = [torch.full(sh, float("nan"), device="cuda")
