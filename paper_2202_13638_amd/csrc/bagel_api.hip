@@ -102,65 +102,6 @@ static void destroy_side(bagel_ctx *c)
     if (c->side) { (void)hipStreamDestroy(c->side); c->side = nullptr; }
 }
 
-static int env_int(const char *name, int dflt)
-{
-    const char *s = getenv(name);
-    if (!s || !*s) return dflt;
-    const int v = atoi(s);
-    return v > 0 ? v : dflt;
-}
-
-// Work decomposition of one sample evaluation (sets CK, CL, nck, ncl, Np, Lp, units, groups and the
-// exp2 form from dm, D, M); returns a message if the problem cannot be decomposed.
-static const char *plan_sample_eval(bagel_ctx *c)
-{
-    // work decomposition of one sample evaluation: power-of-two chunk of training points / features
-    const bagel_dims *dims = &c->dm;
-    const int B = dims->B, N = dims->N, L = dims->L, M = c->M;
-    const int64_t tb = (B + BAGEL_BLOCK - 1) / BAGEL_BLOCK;
-    const int64_t items = (int64_t)(N + L) * M * tb;
-    const int target = env_int("BAGEL_TARGET_WGS", 4096);
-    int chunk = 1024;
-    while (chunk > 32 && items / chunk < target) chunk /= 2;
-    // Longer units for the training points when there are plenty of them (fewer partial sums), shorter
-    // ones for the features of a large problem: workgroups are dispatched in grid order, training-point
-    // units first, so short feature units at the end fill the tail of the launch.  Measured on MI355X:
-    // stress 0.650 ms per launch at (CK, CL) = (1024, 512), 0.628 ms at (1024, 256); the large-policy
-    // step 140.6 ms at (128, 64), 136.8 ms at (256, 64).
-    // A launch that stays under the target even with the smallest chunk has only a handful of waves per
-    // SIMD, and the longest of them sets its duration (measured: launch time grows in proportion to
-    // CK), so its units are kept short and alike: medium 10.7 ms per call at (128, 32), 9.7 ms at
-    // (64, 64); small 3.78 ms at (64, 32), 3.46 ms at (32, 32).  (Staging the operand rows through LDS
-    // and look-ahead loads of the stream changed nothing there: those launches are not latency-bound.)
-    const bool small_launch = chunk == 32 && items / chunk < target;
-    const int ck_default = small_launch ? (N / chunk >= 64 ? 64 : 32)
-                                        : (N / chunk >= 32 ? 4 * chunk : (N / chunk >= 16 ? 2 * chunk : chunk));
-    const int cl_default = small_launch ? (N / chunk >= 64 ? 64 : 32)
-                                        : ((chunk >= 512 && L / chunk >= 8) ? chunk / 2 : chunk);
-    c->CK = env_int("BAGEL_CK", ck_default);
-    c->CL = env_int("BAGEL_CL", cl_default);
-    c->CK = (c->CK + 7) & ~7;         // the sample-evaluation loops take two float4 (eight points) per trip
-    c->CL = (c->CL + 7) & ~7;
-    c->nck = (N + c->CK - 1) / c->CK;
-    c->ncl = (L + c->CL - 1) / c->CL;
-    c->Np = c->nck * c->CK;
-    c->Lp = c->ncl * c->CL;
-    c->units = M * (c->nck + c->ncl);
-    c->groups = M * ((c->nck + 3) / 4 + (c->ncl + 3) / 4);
-    // The table form of the kernel-row loop (gp_step.hip) pays once the launch has a few workgroups per
-    // compute unit; below that its extra set-up per workgroup (the table copy) and the wait counter its
-    // LDS read shares with the scalar loads cost more than its five fewer instructions per training point
-    // save.  Measured on MI355X, table vs general form, per launch: stress (4608 workgroups) 0.561 vs
-    // 0.60 ms; large policy (3072) 83.7 vs 86.4 us; medium (1280) 20.9 vs 22.4 us; small (192) 9.6 vs 9.2 us.
-    {
-        const int64_t wgs = (int64_t)((B + 63) / 64) * c->groups;
-        const int tab = env_int("BAGEL_EXP_TABLE", 0);         // 1: off, 2: on, otherwise by launch size
-        c->exp_table = tab == 2 ? true : (tab == 1 ? false : wgs >= 1024);
-    }
-    if (c->units > 65535 - BAGEL_MAX_STATE) return "too many work units (M * (N + L) / 32 must stay below 65527)";
-    return nullptr;
-}
-
 extern "C" int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_stream)
 {
     if (!out || !dims) CREATE_FAIL(BAGEL_EINVAL, "bagel_create: null argument");
@@ -177,7 +118,7 @@ extern "C" int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_s
     layer_layout(dims, c->width, c->w_off, c->b_off, &c->P);
     c->stream = (hipStream_t)hip_stream;
 
-    if (const char *msg = plan_sample_eval(c)) {     // msg is a string literal: it outlives c
+    if (const char *msg = bagel_plan_sample_eval(c)) {     // msg is a string literal: it outlives c
         delete c;
         CREATE_FAIL(BAGEL_EINVAL, "bagel_create: %s", msg);
     }
@@ -186,7 +127,7 @@ extern "C" int bagel_create(bagel_ctx **out, const bagel_dims *dims, void *hip_s
     const int K = dims->ckpt_interval;
     const int H = dims->H;
     c->T_tape = (K > 0 && K < H) ? K : H;
-    c->ksplit = env_int("BAGEL_KSPLIT", 256);
+    c->ksplit = bagel_env_int("BAGEL_KSPLIT", 256);
     int wf_total = 0, wb_total = 0;
     for (int l = 0; l < c->n_layers; ++l) {
         const int no = c->width[l + 1], ni = c->width[l];
@@ -378,7 +319,7 @@ static int64_t static_scratch_bytes(const bagel_dims *dims)
     c.dm = *dims;
     c.D = dims->d_s + dims->d_a;
     c.M = dims->d_s;
-    if (plan_sample_eval(&c)) return BAGEL_EINVAL;
+    if (bagel_plan_sample_eval(&c)) return BAGEL_EINVAL;
     const int64_t M = c.M, D = c.D, B = dims->B, S = dims->S;
     const int64_t counts[] = {8 * M * c.Np * (D + 1), 8 * M * c.Lp * (D + 1), 16 * M * c.Lp * ((D + 3) / 4), 8 * M * D, 8 * M,
                               16 * M * (c.Np / 4) * S, 16 * M * (c.Lp / 4) * S, 8 * D * B,
@@ -413,7 +354,7 @@ extern "C" int bagel_sample_eval_static(const bagel_dims *dims, void *hip_stream
     c.D = dims->d_s + dims->d_a;
     c.M = dims->d_s;
     c.stream = (hipStream_t)hip_stream;
-    (void)plan_sample_eval(&c);             // cannot fail: static_scratch_bytes has planned the same dims
+    (void)bagel_plan_sample_eval(&c);             // cannot fail: static_scratch_bytes has planned the same dims
     c.exp_table = false;                    // the table form of exp2 reads a table this call does not have
     const size_t M = c.M, D = c.D, B = dims->B, S = dims->S;
     size_t off = 0;

@@ -109,6 +109,11 @@ struct bagel_ctx {
     } while (0)
 
 // ---- gp_step.hip -------------------------------------------------------------------------
+// Integer from the environment (the overrides documented in bagel.h), or dflt if unset or not positive.
+int bagel_env_int(const char *name, int dflt);
+// Work decomposition of one sample evaluation (sets CK, CL, nck, ncl, Np, Lp, units, groups and the
+// exp2 form from dm, D, M); returns a message, a string literal, if the problem cannot be decomposed.
+const char *bagel_plan_sample_eval(bagel_ctx *ctx);
 // One evaluation of all function samples at xbuf: partial sums per work unit into ctx->part.
 // prev_jac: if not null, the same launch also adds up the Jacobian sums of the previous step (in
 // ctx->part_alt, evaluated at ctx->xbuf_alt) into prev_jac[M][D][B] (a slot of the Jacobian tape).

@@ -31,6 +31,8 @@
 //
 // The random-feature phase is accumulated in float64 in revolutions, reduced exactly to
 // [0, 1) and only then rounded to float32 for the hardware sin / cos (which take revolutions).
+#include <stdlib.h>
+
 #include "bagel_internal.h"
 
 namespace {
@@ -542,6 +544,65 @@ hipError_t launch_d(bagel_ctx *c, bool jac, float *prev_jac)
 }
 
 }  // namespace
+
+int bagel_env_int(const char *name, int dflt)
+{
+    const char *s = getenv(name);
+    if (!s || !*s) return dflt;
+    const int v = atoi(s);
+    return v > 0 ? v : dflt;
+}
+
+// Work decomposition of one sample evaluation (sets CK, CL, nck, ncl, Np, Lp, units, groups and the
+// exp2 form from dm, D, M); returns a message if the problem cannot be decomposed.
+const char *bagel_plan_sample_eval(bagel_ctx *c)
+{
+    // work decomposition of one sample evaluation: power-of-two chunk of training points / features
+    const bagel_dims *dims = &c->dm;
+    const int B = dims->B, N = dims->N, L = dims->L, M = c->M;
+    const int64_t tb = (B + BAGEL_BLOCK - 1) / BAGEL_BLOCK;
+    const int64_t items = (int64_t)(N + L) * M * tb;
+    const int target = bagel_env_int("BAGEL_TARGET_WGS", 4096);
+    int chunk = 1024;
+    while (chunk > 32 && items / chunk < target) chunk /= 2;
+    // Longer units for the training points when there are plenty of them (fewer partial sums), shorter
+    // ones for the features of a large problem: workgroups are dispatched in grid order, training-point
+    // units first, so short feature units at the end fill the tail of the launch.  Measured on MI355X:
+    // stress 0.650 ms per launch at (CK, CL) = (1024, 512), 0.628 ms at (1024, 256); the large-policy
+    // step 140.6 ms at (128, 64), 136.8 ms at (256, 64).
+    // A launch that stays under the target even with the smallest chunk has only a handful of waves per
+    // SIMD, and the longest of them sets its duration (measured: launch time grows in proportion to
+    // CK), so its units are kept short and alike: medium 10.7 ms per call at (128, 32), 9.7 ms at
+    // (64, 64); small 3.78 ms at (64, 32), 3.46 ms at (32, 32).  (Staging the operand rows through LDS
+    // and look-ahead loads of the stream changed nothing there: those launches are not latency-bound.)
+    const bool small_launch = chunk == 32 && items / chunk < target;
+    const int ck_default = small_launch ? (N / chunk >= 64 ? 64 : 32)
+                                        : (N / chunk >= 32 ? 4 * chunk : (N / chunk >= 16 ? 2 * chunk : chunk));
+    const int cl_default = small_launch ? (N / chunk >= 64 ? 64 : 32)
+                                        : ((chunk >= 512 && L / chunk >= 8) ? chunk / 2 : chunk);
+    c->CK = bagel_env_int("BAGEL_CK", ck_default);
+    c->CL = bagel_env_int("BAGEL_CL", cl_default);
+    c->CK = (c->CK + 7) & ~7;         // the sample-evaluation loops take two float4 (eight points) per trip
+    c->CL = (c->CL + 7) & ~7;
+    c->nck = (N + c->CK - 1) / c->CK;
+    c->ncl = (L + c->CL - 1) / c->CL;
+    c->Np = c->nck * c->CK;
+    c->Lp = c->ncl * c->CL;
+    c->units = M * (c->nck + c->ncl);
+    c->groups = M * ((c->nck + 3) / 4 + (c->ncl + 3) / 4);
+    // The table form of the kernel-row loop (gp_step.hip) pays once the launch has a few workgroups per
+    // compute unit; below that its extra set-up per workgroup (the table copy) and the wait counter its
+    // LDS read shares with the scalar loads cost more than its five fewer instructions per training point
+    // save.  Measured on MI355X, table vs general form, per launch: stress (4608 workgroups) 0.561 vs
+    // 0.60 ms; large policy (3072) 83.7 vs 86.4 us; medium (1280) 20.9 vs 22.4 us; small (192) 9.6 vs 9.2 us.
+    {
+        const int64_t wgs = (int64_t)((B + 63) / 64) * c->groups;
+        const int tab = bagel_env_int("BAGEL_EXP_TABLE", 0);         // 1: off, 2: on, otherwise by launch size
+        c->exp_table = tab == 2 ? true : (tab == 1 ? false : wgs >= 1024);
+    }
+    if (c->units > 65535 - BAGEL_MAX_STATE) return "too many work units (M * (N + L) / 32 must stay below 65527)";
+    return nullptr;
+}
 
 hipError_t bagel_launch_gp_step(bagel_ctx *c, bool jac, float *prev_jac)
 {
