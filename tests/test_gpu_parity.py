@@ -645,6 +645,49 @@ def test_inner_loop_against_oracle():
     ctx.close()
 
 
+def test_inner_loop_with_checkpointing_equals_its_steps_taken_one_by_one():
+    """With checkpointing the backward pass works on two streams.  Several iterations enqueued back to back by
+    bagel_optimize must equal, bit for bit, gradient call + Adam step issued one at a time with a full
+    synchronisation after each, and must be reproducible."""
+    import torch
+    from paper_2202_13638_amd import binding
+    cfg = _cfg("small", B=96, H=23)
+    inp = synth.make_inputs(cfg)
+    g = harness.to_gpu(inp)
+    ctx = binding.Bagel(binding.dims_from_config(cfg, ckpt_interval=5))
+    ctx.bagel_prepare_samples(g["X"], g["y"], g["lengthscale"], g["signal_var"], g["noise_var"], g["omega"],
+                              g["phase"], g["w"], g["eps"], None)
+    hp = dict(lr=1e-2, beta1=0.9, beta2=0.999, eps=1e-8)
+    n = 4
+    s0_sets, goal_sets = g["s0"][None].contiguous(), g["goals"][None].contiguous()
+
+    def free_running():
+        theta = g["theta"].clone()
+        m, v = torch.zeros_like(theta), torch.zeros_like(theta)
+        hist = torch.zeros(n, device="cuda")
+        ctx.bagel_optimize(theta, m, v, s0_sets, goal_sets, n, hist, **hp)
+        torch.cuda.synchronize()
+        return theta, m, v, hist
+
+    a, b = free_running(), free_running()
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+    theta = g["theta"].clone()
+    m, v = torch.zeros_like(theta), torch.zeros_like(theta)
+    loss, grad = torch.zeros(1, device="cuda"), torch.zeros(ctx.P, device="cuda")
+    hist = []
+    for it in range(n):
+        ctx.bagel_rollout_loss_grad(theta, g["s0"], g["goals"], loss, grad)
+        torch.cuda.synchronize()
+        hist.append(float(loss.item()))
+        ctx.bagel_adam_step(theta, grad, m, v, it + 1, **hp)
+        torch.cuda.synchronize()
+    assert torch.equal(theta, a[0]) and torch.equal(m, a[1]) and torch.equal(v, a[2])
+    assert hist == [float(x) for x in a[3].cpu()]
+    assert hist[-1] < hist[0]
+    ctx.close()
+
+
 # ------------------------------------------------------------------ per-step posterior sampler
 def _posterior_case(cfg, label, S=None, **dims_kw):
     """Oracle (exact eq. (2), (3) moments, reparameterised draws) against bagel_prepare_posterior +
